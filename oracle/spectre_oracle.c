@@ -1,0 +1,477 @@
+/*
+ * SPECTRE spectral mixer and Prefix-FFT cache: slow, plain fp64 CPU definition.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the yardstick the GPU library is
+ * compared against.  It shares no code, header, table or constant with the HIP
+ * path and must never be linked, imported or called from the product path; only
+ * the tests, the smoke check and the CPU-baseline leg of the benchmark use it.
+ *
+ * Everything is evaluated straight from the paper's definitions, in double
+ * precision, one column (one channel of one head of one sequence) at a time:
+ *
+ *   - the real DFT of Sec. 3.1 Eq. (1) and its inverse (App. B, Cor. B.2),
+ *     two independent ways: the O(n^2) sum and a textbook iterative radix-2
+ *     FFT (Bluestein's chirp-z on top of it when n is not a power of two);
+ *   - the content-adaptive gate of Sec. 3.2 step 3 (pooled query -> LayerNorm
+ *     -> two-layer MLP -> complex gate -> modReLU -> positional phase);
+ *   - the mixing layer of Sec. 3.2 steps 2-4 (Eq. 3, Eq. 4);
+ *   - the Prefix-FFT cache of Sec. 3.3 / Algorithm 1 (pre-fill, the rank-one
+ *     update with eviction of Eq. (5), ring buffers, running query sum, and the
+ *     two readouts).
+ *
+ * Readings of passages where the paper is silent or garbled (each one is also
+ * what the GPU library implements; none is pinned by a number the paper prints,
+ * so parity for these choices is "parity unpinned" by the paper and pinned only
+ * by mathematics that holds under the stated reading):
+ *   - forward transform unnormalised, inverse carries 1/n (Eq. 1, Cor. B.2);
+ *   - LayerNorm: affine, biased variance over the d channels, eps a parameter;
+ *   - MLP: hidden = GELU(qbar W1 + b1) with the exact erf form, u = hidden W2 + b2,
+ *     2F real outputs read as F interleaved (re, im) pairs;
+ *   - modReLU (its formula is missing from the paper's step 3c): the standard
+ *     one, z -> max(|z| + b, 0) z/|z| with a real bias per bin, 0 at z = 0;
+ *   - a complex gate makes the DC and Nyquist products non-real; the inverse
+ *     real transform keeps their real parts only (equivalently: extend the gated
+ *     half spectrum by Hermitian symmetry and take the real part);
+ *   - positional phase multiplies bin k by exp(+j 2 pi k p / n) for one scalar
+ *     position p per call.
+ *
+ * Complex arrays are interleaved (re, im) doubles.  Tensors are row-major with
+ * the index order written in each comment.  No function here keeps state.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#ifndef M_PI
+#define M_PI 3.14159265358979323846264338327950288
+#endif
+
+typedef struct { double re, im; } cplx;
+
+static cplx c_mul(cplx a, cplx b) {
+    cplx r = { a.re * b.re - a.im * b.im, a.re * b.im + a.im * b.re };
+    return r;
+}
+
+/* exp(sign * j * 2 pi * num / den); num is first reduced into [0, den) with
+ * integer arithmetic so the angle handed to sin/cos is always below 2 pi. */
+static cplx root_of_unity(long long num, long long den, int sign) {
+    long long m = num % den;
+    if (m < 0) m += den;
+    double ang = 2.0 * M_PI * (double)m / (double)den;
+    cplx r = { cos(ang), sign * sin(ang) };
+    return r;
+}
+
+int so_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------------- */
+/* Discrete Fourier transform, the sum as printed (Thm. B.1; Cor. B.2 for the
+ * inverse, which this routine leaves unscaled).  out[k] = sum_t in[t] *
+ * exp(sign*j*2*pi*k*t/n) for k = 0..n-1.  O(n^2). */
+void so_dft_naive(int n, int sign, const double *in, double *out) {
+    const cplx *x = (const cplx *)in;
+    cplx *X = (cplx *)out;
+    for (int k = 0; k < n; ++k) {
+        double sr = 0.0, si = 0.0;
+        for (int t = 0; t < n; ++t) {
+            cplx w = root_of_unity((long long)k * t, n, sign);
+            cplx p = c_mul(x[t], w);
+            sr += p.re;
+            si += p.im;
+        }
+        X[k].re = sr;
+        X[k].im = si;
+    }
+}
+
+static int is_pow2(int n) { return n > 0 && (n & (n - 1)) == 0; }
+
+/* Textbook iterative radix-2 decimation-in-time FFT, in place, n a power of
+ * two, unscaled for either sign.  Returns 0, or -1 if n is not a power of two. */
+int so_fft_radix2(int n, int sign, double *data) {
+    if (!is_pow2(n)) return -1;
+    cplx *a = (cplx *)data;
+    /* bit-reversal permutation */
+    for (int i = 1, j = 0; i < n; ++i) {
+        int bit = n >> 1;
+        for (; j & bit; bit >>= 1) j ^= bit;
+        j ^= bit;
+        if (i < j) { cplx t = a[i]; a[i] = a[j]; a[j] = t; }
+    }
+    for (int len = 2; len <= n; len <<= 1) {
+        int half = len >> 1;
+        for (int s = 0; s < n; s += len) {
+            for (int m = 0; m < half; ++m) {
+                cplx w = root_of_unity(m, len, sign);
+                cplx u = a[s + m];
+                cplx v = c_mul(a[s + m + half], w);
+                a[s + m].re = u.re + v.re;
+                a[s + m].im = u.im + v.im;
+                a[s + m + half].re = u.re - v.re;
+                a[s + m + half].im = u.im - v.im;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Bluestein's identity kt = (k^2 + t^2 - (k-t)^2)/2 turns an n-point DFT into a
+ * circular convolution of length M >= 2n-1 (a power of two), which the radix-2
+ * routine evaluates.  Chirp angles use m^2 mod 2n so they stay exact. */
+static int fft_bluestein(int n, int sign, const cplx *in, cplx *out) {
+    int M = 1;
+    while (M < 2 * n - 1) M <<= 1;
+    cplx *chirp = (cplx *)malloc(sizeof(cplx) * (size_t)n);
+    cplx *A = (cplx *)calloc((size_t)M, sizeof(cplx));
+    cplx *Bv = (cplx *)calloc((size_t)M, sizeof(cplx));
+    if (!chirp || !A || !Bv) { free(chirp); free(A); free(Bv); return -2; }
+    for (int m = 0; m < n; ++m) /* exp(sign*j*pi*m^2/n) */
+        chirp[m] = root_of_unity((long long)m * m, 2LL * n, sign);
+    for (int m = 0; m < n; ++m) {
+        A[m] = c_mul(in[m], chirp[m]);
+        cplx cc = { chirp[m].re, -chirp[m].im };
+        Bv[m] = cc;
+        if (m) Bv[M - m] = cc;
+    }
+    so_fft_radix2(M, -1, (double *)A);
+    so_fft_radix2(M, -1, (double *)Bv);
+    for (int m = 0; m < M; ++m) A[m] = c_mul(A[m], Bv[m]);
+    so_fft_radix2(M, +1, (double *)A);
+    for (int k = 0; k < n; ++k) {
+        cplx v = { A[k].re / M, A[k].im / M };
+        out[k] = c_mul(v, chirp[k]);
+    }
+    free(chirp); free(A); free(Bv);
+    return 0;
+}
+
+/* Fast complex DFT of any length, unscaled, out of place. */
+int so_fft(int n, int sign, const double *in, double *out) {
+    if (n < 1) return -1;
+    if (is_pow2(n)) {
+        if (out != in) memcpy(out, in, sizeof(cplx) * (size_t)n);
+        return so_fft_radix2(n, sign, out);
+    }
+    return fft_bluestein(n, sign, (const cplx *)in, (cplx *)out);
+}
+
+/* Real transform of Eq. (1): X[k] = sum_t x[t] exp(-j 2 pi k t / n) for
+ * k = 0..floor(n/2).  method 0 = the O(n^2) sum, 1 = the fast transform. */
+int so_rfft(int n, const double *x, double *X, int method) {
+    int F = n / 2 + 1;
+    cplx *Xc = (cplx *)X;
+    if (method == 0) {
+        for (int k = 0; k < F; ++k) {
+            double sr = 0.0, si = 0.0;
+            for (int t = 0; t < n; ++t) {
+                cplx w = root_of_unity((long long)k * t, n, -1);
+                sr += x[t] * w.re;
+                si += x[t] * w.im;
+            }
+            Xc[k].re = sr;
+            Xc[k].im = si;
+        }
+        return 0;
+    }
+    cplx *buf = (cplx *)malloc(sizeof(cplx) * (size_t)n * 2);
+    if (!buf) return -2;
+    for (int t = 0; t < n; ++t) { buf[t].re = x[t]; buf[t].im = 0.0; }
+    int rc = so_fft(n, -1, (double *)buf, (double *)(buf + n));
+    if (rc == 0) memcpy(Xc, buf + n, sizeof(cplx) * (size_t)F);
+    free(buf);
+    return rc;
+}
+
+/* Inverse real transform (Cor. B.2): the half spectrum Y[0..floor(n/2)] is
+ * extended by Y[n-k] = conj(Y[k]); DC and (n even) Nyquist contribute their
+ * real parts only; x[m] = (1/n) sum_k Yfull[k] exp(+j 2 pi k m / n). */
+int so_irfft(int n, const double *Y, double *x, int method) {
+    int F = n / 2 + 1;
+    const cplx *Yc = (const cplx *)Y;
+    if (method == 0) {
+        for (int m = 0; m < n; ++m) {
+            double acc = Yc[0].re;
+            for (int k = 1; k < F; ++k) {
+                cplx w = root_of_unity((long long)k * m, n, +1);
+                if (2 * k == n) acc += Yc[k].re * w.re; /* Nyquist: w = (-1)^m */
+                else acc += 2.0 * (Yc[k].re * w.re - Yc[k].im * w.im);
+            }
+            x[m] = acc / n;
+        }
+        return 0;
+    }
+    cplx *buf = (cplx *)malloc(sizeof(cplx) * (size_t)n * 2);
+    if (!buf) return -2;
+    buf[0].re = Yc[0].re; buf[0].im = 0.0;
+    for (int k = 1; k < F; ++k) {
+        if (2 * k == n) { buf[k].re = Yc[k].re; buf[k].im = 0.0; }
+        else {
+            buf[k] = Yc[k];
+            buf[n - k].re = Yc[k].re;
+            buf[n - k].im = -Yc[k].im;
+        }
+    }
+    int rc = so_fft(n, +1, (double *)buf, (double *)(buf + n));
+    if (rc == 0) for (int m = 0; m < n; ++m) x[m] = buf[n + m].re / n;
+    free(buf);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gate, Sec. 3.2 step 3 (a), (c) and the positional phase paragraph; the same
+ * steps serve Algorithm 1's decode gate with inv_count = 1/N_max.
+ *
+ *   sum_q   [B,H,d]      sum of the query rows (caller pools, or cache state)
+ *   x = inv_count * sum_q;  qbar = gamma*(x-mean)/sqrt(var+eps)+beta
+ *   hid = GELU(qbar W1 + b1);  u = hid W2 + b2;  g_k = u[2k] + j u[2k+1]
+ *   g_k <- max(|g_k| + bias_k, 0) g_k/|g_k|      (bias == NULL: left as is)
+ *   g_k <- g_k exp(+j 2 pi ((k p) mod n)/n)      (p == 0: no phase)
+ *
+ * Parameters are per head when Hg == H and shared by all heads when Hg == 1:
+ *   gamma, beta [Hg,d]; W1 [Hg,d,dg]; b1 [Hg,dg]; W2 [Hg,dg,2F]; b2 [Hg,2F];
+ *   bias [Hg,F] or NULL.   F = n/2+1.   g_out [B,H,F] complex. */
+int so_gate(int B, int H, int d, int dg, int n, int Hg,
+            const double *sum_q, double inv_count,
+            const double *gamma, const double *beta, double eps,
+            const double *W1, const double *b1,
+            const double *W2, const double *b2,
+            const double *bias, long long p, double *g_out) {
+    if (!(Hg == H || Hg == 1) || n < 1 || d < 1 || dg < 1) return -1;
+    int F = n / 2 + 1;
+    cplx *g = (cplx *)g_out;
+    double *qbar = (double *)malloc(sizeof(double) * (size_t)(d + dg));
+    if (!qbar) return -2;
+    double *hid = qbar + d;
+    for (int b = 0; b < B; ++b) for (int h = 0; h < H; ++h) {
+        int hp = (Hg == 1) ? 0 : h;
+        const double *sq = sum_q + ((size_t)b * H + h) * d;
+        double mean = 0.0, var = 0.0;
+        for (int i = 0; i < d; ++i) mean += inv_count * sq[i];
+        mean /= d;
+        for (int i = 0; i < d; ++i) {
+            double c = inv_count * sq[i] - mean;
+            var += c * c;
+        }
+        var /= d;
+        for (int i = 0; i < d; ++i)
+            qbar[i] = gamma[(size_t)hp * d + i] * (inv_count * sq[i] - mean) / sqrt(var + eps)
+                    + beta[(size_t)hp * d + i];
+        for (int j = 0; j < dg; ++j) {
+            double a = b1[(size_t)hp * dg + j];
+            for (int i = 0; i < d; ++i) a += qbar[i] * W1[((size_t)hp * d + i) * dg + j];
+            hid[j] = 0.5 * a * (1.0 + erf(a / sqrt(2.0)));
+        }
+        for (int k = 0; k < F; ++k) {
+            cplx u;
+            u.re = b2[(size_t)hp * 2 * F + 2 * k];
+            u.im = b2[(size_t)hp * 2 * F + 2 * k + 1];
+            for (int j = 0; j < dg; ++j) {
+                const double *w = W2 + ((size_t)hp * dg + j) * 2 * F + 2 * k;
+                u.re += hid[j] * w[0];
+                u.im += hid[j] * w[1];
+            }
+            if (bias) {
+                double mag = sqrt(u.re * u.re + u.im * u.im);
+                if (mag == 0.0) { u.re = 0.0; u.im = 0.0; }
+                else {
+                    double act = mag + bias[(size_t)hp * F + k];
+                    if (act < 0.0) act = 0.0;
+                    u.re *= act / mag;
+                    u.im *= act / mag;
+                }
+            }
+            if (p != 0) {
+                long long pm = p % n; if (pm < 0) pm += n;
+                u = c_mul(u, root_of_unity((long long)k * pm, n, +1));
+            }
+            g[((size_t)b * H + h) * F + k] = u;
+        }
+    }
+    free(qbar);
+    return 0;
+}
+
+/* sum_q[b,h,c] = sum_l Q[b,l,h,c]   (Q is [B,L,H,d]) */
+void so_pool_q(int B, int L, int H, int d, const double *Q, double *sum_q) {
+    for (int b = 0; b < B; ++b) for (int h = 0; h < H; ++h) for (int c = 0; c < d; ++c) {
+        double s = 0.0;
+        for (int l = 0; l < L; ++l) s += Q[(((size_t)b * L + l) * H + h) * d + c];
+        sum_q[((size_t)b * H + h) * d + c] = s;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Mixing layer, Sec. 3.2 steps 2 and 4 (Eq. 3, Eq. 4): for every sequence b,
+ * head h and channel c,  out[b,:,h,c] = irfft_L( g[b,h,:] * rfft_L(V[b,:,h,c]) ).
+ * V, out [B,L,H,d]; g [B,H,F] complex.  method as in so_rfft. */
+int so_mix_forward(int B, int L, int H, int d, const double *V, const double *g,
+                   double *out, int method) {
+    int F = L / 2 + 1;
+    long long ncol = (long long)B * H * d;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long long col = 0; col < ncol; ++col) {
+        int c = (int)(col % d);
+        int h = (int)((col / d) % H);
+        int b = (int)(col / ((long long)d * H));
+        double *x = (double *)malloc(sizeof(double) * ((size_t)L + 2 * (size_t)F));
+        if (!x) { fail = 1; continue; }
+        cplx *X = (cplx *)(x + L);
+        for (int l = 0; l < L; ++l) x[l] = V[(((size_t)b * L + l) * H + h) * d + c];
+        if (so_rfft(L, x, (double *)X, method)) fail = 1;
+        const cplx *gg = (const cplx *)g + ((size_t)b * H + h) * F;
+        for (int k = 0; k < F; ++k) X[k] = c_mul(gg[k], X[k]);
+        if (so_irfft(L, (double *)X, x, method)) fail = 1;
+        for (int l = 0; l < L; ++l) out[(((size_t)b * L + l) * H + h) * d + c] = x[l];
+        free(x);
+    }
+    return fail ? -2 : 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Prefix-FFT cache, Sec. 3.3 and Algorithm 1.  State for B*H heads:
+ *   spec   [B,H,F,d] complex   the N-point half spectrum of the ring buffer
+ *   v_buf  [B,H,N,d], q_buf [B,H,N,d]   ring buffers, slot = position mod N
+ *   sum_q  [B,H,d]             running sum of the live queries
+ * The token counter t (tokens appended so far) is kept by the caller. */
+
+/* Pre-fill (Algorithm 1, PreFill): a prompt of T <= N tokens, zero-padded at
+ * the tail to N, transformed once.  V, Q are [B,T,H,d]. */
+int so_prefix_prefill(int B, int H, int d, int N, int T, const double *V, const double *Q,
+                      double *spec, double *v_buf, double *q_buf, double *sum_q, int method) {
+    if (T > N || T < 0) return -1;
+    int F = N / 2 + 1;
+    long long ncol = (long long)B * H * d;
+    int fail = 0;
+    memset(v_buf, 0, sizeof(double) * (size_t)B * H * N * d);
+    memset(q_buf, 0, sizeof(double) * (size_t)B * H * N * d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long long col = 0; col < ncol; ++col) {
+        int c = (int)(col % d);
+        int h = (int)((col / d) % H);
+        int b = (int)(col / ((long long)d * H));
+        double *x = (double *)calloc((size_t)N + 2 * (size_t)F, sizeof(double));
+        if (!x) { fail = 1; continue; }
+        double s = 0.0;
+        for (int l = 0; l < T; ++l) {
+            size_t src = (((size_t)b * T + l) * H + h) * d + c;
+            size_t dst = (((size_t)b * H + h) * N + l) * d + c;
+            x[l] = V[src];
+            v_buf[dst] = V[src];
+            q_buf[dst] = Q[src];
+            s += Q[src];
+        }
+        sum_q[((size_t)b * H + h) * d + c] = s;
+        if (so_rfft(N, x, x + N, method)) fail = 1;
+        for (int k = 0; k < F; ++k) {
+            size_t o = ((((size_t)b * H + h) * F + k) * d + c) * 2;
+            spec[o] = x[N + 2 * k];
+            spec[o + 1] = x[N + 2 * k + 1];
+        }
+        free(x);
+    }
+    return fail ? -2 : 0;
+}
+
+/* One decode step (Algorithm 1, DecodeStep, up to the gate): append token
+ * number t (0-based count of tokens seen before it).  v_t, q_t are [B,H,d]
+ * (the single new row of a [B,1,H,d] tensor).  Eq. (5): the evicted and the
+ * inserted token share the slot s = t mod N and so the same root of unity,
+ * because exp(-j 2 pi k (t-N)/N) = exp(-j 2 pi k t/N). */
+void so_prefix_update(int B, int H, int d, int N, long long t, const double *v_t, const double *q_t,
+                      double *spec, double *v_buf, double *q_buf, double *sum_q) {
+    int F = N / 2 + 1;
+    long long s = t % N;
+    double *delta = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!delta) return;
+    for (int b = 0; b < B; ++b) for (int h = 0; h < H; ++h) {
+        size_t bh = (size_t)b * H + h;
+        for (int c = 0; c < d; ++c) {
+            size_t slot = (bh * N + (size_t)s) * d + c;
+            double v_old = (t >= N) ? v_buf[slot] : 0.0;
+            double q_old = (t >= N) ? q_buf[slot] : 0.0;
+            double vn = v_t[bh * d + c], qn = q_t[bh * d + c];
+            delta[c] = vn - v_old;
+            v_buf[slot] = vn;
+            q_buf[slot] = qn;
+            sum_q[bh * d + c] += qn - q_old;
+        }
+        for (int k = 0; k < F; ++k) {
+            cplx w = root_of_unity((long long)k * s, N, -1);
+            for (int c = 0; c < d; ++c) {
+                size_t o = ((bh * F + k) * d + c) * 2;
+                spec[o] += delta[c] * w.re;
+                spec[o + 1] += delta[c] * w.im;
+            }
+        }
+    }
+    free(delta);
+}
+
+/* Readout of one row: out[b,h,c] = row m of irfft_N( g[b,h,:] * spec[b,h,:,c] ),
+ * written out as the single-row form of Cor. B.2's inverse (cost O(N/2 d) per
+ * head, the figure Sec. 3.3 quotes for a decode step). */
+void so_prefix_readout_row(int B, int H, int d, int N, long long m, const double *spec,
+                           const double *g, double *out) {
+    int F = N / 2 + 1;
+    long long mm = m % N; if (mm < 0) mm += N;
+    for (int b = 0; b < B; ++b) for (int h = 0; h < H; ++h) {
+        size_t bh = (size_t)b * H + h;
+        const cplx *gg = (const cplx *)g + bh * F;
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int k = 0; k < F; ++k) {
+                size_t o = ((bh * F + k) * d + c) * 2;
+                cplx X = { spec[o], spec[o + 1] };
+                cplx Y = c_mul(gg[k], X);
+                cplx w = root_of_unity((long long)k * mm, N, +1);
+                if (k == 0) acc += Y.re;
+                else if (2 * k == N) acc += Y.re * w.re;
+                else acc += 2.0 * (Y.re * w.re - Y.im * w.im);
+            }
+            out[bh * d + c] = acc / N;
+        }
+    }
+}
+
+/* Full-window readout (Algorithm 1, last three lines): the inverse N-point
+ * real transform of the gated cache, of which rows N-Lw..N-1 are returned as
+ * out [B,Lw,H,d].  The positional phase, if any, is already part of g. */
+int so_prefix_readout_window(int B, int H, int d, int N, int Lw, const double *spec,
+                             const double *g, double *out, int method) {
+    if (Lw < 0 || Lw > N) return -1;
+    int F = N / 2 + 1;
+    long long ncol = (long long)B * H * d;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long long col = 0; col < ncol; ++col) {
+        int c = (int)(col % d);
+        int h = (int)((col / d) % H);
+        int b = (int)(col / ((long long)d * H));
+        size_t bh = (size_t)b * H + h;
+        double *x = (double *)malloc(sizeof(double) * ((size_t)N + 2 * (size_t)F));
+        if (!x) { fail = 1; continue; }
+        cplx *Y = (cplx *)(x + N);
+        const cplx *gg = (const cplx *)g + bh * F;
+        for (int k = 0; k < F; ++k) {
+            size_t o = ((bh * F + k) * d + c) * 2;
+            cplx X = { spec[o], spec[o + 1] };
+            Y[k] = c_mul(gg[k], X);
+        }
+        if (so_irfft(N, (double *)Y, x, method)) fail = 1;
+        for (int i = 0; i < Lw; ++i)
+            out[(((size_t)b * Lw + i) * H + h) * d + c] = x[N - Lw + i];
+        free(x);
+    }
+    return fail ? -2 : 0;
+}

@@ -1,0 +1,201 @@
+"""numpy front end of the fp64 C oracle (``spectre_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY (see the C file's header).  Argument marshalling and
+nothing else: every number is produced by the C code.  All arrays are float64 /
+complex128, C-contiguous; shapes follow the paper's notation:
+
+    V, Q       [B, L, H, d]      value / query rows per head (Sec. 3.2 Eq. 2)
+    g          [B, H, F]         complex gate, F = L//2 + 1   (Sec. 3.2 step 3)
+    spec       [B, H, F, d]      Prefix-FFT cache             (Sec. 3.3, Alg. 1)
+    v_buf,q_buf[B, H, N, d]      ring buffers
+    sum_q      [B, H, d]         running query sum
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "spectre_oracle.c")
+_LIB = os.path.join(_HERE, "libspectre_oracle.so")
+
+NAIVE = 0   # the O(n^2) sums exactly as printed
+FAST = 1    # radix-2 FFT (Bluestein for other lengths)
+
+
+def build(force=False):
+    """Compile the C oracle with gcc (host only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _c128(a):
+    return np.ascontiguousarray(a, dtype=np.complex128)
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
+
+
+def num_threads():
+    return int(_L().so_num_threads())
+
+
+def dft_naive(x, sign=-1):
+    x = _c128(x)
+    out = np.empty_like(x)
+    _L().so_dft_naive(ctypes.c_int(x.shape[0]), ctypes.c_int(sign), _p(x), _p(out))
+    return out
+
+
+def fft(x, sign=-1):
+    x = _c128(x)
+    out = np.empty_like(x)
+    rc = _L().so_fft(ctypes.c_int(x.shape[0]), ctypes.c_int(sign), _p(x), _p(out))
+    if rc:
+        raise RuntimeError(f"so_fft rc={rc}")
+    return out
+
+
+def rfft(x, method=FAST):
+    x = _f64(x)
+    n = x.shape[0]
+    out = np.empty(n // 2 + 1, dtype=np.complex128)
+    rc = _L().so_rfft(ctypes.c_int(n), _p(x), _p(out), ctypes.c_int(method))
+    if rc:
+        raise RuntimeError(f"so_rfft rc={rc}")
+    return out
+
+
+def irfft(Y, n, method=FAST):
+    Y = _c128(Y)
+    assert Y.shape[0] == n // 2 + 1
+    out = np.empty(n, dtype=np.float64)
+    rc = _L().so_irfft(ctypes.c_int(n), _p(Y), _p(out), ctypes.c_int(method))
+    if rc:
+        raise RuntimeError(f"so_irfft rc={rc}")
+    return out
+
+
+def pool_q(Q):
+    Q = _f64(Q)
+    B, L, H, d = Q.shape
+    out = np.empty((B, H, d), dtype=np.float64)
+    _L().so_pool_q(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.c_int(d), _p(Q), _p(out))
+    return out
+
+
+def gate(sum_q, inv_count, params, n, phase_pos=0):
+    """Gate from a pooled query sum.  ``params`` is a dict with ln_gamma, ln_beta
+    [Hg,d], ln_eps, W1 [Hg,d,dg], b1 [Hg,dg], W2 [Hg,dg,2F], b2 [Hg,2F],
+    modrelu_bias [Hg,F] or None."""
+    sum_q = _f64(sum_q)
+    B, H, d = sum_q.shape
+    W1 = _f64(params["W1"])
+    Hg, d_, dg = W1.shape
+    assert d_ == d
+    F = n // 2 + 1
+    W2 = _f64(params["W2"])
+    assert W2.shape == (Hg, dg, 2 * F), (W2.shape, (Hg, dg, 2 * F))
+    gam, bet = _f64(params["ln_gamma"]), _f64(params["ln_beta"])
+    b1, b2 = _f64(params["b1"]), _f64(params["b2"])
+    assert gam.shape == (Hg, d) and bet.shape == (Hg, d) and b1.shape == (Hg, dg) and b2.shape == (Hg, 2 * F)
+    bias = params.get("modrelu_bias")
+    if bias is not None:
+        bias = _f64(bias)
+        assert bias.shape == (Hg, F)
+    out = np.empty((B, H, F), dtype=np.complex128)
+    rc = _L().so_gate(ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(dg),
+                      ctypes.c_int(n), ctypes.c_int(Hg), _p(sum_q), ctypes.c_double(inv_count),
+                      _p(gam), _p(bet), ctypes.c_double(float(params["ln_eps"])),
+                      _p(W1), _p(b1), _p(W2), _p(b2), _p(bias),
+                      ctypes.c_longlong(int(phase_pos)), _p(out))
+    if rc:
+        raise RuntimeError(f"so_gate rc={rc}")
+    return out
+
+
+def mix_forward(V, g, method=FAST):
+    V = _f64(V)
+    g = _c128(g)
+    B, L, H, d = V.shape
+    assert g.shape == (B, H, L // 2 + 1)
+    out = np.empty_like(V)
+    rc = _L().so_mix_forward(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.c_int(d),
+                             _p(V), _p(g), _p(out), ctypes.c_int(method))
+    if rc:
+        raise RuntimeError(f"so_mix_forward rc={rc}")
+    return out
+
+
+class PrefixCache:
+    """State of Algorithm 1 for B*H heads; ``t`` counts the tokens appended."""
+
+    def __init__(self, B, H, d, N):
+        self.B, self.H, self.d, self.N = B, H, d, N
+        self.F = N // 2 + 1
+        self.t = 0
+        self.spec = np.zeros((B, H, self.F, d), dtype=np.complex128)
+        self.v_buf = np.zeros((B, H, N, d), dtype=np.float64)
+        self.q_buf = np.zeros((B, H, N, d), dtype=np.float64)
+        self.sum_q = np.zeros((B, H, d), dtype=np.float64)
+
+    def _dims(self):
+        return (ctypes.c_int(self.B), ctypes.c_int(self.H), ctypes.c_int(self.d), ctypes.c_int(self.N))
+
+    def prefill(self, V, Q, method=FAST):
+        V, Q = _f64(V), _f64(Q)
+        B, T, H, d = V.shape
+        assert (B, H, d) == (self.B, self.H, self.d) and Q.shape == V.shape and self.t == 0
+        rc = _L().so_prefix_prefill(*self._dims(), ctypes.c_int(T), _p(V), _p(Q), _p(self.spec),
+                                    _p(self.v_buf), _p(self.q_buf), _p(self.sum_q), ctypes.c_int(method))
+        if rc:
+            raise RuntimeError(f"so_prefix_prefill rc={rc}")
+        self.t = T
+
+    def update(self, v_t, q_t):
+        """Append one token; v_t, q_t are [B,1,H,d] or [B,H,d]."""
+        v_t = _f64(v_t).reshape(self.B, self.H, self.d)
+        q_t = _f64(q_t).reshape(self.B, self.H, self.d)
+        _L().so_prefix_update(*self._dims(), ctypes.c_longlong(self.t), _p(v_t), _p(q_t), _p(self.spec),
+                              _p(self.v_buf), _p(self.q_buf), _p(self.sum_q))
+        self.t += 1
+
+    def readout_row(self, g, m):
+        g = _c128(g)
+        assert g.shape == (self.B, self.H, self.F)
+        out = np.empty((self.B, self.H, self.d), dtype=np.float64)
+        _L().so_prefix_readout_row(*self._dims(), ctypes.c_longlong(int(m)), _p(self.spec), _p(g), _p(out))
+        return out
+
+    def readout_newest(self, g):
+        """Row of the newest token, slot (t-1) mod N; returned as [B,1,H,d]."""
+        return self.readout_row(g, (self.t - 1) % self.N).reshape(self.B, 1, self.H, self.d)
+
+    def readout_window(self, g, method=FAST):
+        """Rows N-L'..N-1 of the inverse transform, L' = min(t, N); [B,L',H,d]."""
+        g = _c128(g)
+        Lw = min(self.t, self.N)
+        out = np.empty((self.B, Lw, self.H, self.d), dtype=np.float64)
+        rc = _L().so_prefix_readout_window(*self._dims(), ctypes.c_int(Lw), _p(self.spec), _p(g), _p(out),
+                                           ctypes.c_int(method))
+        if rc:
+            raise RuntimeError(f"so_prefix_readout_window rc={rc}")
+        return out

@@ -1,0 +1,221 @@
+"""Pins for the oracle's mixing layer and gate (Sec. 3.2 steps 2-4, positional phase)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_18394_amd import synth
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ----------------------------------------------------------------------------- mixer
+@pytest.mark.parametrize("L", [4, 7, 16, 49, 196, 256])
+def test_identity_gate_returns_input(oracle, L):
+    """g = 1 everywhere: Eq. (4) inverts Eq. (3) (Cor. B.2, lossless)."""
+    V = _rng(L).standard_normal((2, L, 3, 4))
+    g = np.ones((2, 3, L // 2 + 1), complex)
+    for method in (oracle.NAIVE, oracle.FAST):
+        np.testing.assert_allclose(oracle.mix_forward(V, g, method), V, atol=1e-12)
+
+
+@pytest.mark.parametrize("L,s", [(8, 1), (8, 5), (16, 15), (7, 2), (196, 37), (64, 64)])
+def test_pure_phase_gate_is_circular_shift(oracle, L, s):
+    """g_k = exp(-j 2 pi k s/L) delays every channel by s positions, circularly."""
+    V = _rng(10 * L + s).standard_normal((1, L, 2, 3))
+    k = np.arange(L // 2 + 1)
+    g = np.broadcast_to(np.exp(-2j * np.pi * k * s / L), (1, 2, L // 2 + 1))
+    want = np.roll(V, s, axis=1)
+    for method in (oracle.NAIVE, oracle.FAST):
+        np.testing.assert_allclose(oracle.mix_forward(V, g, method), want, atol=1e-11)
+
+
+@pytest.mark.parametrize("L", [8, 9, 32, 196])
+def test_equals_time_domain_circular_convolution(oracle, L):
+    """diag(g) in the spectral basis is a circular convolution with kappa = inverse
+    real transform of g, the same kernel for every channel of the head; evaluated
+    here as a direct O(L^2) sum in the time domain with the library's irfft for kappa."""
+    r = _rng(77 + L)
+    B, H, d = 2, 2, 3
+    V = r.standard_normal((B, L, H, d))
+    F = L // 2 + 1
+    g = r.standard_normal((B, H, F)) + 1j * r.standard_normal((B, H, F))
+    want = np.zeros_like(V)
+    for b in range(B):
+        for h in range(H):
+            kappa = np.fft.irfft(g[b, h], L)
+            for m in range(L):
+                for t in range(L):
+                    want[b, m, h, :] += kappa[(m - t) % L] * V[b, t, h, :]
+    for method in (oracle.NAIVE, oracle.FAST):
+        np.testing.assert_allclose(oracle.mix_forward(V, g, method), want, atol=1e-10)
+
+
+def test_constant_input_sees_only_real_part_of_dc_gate(oracle):
+    L = 16
+    V = np.full((1, L, 1, 2), 3.0)
+    g = _rng(5).standard_normal((1, 1, L // 2 + 1)) + 1j * _rng(6).standard_normal((1, 1, L // 2 + 1))
+    out = oracle.mix_forward(V, g)
+    np.testing.assert_allclose(out, 3.0 * g[0, 0, 0].real * np.ones_like(V), atol=1e-12)
+
+
+def test_layout_heads_and_channels_do_not_leak(oracle):
+    """A single non-zero column (b,h,c) only produces output in that column, and uses gate (b,h)."""
+    B, L, H, d = 2, 8, 3, 4
+    r = _rng(9)
+    g = r.standard_normal((B, H, L // 2 + 1)) + 1j * r.standard_normal((B, H, L // 2 + 1))
+    for (b, h, c) in [(0, 0, 0), (1, 2, 3), (0, 1, 2)]:
+        V = np.zeros((B, L, H, d))
+        V[b, :, h, c] = r.standard_normal(L)
+        out = oracle.mix_forward(V, g)
+        mask = np.zeros_like(V, bool)
+        mask[b, :, h, c] = True
+        assert np.all(out[~mask] == 0.0)
+        want = np.fft.irfft(g[b, h] * np.fft.rfft(V[b, :, h, c]), L)
+        np.testing.assert_allclose(out[b, :, h, c], want, atol=1e-12)
+
+
+def test_linearity(oracle):
+    r = _rng(11)
+    L = 32
+    V1, V2 = r.standard_normal((1, L, 2, 2)), r.standard_normal((1, L, 2, 2))
+    g = r.standard_normal((1, 2, L // 2 + 1)) + 1j * r.standard_normal((1, 2, L // 2 + 1))
+    lhs = oracle.mix_forward(2.0 * V1 - 3.0 * V2, g)
+    rhs = 2.0 * oracle.mix_forward(V1, g) - 3.0 * oracle.mix_forward(V2, g)
+    np.testing.assert_allclose(lhs, rhs, atol=1e-12)
+
+
+def test_fast_and_naive_agree_on_config1_columns(oracle):
+    """Config 1 length, a few columns: the FFT path used for parity equals the printed sum."""
+    L = 1024
+    V = _rng(42).standard_normal((1, L, 1, 4))
+    g = synth.random_gate(43, 1, 1, L).astype(complex)
+    a = oracle.mix_forward(V, g, oracle.NAIVE)
+    b = oracle.mix_forward(V, g, oracle.FAST)
+    np.testing.assert_allclose(a, b, atol=1e-10)
+
+
+# ----------------------------------------------------------------------------- gate
+def _torch_gate(sum_q, inv_count, p, n, phase_pos):
+    """The gate re-assembled from library routines (LayerNorm, GELU, matmul) in fp64."""
+    B, H, d = sum_q.shape
+    Hg = p["W1"].shape[0]
+    F = n // 2 + 1
+    out = np.zeros((B, H, F), complex)
+    for b in range(B):
+        for h in range(H):
+            hp = 0 if Hg == 1 else h
+            x = torch.tensor(sum_q[b, h] * inv_count, dtype=torch.float64)
+            qbar = torch.nn.functional.layer_norm(
+                x, (d,), torch.tensor(p["ln_gamma"][hp], dtype=torch.float64),
+                torch.tensor(p["ln_beta"][hp], dtype=torch.float64), eps=p["ln_eps"])
+            hid = torch.nn.functional.gelu(qbar @ torch.tensor(p["W1"][hp], dtype=torch.float64)
+                                           + torch.tensor(p["b1"][hp], dtype=torch.float64))
+            u = (hid @ torch.tensor(p["W2"][hp], dtype=torch.float64)
+                 + torch.tensor(p["b2"][hp], dtype=torch.float64)).numpy()
+            gk = u[0::2] + 1j * u[1::2]
+            if p.get("modrelu_bias") is not None:
+                mag = np.abs(gk)
+                gk = np.where(mag > 0, np.maximum(mag + p["modrelu_bias"][hp], 0) * gk / np.where(mag > 0, mag, 1), 0)
+            if phase_pos:
+                gk = gk * np.exp(2j * np.pi * ((np.arange(F) * (phase_pos % n)) % n) / n)
+            out[b, h] = gk
+    return out
+
+
+@pytest.mark.parametrize("Hg_shared,n,phase", [(False, 16, 0), (True, 16, 5), (False, 196, 0), (False, 64, 1000003)])
+def test_gate_against_library_pieces(oracle, Hg_shared, n, phase):
+    B, H, d = 2, 3, 8
+    p = synth.gate_params(7, 1 if Hg_shared else H, d, n, d_g=6, std=0.5)
+    sum_q = _rng(8).standard_normal((B, H, d)) * 3.0
+    got = oracle.gate(sum_q, 1.0 / n, p, n, phase)
+    want = _torch_gate(sum_q, 1.0 / n, {k: (np.asarray(v, np.float64) if isinstance(v, np.ndarray) else v)
+                                        for k, v in p.items()}, n, phase)
+    np.testing.assert_allclose(got, want, atol=1e-12)
+
+
+def _hand_params(d, dg, n):
+    F = n // 2 + 1
+    return dict(ln_gamma=np.ones((1, d)), ln_beta=np.zeros((1, d)), ln_eps=0.0,
+                W1=np.zeros((1, d, dg)), b1=np.zeros((1, dg)),
+                W2=np.zeros((1, dg, 2 * F)), b2=np.zeros((1, 2 * F)), modrelu_bias=None)
+
+
+def test_gate_hand_computable(oracle):
+    """One-hot weights: every number can be followed by hand.
+    sum_q = (2, -2), inv_count = 1/2 -> x = (1, -1), mean 0, var 1, eps 0 -> qbar = (1, -1).
+    W1 = I -> hid = GELU(1), GELU(-1).  W2 routes hid_0 to Re g_1 and hid_1 to Im g_2; b2 sets g_0 = 0.5 - 0.25j."""
+    from math import erf, sqrt
+    d = dg = 2
+    n = 4
+    p = _hand_params(d, dg, n)
+    p["W1"][0] = np.eye(2)
+    p["W2"][0, 0, 2] = 1.0   # hid_0 -> re of bin 1
+    p["W2"][0, 1, 5] = 1.0   # hid_1 -> im of bin 2
+    p["b2"][0, 0], p["b2"][0, 1] = 0.5, -0.25
+    g = oracle.gate(np.array([[[2.0, -2.0]]]), 0.5, p, n)
+    gelu = lambda a: 0.5 * a * (1 + erf(a / sqrt(2)))
+    want = np.array([0.5 - 0.25j, gelu(1.0), 1j * gelu(-1.0)])
+    np.testing.assert_allclose(g[0, 0], want, atol=1e-15)
+    assert abs(gelu(1.0) - 0.8413447460685429) < 1e-15   # Phi(1), a tabulated constant
+
+
+def test_layernorm_statistics_and_eps(oracle):
+    """gamma = 1, beta = 0, W1 = I, linear read-out of hid is impossible (GELU), so look at LN through
+    its invariants instead: scaling sum_q together with inv_count leaves the gate unchanged, and a
+    large eps shrinks qbar toward 0 so the gate tends to the bias-only value."""
+    d, dg, n = 8, 8, 16
+    p = synth.gate_params(3, 1, d, n, d_g=dg, std=0.3, modrelu=False)
+    sq = _rng(4).standard_normal((1, 1, d))
+    a = oracle.gate(sq, 1.0 / n, p, n)
+    b = oracle.gate(sq * 4.0, 0.25 / n, p, n)
+    np.testing.assert_allclose(a, b, atol=1e-13)
+    p_big = dict(p, ln_eps=1e12, ln_beta=np.zeros((1, d), np.float32))
+    c = oracle.gate(sq, 1.0 / n, p_big, n)
+    hid0 = torch.nn.functional.gelu(torch.tensor(p["b1"][0], dtype=torch.float64)).numpy()
+    u = hid0 @ p["W2"][0].astype(np.float64) + p["b2"][0]
+    np.testing.assert_allclose(c[0, 0], u[0::2] + 1j * u[1::2], atol=1e-6)
+    # eps is comparable to the variance of a pooled query at long L: it must change the result
+    small = sq * 1e-3
+    g1 = oracle.gate(small, 1.0, dict(p, ln_eps=1e-5), n)
+    g2 = oracle.gate(small, 1.0, dict(p, ln_eps=0.0), n)
+    assert np.abs(g1 - g2).max() > 1e-4
+
+
+def test_modrelu_properties(oracle):
+    d, dg, n = 4, 4, 32
+    F = n // 2 + 1
+    p = synth.gate_params(5, 1, d, n, d_g=dg, std=0.5, modrelu=False)
+    sq = _rng(6).standard_normal((1, 1, d))
+    raw = oracle.gate(sq, 1.0, p, n)[0, 0]
+    zero_bias = oracle.gate(sq, 1.0, dict(p, modrelu_bias=np.zeros((1, F))), n)[0, 0]
+    np.testing.assert_allclose(zero_bias, raw, atol=1e-15)              # b = 0: identity
+    killed = oracle.gate(sq, 1.0, dict(p, modrelu_bias=np.full((1, F), -1e3)), n)[0, 0]
+    assert np.all(killed == 0)                                          # b << 0: gate closed
+    bias = _rng(7).standard_normal((1, F)) * 0.3
+    act = oracle.gate(sq, 1.0, dict(p, modrelu_bias=bias), n)[0, 0]
+    np.testing.assert_allclose(np.abs(act), np.maximum(np.abs(raw) + bias[0], 0), atol=1e-14)
+    live = np.abs(act) > 0
+    np.testing.assert_allclose(np.angle(act[live]), np.angle(raw[live]), atol=1e-12)
+
+
+def test_phase_is_periodic_and_shifts_the_output(oracle):
+    """Phase p multiplies bin k by exp(+j 2 pi k p/n): p and p+n agree, and the mixed output is
+    the un-phased output advanced by p rows (translation property the paragraph relies on)."""
+    B, H, d, n = 1, 2, 4, 16
+    p = synth.gate_params(9, H, d, n, d_g=5, std=0.5)
+    sq = _rng(10).standard_normal((B, H, d))
+    g0 = oracle.gate(sq, 1.0 / n, p, n, 0)
+    g3 = oracle.gate(sq, 1.0 / n, p, n, 3)
+    g3b = oracle.gate(sq, 1.0 / n, p, n, 3 + 5 * n)
+    np.testing.assert_allclose(g3, g3b, atol=1e-13)
+    V = _rng(11).standard_normal((B, n, H, d))
+    y0 = oracle.mix_forward(V, g0)
+    y3 = oracle.mix_forward(V, g3)
+    np.testing.assert_allclose(y3, np.roll(y0, -3, axis=1), atol=1e-12)
+
+
+def test_pool_q(oracle):
+    Q = _rng(12).standard_normal((2, 37, 3, 5))
+    np.testing.assert_allclose(oracle.pool_q(Q), Q.sum(axis=1), atol=1e-12)
