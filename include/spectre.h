@@ -1,0 +1,202 @@
+/*
+ * spectre.h - C ABI of the MI355X (gfx950) SPECTRE spectral-mixing library.
+ *
+ * SPECTRE replaces each self-attention head by a frequency-domain mixing head
+ * (Sec. 3.2): a real FFT of the value rows along the sequence axis, a
+ * multiplication by a content-adaptive complex gate with one entry per
+ * frequency bin, and the inverse real FFT.  At decode time a "Prefix-FFT cache"
+ * (Sec. 3.3, Algorithm 1) keeps the half spectrum of a sliding window of
+ * N_max tokens up to date with one rank-one update per new token.
+ *
+ * Conventions shared by every entry point
+ *   - C linkage, plain pointers and sizes.  Unless a parameter says "host",
+ *     every pointer is a DEVICE pointer on the current HIP device.
+ *   - Token tensors are row-major [B, L, H, d] (batch, position, head, channel),
+ *     dtype SPECTRE_F32 (float) or SPECTRE_BF16 (bfloat16 bit patterns); all
+ *     spectra, gates and cache state are fp32 / complex64 ((re, im) float pairs);
+ *     bf16 outputs are rounded to nearest even from fp32.
+ *   - F = floor(n/2) + 1 is the number of stored bins of an n-point real
+ *     transform (App. B, Cor. B.2).  The forward transform is unnormalised
+ *     (Eq. 1), the inverse carries 1/n.
+ *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and return without synchronising.  Inputs are never
+ *     modified; outputs are fully overwritten; results are bitwise reproducible
+ *     from run to run.
+ *   - The caller owns every buffer, including the scratch workspace `ws`, whose
+ *     minimum size the matching *_workspace_bytes function returns.  The library
+ *     itself only keeps small per-device read-only tables (roots of unity), built
+ *     on first use of a transform length and kept until spectre_shutdown().
+ *   - Every function returning int returns a spectre_status; on failure nothing
+ *     has been enqueued (argument errors are detected on the host before any
+ *     launch) and spectre_last_error() describes the reason.  The library never
+ *     aborts or throws.
+ *   - Supported shapes: d even, 2 <= d <= 256 and d a multiple of 2; transform
+ *     lengths n that are a power of two with 2 <= n <= 131072, and n = 4^a 7^b
+ *     style lengths listed by spectre_length_supported().  Anything else returns
+ *     SPECTRE_EUNSUPPORTED.
+ */
+#ifndef SPECTRE_H
+#define SPECTRE_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPECTRE_OK = 0,
+    SPECTRE_EINVAL = 1,       /* null pointer, non-positive size, overlapping in/out, bad enum */
+    SPECTRE_EUNSUPPORTED = 2, /* valid request this build has no kernel for (length, d, ...)   */
+    SPECTRE_EWORKSPACE = 3,   /* ws == NULL or ws_bytes below the *_workspace_bytes figure      */
+    SPECTRE_EHIP = 4          /* a HIP runtime call failed; text in spectre_last_error()        */
+} spectre_status;
+
+typedef enum { SPECTRE_F32 = 0, SPECTRE_BF16 = 1 } spectre_dtype;
+
+/* Host string describing the last failure on the calling thread ("" if none). */
+const char *spectre_last_error(void);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int spectre_version(void);
+
+/* 1 if an n-point transform is available for channel count d, else 0. */
+int spectre_length_supported(int n, int d);
+
+/* Frees the per-device tables.  Optional; safe to call more than once. */
+void spectre_shutdown(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Gate parameters (Sec. 3.2 step 3a and 3c; the same network serves Algorithm 1's decode gate).
+ * All arrays are device fp32.  Hg = H gives every head its own network, Hg = 1 shares one across
+ * heads (the two parameter budgets of Sec. 3.6).  The MLP's second layer emits 2F reals that are
+ * read as F interleaved (re, im) pairs, so its width is tied to the transform length n_fft.
+ */
+typedef struct {
+    int Hg;                    /* H (per-head weights) or 1 (shared)                          */
+    int d;                     /* channels per head                                           */
+    int d_g;                   /* hidden width of the MLP, 1..256                             */
+    int n_fft;                 /* transform length the gate is for; F = n_fft/2 + 1           */
+    const float *ln_gamma;     /* [Hg, d]   LayerNorm scale                                   */
+    const float *ln_beta;      /* [Hg, d]   LayerNorm shift                                   */
+    float ln_eps;              /* added to the biased variance over the d channels            */
+    const float *W1;           /* [Hg, d, d_g]                                                */
+    const float *b1;           /* [Hg, d_g]                                                   */
+    const float *W2;           /* [Hg, d_g, 2F]                                               */
+    const float *b2;           /* [Hg, 2F]                                                    */
+    const float *modrelu_bias; /* [Hg, F] real bias of modReLU, or NULL to skip the activation */
+} spectre_gate_params;
+
+size_t spectre_gate_workspace_bytes(int B, int L, int H, const spectre_gate_params *P /*host*/);
+
+/*
+ * spectre_gate - content-adaptive spectral gate, Sec. 3.2 step 3 (a), (c) and the positional-phase
+ * paragraph of Sec. 3.5; Algorithm 1's "LN(sum_q/N_max) -> MLP -> modReLU -> phase" lines.
+ *
+ *   x      = inv_count * sum over positions of the query rows          (global descriptor)
+ *   qbar   = ln_gamma * (x - mean(x)) / sqrt(var(x) + ln_eps) + ln_beta
+ *   hid    = GELU(qbar W1 + b1)                 (exact erf form)
+ *   u      = hid W2 + b2,   g_k = u[2k] + j u[2k+1],  k = 0..F-1
+ *   g_k   <- max(|g_k| + bias_k, 0) * g_k / |g_k|      (0 where |g_k| = 0; skipped if bias NULL)
+ *   g_k   <- g_k * exp(+j 2 pi ((k * phase_pos) mod n_fft) / n_fft)    (skipped if phase_pos = 0)
+ *
+ *   q            q_is_pooled = 0: query rows [B, L, H, d] of dtype q_dtype (pooled here, in
+ *                order-fixed partial sums combined in fp64);
+ *                q_is_pooled = 1: the sum itself, double [B, H, d] (q_dtype, L ignored) - this is
+ *                the cache's running sum at decode time.
+ *   inv_count    1/L for the mixing layer, 1/N_max at decode time (as Algorithm 1 prints it).
+ *   P            host pointer to the parameter block (its arrays are device pointers).
+ *   phase_pos    scalar position p >= 0 of the phase; 0 = none.
+ *   g_out        complex64 [B, H, F], F = P->n_fft/2 + 1.
+ */
+int spectre_gate(const void *q, int q_is_pooled, spectre_dtype q_dtype, double inv_count,
+                 const spectre_gate_params *P /*host*/, int B, int L, int H,
+                 long long phase_pos, void *g_out, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * spectre_mix_forward - the mixing layer, Sec. 3.2 steps 2 and 4 (Eq. 3, Eq. 4): for every
+ * sequence b, head h and channel c
+ *        out[b, :, h, c] = irfft_L( g[b, h, :] * rfft_L( v[b, :, h, c] ) ).
+ * The gated DC and Nyquist bins contribute their real parts only (the product is extended by
+ * Hermitian symmetry before the inverse, as Cor. B.2's inverse assumes).
+ *
+ *   v     [B, L, H, d] of dtype io        g    complex64 [B, H, F], F = L/2 + 1
+ *   out   [B, L, H, d] of dtype io; must not overlap v (SPECTRE_EINVAL if it does)
+ *   ws    scratch of at least spectre_mix_workspace_bytes(B, L, H, d, io) bytes, 256-byte aligned
+ */
+size_t spectre_mix_workspace_bytes(int B, int L, int H, int d, spectre_dtype io);
+int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, int H, int d,
+                        spectre_dtype io, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Prefix-FFT cache, Sec. 3.3 and Algorithm 1.  One cache serves B*H heads that advance in
+ * lock-step (one token counter).  The caller allocates the five device arrays (sizes from
+ * spectre_prefix_bytes), fills in the dimensions, and calls spectre_prefix_init once.
+ */
+typedef struct {
+    int B, H, d, N_max;   /* N_max: window length = transform length, a supported power of two  */
+    long long t;          /* HOST field: tokens appended so far; advanced by update/step        */
+    void *prefix_fft;     /* complex64 [B, H, F, d]: half spectrum of the ring buffer           */
+    void *v_buf;          /* float [B, H, N_max, d]: ring buffer of values, slot = index mod N  */
+    void *q_buf;          /* float [B, H, N_max, d]: ring buffer of queries                     */
+    void *sum_q;          /* double [B, H, d]: running sum of the live queries                  */
+    void *twiddle;        /* complex64 [N_max]: exp(-j 2 pi m / N_max), the pre-cached factors  */
+} spectre_prefix_cache;
+
+enum { SPECTRE_PREFIX_FFT = 0, SPECTRE_PREFIX_VBUF = 1, SPECTRE_PREFIX_QBUF = 2,
+       SPECTRE_PREFIX_SUMQ = 3, SPECTRE_PREFIX_TWIDDLE = 4 };
+/* Bytes of cache field `which` (one of the enumerators above); 0 on bad arguments. */
+size_t spectre_prefix_bytes(int B, int H, int d, int N_max, int which);
+
+/* Zeroes the state, fills the twiddle table (computed in fp64, rounded once), sets t = 0. */
+int spectre_prefix_init(spectre_prefix_cache *cache /*host*/, void *stream);
+
+/*
+ * spectre_prefix_update - append T tokens.  v_new, q_new are [B, T, H, d] of dtype `io`.
+ *   cache->t == 0 and T > 1 : pre-fill (Algorithm 1, PreFill): one N_max-point real transform of
+ *        the prompt zero-padded at the tail, ring buffers filled, sum_q = sum of the prompt's
+ *        queries.  Requires T <= N_max.
+ *   otherwise : T successive decode updates (Algorithm 1, DecodeStep up to the gate; Eq. 5):
+ *        s = t mod N_max;  delta = v_t - [t >= N_max] v_buf[s];
+ *        prefix_fft[k, :] += delta * exp(-j 2 pi ((k s) mod N_max)/N_max)   for every bin k;
+ *        sum_q += q_t - [t >= N_max] q_buf[s];  v_buf[s] = v_t;  q_buf[s] = q_t;  t += 1.
+ * On success cache->t has advanced by T.
+ */
+size_t spectre_prefix_update_workspace_bytes(const spectre_prefix_cache *cache /*host*/, int T,
+                                             spectre_dtype io);
+int spectre_prefix_update(spectre_prefix_cache *cache /*host*/, const void *v_new, const void *q_new,
+                          int T, spectre_dtype io, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * spectre_prefix_readout - Algorithm 1's last three lines, z = irfft_N( g * prefix_fft ).
+ *   mode SPECTRE_READ_NEWEST : out [B, 1, H, d] = row (t-1) mod N_max of z, the newest token's row,
+ *        evaluated as a direct sum over the bins (the O(N_max/2 d) per-step cost Sec. 3.3 quotes);
+ *        pass the gate WITHOUT positional phase.
+ *   mode SPECTRE_READ_WINDOW : out [B, L', H, d] = rows N_max-L' .. N_max-1 of z, L' = min(t, N_max)
+ *        (a full inverse transform).  With a gate built with phase_pos = t these rows are the live
+ *        tokens in chronological order, the last one equal to the NEWEST readout.
+ *   g     complex64 [B, H, F], F = N_max/2 + 1.   Requires t >= 1.
+ */
+enum { SPECTRE_READ_NEWEST = 0, SPECTRE_READ_WINDOW = 1 };
+size_t spectre_prefix_readout_workspace_bytes(const spectre_prefix_cache *cache /*host*/, int mode,
+                                              spectre_dtype io);
+int spectre_prefix_readout(const spectre_prefix_cache *cache /*host*/, const void *g, int mode,
+                           void *out, spectre_dtype io, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * spectre_prefix_step - one fused decode step with the results of
+ *   spectre_prefix_update(T = 1), spectre_gate(sum_q, 1/N_max, phase 0), spectre_prefix_readout(NEWEST)
+ * but a single sweep over the cache (each cache entry is read once and written once).
+ *   v_t, q_t  [B, 1, H, d] of dtype io       out  [B, 1, H, d] of dtype io
+ *   P         gate parameters with P->n_fft == N_max
+ */
+size_t spectre_prefix_step_workspace_bytes(const spectre_prefix_cache *cache /*host*/,
+                                           const spectre_gate_params *P /*host*/);
+int spectre_prefix_step(spectre_prefix_cache *cache /*host*/, const void *v_t, const void *q_t,
+                        const spectre_gate_params *P /*host*/, void *out, spectre_dtype io,
+                        void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECTRE_H */

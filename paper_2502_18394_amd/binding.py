@@ -1,0 +1,218 @@
+"""Thin Python binding of the C ABI in ``include/spectre.h``.
+
+Argument marshalling only: torch supplies device memory and the current stream,
+every step of the computation runs in the HIP library.  There is no fallback: if
+``libspectre_hip.so`` has not been built (``python -m paper_2502_18394_amd.build``)
+the first call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspectre_hip.so")
+
+F32, BF16 = 0, 1
+READ_NEWEST, READ_WINDOW = 0, 1
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
+
+_lib = None
+
+
+class SpectreError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"spectre status {code}: {msg}")
+        self.code = code
+
+
+class GateParamsC(ctypes.Structure):
+    _fields_ = [("Hg", ctypes.c_int), ("d", ctypes.c_int), ("d_g", ctypes.c_int), ("n_fft", ctypes.c_int),
+                ("ln_gamma", ctypes.c_void_p), ("ln_beta", ctypes.c_void_p), ("ln_eps", ctypes.c_float),
+                ("W1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("W2", ctypes.c_void_p), ("b2", ctypes.c_void_p),
+                ("modrelu_bias", ctypes.c_void_p)]
+
+
+class PrefixCacheC(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("d", ctypes.c_int), ("N_max", ctypes.c_int),
+                ("t", ctypes.c_longlong),
+                ("prefix_fft", ctypes.c_void_p), ("v_buf", ctypes.c_void_p), ("q_buf", ctypes.c_void_p),
+                ("sum_q", ctypes.c_void_p), ("twiddle", ctypes.c_void_p)]
+
+
+def lib():
+    """The loaded C library; raises if it is missing (never falls back to another path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2502_18394_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        L.spectre_last_error.restype = ctypes.c_char_p
+        for name in ("spectre_gate_workspace_bytes", "spectre_mix_workspace_bytes", "spectre_prefix_bytes",
+                     "spectre_prefix_update_workspace_bytes", "spectre_prefix_readout_workspace_bytes",
+                     "spectre_prefix_step_workspace_bytes"):
+            if hasattr(L, name):
+                getattr(L, name).restype = ctypes.c_size_t
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != OK:
+        raise SpectreError(rc, lib().spectre_last_error().decode())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(t, name):
+    if not (t.is_cuda and t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _workspace(nbytes, device, ws):
+    nbytes = max(int(nbytes), 256)
+    if ws is None or ws.numel() * ws.element_size() < nbytes:
+        ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+    off = (-ws.data_ptr()) % 256
+    return ws, ctypes.c_void_p(ws.data_ptr() + off), ctypes.c_size_t(ws.numel() * ws.element_size() - off)
+
+
+def version():
+    return int(lib().spectre_version())
+
+
+def length_supported(n, d):
+    return bool(lib().spectre_length_supported(ctypes.c_int(n), ctypes.c_int(d)))
+
+
+def mix_workspace_bytes(B, L, H, d, io):
+    return int(lib().spectre_mix_workspace_bytes(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H),
+                                                 ctypes.c_int(d), ctypes.c_int(io)))
+
+
+def mix_forward(v, g, out=None, ws=None, stream=None):
+    """out[b,:,h,c] = irfft_L(g[b,h,:] * rfft_L(v[b,:,h,c])); v [B,L,H,d] f32/bf16, g complex64 [B,H,L//2+1]."""
+    B, L, H, d = v.shape
+    io = _dtype_code(v)
+    if g.dtype != torch.complex64 or tuple(g.shape) != (B, H, L // 2 + 1):
+        raise ValueError("g must be complex64 [B,H,L//2+1]")
+    if out is None:
+        out = torch.empty_like(v)
+    ws, wsp, wsn = _workspace(mix_workspace_bytes(B, L, H, d, io), v.device, ws)
+    _check(lib().spectre_mix_forward(_dev(v, "v"), _dev(g, "g"), _dev(out, "out"), ctypes.c_int(B), ctypes.c_int(L),
+                                     ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(io), wsp, wsn, _stream(stream)))
+    return out
+
+
+class GateParams:
+    """Device copies of the gate parameters plus the C parameter block."""
+
+    def __init__(self, params, device="cuda"):
+        def dev(a):
+            return None if a is None else torch.as_tensor(a, dtype=torch.float32).contiguous().to(device)
+        self.t = {k: dev(params[k]) for k in ("ln_gamma", "ln_beta", "W1", "b1", "W2", "b2")}
+        self.t["modrelu_bias"] = dev(params.get("modrelu_bias"))
+        Hg, d, d_g = self.t["W1"].shape
+        self.n_fft = int(params["n_fft"])
+        F = self.n_fft // 2 + 1
+        assert tuple(self.t["W2"].shape) == (Hg, d_g, 2 * F)
+        self.Hg, self.d, self.d_g, self.F = Hg, d, d_g, F
+        p = lambda k: None if self.t[k] is None else ctypes.c_void_p(self.t[k].data_ptr())
+        self.c = GateParamsC(Hg, d, d_g, self.n_fft, p("ln_gamma"), p("ln_beta"), float(params["ln_eps"]),
+                             p("W1"), p("b1"), p("W2"), p("b2"), p("modrelu_bias"))
+
+
+def gate_workspace_bytes(B, L, H, P):
+    return int(lib().spectre_gate_workspace_bytes(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.byref(P.c)))
+
+
+def gate(q, P, inv_count, pooled=False, phase_pos=0, g_out=None, ws=None, stream=None):
+    """Spectral gate complex64 [B,H,F].  q: query rows [B,L,H,d] (f32/bf16), or with pooled=True
+    their sum over positions as float64 [B,H,d]."""
+    if pooled:
+        if q.dtype != torch.float64:
+            raise TypeError("pooled q must be float64 [B,H,d]")
+        B, H, d = q.shape
+        L, code = 1, F32
+    else:
+        B, L, H, d = q.shape
+        code = _dtype_code(q)
+    if d != P.d:
+        raise ValueError("d mismatch")
+    if g_out is None:
+        g_out = torch.empty((B, H, P.F), dtype=torch.complex64, device=q.device)
+    ws, wsp, wsn = _workspace(gate_workspace_bytes(B, L, H, P), q.device, ws)
+    _check(lib().spectre_gate(_dev(q, "q"), ctypes.c_int(1 if pooled else 0), ctypes.c_int(code),
+                              ctypes.c_double(inv_count), ctypes.byref(P.c), ctypes.c_int(B), ctypes.c_int(L),
+                              ctypes.c_int(H), ctypes.c_longlong(int(phase_pos)), _dev(g_out, "g_out"),
+                              wsp, wsn, _stream(stream)))
+    return g_out
+
+
+class PrefixCache:
+    """Caller-owned Prefix-FFT cache state (Algorithm 1) in device memory."""
+
+    def __init__(self, B, H, d, N_max, device="cuda"):
+        L = lib()
+        self.B, self.H, self.d, self.N = B, H, d, N_max
+        self.F = N_max // 2 + 1
+        nb = [int(L.spectre_prefix_bytes(ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(N_max),
+                                         ctypes.c_int(w))) for w in range(5)]
+        if min(nb) == 0:
+            raise SpectreError(EUNSUPPORTED, f"no prefix cache for B={B} H={H} d={d} N_max={N_max}")
+        self.prefix_fft = torch.empty((B, H, self.F, d), dtype=torch.complex64, device=device)
+        self.v_buf = torch.empty((B, H, N_max, d), dtype=torch.float32, device=device)
+        self.q_buf = torch.empty((B, H, N_max, d), dtype=torch.float32, device=device)
+        self.sum_q = torch.empty((B, H, d), dtype=torch.float64, device=device)
+        self.twiddle = torch.empty((N_max,), dtype=torch.complex64, device=device)
+        for t, n in zip((self.prefix_fft, self.v_buf, self.q_buf, self.sum_q, self.twiddle), nb):
+            assert t.numel() * t.element_size() == n, (t.shape, n)
+        self.c = PrefixCacheC(B, H, d, N_max, 0, self.prefix_fft.data_ptr(), self.v_buf.data_ptr(),
+                              self.q_buf.data_ptr(), self.sum_q.data_ptr(), self.twiddle.data_ptr())
+        self._ws = None
+        _check(L.spectre_prefix_init(ctypes.byref(self.c), _stream(None)))
+
+    @property
+    def t(self):
+        return int(self.c.t)
+
+    def update(self, v_new, q_new, stream=None):
+        B, T, H, d = v_new.shape
+        assert (B, H, d) == (self.B, self.H, self.d) and q_new.shape == v_new.shape and q_new.dtype == v_new.dtype
+        io = _dtype_code(v_new)
+        need = lib().spectre_prefix_update_workspace_bytes(ctypes.byref(self.c), ctypes.c_int(T), ctypes.c_int(io))
+        self._ws, wsp, wsn = _workspace(need, v_new.device, self._ws)
+        _check(lib().spectre_prefix_update(ctypes.byref(self.c), _dev(v_new, "v_new"), _dev(q_new, "q_new"),
+                                           ctypes.c_int(T), ctypes.c_int(io), wsp, wsn, _stream(stream)))
+
+    def readout(self, g, mode=READ_NEWEST, dtype=torch.float32, stream=None):
+        io = F32 if dtype == torch.float32 else BF16
+        rows = 1 if mode == READ_NEWEST else min(self.t, self.N)
+        out = torch.empty((self.B, rows, self.H, self.d), dtype=dtype, device=g.device)
+        need = lib().spectre_prefix_readout_workspace_bytes(ctypes.byref(self.c), ctypes.c_int(mode), ctypes.c_int(io))
+        self._ws, wsp, wsn = _workspace(need, g.device, self._ws)
+        _check(lib().spectre_prefix_readout(ctypes.byref(self.c), _dev(g, "g"), ctypes.c_int(mode), _dev(out, "out"),
+                                            ctypes.c_int(io), wsp, wsn, _stream(stream)))
+        return out
+
+    def step(self, v_t, q_t, P, out=None, stream=None):
+        io = _dtype_code(v_t)
+        if out is None:
+            out = torch.empty((self.B, 1, self.H, self.d), dtype=v_t.dtype, device=v_t.device)
+        need = lib().spectre_prefix_step_workspace_bytes(ctypes.byref(self.c), ctypes.byref(P.c))
+        self._ws, wsp, wsn = _workspace(need, v_t.device, self._ws)
+        _check(lib().spectre_prefix_step(ctypes.byref(self.c), _dev(v_t, "v_t"), _dev(q_t, "q_t"), ctypes.byref(P.c),
+                                         _dev(out, "out"), ctypes.c_int(io), wsp, wsn, _stream(stream)))
+        return out

@@ -1,0 +1,44 @@
+// Shared device helpers of the SPECTRE HIP kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spectre {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// float2 + and - are HIP's own component-wise operators.
+__host__ __device__ __forceinline__ float2 cmul(float2 a, float2 b) {   // a * b
+    return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+__host__ __device__ __forceinline__ float2 cmulc(float2 a, float2 b) {  // a * conj(b)
+    return make_float2(a.x * b.x + a.y * b.y, a.y * b.x - a.x * b.y);
+}
+__host__ __device__ __forceinline__ float2 cconj(float2 a) { return make_float2(a.x, -a.y); }
+
+// Two adjacent channels (2c, 2c+1) of one token row travel as one complex number
+// (even channel = real part).  Storage types: float2 for fp32 rows, one 32-bit
+// word holding two bfloat16 for bf16 rows.
+struct IoF32 {
+    typedef float2 pair_t;
+    static constexpr int kBytes = 4;
+    __device__ static __forceinline__ float2 unpack(pair_t p) { return p; }
+    __device__ static __forceinline__ pair_t pack(float2 v) { return v; }
+    __device__ static __forceinline__ pair_t zero() { return make_float2(0.f, 0.f); }
+};
+struct IoBf16 {
+    typedef uint32_t pair_t;
+    static constexpr int kBytes = 2;
+    __device__ static __forceinline__ float2 unpack(pair_t w) {
+        return make_float2(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
+    }
+    __device__ static __forceinline__ pair_t pack(float2 v) {   // round to nearest even
+        f32x2_t f = {v.x, v.y};
+        bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+        return __builtin_bit_cast(uint32_t, b);
+    }
+    __device__ static __forceinline__ pair_t zero() { return 0u; }
+};
+
+}  // namespace spectre

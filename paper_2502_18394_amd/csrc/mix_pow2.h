@@ -1,0 +1,41 @@
+// Power-of-two transform path: host-side plan and launch declarations.
+//
+// An L-point transform (L = N1 * N2) of the channel pairs of one head is split the
+// four-step way: N2-point DFTs over the far index inside single lanes ("small"
+// kernels, which also own all traffic with the caller's [B,L,H,d] tensors), a
+// root-of-unity scaling, and N1-point DFTs staged through LDS ("big" kernel,
+// which only touches the library's own scratch layout).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace spectre {
+
+struct Pow2Plan {
+    int L = 0;            // transform length
+    int N1 = 0, N2 = 0;   // L = N1 * N2; N1 = 16^P
+    int P = 0;
+    const float2 *twL = nullptr;   // [L]  exp(-j 2 pi m / L), device
+    const float2 *twN1 = nullptr;  // [N1] exp(-j 2 pi m / N1), device
+};
+
+// Decomposition rule; returns false if L has no power-of-two plan.
+bool pow2_split(int L, int *N1, int *N2, int *P);
+
+// Launchers (enqueue only).  `pairs` = d/2 must be 32.  All return hipError_t.
+//   small_fwd : rows of v (tensor [B, rows, H, d], zero beyond `rows`) -> scratch[bh_local][k2][pair][t1]
+//   big       : in-place N1-point transforms on scratch; mode 0 = forward, gate, inverse;
+//               1 = forward only; 2 = inverse only.  gp = expanded gate for mode 0.
+//   small_inv : scratch -> rows [row0, row0 + out_rows) of the inverse transform into
+//               out (tensor [B, out_rows, H, d])
+hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
+                            int bh0, int nbh, hipStream_t st);
+hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
+                      hipStream_t st);
+hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
+                            int out_rows, int H, int bh0, int nbh, hipStream_t st);
+// g [BH, L/2+1] -> gp [BH][N2][N1] in the big kernel's register order, scaled by 1/L and
+// extended to all L bins by Hermitian symmetry (real parts only at DC and Nyquist).
+hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st);
+
+}  // namespace spectre

@@ -1,0 +1,331 @@
+// Power-of-two transform path of the SPECTRE mixing layer (Sec. 3.2 steps 2-4,
+// Eq. 3 and Eq. 4) for gfx950.
+//
+// Two adjacent channels of a head are transformed together as one complex
+// sequence z = v_even + j v_odd.  Because the gate is extended to all L bins by
+// Hermitian symmetry (App. B, Thm. B.1), multiplying the complex spectrum of z
+// by it and transforming back leaves the two real results in the real and
+// imaginary parts, so no split/merge pass is needed and a bf16 channel pair is
+// one 32-bit load.
+//
+// L = N1 * N2, time index t = t1 + N1*t2, frequency index k = k2 + N2*k1:
+//   small_fwd : A[t1,k2]  = W_L^(t1 k2) * sum_t2 z[t1 + N1 t2] W_N2^(t2 k2)      (one lane per (t1, pair))
+//   big       : Z[k2+N2 k1] = sum_t1 A[t1,k2] W_N1^(t1 k1);  Y = G * Z;  B[t1,k2] = sum_k1 Y W_N1^(-t1 k1)
+//   small_inv : out[t1 + N1 t2] = sum_k2 conj(W_L^(t1 k2)) B[t1,k2] W_N2^(-t2 k2)
+// with W_n = exp(-j 2 pi / n) and the 1/L of the inverse folded into G.
+#include "mix_pow2.h"
+
+#include "fft_regs.h"
+
+namespace spectre {
+
+// LDS row strides (in pair_t units) of the [t2][t1_local][pair] staging tile, chosen so
+// that a wave reading along t1_local with 16 lanes per pair index hits every bank equally.
+template <typename IO> struct TileStride;
+template <> struct TileStride<IoBf16> { static constexpr int value = 36; };
+template <> struct TileStride<IoF32> { static constexpr int value = 34; };
+
+// ------------------------------------------------------------------------------------------
+// small_fwd: grid (N1/TT, nbh); block 32*TT threads.  Reads the N2*TT rows
+// {t1_0 + r + N1*t2} of one head (32 pairs each, one 128 B / 256 B segment per row),
+// stages them in LDS, then lane (pair p, t1_local) runs the N2-point DFT over t2.
+template <int N2, int TT, typename IO>
+__global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t *__restrict__ v,
+                                                       float2 *__restrict__ scr,
+                                                       const float2 *__restrict__ twL, int rows, int H,
+                                                       int N1, int bh0) {
+    typedef typename IO::pair_t pair_t;
+    constexpr int S = TileStride<IO>::value;
+    extern __shared__ unsigned char smem_raw[];
+    pair_t *lds = reinterpret_cast<pair_t *>(smem_raw);
+    const int tid = threadIdx.x;
+    const int t1_0 = blockIdx.x * TT;
+    const int bhl = blockIdx.y, bh = bh0 + bhl, b = bh / H, h = bh % H;
+    {
+        const int lp = tid & 31, r = tid >> 5;
+        pair_t val[N2];
+#pragma unroll
+        for (int t2 = 0; t2 < N2; ++t2) {
+            const int l = t1_0 + r + N1 * t2;
+            val[t2] = (l < rows) ? v[(((size_t)b * rows + l) * H + h) * 32 + lp] : IO::zero();
+        }
+#pragma unroll
+        for (int t2 = 0; t2 < N2; ++t2) lds[(t2 * TT + r) * S + lp] = val[t2];
+    }
+    __syncthreads();
+    const int tl = tid % TT, p = tid / TT, t1 = t1_0 + tl;
+    float2 x[N2];
+#pragma unroll
+    for (int t2 = 0; t2 < N2; ++t2) x[t2] = IO::unpack(lds[(t2 * TT + tl) * S + p]);
+    dft<N2, false>(x);
+    float2 *dst = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
+#pragma unroll
+    for (int k2 = 0; k2 < N2; ++k2) {
+        const float2 y = (k2 == 0) ? x[0] : cmul(x[k2], twL[t1 * k2]);
+        dst[(size_t)k2 * 32 * N1] = y;
+    }
+}
+
+// small_inv: mirror image.  Rows l of the inverse transform with row0 <= l < row0+out_rows
+// are written to row l-row0 of out [B, out_rows, H, d].
+template <int N2, int TT, typename IO>
+__global__ __launch_bounds__(32 * TT) void k_small_inv(const float2 *__restrict__ scr,
+                                                       typename IO::pair_t *__restrict__ out,
+                                                       const float2 *__restrict__ twL, int row0,
+                                                       int out_rows, int H, int N1, int bh0) {
+    typedef typename IO::pair_t pair_t;
+    constexpr int S = TileStride<IO>::value;
+    extern __shared__ unsigned char smem_raw[];
+    pair_t *lds = reinterpret_cast<pair_t *>(smem_raw);
+    const int tid = threadIdx.x;
+    const int t1_0 = blockIdx.x * TT;
+    const int bhl = blockIdx.y, bh = bh0 + bhl, b = bh / H, h = bh % H;
+    {
+        const int tl = tid % TT, p = tid / TT, t1 = t1_0 + tl;
+        const float2 *src = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
+        float2 y[N2];
+#pragma unroll
+        for (int k2 = 0; k2 < N2; ++k2) y[k2] = src[(size_t)k2 * 32 * N1];
+#pragma unroll
+        for (int k2 = 1; k2 < N2; ++k2) y[k2] = cmulc(y[k2], twL[t1 * k2]);
+        dft<N2, true>(y);
+#pragma unroll
+        for (int t2 = 0; t2 < N2; ++t2) lds[(t2 * TT + tl) * S + p] = IO::pack(y[t2]);
+    }
+    __syncthreads();
+    const int lp = tid & 31, r = tid >> 5;
+#pragma unroll
+    for (int t2 = 0; t2 < N2; ++t2) {
+        const int orow = t1_0 + r + N1 * t2 - row0;
+        if (orow >= 0 && orow < out_rows)
+            out[(((size_t)b * out_rows + orow) * H + h) * 32 + lp] = lds[(t2 * TT + r) * S + lp];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// big: N1 = 16^P points per column, 16 per lane, P radix-16 passes each way with an LDS
+// exchange between passes.  Forward passes are decimation in frequency (natural order in,
+// base-16 digit-reversed order out), inverse passes undo them in reverse, so the gate is
+// applied in digit-reversed order (the expanded gate is stored that way) and no reordering
+// pass exists.  Pass q (0-based) has stride S = 16^(P-1-q): lane tau owns positions
+// (tau / S) * 16 S + tau % S + S * j, j = 0..15.
+__device__ __forceinline__ int lds_pad(int p) { return p + (p >> 4); }
+
+template <int P, int Q>
+__device__ __forceinline__ int pass_pos(int tau, int j) {
+    constexpr int S = 1 << (4 * (P - 1 - Q));
+    return (tau / S) * (16 * S) + (tau % S) + S * j;
+}
+
+template <int P, int QFROM, int QTO>
+__device__ __forceinline__ void exchange(float2 (&x)[16], float2 *ldc, int tau) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) ldc[lds_pad(pass_pos<P, QFROM>(tau, j))] = x[j];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 16; ++j) x[j] = ldc[lds_pad(pass_pos<P, QTO>(tau, j))];
+    __syncthreads();
+}
+
+template <int P, int MODE>
+__global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const float2 *__restrict__ gp,
+                                             const float2 *__restrict__ twN1, int N2, int ppw, int bh0) {
+    static_assert(P == 2 || P == 3, "N1 is 256 or 4096");
+    constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
+    extern __shared__ float2 lds_big[];
+    const int tid = threadIdx.x, tau = tid % TPC, ci = tid / TPC;
+    const int groups = 32 / ppw;
+    int blk = blockIdx.x;
+    const int pg = blk % groups;
+    blk /= groups;
+    const int k2 = blk % N2, bhl = blk / N2;
+    float2 *ldc = lds_big + ci * COLW;
+
+    float2 tw[P - 1][15];
+#pragma unroll
+    for (int q = 0; q < P - 1; ++q) {
+        const int S = 1 << (4 * (P - 1 - q));
+        const int i = tau % S, step = N1 / (16 * S);
+#pragma unroll
+        for (int u = 1; u < 16; ++u) tw[q][u - 1] = twN1[i * u * step];
+    }
+    float2 G[16];
+    if (MODE == 0) {
+        const float2 *gsrc = gp + ((size_t)(bh0 + bhl) * N2 + k2) * N1;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) G[j] = gsrc[j * TPC + tau];
+    }
+
+    for (int c = ci; c < ppw; c += CPI) {
+        float2 *col = scr + (((size_t)bhl * N2 + k2) * 32 + pg * ppw + c) * N1;
+        float2 x[16];
+        if (MODE != 2) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) x[j] = col[tau + TPC * j];
+            dft<16, false>(x);
+#pragma unroll
+            for (int u = 1; u < 16; ++u) x[u] = cmul(x[u], tw[0][u - 1]);
+            exchange<P, 0, 1>(x, ldc, tau);
+            dft<16, false>(x);
+            if constexpr (P == 3) {
+#pragma unroll
+                for (int u = 1; u < 16; ++u) x[u] = cmul(x[u], tw[P - 2][u - 1]);
+                exchange<P, P - 2, P - 1>(x, ldc, tau);
+                dft<16, false>(x);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) x[j] = col[16 * tau + j];
+        }
+        if (MODE == 0) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) x[j] = cmul(x[j], G[j]);
+        }
+        if (MODE == 1) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) col[16 * tau + j] = x[j];
+            continue;
+        }
+        dft<16, true>(x);
+        if constexpr (P == 3) {
+            exchange<P, P - 1, P - 2>(x, ldc, tau);
+#pragma unroll
+            for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[P - 2][u - 1]);
+            dft<16, true>(x);
+        }
+        exchange<P, 1, 0>(x, ldc, tau);
+#pragma unroll
+        for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[0][u - 1]);
+        dft<16, true>(x);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) col[tau + TPC * j] = x[j];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// gate_expand: one lane per expanded entry.
+__device__ __forceinline__ int digit_reverse16(int pos, int P) {
+    return P == 2 ? (((pos & 15) << 4) | (pos >> 4))
+                  : (((pos & 15) << 8) | (pos & 0xF0) | (pos >> 8));
+}
+
+__global__ __launch_bounds__(256) void k_gate_expand(const float2 *__restrict__ g, float2 *__restrict__ gp,
+                                                     int L, int N1, int N2, int P, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int TPC = N1 / 16;
+    const int F = L / 2 + 1;
+    const size_t bh = idx / L;
+    const int rem = (int)(idx % L);
+    const int k2 = rem / N1, r = rem % N1;
+    const int j = r / TPC, tau = r % TPC;
+    const int k1 = digit_reverse16(16 * tau + j, P);
+    const int k = k2 + N2 * k1;
+    const float scale = 1.0f / (float)L;
+    float2 val;
+    if (k == 0 || 2 * k == L) {
+        val = make_float2(g[bh * F + k].x, 0.0f);
+    } else if (2 * k < L) {
+        val = g[bh * F + k];
+    } else {
+        val = cconj(g[bh * F + (L - k)]);
+    }
+    gp[idx] = make_float2(val.x * scale, val.y * scale);
+}
+
+// ------------------------------------------------------------------------------------------
+bool pow2_split(int L, int *N1, int *N2, int *P) {
+    if (L < 256 || (L & (L - 1)) != 0 || L > 131072) return false;
+    if (L <= 8192) { *N1 = 256; *P = 2; }
+    else { *N1 = 4096; *P = 3; }
+    *N2 = L / *N1;
+    return true;
+}
+
+template <typename K>
+static hipError_t allow_lds(K kernel, size_t bytes) {
+    if (bytes <= 48 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <int N2, int TT, typename IO>
+static hipError_t small_fwd_t(const Pow2Plan &pl, const void *v, float2 *scr, int rows, int H, int bh0,
+                              int nbh, hipStream_t st) {
+    const size_t lds = (size_t)N2 * TT * TileStride<IO>::value * sizeof(typename IO::pair_t);
+    auto kern = k_small_fwd<N2, TT, IO>;
+    hipError_t e = allow_lds(kern, lds);
+    if (e != hipSuccess) return e;
+    kern<<<dim3(pl.N1 / TT, nbh), dim3(32 * TT), lds, st>>>(
+        static_cast<const typename IO::pair_t *>(v), scr, pl.twL, rows, H, pl.N1, bh0);
+    return hipGetLastError();
+}
+
+template <int N2, int TT, typename IO>
+static hipError_t small_inv_t(const Pow2Plan &pl, const float2 *scr, void *out, int row0, int out_rows,
+                              int H, int bh0, int nbh, hipStream_t st) {
+    const size_t lds = (size_t)N2 * TT * TileStride<IO>::value * sizeof(typename IO::pair_t);
+    auto kern = k_small_inv<N2, TT, IO>;
+    hipError_t e = allow_lds(kern, lds);
+    if (e != hipSuccess) return e;
+    kern<<<dim3(pl.N1 / TT, nbh), dim3(32 * TT), lds, st>>>(
+        scr, static_cast<typename IO::pair_t *>(out), pl.twL, row0, out_rows, H, pl.N1, bh0);
+    return hipGetLastError();
+}
+
+#define SPECTRE_DISPATCH_N2(FN, ...)                                         \
+    switch (pl.N2) {                                                         \
+        case 1: return io ? FN<1, 16, IoBf16>(__VA_ARGS__) : FN<1, 8, IoF32>(__VA_ARGS__);   \
+        case 2: return io ? FN<2, 16, IoBf16>(__VA_ARGS__) : FN<2, 8, IoF32>(__VA_ARGS__);   \
+        case 4: return io ? FN<4, 16, IoBf16>(__VA_ARGS__) : FN<4, 8, IoF32>(__VA_ARGS__);   \
+        case 8: return io ? FN<8, 16, IoBf16>(__VA_ARGS__) : FN<8, 8, IoF32>(__VA_ARGS__);   \
+        case 16: return io ? FN<16, 16, IoBf16>(__VA_ARGS__) : FN<16, 8, IoF32>(__VA_ARGS__); \
+        case 32: return io ? FN<32, 16, IoBf16>(__VA_ARGS__) : FN<32, 8, IoF32>(__VA_ARGS__); \
+        default: return hipErrorInvalidValue;                                \
+    }
+
+hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
+                            int bh0, int nbh, hipStream_t st) {
+    SPECTRE_DISPATCH_N2(small_fwd_t, pl, v, scratch, rows, H, bh0, nbh, st)
+}
+
+hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
+                            int out_rows, int H, int bh0, int nbh, hipStream_t st) {
+    SPECTRE_DISPATCH_N2(small_inv_t, pl, scratch, out, row0, out_rows, H, bh0, nbh, st)
+}
+
+template <int P, int MODE>
+static hipError_t big_t(const Pow2Plan &pl, float2 *scr, const float2 *gp, int bh0, int nbh, hipStream_t st) {
+    constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
+    const size_t lds = (size_t)CPI * COLW * sizeof(float2);
+    const int ppw = (P == 2) ? 16 : 4;   // pairs per workgroup; a multiple of CPI dividing 32
+    auto kern = k_big<P, MODE>;
+    hipError_t e = allow_lds(kern, lds);
+    if (e != hipSuccess) return e;
+    const unsigned grid = (unsigned)nbh * pl.N2 * (32 / ppw);
+    kern<<<dim3(grid), dim3(256), lds, st>>>(scr, gp, pl.twN1, pl.N2, ppw, bh0);
+    return hipGetLastError();
+}
+
+hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
+                      hipStream_t st) {
+    if (pl.P == 2) {
+        if (mode == 0) return big_t<2, 0>(pl, scratch, gp, bh0, nbh, st);
+        if (mode == 1) return big_t<2, 1>(pl, scratch, gp, bh0, nbh, st);
+        if (mode == 2) return big_t<2, 2>(pl, scratch, gp, bh0, nbh, st);
+    } else if (pl.P == 3) {
+        if (mode == 0) return big_t<3, 0>(pl, scratch, gp, bh0, nbh, st);
+        if (mode == 1) return big_t<3, 1>(pl, scratch, gp, bh0, nbh, st);
+        if (mode == 2) return big_t<3, 2>(pl, scratch, gp, bh0, nbh, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st) {
+    const size_t total = (size_t)BH * pl.L;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    k_gate_expand<<<dim3(grid), dim3(256), 0, st>>>(g, gp, pl.L, pl.N1, pl.N2, pl.P, total);
+    return hipGetLastError();
+}
+
+}  // namespace spectre

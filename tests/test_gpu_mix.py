@@ -1,0 +1,88 @@
+"""GPU parity of spectre_mix_forward against the fp64 oracle (Sec. 3.2 Eq. 3-4).
+
+Bars (relative L2 over the whole output): 1e-5 for fp32 I/O, 2e-2 for bf16 I/O.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_18394_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    return float(np.linalg.norm((a - b).ravel()) / max(np.linalg.norm(b.ravel()), 1e-300))
+
+
+def to_device(vals, store, io):
+    if io == "bf16":
+        return torch.from_numpy(store.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(store).cuda()
+
+
+def from_device(t):
+    if t.dtype == torch.bfloat16:
+        return synth.bf16_bits_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16))
+    return t.cpu().numpy()
+
+
+def run_case(oracle, B, L, H, d, io, seed, gate="random"):
+    from paper_2502_18394_amd import binding
+    vals, store = synth.tokens(seed, (B, L, H, d), io)
+    if isinstance(gate, str):
+        g = synth.random_gate(seed + 1, B, H, L)
+    else:
+        g = gate
+    out = binding.mix_forward(to_device(vals, store, io), torch.from_numpy(g).cuda())
+    torch.cuda.synchronize()
+    got = from_device(out)
+    want = oracle.mix_forward(vals.astype(np.float64), g.astype(np.complex128))
+    return got, want, vals
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,L,H", [(1, 256, 1), (2, 512, 3), (1, 1024, 1), (1, 2048, 2), (2, 4096, 2),
+                                   (1, 8192, 3), (1, 16384, 1), (1, 32768, 2)])
+def test_mix_forward_matches_oracle(oracle, B, L, H, io):
+    print(f"case B={B} L={L} H={H} io={io}", flush=True)
+    got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + L + H)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL[io]
+    if io == "bf16":
+        # tighter than the bar: every element within one bf16 step of the oracle value, plus the
+        # fp32 arithmetic error (absolute, relative to the output's rms) that matters near zero
+        tol = np.abs(want) * 2.0 ** -7 + 1e-5 * np.sqrt(np.mean(want ** 2))
+        assert np.all(np.abs(got - want) <= tol)
+
+
+def test_identity_gate_returns_input_on_gpu(oracle):
+    B, L, H, d = 1, 4096, 2, 64
+    g = np.ones((B, H, L // 2 + 1), np.complex64)
+    got, want, vals = run_case(oracle, B, L, H, d, "f32", seed=7, gate=g)
+    assert rel_l2(got, vals) <= 1e-5
+    assert rel_l2(got, want) <= 1e-5
+
+
+def test_pure_phase_gate_shifts_on_gpu(oracle):
+    B, L, H, d, s = 1, 1024, 2, 64, 137
+    k = np.arange(L // 2 + 1)
+    g = np.broadcast_to(np.exp(-2j * np.pi * ((k * s) % L) / L), (B, H, L // 2 + 1)).astype(np.complex64)
+    got, want, vals = run_case(oracle, B, L, H, d, "f32", seed=8, gate=np.ascontiguousarray(g))
+    assert rel_l2(got, np.roll(vals, s, axis=1)) <= 1e-5
+
+
+def test_run_to_run_bitwise_identical():
+    from paper_2502_18394_amd import binding
+    vals, store = synth.tokens(3, (1, 8192, 4, 64), "bf16")
+    g = torch.from_numpy(synth.random_gate(4, 1, 4, 8192)).cuda()
+    v = to_device(vals, store, "bf16")
+    a = binding.mix_forward(v, g).view(torch.int16).clone()
+    b = binding.mix_forward(v, g).view(torch.int16)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
