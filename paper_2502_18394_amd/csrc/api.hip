@@ -14,7 +14,9 @@
 #include <utility>
 #include <vector>
 
+#include "gate.h"
 #include "internal.h"
+#include "prefix.h"
 
 namespace spectre {
 
@@ -173,6 +175,273 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, st);
         if (e != hipSuccess) return fail_hip(e, "small_inv");
     }
+    return SPECTRE_OK;
+}
+
+// ------------------------------------------------------------------------------------------ gate
+static int check_gate_params(const spectre_gate_params *P, int H, const char *who) {
+    if (!P) return fail(SPECTRE_EINVAL, "%s: null gate parameters", who);
+    if (!(P->Hg == H || P->Hg == 1)) return fail(SPECTRE_EINVAL, "%s: Hg must be H or 1", who);
+    if (P->d < 2 || P->d > 256 || (P->d & 1)) return fail(SPECTRE_EUNSUPPORTED, "%s: d=%d not in 2..256 even", who, P->d);
+    if (P->d_g < 1 || P->d_g > 256) return fail(SPECTRE_EUNSUPPORTED, "%s: d_g=%d not in 1..256", who, P->d_g);
+    if (P->n_fft < 2) return fail(SPECTRE_EINVAL, "%s: n_fft < 2", who);
+    if (!P->ln_gamma || !P->ln_beta || !P->W1 || !P->b1 || !P->W2 || !P->b2)
+        return fail(SPECTRE_EINVAL, "%s: null parameter array", who);
+    if (!(P->ln_eps >= 0.0f)) return fail(SPECTRE_EINVAL, "%s: ln_eps must be >= 0", who);
+    return SPECTRE_OK;
+}
+
+static GateDev gate_dev(const spectre_gate_params *P) {
+    GateDev g;
+    g.Hg = P->Hg; g.d = P->d; g.d_g = P->d_g; g.n_fft = P->n_fft;
+    g.ln_gamma = P->ln_gamma; g.ln_beta = P->ln_beta; g.ln_eps = P->ln_eps;
+    g.W1 = P->W1; g.b1 = P->b1; g.W2 = P->W2; g.b2 = P->b2; g.modrelu_bias = P->modrelu_bias;
+    return g;
+}
+
+size_t spectre_gate_workspace_bytes(int B, int L, int H, const spectre_gate_params *P) {
+    if (!P || B < 1 || L < 1 || H < 1 || P->d < 2 || P->d_g < 1) return 0;
+    return align256(gate_partial_bytes(B, L, H, P->d)) + align256((size_t)B * H * P->d * sizeof(double)) +
+           align256((size_t)B * H * P->d_g * sizeof(float));
+}
+
+int spectre_gate(const void *q, int q_is_pooled, spectre_dtype q_dtype, double inv_count,
+                 const spectre_gate_params *P, int B, int L, int H, long long phase_pos, void *g_out, void *ws,
+                 size_t ws_bytes, void *stream) {
+    if (!q || !g_out) return fail(SPECTRE_EINVAL, "gate: null pointer");
+    if (B < 1 || H < 1 || (!q_is_pooled && L < 1)) return fail(SPECTRE_EINVAL, "gate: non-positive size");
+    if (!q_is_pooled && q_dtype != SPECTRE_F32 && q_dtype != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "gate: bad dtype");
+    if (phase_pos < 0) return fail(SPECTRE_EINVAL, "gate: negative phase position");
+    if (!(inv_count == inv_count)) return fail(SPECTRE_EINVAL, "gate: inv_count is NaN");
+    int rc = check_gate_params(P, H, "gate");
+    if (rc) return rc;
+    if (q_is_pooled) L = 1;
+    if ((long long)B * H * P->d > 0x7fffffffLL) return fail(SPECTRE_EUNSUPPORTED, "gate: B*H*d too large");
+    const size_t need = spectre_gate_workspace_bytes(B, L, H, P);
+    if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "gate: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "gate: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *w = static_cast<char *>(ws);
+    double *partial = reinterpret_cast<double *>(w);
+    w += align256(gate_partial_bytes(B, L, H, P->d));
+    double *sum_ws = reinterpret_cast<double *>(w);
+    w += align256((size_t)B * H * P->d * sizeof(double));
+    float *hid = reinterpret_cast<float *>(w);
+    const double *sum_q = static_cast<const double *>(q);
+    if (!q_is_pooled) {
+        hipError_t e = launch_pool((int)q_dtype, q, partial, sum_ws, B, L, H, P->d, st);
+        if (e != hipSuccess) return fail_hip(e, "pool");
+        sum_q = sum_ws;
+    }
+    hipError_t e = launch_gate_mlp(sum_q, inv_count, gate_dev(P), hid, B, H, phase_pos % P->n_fft,
+                                   static_cast<float2 *>(g_out), st);
+    if (e != hipSuccess) return fail_hip(e, "gate_mlp");
+    return SPECTRE_OK;
+}
+
+// ------------------------------------------------------------------------------------------ prefix cache
+static int check_cache(const spectre_prefix_cache *c, const char *who) {
+    if (!c) return fail(SPECTRE_EINVAL, "%s: null cache", who);
+    if (c->B < 1 || c->H < 1 || c->d < 1 || c->N_max < 2) return fail(SPECTRE_EINVAL, "%s: bad cache dimensions", who);
+    if (!spectre_length_supported(c->N_max, c->d))
+        return fail(SPECTRE_EUNSUPPORTED, "%s: no kernel for N_max=%d, d=%d", who, c->N_max, c->d);
+    if (!c->prefix_fft || !c->v_buf || !c->q_buf || !c->sum_q || !c->twiddle)
+        return fail(SPECTRE_EINVAL, "%s: null cache array", who);
+    if (c->t < 0) return fail(SPECTRE_EINVAL, "%s: negative token counter", who);
+    if ((long long)c->B * c->H > 0x7fffffffLL / 64) return fail(SPECTRE_EUNSUPPORTED, "%s: B*H too large", who);
+    return SPECTRE_OK;
+}
+
+size_t spectre_prefix_bytes(int B, int H, int d, int N_max, int which) {
+    if (B < 1 || H < 1 || d < 1 || N_max < 2) return 0;
+    if (!spectre_length_supported(N_max, d)) return 0;
+    const size_t BH = (size_t)B * H, F = (size_t)N_max / 2 + 1;
+    switch (which) {
+        case SPECTRE_PREFIX_FFT: return BH * F * d * sizeof(float2);
+        case SPECTRE_PREFIX_VBUF:
+        case SPECTRE_PREFIX_QBUF: return BH * (size_t)N_max * d * sizeof(float);
+        case SPECTRE_PREFIX_SUMQ: return BH * d * sizeof(double);
+        case SPECTRE_PREFIX_TWIDDLE: return (size_t)N_max * sizeof(float2);
+        default: return 0;
+    }
+}
+
+int spectre_prefix_init(spectre_prefix_cache *c, void *stream) {
+    int rc = check_cache(c, "prefix_init");
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    void *arr[4] = {c->prefix_fft, c->v_buf, c->q_buf, c->sum_q};
+    const int which[4] = {SPECTRE_PREFIX_FFT, SPECTRE_PREFIX_VBUF, SPECTRE_PREFIX_QBUF, SPECTRE_PREFIX_SUMQ};
+    for (int i = 0; i < 4; ++i) {
+        if (reinterpret_cast<uintptr_t>(arr[i]) & 15) return fail(SPECTRE_EINVAL, "prefix_init: cache array not 16-byte aligned");
+        hipError_t e = launch_fill_zero(arr[i], spectre_prefix_bytes(c->B, c->H, c->d, c->N_max, which[i]), st);
+        if (e != hipSuccess) return fail_hip(e, "fill_zero");
+    }
+    hipError_t e = launch_fill_twiddle(static_cast<float2 *>(c->twiddle), c->N_max, st);
+    if (e != hipSuccess) return fail_hip(e, "fill_twiddle");
+    c->t = 0;
+    return SPECTRE_OK;
+}
+
+static size_t scratch_bytes(int BH, int N, int d) {
+    return align256((size_t)mix_chunk_heads(BH, N, d) * N * (d / 2) * sizeof(float2));
+}
+
+size_t spectre_prefix_update_workspace_bytes(const spectre_prefix_cache *c, int T, spectre_dtype io) {
+    (void)io;
+    if (!c || T < 1 || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 2) return 0;
+    const int BH = c->B * c->H;
+    return align256((size_t)BH * c->d * sizeof(float)) + align256(gate_partial_bytes(c->B, T, c->H, c->d)) +
+           scratch_bytes(BH, c->N_max, c->d);
+}
+
+int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void *q_new, int T, spectre_dtype io,
+                          void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_cache(c, "prefix_update");
+    if (rc) return rc;
+    if (!v_new || !q_new) return fail(SPECTRE_EINVAL, "prefix_update: null pointer");
+    if (T < 1) return fail(SPECTRE_EINVAL, "prefix_update: T < 1");
+    if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "prefix_update: bad dtype");
+    const size_t need = spectre_prefix_update_workspace_bytes(c, T, io);
+    if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_update: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_update: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int B = c->B, H = c->H, d = c->d, N = c->N_max, BH = B * H, F = N / 2 + 1;
+    char *w = static_cast<char *>(ws);
+    float *delta = reinterpret_cast<float *>(w);
+    w += align256((size_t)BH * d * sizeof(float));
+    double *partial = reinterpret_cast<double *>(w);
+    w += align256(gate_partial_bytes(B, T, H, d));
+    float2 *scr = reinterpret_cast<float2 *>(w);
+    float2 *X = static_cast<float2 *>(c->prefix_fft);
+    hipError_t e;
+    if (c->t == 0 && T > 1) {
+        if (T > N) return fail(SPECTRE_EINVAL, "prefix_update: prompt of %d tokens exceeds N_max=%d", T, N);
+        Pow2Plan pl;
+        rc = get_pow2_plan(N, &pl);
+        if (rc) return rc;
+        e = launch_fill_ring((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), B, T, H, N, st);
+        if (e != hipSuccess) return fail_hip(e, "fill_ring");
+        e = launch_pool((int)io, q_new, partial, static_cast<double *>(c->sum_q), B, T, H, d, st);
+        if (e != hipSuccess) return fail_hip(e, "pool");
+        const int chunk = mix_chunk_heads(BH, N, d);
+        for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
+            const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
+            e = launch_small_fwd(pl, (int)io, v_new, scr, T, H, bh0, nbh, st);
+            if (e != hipSuccess) return fail_hip(e, "small_fwd");
+            e = launch_big(pl, scr, nullptr, bh0, nbh, 1, st);
+            if (e != hipSuccess) return fail_hip(e, "big(forward)");
+            e = launch_untangle(scr, X, N, pl.N1, pl.N2, pl.P, bh0, nbh, st);
+            if (e != hipSuccess) return fail_hip(e, "untangle");
+        }
+        c->t = T;
+        return SPECTRE_OK;
+    }
+    for (int ti = 0; ti < T; ++ti) {
+        const int slot = (int)(c->t % N), evict = c->t >= N ? 1 : 0;
+        e = launch_ring_update((int)io, v_new, q_new, T, ti, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf),
+                               static_cast<double *>(c->sum_q), delta, B, H, d, N, slot, evict, st);
+        if (e != hipSuccess) return fail_hip(e, "ring_update");
+        e = launch_sweep(true, false, X, delta, static_cast<const float2 *>(c->twiddle), nullptr, nullptr, BH, F, N, slot, st);
+        if (e != hipSuccess) return fail_hip(e, "sweep(update)");
+        c->t += 1;
+    }
+    return SPECTRE_OK;
+}
+
+size_t spectre_prefix_readout_workspace_bytes(const spectre_prefix_cache *c, int mode, spectre_dtype io) {
+    (void)io;
+    if (!c || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 2) return 0;
+    const int BH = c->B * c->H, F = c->N_max / 2 + 1;
+    if (mode == SPECTRE_READ_NEWEST) return align256((size_t)BH * sweep_chunks(F) * c->d * sizeof(float));
+    if (mode == SPECTRE_READ_WINDOW) return scratch_bytes(BH, c->N_max, c->d);
+    return 0;
+}
+
+int spectre_prefix_readout(const spectre_prefix_cache *c, const void *g, int mode, void *out, spectre_dtype io,
+                           void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_cache(c, "prefix_readout");
+    if (rc) return rc;
+    if (!g || !out) return fail(SPECTRE_EINVAL, "prefix_readout: null pointer");
+    if (mode != SPECTRE_READ_NEWEST && mode != SPECTRE_READ_WINDOW) return fail(SPECTRE_EINVAL, "prefix_readout: bad mode");
+    if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "prefix_readout: bad dtype");
+    if (c->t < 1) return fail(SPECTRE_EINVAL, "prefix_readout: cache is empty");
+    const size_t need = spectre_prefix_readout_workspace_bytes(c, mode, io);
+    if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_readout: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_readout: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int B = c->B, H = c->H, d = c->d, N = c->N_max, BH = B * H, F = N / 2 + 1;
+    float2 *X = static_cast<float2 *>(c->prefix_fft);
+    const float2 *gg = static_cast<const float2 *>(g);
+    hipError_t e;
+    if (mode == SPECTRE_READ_NEWEST) {
+        float *partial = static_cast<float *>(ws);
+        const int slot = (int)((c->t - 1) % N);
+        e = launch_sweep(false, true, X, nullptr, static_cast<const float2 *>(c->twiddle), gg, partial, BH, F, N, slot, st);
+        if (e != hipSuccess) return fail_hip(e, "sweep(read)");
+        e = launch_readout_final((int)io, partial, out, BH, F, st);
+        if (e != hipSuccess) return fail_hip(e, "readout_final");
+        return SPECTRE_OK;
+    }
+    Pow2Plan pl;
+    rc = get_pow2_plan(N, &pl);
+    if (rc) return rc;
+    float2 *scr = static_cast<float2 *>(ws);
+    const int Lw = (int)(c->t < N ? c->t : N);
+    const int chunk = mix_chunk_heads(BH, N, d);
+    for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
+        const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
+        e = launch_tangle(X, gg, scr, N, pl.N1, pl.N2, pl.P, bh0, nbh, st);
+        if (e != hipSuccess) return fail_hip(e, "tangle");
+        e = launch_big(pl, scr, nullptr, bh0, nbh, 2, st);
+        if (e != hipSuccess) return fail_hip(e, "big(inverse)");
+        e = launch_small_inv(pl, (int)io, scr, out, N - Lw, Lw, H, bh0, nbh, st);
+        if (e != hipSuccess) return fail_hip(e, "small_inv");
+    }
+    return SPECTRE_OK;
+}
+
+size_t spectre_prefix_step_workspace_bytes(const spectre_prefix_cache *c, const spectre_gate_params *P) {
+    if (!c || !P || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 2 || P->d_g < 1) return 0;
+    const int BH = c->B * c->H, F = c->N_max / 2 + 1;
+    return align256((size_t)BH * c->d * sizeof(float)) + align256((size_t)BH * P->d_g * sizeof(float)) +
+           align256((size_t)BH * F * sizeof(float2)) + align256((size_t)BH * sweep_chunks(F) * c->d * sizeof(float));
+}
+
+int spectre_prefix_step(spectre_prefix_cache *c, const void *v_t, const void *q_t, const spectre_gate_params *P,
+                        void *out, spectre_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_cache(c, "prefix_step");
+    if (rc) return rc;
+    if (!v_t || !q_t || !out) return fail(SPECTRE_EINVAL, "prefix_step: null pointer");
+    if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "prefix_step: bad dtype");
+    rc = check_gate_params(P, c->H, "prefix_step");
+    if (rc) return rc;
+    if (P->n_fft != c->N_max || P->d != c->d) return fail(SPECTRE_EINVAL, "prefix_step: gate is for n_fft=%d, d=%d", P->n_fft, P->d);
+    const size_t need = spectre_prefix_step_workspace_bytes(c, P);
+    if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_step: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_step: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int B = c->B, H = c->H, d = c->d, N = c->N_max, BH = B * H, F = N / 2 + 1;
+    char *w = static_cast<char *>(ws);
+    float *delta = reinterpret_cast<float *>(w);
+    w += align256((size_t)BH * d * sizeof(float));
+    float *hid = reinterpret_cast<float *>(w);
+    w += align256((size_t)BH * P->d_g * sizeof(float));
+    float2 *g = reinterpret_cast<float2 *>(w);
+    w += align256((size_t)BH * F * sizeof(float2));
+    float *partial = reinterpret_cast<float *>(w);
+    const int slot = (int)(c->t % N), evict = c->t >= N ? 1 : 0;
+    hipError_t e = launch_ring_update((int)io, v_t, q_t, 1, 0, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf),
+                                      static_cast<double *>(c->sum_q), delta, B, H, d, N, slot, evict, st);
+    if (e != hipSuccess) return fail_hip(e, "ring_update");
+    e = launch_gate_mlp(static_cast<const double *>(c->sum_q), 1.0 / (double)N, gate_dev(P), hid, B, H, 0, g, st);
+    if (e != hipSuccess) return fail_hip(e, "gate_mlp");
+    e = launch_sweep(true, true, static_cast<float2 *>(c->prefix_fft), delta, static_cast<const float2 *>(c->twiddle), g,
+                     partial, BH, F, N, slot, st);
+    if (e != hipSuccess) return fail_hip(e, "sweep(update+read)");
+    e = launch_readout_final((int)io, partial, out, BH, F, st);
+    if (e != hipSuccess) return fail_hip(e, "readout_final");
+    c->t += 1;
     return SPECTRE_OK;
 }
 

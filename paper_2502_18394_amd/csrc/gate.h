@@ -1,0 +1,28 @@
+// Gate kernels: host-side launch declarations.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace spectre {
+
+constexpr int kPoolRows = 256;   // rows summed by one workgroup of the pooling pass
+
+struct GateDev {                 // device pointers; layout as in the public parameter block
+    int Hg, d, d_g, n_fft;
+    const float *ln_gamma, *ln_beta;
+    float ln_eps;
+    const float *W1, *b1, *W2, *b2, *modrelu_bias;
+};
+
+// Bytes of the pooling partial sums for query rows [B, L, H, d].
+size_t gate_partial_bytes(int B, int L, int H, int d);
+
+// sum_q [B,H,d] (double) = sum over the L rows of q [B,L,H,d]; io 0 = fp32, 1 = bf16.
+hipError_t launch_pool(int io, const void *q, double *partial, double *sum_q, int B, int L, int H, int d,
+                       hipStream_t st);
+
+// g [B,H,F] from sum_q; hid is scratch [B,H,d_g]; phase already reduced modulo n_fft.
+hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev &P, float *hid, int B, int H,
+                           long long phase, float2 *g, hipStream_t st);
+
+}  // namespace spectre

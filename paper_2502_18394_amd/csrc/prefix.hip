@@ -1,0 +1,306 @@
+// Prefix-FFT cache kernels (Sec. 3.3, Eq. 5, Algorithm 1) for gfx950.
+//
+// Cache layout: prefix_fft [B*H][F][d] complex64 (a bin's d channels are one contiguous
+// 8*d-byte row), ring buffers [B*H][N][d] fp32, sum_q [B*H][d] fp64, twiddle [N] complex64.
+// The decode sweep is a pure stream over prefix_fft: each entry is read once, updated by the
+// rank-one term of Eq. (5), written once, and (fused) contributes to the newest row's readout.
+#include "prefix.h"
+
+#include "common.h"
+
+namespace spectre {
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_fill_zero(uint4 *__restrict__ p, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+// twiddle[m] = exp(-j 2 pi m / N), evaluated in fp64 and rounded once.
+__global__ __launch_bounds__(256) void k_fill_twiddle(float2 *__restrict__ tw, int N) {
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= N) return;
+    double s, c;
+    sincospi(2.0 * (double)m / (double)N, &s, &c);
+    tw[m] = make_float2((float)c, (float)(-s));
+}
+
+// ------------------------------------------------------------------------------------------
+// ring update for one token (Algorithm 1, DecodeStep: slot, eviction, buffers, running sum).
+// One lane per (b, h, c).  v_t, q_t are the rows [B, T, H, d] at position `ti`.
+template <typename T>
+__device__ __forceinline__ float load_scalar(const T *p, size_t i);
+template <>
+__device__ __forceinline__ float load_scalar<float>(const float *p, size_t i) { return p[i]; }
+template <>
+__device__ __forceinline__ float load_scalar<uint16_t>(const uint16_t *p, size_t i) {
+    return __uint_as_float((uint32_t)p[i] << 16);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_ring_update(const T *__restrict__ v_new, const T *__restrict__ q_new,
+                                                     int Tn, int ti, float *__restrict__ v_buf,
+                                                     float *__restrict__ q_buf, double *__restrict__ sum_q,
+                                                     float *__restrict__ delta, int H, int d, int N, int slot,
+                                                     int evict, int total) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int c = idx % d, bh = idx / d, h = bh % H, b = bh / H;
+    const size_t src = (((size_t)b * Tn + ti) * H + h) * d + c;
+    const size_t ring = ((size_t)bh * N + slot) * d + c;
+    const float vn = load_scalar<T>(v_new, src), qn = load_scalar<T>(q_new, src);
+    const float vo = evict ? v_buf[ring] : 0.0f, qo = evict ? q_buf[ring] : 0.0f;
+    delta[idx] = vn - vo;
+    sum_q[idx] += (double)qn - (double)qo;
+    v_buf[ring] = vn;
+    q_buf[ring] = qn;
+}
+
+// ------------------------------------------------------------------------------------------
+// sweep over the cache.  grid (ceil(F/KCH), B*H); 256 lanes = 8 bins x 32 lanes, a lane owns
+// two adjacent channels (one 16-byte access).  UPDATE: X[k,:] += delta * w_k with
+// w_k = twiddle[(k*slot) mod N] (Eq. 5).  READ: partial[bh][chunk][c] = sum over the chunk's
+// bins of Re(r_k X[k,c]) with r_k = (c_k/N) g_k conj(w_k), c_k = 1 at DC and Nyquist, else 2
+// (the newest row of Cor. B.2's inverse; exp(+j 2 pi k slot/N) = conj(w_k)).
+constexpr int kSweepBins = 128;
+
+template <bool UPDATE, bool READ>
+__global__ __launch_bounds__(256) void k_sweep(float4 *__restrict__ X, const float *__restrict__ delta,
+                                               const float2 *__restrict__ tw, const float2 *__restrict__ g,
+                                               float *__restrict__ partial, int F, int N, int slot,
+                                               int nchunks) {
+    __shared__ float2 red[8][32];
+    const int lane = threadIdx.x & 31, row = threadIdx.x >> 5;
+    const int chunk = blockIdx.x, bh = blockIdx.y;
+    const int k0 = chunk * kSweepBins, k1 = min(F, k0 + kSweepBins);
+    float2 dl = make_float2(0.f, 0.f);
+    if (UPDATE) dl = *reinterpret_cast<const float2 *>(delta + (size_t)bh * 64 + 2 * lane);
+    const float invN = 1.0f / (float)N;
+    float acc0 = 0.f, acc1 = 0.f;
+    float4 *Xp = X + ((size_t)bh * F) * 32 + lane;
+    for (int k = k0 + row; k < k1; k += 8) {
+        const unsigned m = ((unsigned)k * (unsigned)slot) & (unsigned)(N - 1);
+        const float2 w = tw[m];
+        float4 x = Xp[(size_t)k * 32];
+        if (UPDATE) {
+            x.x = fmaf(dl.x, w.x, x.x);
+            x.y = fmaf(dl.x, w.y, x.y);
+            x.z = fmaf(dl.y, w.x, x.z);
+            x.w = fmaf(dl.y, w.y, x.w);
+            Xp[(size_t)k * 32] = x;
+        }
+        if (READ) {
+            const float2 gk = g[(size_t)bh * F + k];
+            const float ck = (k == 0 || 2 * k == N) ? invN : 2.0f * invN;
+            const float2 r = cmulc(gk, w);   // g_k conj(w_k)
+            const float rr = r.x * ck, ri = r.y * ck;
+            acc0 = fmaf(rr, x.x, fmaf(-ri, x.y, acc0));
+            acc1 = fmaf(rr, x.z, fmaf(-ri, x.w, acc1));
+        }
+    }
+    if (READ) {
+        red[row][lane] = make_float2(acc0, acc1);
+        __syncthreads();
+        if (row == 0) {
+            float2 s = red[0][lane];
+#pragma unroll
+            for (int r = 1; r < 8; ++r) {
+                s.x += red[r][lane].x;
+                s.y += red[r][lane].y;
+            }
+            *reinterpret_cast<float2 *>(partial + ((size_t)bh * nchunks + chunk) * 64 + 2 * lane) = s;
+        }
+    }
+}
+
+// out[b, 0, h, c] = sum over chunks of partial, in chunk order.
+template <typename IO>
+__global__ __launch_bounds__(256) void k_readout_final(const float *__restrict__ partial,
+                                                       typename IO::pair_t *__restrict__ out, int nchunks,
+                                                       int total_pairs) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total_pairs) return;
+    const int bh = idx / 32, p = idx % 32;
+    const float2 *src = reinterpret_cast<const float2 *>(partial + (size_t)bh * nchunks * 64) + p;
+    float2 s = make_float2(0.f, 0.f);
+    for (int c = 0; c < nchunks; ++c) {
+        const float2 v = src[(size_t)c * 32];
+        s.x += v.x;
+        s.y += v.y;
+    }
+    out[idx] = IO::pack(s);
+}
+
+// ------------------------------------------------------------------------------------------
+// pre-fill helpers.
+// Ring buffers from the prompt: v_buf[bh][l][c] = V[b][l][h][c] for l < T, 0 beyond.
+template <typename IO>
+__global__ __launch_bounds__(256) void k_fill_ring(const typename IO::pair_t *__restrict__ V,
+                                                   const typename IO::pair_t *__restrict__ Q,
+                                                   float2 *__restrict__ v_buf, float2 *__restrict__ q_buf, int T,
+                                                   int H, int N, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int p = (int)(idx % 32);
+    const size_t r = idx / 32;
+    const int l = (int)(r % N);
+    const size_t bh = r / N;
+    const int h = (int)(bh % H);
+    const size_t b = bh / H;
+    float2 v = make_float2(0.f, 0.f), q = v;
+    if (l < T) {
+        const size_t src = ((b * T + l) * H + h) * 32 + p;
+        v = IO::unpack(V[src]);
+        q = IO::unpack(Q[src]);
+    }
+    v_buf[idx] = v;
+    q_buf[idx] = q;
+}
+
+__device__ __forceinline__ int digit_reverse16p(int k1, int P) {
+    return P == 2 ? (((k1 & 15) << 4) | (k1 >> 4)) : (((k1 & 15) << 8) | (k1 & 0xF0) | (k1 >> 8));
+}
+
+// Scratch position of bin k of the complex transform of a channel pair.
+__device__ __forceinline__ size_t scratch_index(int bhl, int k, int p, int N1, int N2, int P) {
+    const int k2 = k % N2, k1 = k / N2;
+    return (((size_t)bhl * N2 + k2) * 32 + p) * N1 + digit_reverse16p(k1, P);
+}
+
+// untangle: the complex transform Z of z = v_even + j v_odd separates into the two real
+// channels' half spectra, X_even[k] = (Z_k + conj Z_{N-k})/2, X_odd[k] = (Z_k - conj Z_{N-k})/(2j).
+// One lane per (bh, k <= N/2, pair).
+__global__ __launch_bounds__(256) void k_untangle(const float2 *__restrict__ scr, float4 *__restrict__ X,
+                                                  int N, int N1, int N2, int P, int bh0, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int F = N / 2 + 1;
+    const int p = (int)(idx % 32);
+    const size_t r = idx / 32;
+    const int k = (int)(r % F);
+    const int bhl = (int)(r / F);
+    const float2 zk = scr[scratch_index(bhl, k, p, N1, N2, P)];
+    const float2 zn = scr[scratch_index(bhl, (N - k) % N, p, N1, N2, P)];
+    float4 o;
+    o.x = 0.5f * (zk.x + zn.x);
+    o.y = 0.5f * (zk.y - zn.y);
+    o.z = 0.5f * (zk.y + zn.y);
+    o.w = -0.5f * (zk.x - zn.x);
+    X[((size_t)(bh0 + bhl) * F + k) * 32 + p] = o;
+}
+
+// tangle: the inverse of untangle with the gate applied.  Y_c[k] = g_k X_c[k] for k <= N/2
+// (real parts only at DC and Nyquist), Hermitian-extended to k > N/2; Z_k = (Y_even + j Y_odd)/N
+// goes to the scratch layout of the inverse big kernel.  One lane per (bhl, k < N, pair).
+__global__ __launch_bounds__(256) void k_tangle(const float4 *__restrict__ X, const float2 *__restrict__ g,
+                                                float2 *__restrict__ scr, int N, int N1, int N2, int P, int bh0,
+                                                size_t total) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int F = N / 2 + 1;
+    const int p = (int)(idx % 32);
+    const size_t r = idx / 32;
+    const int k = (int)(r % N);
+    const int bhl = (int)(r / N);
+    const size_t bh = (size_t)(bh0 + bhl);
+    const bool upper = 2 * k > N;
+    const int ks = upper ? N - k : k;
+    const float4 x = X[(bh * F + ks) * 32 + p];
+    const float2 gk = g[bh * F + ks];
+    float2 ya = cmul(gk, make_float2(x.x, x.y)), yb = cmul(gk, make_float2(x.z, x.w));
+    if (k == 0 || 2 * k == N) {
+        ya.y = 0.f;
+        yb.y = 0.f;
+    }
+    if (upper) {
+        ya.y = -ya.y;
+        yb.y = -yb.y;
+    }
+    const float s = 1.0f / (float)N;
+    scr[scratch_index(bhl, k, p, N1, N2, P)] = make_float2((ya.x - yb.y) * s, (ya.y + yb.x) * s);
+}
+
+// ------------------------------------------------------------------------------------------
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st) {
+    const size_t n16 = bytes / 16;   // callers pass multiples of 16 bytes
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    k_fill_zero<<<(unsigned)blocks, 256, 0, st>>>(static_cast<uint4 *>(p), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_twiddle(float2 *tw, int N, hipStream_t st) {
+    k_fill_twiddle<<<(N + 255) / 256, 256, 0, st>>>(tw, N);
+    return hipGetLastError();
+}
+
+hipError_t launch_ring_update(int io, const void *v_new, const void *q_new, int Tn, int ti, float *v_buf,
+                              float *q_buf, double *sum_q, float *delta, int B, int H, int d, int N, int slot,
+                              int evict, hipStream_t st) {
+    const int total = B * H * d;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (io)
+        k_ring_update<uint16_t><<<grid, 256, 0, st>>>(static_cast<const uint16_t *>(v_new),
+                                                     static_cast<const uint16_t *>(q_new), Tn, ti, v_buf, q_buf,
+                                                     sum_q, delta, H, d, N, slot, evict, total);
+    else
+        k_ring_update<float><<<grid, 256, 0, st>>>(static_cast<const float *>(v_new),
+                                                  static_cast<const float *>(q_new), Tn, ti, v_buf, q_buf, sum_q,
+                                                  delta, H, d, N, slot, evict, total);
+    return hipGetLastError();
+}
+
+int sweep_chunks(int F) { return (F + kSweepBins - 1) / kSweepBins; }
+
+hipError_t launch_sweep(bool update, bool read, float2 *X, const float *delta, const float2 *tw, const float2 *g,
+                        float *partial, int BH, int F, int N, int slot, hipStream_t st) {
+    const int nch = sweep_chunks(F);
+    dim3 grid(nch, BH);
+    float4 *X4 = reinterpret_cast<float4 *>(X);
+    if (update && read) k_sweep<true, true><<<grid, 256, 0, st>>>(X4, delta, tw, g, partial, F, N, slot, nch);
+    else if (update) k_sweep<true, false><<<grid, 256, 0, st>>>(X4, delta, tw, g, partial, F, N, slot, nch);
+    else k_sweep<false, true><<<grid, 256, 0, st>>>(X4, delta, tw, g, partial, F, N, slot, nch);
+    return hipGetLastError();
+}
+
+hipError_t launch_readout_final(int io, const float *partial, void *out, int BH, int F, hipStream_t st) {
+    const int total = BH * 32;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (io) k_readout_final<IoBf16><<<grid, 256, 0, st>>>(partial, static_cast<uint32_t *>(out), sweep_chunks(F), total);
+    else k_readout_final<IoF32><<<grid, 256, 0, st>>>(partial, static_cast<float2 *>(out), sweep_chunks(F), total);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_ring(int io, const void *V, const void *Q, float *v_buf, float *q_buf, int B, int T, int H,
+                            int N, hipStream_t st) {
+    const size_t total = (size_t)B * H * N * 32;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (io)
+        k_fill_ring<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(V), static_cast<const uint32_t *>(Q),
+                                                  reinterpret_cast<float2 *>(v_buf),
+                                                  reinterpret_cast<float2 *>(q_buf), T, H, N, total);
+    else
+        k_fill_ring<IoF32><<<grid, 256, 0, st>>>(static_cast<const float2 *>(V), static_cast<const float2 *>(Q),
+                                                 reinterpret_cast<float2 *>(v_buf), reinterpret_cast<float2 *>(q_buf),
+                                                 T, H, N, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_untangle(const float2 *scr, float2 *X, int N, int N1, int N2, int P, int bh0, int nbh,
+                           hipStream_t st) {
+    const size_t total = (size_t)nbh * (N / 2 + 1) * 32;
+    k_untangle<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(scr, reinterpret_cast<float4 *>(X), N, N1, N2, P,
+                                                                bh0, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_tangle(const float2 *X, const float2 *g, float2 *scr, int N, int N1, int N2, int P, int bh0,
+                         int nbh, hipStream_t st) {
+    const size_t total = (size_t)nbh * N * 32;
+    k_tangle<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(reinterpret_cast<const float4 *>(X), g, scr, N, N1,
+                                                              N2, P, bh0, total);
+    return hipGetLastError();
+}
+
+}  // namespace spectre

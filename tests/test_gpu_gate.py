@@ -1,0 +1,70 @@
+"""GPU parity of spectre_gate against the fp64 oracle (Sec. 3.2 step 3; Sec. 3.5 phase)."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import TOL, f64, rel_l2, to_device
+from paper_2502_18394_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gate(oracle, B, L, H, d, dg, n, io, shared=False, modrelu=True, phase=0, seed=1, std=0.02, bias_shift=0.0):
+    from paper_2502_18394_amd import binding
+    p = synth.gate_params(seed, 1 if shared else H, d, n, d_g=dg, modrelu=modrelu, std=std)
+    if bias_shift:
+        p["modrelu_bias"] = (p["modrelu_bias"] + np.float32(bias_shift)).astype(np.float32)
+    vals, store = synth.tokens(seed + 1, (B, L, H, d), io)
+    P = binding.GateParams(p)
+    g = binding.gate(to_device(store, io), P, 1.0 / L, phase_pos=phase)
+    torch.cuda.synchronize()
+    want = oracle.gate(oracle.pool_q(vals.astype(np.float64)), 1.0 / L, f64(p), n, phase)
+    return g.cpu().numpy(), want
+
+
+@pytest.mark.parametrize("B,L,H,d,dg,io,shared", [
+    (1, 1024, 1, 64, 64, "f32", False),      # config 1
+    (1, 8192, 32, 64, 64, "bf16", False),    # config 2 shape
+    (3, 512, 5, 64, 64, "f32", True),        # shared weights, 15 rows on the MFMA column side
+    (40, 256, 1, 64, 64, "f32", False),      # more than 32 rows: two row tiles
+    (5, 256, 12, 64, 64, "bf16", True),      # shared, 60 rows
+    (4, 196, 12, 64, 64, "f32", False),      # ViT length: 2F = 198, ragged last tile
+    (2, 300, 3, 32, 48, "f32", False),       # other d, d_g not a multiple of 16, odd chunking
+    (1, 7, 2, 8, 5, "f32", False),           # tiny everything, odd n
+])
+def test_gate_matches_oracle(oracle, B, L, H, d, dg, io, shared):
+    print(f"case B={B} L={L} H={H} d={d} dg={dg} io={io} shared={shared}", flush=True)
+    got, want = run_gate(oracle, B, L, H, d, dg, L, io, shared=shared)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= 1e-5   # the gate is fp32 throughout; bf16 only affects the (exactly represented) inputs
+
+
+def test_gate_large_std_exercises_modrelu_threshold(oracle):
+    got, want = run_gate(oracle, 2, 256, 3, 64, 64, 256, "f32", std=0.5, seed=5, bias_shift=-2.0)
+    assert rel_l2(got, want) <= 1e-5
+    assert (np.abs(want) == 0).any() and (np.abs(want) > 0).any()
+    np.testing.assert_array_equal(np.abs(got) == 0, np.abs(want) == 0)
+
+
+def test_gate_without_modrelu_and_with_phase(oracle):
+    got, want = run_gate(oracle, 2, 512, 2, 64, 64, 512, "f32", modrelu=False, phase=777, seed=9)
+    assert rel_l2(got, want) <= 1e-5
+
+
+def test_gate_from_pooled_sum_decode_form(oracle):
+    from paper_2502_18394_amd import binding
+    B, H, d, N = 3, 4, 64, 4096
+    p = synth.gate_params(11, H, d, N)
+    sq = np.random.default_rng(12).standard_normal((B, H, d)) * 40.0
+    P = binding.GateParams(p)
+    for phase in (0, 4097, 123456789):
+        g = binding.gate(torch.from_numpy(sq).cuda(), P, 1.0 / N, pooled=True, phase_pos=phase)
+        want = oracle.gate(sq, 1.0 / N, f64(p), N, phase)
+        assert rel_l2(g.cpu().numpy(), want) <= 1e-5
+
+
+def test_pooling_of_long_sequence_is_accurate(oracle):
+    """128k rows: the pooled mean is ~0.003 and LayerNorm rescales it to O(1), so the sum must be tight."""
+    got, want = run_gate(oracle, 1, 131072, 2, 64, 64, 1024, "bf16", seed=21)
+    assert rel_l2(got, want) <= 1e-5

@@ -6,17 +6,12 @@ import numpy as np
 import pytest
 import torch
 
+from gpu_util import TOL, rel_l2
 from paper_2502_18394_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
 
-
-def rel_l2(a, b):
-    a = np.asarray(a, np.float64)
-    b = np.asarray(b, np.float64)
-    return float(np.linalg.norm((a - b).ravel()) / max(np.linalg.norm(b.ravel()), 1e-300))
 
 
 def to_device(vals, store, io):
