@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the SPECTRE hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-decode] [--no-cpu]
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+spectre_gate (pool the query rows, LayerNorm, MLP on the matrix cores, modReLU) followed
+by spectre_mix_forward (rfft -> gate -> irfft) on the Llama-3.2-1B head shape at L = 131072.
+The decode half of the path (one fused Prefix-FFT step per new token, B = 8, N_max = 32768)
+is timed in the same run and reported under "decode".  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+# fp32 vector peak without packed math: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s
+VALU_PEAK_GINSTR = 256 * 4 * 16 * 2.4
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama1b_128k")
+    ap.add_argument("--L", type=int, default=0, help="override the sequence length of the workload")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--decode-steps", type=int, default=32)
+    return ap.parse_args()
+
+
+def time_loop(fn, steps, warmup):
+    """Average milliseconds per call between HIP events on the current stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def device_tokens(shape, seed, dtype):
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    return torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(dtype)
+
+
+def device_gate_params(seed, Hg, d, n_fft, d_g, binding):
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    F = n_fft // 2 + 1
+
+    def nrm(*s):
+        return 0.02 * torch.randn(s, generator=gen, device="cuda", dtype=torch.float32)
+    p = dict(n_fft=n_fft, ln_eps=1e-5, ln_gamma=1.0 + nrm(Hg, d), ln_beta=nrm(Hg, d), W1=nrm(Hg, d, d_g),
+             b1=nrm(Hg, d_g), W2=nrm(Hg, d_g, 2 * F), b2=nrm(Hg, 2 * F), modrelu_bias=nrm(Hg, F))
+    return binding.GateParams(p)
+
+
+def cpu_baseline(cfg, L):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload (whole heads)."""
+    import numpy as np
+    import oracle
+    from paper_2502_18394_amd import synth
+    oracle.build()
+    H, d = cfg["H"], cfg["d"]
+    Hs = max(1, min(H, (16 * 131072) // L))          # about 16 heads at 128k; all heads when short
+    Hs = min(Hs, H)
+    vals, _ = synth.tokens(synth.BASE_SEED, (1, L, Hs, d), cfg["io"])
+    qv, _ = synth.tokens(synth.BASE_SEED + 1, (1, L, Hs, d), cfg["io"])
+    p = synth.gate_params(synth.BASE_SEED + 2, Hs, d, L)
+    p64 = {k: (np.asarray(v, np.float64) if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    V, Q = vals.astype(np.float64), qv.astype(np.float64)
+    t0 = time.time()
+    g = oracle.gate(oracle.pool_q(Q), 1.0 / L, p64, L, 0)
+    oracle.mix_forward(V, g)
+    dt = time.time() - t0
+    full = dt * (cfg["B"] * H / Hs)
+    return {"value": cfg["B"] * L / full, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"gate+mix_forward of {Hs} of {cfg['B'] * H} heads at L={L} took {dt:.2f} s, scaled to all heads"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a single-GPU kernel path; run with --gpus 1 (no multi-GPU figure exists).",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2502_18394_amd import binding, synth
+
+    cfg = dict(synth.CONFIGS[args.workload])
+    if args.L:
+        cfg["L"] = args.L
+    B, H, L, d = cfg["B"], cfg["H"], cfg["L"], cfg["d"]
+    dtype = torch.bfloat16 if cfg["io"] == "bf16" else torch.float32
+    esize = 2 if cfg["io"] == "bf16" else 4
+    torch.cuda.set_device(0)
+    binding.lib()   # raises if the HIP library is missing: there is no other path
+
+    V = device_tokens((B, L, H, d), synth.BASE_SEED, dtype)
+    Q = device_tokens((B, L, H, d), synth.BASE_SEED + 1, dtype)
+    P = device_gate_params(synth.BASE_SEED + 2, H, d, L, synth.D_GATE, binding)
+    out = torch.empty_like(V)
+    g = torch.empty((B, H, L // 2 + 1), dtype=torch.complex64, device="cuda")
+    ws_mix = torch.empty(binding.mix_workspace_bytes(B, L, H, d, binding._dtype_code(V)) + 256, dtype=torch.uint8, device="cuda")
+    ws_gate = torch.empty(binding.gate_workspace_bytes(B, L, H, P) + 256, dtype=torch.uint8, device="cuda")
+
+    def step():
+        binding.gate(Q, P, 1.0 / L, g_out=g, ws=ws_gate)
+        binding.mix_forward(V, g, out=out, ws=ws_mix)
+
+    def mix_only():
+        binding.mix_forward(V, g, out=out, ws=ws_mix)
+
+    def gate_only():
+        binding.gate(Q, P, 1.0 / L, g_out=g, ws=ws_gate)
+
+    # whole step: barrier-free single process; synchronize on both sides of the timed region
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms_mix = time_loop(mix_only, args.steps, 2)
+    ms_gate = time_loop(gate_only, args.steps, 2)
+
+    tokens = B * L
+    F = L // 2 + 1
+    mix_bytes = 2 * tokens * H * d * esize + B * H * F * 8                # read V, write out, read g
+    gate_bytes = tokens * H * d * esize + P.Hg * P.d_g * 2 * F * 4 + B * H * F * 8   # read Q, read W2, write g
+    mix_flops_instr = tokens * H * (d // 2) * (2 * 3.5 * (L.bit_length() - 1) + 6)   # lane-instructions, see the design doc
+    res = {
+        "metric": "mixer tokens/sec at L=128k (H=32,d=64) + % HBM roofline; decode tokens/sec",
+        "value": tokens / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: gate+mix_forward B={B} H={H} d={d} L={L} {cfg['io']} I/O, fp32 spectra",
+                   "global_batch": B, "seq_len": L, "parallelism": "single GPU"},
+        "roofline": {"bound": "hbm", "kernel": "spectre_mix_forward (gate_expand + per head group: small_fwd, big, small_inv)",
+                     "achieved": mix_bytes / (ms_mix * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": mix_bytes / (ms_mix * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": mix_bytes, "ms": ms_mix},
+        "roofline_alu": {"bound": "alu", "achieved": mix_flops_instr / (ms_mix * 1e-3) / 1e9, "peak": VALU_PEAK_GINSTR,
+                         "unit": "G lane-instr/s", "frac": mix_flops_instr / (ms_mix * 1e-3) / 1e9 / VALU_PEAK_GINSTR},
+        "mix_only": {"tokens_per_s": tokens / (ms_mix * 1e-3), "ms": ms_mix},
+        "gate_only": {"ms": ms_gate, "algorithmic_bytes": gate_bytes,
+                      "hbm_frac": gate_bytes / (ms_gate * 1e-3) / 1e9 / HBM_PEAK_GBS},
+    }
+    del V, Q, out, g, ws_mix, ws_gate, P
+    torch.cuda.empty_cache()
+
+    if not args.no_decode:
+        dc = synth.CONFIGS["decode_32k"]
+        Bd, Hd, N, dd = dc["B"], dc["H"], dc["N_max"], dc["d"]
+        cache = binding.PrefixCache(Bd, Hd, dd, N)
+        Pd = device_gate_params(synth.BASE_SEED + 3, Hd, dd, N, synth.D_GATE, binding)
+        cache.update(device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 4, torch.float32),
+                     device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 5, torch.float32))
+        vt = device_tokens((Bd, 1, Hd, dd), synth.BASE_SEED + 6, torch.float32)
+        qt = device_tokens((Bd, 1, Hd, dd), synth.BASE_SEED + 7, torch.float32)
+        od = torch.empty_like(vt)
+        ms_dec = time_loop(lambda: cache.step(vt, qt, Pd, out=od), args.decode_steps, 3)
+        Fd = N // 2 + 1
+        sweep_bytes = 2 * 8 * Bd * Hd * Fd * dd
+        res["decode"] = {"workload": f"decode_32k: fused Prefix-FFT step B={Bd} H={Hd} d={dd} N_max={N}, cache full (eviction branch), fp32",
+                         "tokens_per_s": Bd / (ms_dec * 1e-3), "ms_per_step": ms_dec, "steps": args.decode_steps,
+                         "roofline": {"bound": "hbm", "kernel": "k_sweep<update,read>", "achieved": sweep_bytes / (ms_dec * 1e-3) / 1e9,
+                                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sweep_bytes / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                      "algorithmic_bytes": sweep_bytes}}
+        del cache, Pd
+        torch.cuda.empty_cache()
+
+    if not args.no_cpu:
+        res["cpu_baseline"] = cpu_baseline(cfg, L)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

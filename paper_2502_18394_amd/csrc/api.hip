@@ -16,6 +16,7 @@
 
 #include "gate.h"
 #include "internal.h"
+#include "mix_slab.h"
 #include "prefix.h"
 
 namespace spectre {
@@ -91,7 +92,7 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // cache between the three kernels of a group.
 int mix_chunk_heads(int BH, int L, int d) {
     size_t per_head = (size_t)L * (size_t)(d / 2) * sizeof(float2);
-    size_t budget = (size_t)64 << 20;
+    size_t budget = (size_t)136 << 20;
     if (const char *e = getenv("SPECTRE_CHUNK_MB")) {
         long mb = atol(e);
         if (mb > 0) budget = (size_t)mb << 20;
@@ -113,11 +114,16 @@ const char *spectre_last_error(void) { return g_err.c_str(); }
 
 int spectre_version(void) { return 100; }
 
-int spectre_length_supported(int n, int d) {
+// 0 = no kernel, 1 = whole slab in LDS, 2 = four-step power-of-two path.
+static int mix_route(int BH, int L, int d) {
     if (d != 64) return 0;
     int N1, N2, P;
-    return pow2_split(n, &N1, &N2, &P) ? 1 : 0;
+    const bool p2 = pow2_split(L, &N1, &N2, &P), sl = slab_supported(L);
+    if (sl && (!p2 || BH >= 256)) return 1;
+    return p2 ? 2 : 0;
 }
+
+int spectre_length_supported(int n, int d) { return mix_route(1, n, d) != 0; }
 
 void spectre_shutdown(void) {
     std::lock_guard<std::mutex> lk(g_mu);
@@ -134,8 +140,10 @@ void spectre_shutdown(void) {
 size_t spectre_mix_workspace_bytes(int B, int L, int H, int d, spectre_dtype io) {
     (void)io;
     if (B < 1 || L < 2 || H < 1 || d < 2) return 0;
-    if (!spectre_length_supported(L, d)) return 0;
     const int BH = B * H;
+    const int route = mix_route(BH, L, d);
+    if (route == 0) return 0;
+    if (route == 1) return 256;
     const int chunk = mix_chunk_heads(BH, L, d);
     return align256((size_t)BH * L * sizeof(float2)) + align256((size_t)chunk * L * (d / 2) * sizeof(float2));
 }
@@ -156,11 +164,19 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         return fail(SPECTRE_EWORKSPACE, "mix_forward: workspace %zu < %zu bytes", ws_bytes, need);
     if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "mix_forward: ws not 256-byte aligned");
 
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int BH = B * H;
+    if (mix_route(BH, L, d) == 1) {
+        const float2 *roots = nullptr;
+        int rc = get_roots(L, &roots);
+        if (rc) return rc;
+        hipError_t e = launch_mix_slab((int)io, v, static_cast<const float2 *>(g), out, roots, B, L, H, st);
+        if (e != hipSuccess) return fail_hip(e, "mix_slab");
+        return SPECTRE_OK;
+    }
     Pow2Plan pl;
     int rc = get_pow2_plan(L, &pl);
     if (rc) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int BH = B * H;
     float2 *gp = static_cast<float2 *>(ws);
     float2 *scr = reinterpret_cast<float2 *>(static_cast<char *>(ws) + align256((size_t)BH * L * sizeof(float2)));
     hipError_t e = launch_gate_expand(pl, static_cast<const float2 *>(g), gp, BH, st);
@@ -240,10 +256,15 @@ int spectre_gate(const void *q, int q_is_pooled, spectre_dtype q_dtype, double i
 }
 
 // ------------------------------------------------------------------------------------------ prefix cache
+static bool prefix_length_ok(int N, int d) {
+    int N1, N2, P;
+    return d == 64 && pow2_split(N, &N1, &N2, &P);
+}
+
 static int check_cache(const spectre_prefix_cache *c, const char *who) {
     if (!c) return fail(SPECTRE_EINVAL, "%s: null cache", who);
     if (c->B < 1 || c->H < 1 || c->d < 1 || c->N_max < 2) return fail(SPECTRE_EINVAL, "%s: bad cache dimensions", who);
-    if (!spectre_length_supported(c->N_max, c->d))
+    if (!prefix_length_ok(c->N_max, c->d))
         return fail(SPECTRE_EUNSUPPORTED, "%s: no kernel for N_max=%d, d=%d", who, c->N_max, c->d);
     if (!c->prefix_fft || !c->v_buf || !c->q_buf || !c->sum_q || !c->twiddle)
         return fail(SPECTRE_EINVAL, "%s: null cache array", who);
@@ -254,7 +275,7 @@ static int check_cache(const spectre_prefix_cache *c, const char *who) {
 
 size_t spectre_prefix_bytes(int B, int H, int d, int N_max, int which) {
     if (B < 1 || H < 1 || d < 1 || N_max < 2) return 0;
-    if (!spectre_length_supported(N_max, d)) return 0;
+    if (!prefix_length_ok(N_max, d)) return 0;
     const size_t BH = (size_t)B * H, F = (size_t)N_max / 2 + 1;
     switch (which) {
         case SPECTRE_PREFIX_FFT: return BH * F * d * sizeof(float2);

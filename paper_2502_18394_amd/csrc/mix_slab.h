@@ -1,0 +1,16 @@
+// Short-sequence (whole slab in LDS) mixer path: host-side declarations.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace spectre {
+
+constexpr int kSlabMaxL = 512;
+
+// True if L <= kSlabMaxL and L = 2^a 3^b 5^c 7^d.
+bool slab_supported(int L);
+
+// out = irfft_L(g * rfft_L(v)) for d = 64; roots = device table [L] of exp(-j 2 pi m / L).
+hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, const float2 *roots, int B, int L,
+                           int H, hipStream_t st);
+
+}  // namespace spectre

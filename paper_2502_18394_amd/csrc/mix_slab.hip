@@ -1,0 +1,248 @@
+// Short-sequence path of the SPECTRE mixing layer (Sec. 3.2 steps 2-4, Eq. 3 and Eq. 4):
+// one workgroup owns the whole [L, d = 64] slab of one head of one sequence in LDS.
+//
+// Serves every L <= 512 whose prime factors are in {2, 3, 5, 7} - in particular the
+// 14 x 14 = 196 = 4 * 7 * 7 patch grid of the ViT workload and power-of-two lengths
+// below 256.  Channel pairs are transformed as complex sequences (see mix_pow2.hip).
+// The transform is an in-place mixed-radix decimation-in-frequency FFT: after the last
+// forward pass position p holds bin k = reverse(p) (mixed-radix digit reversal), the gate
+// is applied in that order from a per-workgroup table, and the inverse passes undo the
+// forward ones in reverse, so nothing is ever reordered.
+#include "mix_slab.h"
+
+#include "fft_regs.h"
+
+namespace spectre {
+
+// ------------------------------------------------------------------------------------------
+// odd prime radices: X_0 = x_0 + sum a_j;  X_k, X_{R-k} = (x_0 + sum_j cos(2 pi jk/R) a_j)
+//   -/+ j sum_j sin(2 pi jk/R) b_j  with a_j = x_j + x_{R-j}, b_j = x_j - x_{R-j}.
+template <int R> struct OddRoots;
+template <> struct OddRoots<3> {
+    static constexpr float c[1] = {-0.5f};
+    static constexpr float s[1] = {0.86602540378443864676f};
+};
+template <> struct OddRoots<5> {
+    static constexpr float c[2] = {0.30901699437494742410f, -0.80901699437494742410f};
+    static constexpr float s[2] = {0.95105651629515357212f, 0.58778525229247312917f};
+};
+template <> struct OddRoots<7> {
+    static constexpr float c[3] = {0.62348980185873353053f, -0.22252093395631440429f, -0.90096886790241912624f};
+    static constexpr float s[3] = {0.78183148246802980871f, 0.97492791218182360702f, 0.43388373911755812048f};
+};
+
+template <int R>
+__device__ constexpr float odd_cos(int m) {   // cos(2 pi m / R)
+    m %= R;
+    if (m == 0) return 1.0f;
+    if (m > R / 2) m = R - m;
+    return OddRoots<R>::c[m - 1];
+}
+template <int R>
+__device__ constexpr float odd_sin(int m) {   // sin(2 pi m / R)
+    m %= R;
+    if (m == 0) return 0.0f;
+    if (m > R / 2) return -OddRoots<R>::s[R - m - 1];
+    return OddRoots<R>::s[m - 1];
+}
+
+template <int R, bool INV>
+__device__ __forceinline__ void dft_odd(float2 (&x)[R]) {
+    constexpr int Hf = R / 2;
+    float2 a[Hf], b[Hf];
+#pragma unroll
+    for (int j = 1; j <= Hf; ++j) {
+        a[j - 1] = x[j] + x[R - j];
+        b[j - 1] = x[j] - x[R - j];
+    }
+    float2 x0 = x[0];
+    float2 sum = x0;
+#pragma unroll
+    for (int j = 0; j < Hf; ++j) sum = sum + a[j];
+    x[0] = sum;
+#pragma unroll
+    for (int k = 1; k <= Hf; ++k) {
+        float2 cr = x0, si = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int j = 1; j <= Hf; ++j) {
+            const float c = odd_cos<R>(j * k), s = odd_sin<R>(j * k);
+            cr.x = fmaf(c, a[j - 1].x, cr.x);
+            cr.y = fmaf(c, a[j - 1].y, cr.y);
+            si.x = fmaf(s, b[j - 1].x, si.x);
+            si.y = fmaf(s, b[j - 1].y, si.y);
+        }
+        // forward: X_k = cr - j si, X_{R-k} = cr + j si  (j*si = (-si.y, si.x)); inverse swaps
+        const float2 jsi = make_float2(-si.y, si.x);
+        x[k] = INV ? cr + jsi : cr - jsi;
+        x[R - k] = INV ? cr - jsi : cr + jsi;
+    }
+}
+
+template <int R, bool INV>
+__device__ __forceinline__ void dft_any(float2 (&x)[R]) {
+    if constexpr (R == 3 || R == 5 || R == 7) dft_odd<R, INV>(x);
+    else dft<R, INV>(x);
+}
+
+// One in-place pass over all 32 columns of the slab.  n = current sub-transform length,
+// S = n / R its stride; roots[m] = exp(-j 2 pi m / L).  Forward: butterfly then twiddle (and
+// the gate, when GATE, which makes this the last forward pass).  Inverse: conjugate twiddle then
+// inverse butterfly.
+template <int R, bool INV, bool GATE>
+__device__ __forceinline__ void slab_pass(float2 *__restrict__ slab, const float2 *__restrict__ roots,
+                                          const float2 *__restrict__ gpos, int L, int n, int tid, int nthreads) {
+    const int S = n / R, tstep = L / n;
+    const int nb = (L / R) * 32;
+    for (int w = tid; w < nb; w += nthreads) {
+        const int col = w & 31, bi = w >> 5;
+        const int i = bi % S, blk = bi / S;
+        const int base = blk * n + i;
+        float2 x[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) x[j] = slab[(base + S * j) * 32 + col];
+        if (INV) {
+#pragma unroll
+            for (int u = 1; u < R; ++u) x[u] = cmulc(x[u], roots[i * u * tstep]);
+        }
+        dft_any<R, INV>(x);
+        if (!INV) {
+#pragma unroll
+            for (int u = 1; u < R; ++u) x[u] = cmul(x[u], roots[i * u * tstep]);
+            if (GATE) {
+#pragma unroll
+                for (int u = 0; u < R; ++u) x[u] = cmul(x[u], gpos[base + S * u]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j) slab[(base + S * j) * 32 + col] = x[j];
+    }
+}
+
+template <bool INV, bool GATE>
+__device__ __forceinline__ void slab_pass_dispatch(int R, float2 *slab, const float2 *roots, const float2 *gpos,
+                                                   int L, int n, int tid, int nthreads) {
+    switch (R) {
+        case 2: slab_pass<2, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 3: slab_pass<3, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 4: slab_pass<4, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 5: slab_pass<5, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 7: slab_pass<7, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 8: slab_pass<8, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 16: slab_pass<16, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
+        default: break;
+    }
+}
+
+struct SlabRadices {
+    int count;
+    int r[10];
+};
+
+// grid = B*H workgroups of 256 lanes.  LDS: slab [L][32] float2, roots [L], gpos [L].
+template <typename IO>
+__global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__restrict__ v,
+                                                  const float2 *__restrict__ g,
+                                                  typename IO::pair_t *__restrict__ out,
+                                                  const float2 *__restrict__ roots_g, int L, int H,
+                                                  SlabRadices rad) {
+    extern __shared__ float2 lds_slab[];
+    float2 *slab = lds_slab;
+    float2 *roots = slab + (size_t)L * 32;
+    float2 *gpos = roots + L;
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.x, b = bh / H, h = bh % H;
+    const int F = L / 2 + 1;
+
+    // roots of unity and the gate in position order: position p = sum_q u_q S_q holds bin
+    // k = sum_q u_q (R_1 ... R_{q-1}); full-length Hermitian extension, 1/L folded in.
+    for (int p = tid; p < L; p += 256) {
+        roots[p] = roots_g[p];
+        int rem = p, n = L, k = 0, w = 1;
+        for (int q = 0; q < rad.count; ++q) {
+            const int S = n / rad.r[q];
+            const int u = rem / S;
+            rem -= u * S;
+            k += u * w;
+            w *= rad.r[q];
+            n = S;
+        }
+        float2 val;
+        if (k == 0 || 2 * k == L) val = make_float2(g[(size_t)bh * F + k].x, 0.f);
+        else if (2 * k < L) val = g[(size_t)bh * F + k];
+        else val = cconj(g[(size_t)bh * F + (L - k)]);
+        const float sc = 1.0f / (float)L;
+        gpos[p] = make_float2(val.x * sc, val.y * sc);
+    }
+    {
+        const int lp = tid & 31;
+        const typename IO::pair_t *src = v + (((size_t)b * L) * H + h) * 32 + lp;
+        for (int l = tid >> 5; l < L; l += 8) slab[l * 32 + lp] = IO::unpack(src[(size_t)l * H * 32]);
+    }
+    __syncthreads();
+    int n = L;
+    for (int q = 0; q < rad.count; ++q) {
+        if (q == rad.count - 1) slab_pass_dispatch<false, true>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        else slab_pass_dispatch<false, false>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        n /= rad.r[q];
+        __syncthreads();
+    }
+    for (int q = rad.count - 1; q >= 0; --q) {
+        n *= rad.r[q];
+        slab_pass_dispatch<true, false>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        __syncthreads();
+    }
+    {
+        const int lp = tid & 31;
+        typename IO::pair_t *dst = out + (((size_t)b * L) * H + h) * 32 + lp;
+        for (int l = tid >> 5; l < L; l += 8) dst[(size_t)l * H * 32] = IO::pack(slab[l * 32 + lp]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+bool slab_supported(int L) {
+    if (L < 2 || L > kSlabMaxL) return false;
+    int n = L;
+    for (int p : {2, 3, 5, 7})
+        while (n % p == 0) n /= p;
+    return n == 1;
+}
+
+static SlabRadices slab_radices(int L) {
+    SlabRadices r;
+    r.count = 0;
+    int n = L;
+    for (int p : {7, 5, 3})
+        while (n % p == 0) { r.r[r.count++] = p; n /= p; }
+    while (n % 16 == 0) { r.r[r.count++] = 16; n /= 16; }
+    if (n % 8 == 0) { r.r[r.count++] = 8; n /= 8; }
+    if (n % 4 == 0) { r.r[r.count++] = 4; n /= 4; }
+    if (n % 2 == 0) { r.r[r.count++] = 2; n /= 2; }
+    return r;
+}
+
+hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, const float2 *roots, int B, int L,
+                           int H, hipStream_t st) {
+    const size_t lds = ((size_t)L * 32 + 2 * (size_t)L) * sizeof(float2);
+    const SlabRadices rad = slab_radices(L);
+    hipError_t e;
+    if (io) {
+        auto kern = k_mix_slab<IoBf16>;
+        if (lds > 48 * 1024) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        kern<<<dim3(B * H), dim3(256), lds, st>>>(static_cast<const uint32_t *>(v), g, static_cast<uint32_t *>(out),
+                                                  roots, L, H, rad);
+    } else {
+        auto kern = k_mix_slab<IoF32>;
+        if (lds > 48 * 1024) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        kern<<<dim3(B * H), dim3(256), lds, st>>>(static_cast<const float2 *>(v), g, static_cast<float2 *>(out), roots,
+                                                  L, H, rad);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace spectre

@@ -81,3 +81,34 @@ def test_run_to_run_bitwise_identical():
     b = binding.mix_forward(v, g).view(torch.int16)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,L,H", [(2, 196, 3), (1, 2, 1), (3, 4, 2), (2, 8, 2), (1, 49, 2), (2, 60, 1), (1, 105, 3),
+                                   (2, 128, 2), (1, 360, 2), (1, 500, 1), (1, 175, 2), (16, 256, 16), (8, 512, 32)])
+def test_short_and_mixed_radix_lengths(oracle, B, L, H, io):
+    """Whole-slab path: non-power-of-two lengths (4*7*7 = 196 of the ViT grid, odd lengths) and short ones."""
+    print(f"case B={B} L={L} H={H} io={io}", flush=True)
+    got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 7 * L + H)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL[io]
+
+
+def test_vit_config_full_size(oracle):
+    """Config 5 at its real size: B=256, L=196, H=12, fp32."""
+    c = synth.CONFIGS["vit_196"]
+    got, want, _ = run_case(oracle, c["B"], c["L"], c["H"], c["d"], c["io"], seed=synth.BASE_SEED + 5)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= 1e-5
+
+
+def test_unsupported_lengths_are_refused():
+    from paper_2502_18394_amd import binding
+    v = torch.zeros((1, 11, 1, 64), device="cuda")
+    g = torch.zeros((1, 1, 6), dtype=torch.complex64, device="cuda")
+    with pytest.raises(binding.SpectreError) as e:
+        binding.mix_forward(v, g)
+    assert e.value.code == binding.EUNSUPPORTED
+    assert not binding.length_supported(3 * 131072, 64) and binding.length_supported(196, 64)
