@@ -1,0 +1,100 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host before touching a device (no compute is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "spectre.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2502_18394_amd import build
+    path = os.path.join(ROOT, "paper_2502_18394_amd", "libspectre_hip.so")
+    if not os.path.exists(path):
+        build.build()
+    L = ctypes.CDLL(path)
+    L.spectre_last_error.restype = ctypes.c_char_p
+    for n in ("spectre_mix_workspace_bytes", "spectre_prefix_bytes", "spectre_gate_workspace_bytes"):
+        getattr(L, n).restype = ctypes.c_size_t
+    return L
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spectre_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_named_entry_points():
+    names = declared_functions()
+    for n in ("spectre_mix_forward", "spectre_gate", "spectre_prefix_update", "spectre_prefix_readout"):
+        assert n in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in spectre.h but not exported"
+
+
+def test_version_and_supported_lengths(lib):
+    assert lib.spectre_version() >= 100
+    for n in (2, 4, 128, 196, 256, 512, 1024, 4096, 8192, 32768, 131072, 49, 360):
+        assert lib.spectre_length_supported(n, 64) == 1, n
+    for n in (1, 0, -4, 11, 26, 1022, 3 * 4096, 262144, 1031):
+        assert lib.spectre_length_supported(n, 64) == 0, n
+    assert lib.spectre_length_supported(1024, 48) == 0
+
+
+def test_workspace_queries(lib):
+    assert lib.spectre_mix_workspace_bytes(1, 131072, 32, 64, 1) > 32 * 131072 * 8
+    assert lib.spectre_mix_workspace_bytes(256, 196, 12, 64, 0) == 256          # slab path needs no scratch
+    assert lib.spectre_mix_workspace_bytes(1, 11, 1, 64, 0) == 0                # unsupported
+    F = 32768 // 2 + 1
+    assert lib.spectre_prefix_bytes(8, 32, 64, 32768, 0) == 8 * 32 * F * 64 * 8
+    assert lib.spectre_prefix_bytes(8, 32, 64, 32768, 1) == 8 * 32 * 32768 * 64 * 4
+    assert lib.spectre_prefix_bytes(8, 32, 64, 32768, 3) == 8 * 32 * 64 * 8
+    assert lib.spectre_prefix_bytes(8, 32, 64, 32768, 4) == 32768 * 8
+    assert lib.spectre_prefix_bytes(8, 32, 64, 1000, 0) == 0
+    assert lib.spectre_prefix_bytes(8, 32, 64, 32768, 9) == 0
+
+
+def test_bad_arguments_fail_on_the_host(lib):
+    fake = ctypes.c_void_p(4096)      # never dereferenced: every call below fails validation first
+    rc = lib.spectre_mix_forward(None, fake, fake, 1, 1024, 1, 64, 0, fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == 1 and b"null" in lib.spectre_last_error()
+    rc = lib.spectre_mix_forward(fake, fake, ctypes.c_void_p(1 << 40), 1, 0, 1, 64, 0, fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == 1
+    rc = lib.spectre_mix_forward(fake, fake, fake, 1, 1024, 1, 64, 0, fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == 1 and b"overlap" in lib.spectre_last_error()
+    far = ctypes.c_void_p(1 << 40)
+    rc = lib.spectre_mix_forward(fake, fake, far, 1, 1000, 1, 64, 0, fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == 2                                                                # unsupported length
+    rc = lib.spectre_mix_forward(fake, fake, far, 1, 1024, 1, 32, 0, fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == 2                                                                # unsupported d
+    rc = lib.spectre_mix_forward(fake, fake, far, 1, 1024, 1, 64, 7, fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == 1                                                                # bad dtype
+    rc = lib.spectre_mix_forward(fake, fake, far, 1, 1024, 1, 64, 0, fake, ctypes.c_size_t(16), None)
+    assert rc == 3 and b"workspace" in lib.spectre_last_error()
+    rc = lib.spectre_mix_forward(fake, fake, far, 1, 1024, 1, 64, 0, ctypes.c_void_p(4097), ctypes.c_size_t(1 << 30), None)
+    assert rc == 1 and b"aligned" in lib.spectre_last_error()
+    rc = lib.spectre_gate(fake, 0, 0, ctypes.c_double(1.0), None, 1, 8, 1, ctypes.c_longlong(0), fake, fake,
+                          ctypes.c_size_t(1 << 20), None)
+    assert rc == 1
+    rc = lib.spectre_prefix_init(None, None)
+    assert rc == 1
+    rc = lib.spectre_prefix_readout(None, fake, 0, fake, 0, fake, ctypes.c_size_t(1 << 20), None)
+    assert rc == 1
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    from paper_2502_18394_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError):
+        binding.lib()

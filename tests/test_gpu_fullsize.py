@@ -1,0 +1,112 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The GPU runs the whole workload; the oracle evaluates sampled heads (every channel of a head
+is an independent column, so a head can be checked on its own)."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import TOL, f64, from_device, rel_l2, to_device
+from paper_2502_18394_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("L", list(synth.SWEEP_L))
+def test_length_sweep_llama_shape_bf16(oracle, L):
+    """Configs 2/3: B=1, H=32, d=64, bf16 I/O, every L of the sweep (8192 is config 2, 131072 the headline)."""
+    from paper_2502_18394_amd import binding
+    B, H, d = 1, 32, 64
+    print(f"case L={L}", flush=True)
+    vals, store = synth.tokens(synth.BASE_SEED + L, (B, L, H, d), "bf16")
+    g = synth.random_gate(synth.BASE_SEED + L + 1, B, H, L)
+    out = binding.mix_forward(to_device(store, "bf16"), torch.from_numpy(g).cuda())
+    torch.cuda.synchronize()
+    heads = list(range(H)) if L <= 8192 else [0, 13, 31]
+    got = from_device(out[:, :, heads, :].contiguous())
+    want = oracle.mix_forward(vals[:, :, heads, :].astype(np.float64), g[:, heads].astype(np.complex128))
+    err = rel_l2(got, want)
+    worst = max(rel_l2(got[:, :, i], want[:, :, i]) for i in range(len(heads)))
+    print(f"  rel_l2={err:.3e} worst head {worst:.3e} over {len(heads)} heads", flush=True)
+    assert err <= TOL["bf16"] and worst <= TOL["bf16"]
+    tol = np.abs(want) * 2.0 ** -7 + 1e-5 * np.sqrt(np.mean(want ** 2))
+    assert np.all(np.abs(got - want) <= tol)
+
+
+def test_headline_shape_fp32_io(oracle):
+    """Same shape with fp32 I/O so that the 1e-5 bar is exercised at L = 131072."""
+    from paper_2502_18394_amd import binding
+    B, H, d, L = 1, 8, 64, 131072
+    vals, store = synth.tokens(synth.BASE_SEED + 9, (B, L, H, d), "f32")
+    g = synth.random_gate(synth.BASE_SEED + 10, B, H, L)
+    out = binding.mix_forward(to_device(store, "f32"), torch.from_numpy(g).cuda())
+    torch.cuda.synchronize()
+    heads = [0, 5]
+    got = from_device(out[:, :, heads, :].contiguous())
+    want = oracle.mix_forward(vals[:, :, heads, :].astype(np.float64), g[:, heads].astype(np.complex128))
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL["f32"]
+
+
+def test_gate_plus_mixer_end_to_end_128k(oracle):
+    """The benchmark's step: gate from the query rows (per-head weights, F = 65537), then the mixer."""
+    from paper_2502_18394_amd import binding
+    B, H, d, L = 1, 32, 64, 131072
+    vals, vstore = synth.tokens(synth.BASE_SEED + 20, (B, L, H, d), "bf16")
+    qv, qstore = synth.tokens(synth.BASE_SEED + 21, (B, L, H, d), "bf16")
+    p = synth.gate_params(synth.BASE_SEED + 22, H, d, L)
+    P = binding.GateParams(p)
+    g = binding.gate(to_device(qstore, "bf16"), P, 1.0 / L)
+    out = binding.mix_forward(to_device(vstore, "bf16"), g)
+    torch.cuda.synchronize()
+    heads = [3, 30]
+    sub = {k: (np.asarray(v[heads], np.float64) if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    sub["Hg"] = len(heads)
+    og = oracle.gate(oracle.pool_q(qv[:, :, heads, :].astype(np.float64)), 1.0 / L, sub, L, 0)
+    e_gate = rel_l2(g[:, heads].cpu().numpy(), og)
+    want = oracle.mix_forward(vals[:, :, heads, :].astype(np.float64), og)
+    e_mix = rel_l2(from_device(out[:, :, heads, :].contiguous()), want)
+    print(f"  gate {e_gate:.3e}  mixer {e_mix:.3e}", flush=True)
+    assert e_gate <= 1e-5 and e_mix <= TOL["bf16"]
+
+
+def test_decode_config_sampled_heads(oracle):
+    """Config 4: B=8, H=32, d=64, N_max=32768 pre-filled to the brim, then fused decode steps (all take the
+    eviction branch of Eq. 5).  State and outputs of sampled (b,h) are compared at steps 0, 1, 128, 255."""
+    from paper_2502_18394_amd import binding
+    c = synth.CONFIGS["decode_32k"]
+    B, H, d, N, steps = c["B"], c["H"], c["d"], c["N_max"], c["steps"]
+    sample = [(0, 0), (5, 17), (7, 31)]
+    rng = np.random.default_rng(synth.BASE_SEED + 30)
+    cache = binding.PrefixCache(B, H, d, N)
+    p = synth.gate_params(synth.BASE_SEED + 31, H, d, N)
+    P = binding.GateParams(p)
+    V = rng.standard_normal((B, N, H, d), dtype=np.float32)
+    Q = rng.standard_normal((B, N, H, d), dtype=np.float32)
+    cache.update(torch.from_numpy(V).cuda(), torch.from_numpy(Q).cuda())
+    ocs = []
+    for (b, h) in sample:
+        oc = oracle.PrefixCache(1, 1, d, N)
+        oc.prefill(V[b:b + 1, :, h:h + 1].astype(np.float64), Q[b:b + 1, :, h:h + 1].astype(np.float64))
+        ocs.append(oc)
+    del V, Q
+    vt = rng.standard_normal((steps, B, 1, H, d), dtype=np.float32)
+    qt = rng.standard_normal((steps, B, 1, H, d), dtype=np.float32)
+    vt_d, qt_d = torch.from_numpy(vt).cuda(), torch.from_numpy(qt).cuda()
+    check = {0, 1, 128, steps - 1}
+    for i in range(steps):
+        out = cache.step(vt_d[i], qt_d[i], P)
+        for (b, h), oc in zip(sample, ocs):
+            oc.update(vt[i, b:b + 1, :, h:h + 1].astype(np.float64), qt[i, b:b + 1, :, h:h + 1].astype(np.float64))
+        if i in check:
+            torch.cuda.synchronize()
+            for (b, h), oc in zip(sample, ocs):
+                sub = {k: (np.asarray(v[h:h + 1], np.float64) if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+                want = oc.readout_newest(oracle.gate(oc.sum_q, 1.0 / N, sub, N, 0))
+                e_out = rel_l2(out[b, 0, h].cpu().numpy(), want[0, 0, 0])
+                e_spec = rel_l2(cache.prefix_fft[b, h].cpu().numpy(), oc.spec[0, 0])
+                e_sum = rel_l2(cache.sum_q[b, h].cpu().numpy(), oc.sum_q[0, 0])
+                print(f"  step {i} (b,h)=({b},{h}): out {e_out:.3e} spec {e_spec:.3e} sum_q {e_sum:.3e}", flush=True)
+                assert e_out <= 1e-5 and e_spec <= 1e-5 and e_sum <= 1e-12
+    assert cache.t == N + steps
