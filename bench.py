@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=32)
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run a plain 1 GiB device copy 5 times (reference for scaling hardware byte counters)")
     return ap.parse_args()
 
 
@@ -168,6 +170,15 @@ def main():
     }
     del V, Q, out, g, ws_mix, ws_gate, P
     torch.cuda.empty_cache()
+
+    if args.copy_calib:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     if not args.no_decode:
         dc = synth.CONFIGS["decode_32k"]

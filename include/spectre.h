@@ -30,10 +30,12 @@
  *     has been enqueued (argument errors are detected on the host before any
  *     launch) and spectre_last_error() describes the reason.  The library never
  *     aborts or throws.
- *   - Supported shapes: d even, 2 <= d <= 256 and d a multiple of 2; transform
- *     lengths n that are a power of two with 2 <= n <= 131072, and n = 4^a 7^b
- *     style lengths listed by spectre_length_supported().  Anything else returns
- *     SPECTRE_EUNSUPPORTED.
+ *   - Supported shapes.  Mixer and cache: d = 64 channels per head.  Transform
+ *     lengths: every n <= 512 whose prime factors are 2, 3, 5 or 7 (196 = 4*7*7
+ *     among them) and every power of two from 256 to 131072 for the mixer; a power
+ *     of two from 256 to 131072 for the cache window N_max.  The gate takes any
+ *     d <= 256, d_g <= 256 and any n_fft >= 2.  spectre_length_supported() answers
+ *     for the mixer; anything else returns SPECTRE_EUNSUPPORTED.
  */
 #ifndef SPECTRE_H
 #define SPECTRE_H
@@ -70,7 +72,9 @@ void spectre_shutdown(void);
  * Gate parameters (Sec. 3.2 step 3a and 3c; the same network serves Algorithm 1's decode gate).
  * All arrays are device fp32.  Hg = H gives every head its own network, Hg = 1 shares one across
  * heads (the two parameter budgets of Sec. 3.6).  The MLP's second layer emits 2F reals that are
- * read as F interleaved (re, im) pairs, so its width is tied to the transform length n_fft.
+ * read as F interleaved (re, im) pairs, so its width is tied to the transform length n_fft.  W1 is
+ * stored input-major (hid = qbar W1), W2 output-major (row n holds the d_g weights of output real
+ * n, the layout torch.nn.Linear keeps), so that the weights of one bin are contiguous.
  */
 typedef struct {
     int Hg;                    /* H (per-head weights) or 1 (shared)                          */
@@ -82,7 +86,7 @@ typedef struct {
     float ln_eps;              /* added to the biased variance over the d channels            */
     const float *W1;           /* [Hg, d, d_g]                                                */
     const float *b1;           /* [Hg, d_g]                                                   */
-    const float *W2;           /* [Hg, d_g, 2F]                                               */
+    const float *W2;           /* [Hg, 2F, d_g]   u[n] = sum_j hid[j] W2[n][j] + b2[n]        */
     const float *b2;           /* [Hg, 2F]                                                    */
     const float *modrelu_bias; /* [Hg, F] real bias of modReLU, or NULL to skip the activation */
 } spectre_gate_params;
@@ -96,7 +100,7 @@ size_t spectre_gate_workspace_bytes(int B, int L, int H, const spectre_gate_para
  *   x      = inv_count * sum over positions of the query rows          (global descriptor)
  *   qbar   = ln_gamma * (x - mean(x)) / sqrt(var(x) + ln_eps) + ln_beta
  *   hid    = GELU(qbar W1 + b1)                 (exact erf form)
- *   u      = hid W2 + b2,   g_k = u[2k] + j u[2k+1],  k = 0..F-1
+ *   u      = W2 hid + b2,   g_k = u[2k] + j u[2k+1],  k = 0..F-1
  *   g_k   <- max(|g_k| + bias_k, 0) * g_k / |g_k|      (0 where |g_k| = 0; skipped if bias NULL)
  *   g_k   <- g_k * exp(+j 2 pi ((k * phase_pos) mod n_fft) / n_fft)    (skipped if phase_pos = 0)
  *

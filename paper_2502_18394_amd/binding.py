@@ -117,17 +117,24 @@ def mix_forward(v, g, out=None, ws=None, stream=None):
 
 
 class GateParams:
-    """Device copies of the gate parameters plus the C parameter block."""
+    """Device copies of the gate parameters plus the C parameter block.
+
+    ``params`` uses the paper's row-vector convention (hid = qbar W1, u = hid W2) with
+    W1 [Hg,d,d_g] and W2 [Hg,d_g,2F]; the library wants W2 output-major, [Hg,2F,d_g], so it is
+    transposed once here while it is copied to the device."""
 
     def __init__(self, params, device="cuda"):
         def dev(a):
-            return None if a is None else torch.as_tensor(a, dtype=torch.float32).contiguous().to(device)
-        self.t = {k: dev(params[k]) for k in ("ln_gamma", "ln_beta", "W1", "b1", "W2", "b2")}
+            return None if a is None else torch.as_tensor(a, dtype=torch.float32).to(device).contiguous()
+        self.t = {k: dev(params[k]) for k in ("ln_gamma", "ln_beta", "W1", "b1", "b2")}
         self.t["modrelu_bias"] = dev(params.get("modrelu_bias"))
         Hg, d, d_g = self.t["W1"].shape
         self.n_fft = int(params["n_fft"])
         F = self.n_fft // 2 + 1
-        assert tuple(self.t["W2"].shape) == (Hg, d_g, 2 * F)
+        w2 = torch.as_tensor(params["W2"], dtype=torch.float32).to(device)
+        assert tuple(w2.shape) == (Hg, d_g, 2 * F)
+        self.t["W2"] = w2.transpose(1, 2).contiguous()
+        del w2
         self.Hg, self.d, self.d_g, self.F = Hg, d, d_g, F
         p = lambda k: None if self.t[k] is None else ctypes.c_void_p(self.t[k].data_ptr())
         self.c = GateParamsC(Hg, d, d_g, self.n_fft, p("ln_gamma"), p("ln_beta"), float(params["ln_eps"]),

@@ -3,9 +3,9 @@
 //
 //   pool    : sum of the query rows over positions, accumulated in fp64 in a fixed order
 //   hidden  : x = inv_count * sum;  qbar = LayerNorm(x);  hid = GELU(qbar W1 + b1)
-//   out     : u = hid W2 + b2 on the matrix cores (fp32 MFMA, the 2F output reals on the
-//             32-row side of v_mfma_f32_32x32x2_f32, the (b,h) rows on the 32-column side),
-//             with bias, modReLU and the positional phase applied in the epilogue.
+//   out     : u = W2 hid + b2 on the matrix cores (fp32 MFMA, v_mfma_f32_4x4x1_16B_f32: 64
+//             output reals x 4 rows per instruction), with bias and modReLU in the epilogue
+//   phase   : the positional phase, a separate pass over g, only when a position is given
 #include "gate.h"
 
 #include "common.h"
@@ -45,17 +45,26 @@ __global__ __launch_bounds__(256) void k_pool_partial(const typename IO::pair_t 
     partial[((size_t)b * nchunks + chunk) * ppr + pi] = make_double2(sx, sy);
 }
 
-// pool, stage 2: sum_q[b][ch] = sum over chunks, in chunk order.  One lane per channel.
+// pool, stage 2: sum_q[b][ch] = sum over chunks.  grid (row/32, B); 256 lanes = 32 channels x 8
+// chunk groups; group r adds chunks r, r+8, ... in order, the 8 group sums are then added in order.
 __global__ __launch_bounds__(256) void k_pool_final(const double *__restrict__ partial,
-                                                    double *__restrict__ sum_q, int row, int nchunks,
-                                                    int total) {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int b = idx / row, ch = idx % row;
-    const double *src = partial + (size_t)b * nchunks * row + ch;
+                                                    double *__restrict__ sum_q, int row, int nchunks) {
+    __shared__ double red[8][32];
+    const int lane = threadIdx.x & 31, grp = threadIdx.x >> 5;
+    const int ch = blockIdx.x * 32 + lane, b = blockIdx.y;
     double s = 0.0;
-    for (int c = 0; c < nchunks; ++c) s += src[(size_t)c * row];
-    sum_q[idx] = s;
+    if (ch < row) {
+        const double *src = partial + (size_t)b * nchunks * row + ch;
+        for (int c = grp; c < nchunks; c += 8) s += src[(size_t)c * row];
+    }
+    red[grp][lane] = s;
+    __syncthreads();
+    if (grp == 0 && ch < row) {
+        double t = red[0][lane];
+#pragma unroll
+        for (int r = 1; r < 8; ++r) t += red[r][lane];
+        sum_q[(size_t)b * row + ch] = t;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -96,76 +105,156 @@ __global__ __launch_bounds__(256) void k_gate_hidden(const double *__restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// out: grid (ceil(2F/128), Hg == 1 ? 1 : H); 4 waves per workgroup, each wave owns 32
-// consecutive output reals n (16 complex bins) and walks over the rows in tiles of 32.
-// Row r means (b, h): r = b for per-head weights (h = blockIdx.y), r = b*H + h for shared.
+// out: u = W2 hid + b2 on the matrix cores, then modReLU.  W2 is stored [Hg][2F][d_g] (the d_g
+// weights of one output real are contiguous), so a tile of 64 consecutive output reals n is one
+// contiguous 64*d_g*4-byte block; every wave walks over tiles with a grid stride and streams them.
 //
-// v_mfma_f32_32x32x2_f32 operands (lane l): A[i = l%32][k = l/32], B[k = l/32][j = l%32];
-// accumulator register v holds D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32], so a lane owns, for
-// its row j, the four reals v%4 = 0..3 = two whole complex bins of every 8-real group.
+// v_mfma_f32_4x4x1_16B_f32 multiplies 16 independent 4x1 by 1x4 blocks: lane l belongs to block
+// l/4; it supplies A_b[i = l%4] and B_b[j = l%4] and receives D_b[i = v][j = l%4] in register v.
+// Block b holds output reals n = n0 + 4b + i (so lane l supplies the weight of n = n0 + l for the
+// current hidden index, and ends up with two whole complex bins), j is one of four rows (b, h) of
+// the product.  Up to 8 row groups (32 rows) are accumulated per pass over W2.
+// Row r means (b, h): r = b for per-head weights (head = blockIdx.y), r = b*H + h for shared.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+constexpr int kTileStride = 66;   // floats per staged row: 64 + 2, conflict-free for 8-byte row reads
+
+template <bool VEC>
+__device__ __forceinline__ float4 load4(const float *__restrict__ p, int j, int dg, bool ok) {
+    if (VEC) return ok ? *reinterpret_cast<const float4 *>(p + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 v;
+    v.x = (ok && j + 0 < dg) ? p[j + 0] : 0.f;
+    v.y = (ok && j + 1 < dg) ? p[j + 1] : 0.f;
+    v.z = (ok && j + 2 < dg) ? p[j + 2] : 0.f;
+    v.w = (ok && j + 3 < dg) ? p[j + 3] : 0.f;
+    return v;
+}
+
+// four hidden indices of one staged weight row against RG row groups of hidden activations
+template <int RG>
+__device__ __forceinline__ void gate_mfma4(floatx4 (&acc)[RG], const float *arow, const float *hrow, int dgs) {
+    const float2 a01 = *reinterpret_cast<const float2 *>(arow);
+    const float2 a23 = *reinterpret_cast<const float2 *>(arow + 2);
+#pragma unroll
+    for (int q = 0; q < RG; ++q) {
+        const float4 bv = *reinterpret_cast<const float4 *>(hrow + 4 * q * dgs);
+        acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(a01.x, bv.x, acc[q], 0, 0, 0);
+        acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(a01.y, bv.y, acc[q], 0, 0, 0);
+        acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(a23.x, bv.z, acc[q], 0, 0, 0);
+        acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(a23.y, bv.w, acc[q], 0, 0, 0);
+    }
+}
+
+template <bool VEC, int RG>   // VEC: d_g % 4 == 0 and 16-byte aligned rows; RG: row groups of 4
 __global__ __launch_bounds__(256) void k_gate_out(const float *__restrict__ hid, const float *__restrict__ W2,
                                                   const float *__restrict__ b2,
                                                   const float *__restrict__ mbias, float2 *__restrict__ g,
-                                                  int B, int H, int Hg, int dg, int F, int n_fft,
-                                                  long long phase) {
+                                                  int B, int H, int Hg, int dg, int F, int r_base) {
+    extern __shared__ float hs[];                    // [4*RG][dgs] hidden rows of this pass, zero padded
+    const int dgp = (dg + 3) & ~3, dgs = dgp + 4;    // row stride padded against bank conflicts
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int twoF = 2 * F;
-    const int n0 = (blockIdx.x * 4 + wave) * 32;
-    if (n0 >= twoF) return;
     const int hsel = blockIdx.y;                     // head of this block when weights are per head
     const int hp = (Hg == 1) ? 0 : hsel;
     const int M = (Hg == 1) ? B * H : B;
-    const int li = lane & 31, lk = lane >> 5;
-    const int n_a = n0 + li;                         // this lane's A row (output real index)
-    const float *w2 = W2 + (size_t)hp * dg * twoF;
-
-    for (int r0 = 0; r0 < M; r0 += 32) {
-        const int r = r0 + li;                       // this lane's B column (row of the product)
-        const int bh = (Hg == 1) ? r : r * H + hsel;
-        const float *hrow = hid + (size_t)bh * dg;
-        floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-        for (int j0 = 0; j0 < dg; j0 += 16) {
-            float a[8], bv[8];
+    for (int idx = threadIdx.x; idx < 4 * RG * dgs; idx += 256) {
+        const int rr = idx / dgs, j = idx % dgs, r = r_base + rr;
+        float v = 0.f;
+        if (r < M && j < dg) v = hid[(size_t)((Hg == 1) ? r : r * H + hsel) * dg + j];
+        hs[idx] = v;
+    }
+    __syncthreads();
+    const int jrow = lane & 3;
+    const int ntiles = (twoF + 63) / 64;
+    // per-wave staging tile [64 rows][kTileStride floats]: filled with fully coalesced 16-byte
+    // loads (a wave instruction covers 4 whole rows of 64 weights), read back one row per lane
+    float *tile_w = hs + 4 * RG * dgs + wave * (64 * kTileStride);
+    const float *w2h = W2 + (size_t)hp * twoF * dg;
+    for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
+        floatx4 acc[RG];
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const int j = j0 + 2 * s + lk;
-                a[s] = (j < dg && n_a < twoF) ? w2[(size_t)j * twoF + n_a] : 0.0f;
-                bv[s] = (j < dg && r < M) ? hrow[j] : 0.0f;
-            }
+        for (int q = 0; q < RG; ++q) acc[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int j0 = 0; j0 < dgp; j0 += 64) {
+            const int width = min(64, dgp - j0);          // hidden indices in this slab, multiple of 4
+            const int lpr = width / 4;                     // lanes per row
+            const int rows_per_instr = 64 / lpr;
+            const int lr = lane / lpr, lc = 4 * (lane % lpr);
+            if (VEC && lpr == 16) {
+                float4 a[16];
 #pragma unroll
-            for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], bv[s], acc, 0, 0, 0);
-        }
-        if (r < M) {
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int n = n0 + 8 * v4 + 4 * lk + 2 * half;   // even: real part index
-                    if (n >= twoF) continue;
-                    const int k = n >> 1;
-                    float re = acc[4 * v4 + 2 * half] + b2[(size_t)hp * twoF + n];
-                    float im = acc[4 * v4 + 2 * half + 1] + b2[(size_t)hp * twoF + n + 1];
-                    if (mbias) {
-                        const float mag = sqrtf(re * re + im * im);
-                        const float act = fmaxf(mag + mbias[(size_t)hp * F + k], 0.0f);
-                        const float sc = (mag > 0.0f) ? act / mag : 0.0f;
-                        re *= sc;
-                        im *= sc;
-                    }
-                    if (phase != 0) {
-                        const long long m = ((long long)k * phase) % n_fft;
-                        double s, c;
-                        sincospi(2.0 * (double)m / (double)n_fft, &s, &c);
-                        const float cf = (float)c, sf = (float)s;
-                        const float nr = re * cf - im * sf, ni = re * sf + im * cf;
-                        re = nr;
-                        im = ni;
-                    }
-                    g[(size_t)bh * F + k] = make_float2(re, im);
+                for (int s = 0; s < 16; ++s) {
+                    const int n = tile * 64 + 4 * s + lr;
+                    a[s] = (n < twoF) ? *reinterpret_cast<const float4 *>(w2h + (size_t)n * dg + j0 + lc)
+                                      : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
+#pragma unroll
+                for (int s = 0; s < 16; ++s) {
+                    float2 *dst = reinterpret_cast<float2 *>(tile_w + (4 * s + lr) * kTileStride + lc);
+                    dst[0] = make_float2(a[s].x, a[s].y);
+                    dst[1] = make_float2(a[s].z, a[s].w);
+                }
+            } else {
+                for (int r0 = 0; r0 < 64; r0 += rows_per_instr) {
+                    const int row = r0 + lr, n = tile * 64 + row;
+                    if (row < 64) {
+                        const float4 v = load4<VEC>(w2h + (size_t)(n < twoF ? n : 0) * dg, j0 + lc, dg, n < twoF);
+                        float *dst = tile_w + row * kTileStride + lc;
+                        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+                    }
+                }
+            }
+            // LDS operations of one wave complete in issue order, so the reads below see the writes
+            // above; the wave barrier only stops the compiler from moving code across this point
+            __builtin_amdgcn_wave_barrier();
+            const float *arow = tile_w + lane * kTileStride;
+            const float *hrow = hs + jrow * dgs + j0;
+            if (width == 64) {
+#pragma unroll
+                for (int jj = 0; jj < 64; jj += 4) gate_mfma4<RG>(acc, arow + jj, hrow + jj, dgs);
+            } else {
+                for (int jj = 0; jj < width; jj += 4) gate_mfma4<RG>(acc, arow + jj, hrow + jj, dgs);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        // epilogue: this lane holds reals n4 .. n4+3 (two bins) of row r for every row group
+        const int n4 = tile * 64 + (lane & ~3);
+#pragma unroll
+        for (int q = 0; q < RG; ++q) {
+            const int r = r_base + 4 * q + jrow;
+            if (r >= M) continue;
+            const int bh = (Hg == 1) ? r : r * H + hsel;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int nn = n4 + 2 * half;
+                if (nn >= twoF) continue;
+                const int k = nn >> 1;
+                float re = acc[q][2 * half] + b2[(size_t)hp * twoF + nn];
+                float im = acc[q][2 * half + 1] + b2[(size_t)hp * twoF + nn + 1];
+                if (mbias) {
+                    const float mag = sqrtf(re * re + im * im);
+                    const float act = fmaxf(mag + mbias[(size_t)hp * F + k], 0.0f);
+                    const float sc = (mag > 0.0f) ? act / mag : 0.0f;
+                    re *= sc;
+                    im *= sc;
+                }
+                g[(size_t)bh * F + k] = make_float2(re, im);
             }
         }
     }
+}
+
+// positional phase: g[bh][k] *= exp(+j 2 pi ((k p) mod n)/n), angle reduced in integers and
+// evaluated in fp64.  One lane per gate entry; only launched when p != 0.
+__global__ __launch_bounds__(256) void k_gate_phase(float2 *__restrict__ g, int F, int n_fft, long long phase,
+                                                    size_t total) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const long long k = (long long)(idx % F);
+    const long long m = (k * phase) % n_fft;
+    double s, c;
+    sincospi(2.0 * (double)m / (double)n_fft, &s, &c);
+    const float cf = (float)c, sf = (float)s;
+    const float2 v = g[idx];
+    g[idx] = make_float2(v.x * cf - v.y * sf, v.x * sf + v.y * cf);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -187,8 +276,7 @@ hipError_t launch_pool(int io, const void *q, double *partial, double *sum_q, in
                                                     reinterpret_cast<double2 *>(partial), L, ppr, kPoolRows, nchunks);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int total = B * H * d;
-    k_pool_final<<<(total + 255) / 256, 256, 0, st>>>(partial, sum_q, H * d, nchunks, total);
+    k_pool_final<<<dim3((H * d + 31) / 32, B), 256, 0, st>>>(partial, sum_q, H * d, nchunks);
     return hipGetLastError();
 }
 
@@ -199,8 +287,34 @@ hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int F = P.n_fft / 2 + 1;
-    dim3 grid((2 * F + 127) / 128, P.Hg == 1 ? 1 : H);
-    k_gate_out<<<grid, 256, 0, st>>>(hid, P.W2, P.b2, P.modrelu_bias, g, B, H, P.Hg, P.d_g, F, P.n_fft, phase);
+    const int M = (P.Hg == 1) ? B * H : B;
+    const int ntiles = (2 * F + 63) / 64;
+    const int gy = P.Hg == 1 ? 1 : H;
+    int gx = (1024 + gy - 1) / gy;                 // about 4 workgroups per compute unit in total
+    if (gx > (ntiles + 3) / 4) gx = (ntiles + 3) / 4;
+    dim3 grid(gx, gy);
+    const bool vec = (P.d_g % 4 == 0) && (reinterpret_cast<uintptr_t>(P.W2) & 15) == 0;
+    const int dgp = (P.d_g + 3) & ~3;
+    for (int r_base = 0; r_base < M; r_base += 32) {
+        const int rows = (M - r_base < 32) ? M - r_base : 32;
+        const int rg = (rows + 3) / 4;            // 1..8 row groups in this pass
+        const size_t lds = ((size_t)4 * (rg <= 1 ? 1 : rg <= 2 ? 2 : rg <= 4 ? 4 : 8) * (dgp + 4) + 4 * 64 * 66) * sizeof(float);
+#define SPECTRE_GATE_OUT(V, R) k_gate_out<V, R><<<grid, 256, lds, st>>>(hid, P.W2, P.b2, P.modrelu_bias, g, B, H, P.Hg, P.d_g, F, r_base)
+        if (vec) {
+            if (rg <= 1) SPECTRE_GATE_OUT(true, 1); else if (rg <= 2) SPECTRE_GATE_OUT(true, 2);
+            else if (rg <= 4) SPECTRE_GATE_OUT(true, 4); else SPECTRE_GATE_OUT(true, 8);
+        } else {
+            if (rg <= 1) SPECTRE_GATE_OUT(false, 1); else if (rg <= 2) SPECTRE_GATE_OUT(false, 2);
+            else if (rg <= 4) SPECTRE_GATE_OUT(false, 4); else SPECTRE_GATE_OUT(false, 8);
+        }
+#undef SPECTRE_GATE_OUT
+        hipError_t e2 = hipGetLastError();
+        if (e2 != hipSuccess) return e2;
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess || phase == 0) return e;
+    const size_t total = (size_t)B * H * F;
+    k_gate_phase<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(g, F, P.n_fft, phase, total);
     return hipGetLastError();
 }
 

@@ -113,22 +113,31 @@ __global__ __launch_bounds__(256) void k_sweep(float4 *__restrict__ X, const flo
     }
 }
 
-// out[b, 0, h, c] = sum over chunks of partial, in chunk order.
+// out[b, 0, h, c] = sum over chunks of partial.  One workgroup per head: 256 lanes = 32 channel
+// pairs x 8 chunk groups; group r adds chunks r, r+8, ... in order, then the 8 sums in order.
 template <typename IO>
 __global__ __launch_bounds__(256) void k_readout_final(const float *__restrict__ partial,
-                                                       typename IO::pair_t *__restrict__ out, int nchunks,
-                                                       int total_pairs) {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total_pairs) return;
-    const int bh = idx / 32, p = idx % 32;
+                                                       typename IO::pair_t *__restrict__ out, int nchunks) {
+    __shared__ float2 red[8][32];
+    const int p = threadIdx.x & 31, grp = threadIdx.x >> 5, bh = blockIdx.x;
     const float2 *src = reinterpret_cast<const float2 *>(partial + (size_t)bh * nchunks * 64) + p;
     float2 s = make_float2(0.f, 0.f);
-    for (int c = 0; c < nchunks; ++c) {
+    for (int c = grp; c < nchunks; c += 8) {
         const float2 v = src[(size_t)c * 32];
         s.x += v.x;
         s.y += v.y;
     }
-    out[idx] = IO::pack(s);
+    red[grp][p] = s;
+    __syncthreads();
+    if (grp == 0) {
+        float2 t = red[0][p];
+#pragma unroll
+        for (int r = 1; r < 8; ++r) {
+            t.x += red[r][p].x;
+            t.y += red[r][p].y;
+        }
+        out[(size_t)bh * 32 + p] = IO::pack(t);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -265,10 +274,8 @@ hipError_t launch_sweep(bool update, bool read, float2 *X, const float *delta, c
 }
 
 hipError_t launch_readout_final(int io, const float *partial, void *out, int BH, int F, hipStream_t st) {
-    const int total = BH * 32;
-    const unsigned grid = (unsigned)((total + 255) / 256);
-    if (io) k_readout_final<IoBf16><<<grid, 256, 0, st>>>(partial, static_cast<uint32_t *>(out), sweep_chunks(F), total);
-    else k_readout_final<IoF32><<<grid, 256, 0, st>>>(partial, static_cast<float2 *>(out), sweep_chunks(F), total);
+    if (io) k_readout_final<IoBf16><<<BH, 256, 0, st>>>(partial, static_cast<uint32_t *>(out), sweep_chunks(F));
+    else k_readout_final<IoF32><<<BH, 256, 0, st>>>(partial, static_cast<float2 *>(out), sweep_chunks(F));
     return hipGetLastError();
 }
 
