@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=32)
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline line, print one JSON line per configuration (mixer only): the "
+                         "length sweep at the Llama head shape, config 1 and the ViT shape")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference for scaling hardware byte counters)")
     return ap.parse_args()
@@ -97,6 +100,43 @@ def cpu_baseline(cfg, L):
             "sample": f"gate+mix_forward of {Hs} of {cfg['B'] * H} heads at L={L} took {dt:.2f} s, scaled to all heads"}
 
 
+def sweep(args):
+    """Mixer-only timing of every configuration; working sets below the memory-side cache are
+    rotated over enough buffers (> 512 MB in total) that the figure is not a cache-resident one."""
+    import torch
+    from paper_2502_18394_amd import binding, synth
+    cases = [("single_head_1k", synth.CONFIGS["single_head_1k"])]
+    cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in synth.SWEEP_L]
+    cases += [("vit_196", synth.CONFIGS["vit_196"])]
+    for name, c in cases:
+        B, H, L, d = c["B"], c["H"], c["L"], c["d"]
+        dtype = torch.bfloat16 if c["io"] == "bf16" else torch.float32
+        esize = 2 if c["io"] == "bf16" else 4
+        nbytes = B * L * H * d * esize
+        nbuf = max(1, min(64, (512 << 20) // (2 * nbytes) + 1))
+        Vs = [device_tokens((B, L, H, d), synth.BASE_SEED + i, dtype) for i in range(nbuf)]
+        outs = [torch.empty_like(Vs[0]) for _ in range(nbuf)]
+        g = torch.from_numpy(synth.random_gate(synth.BASE_SEED, B, H, L)).cuda()
+        ws = torch.empty(binding.mix_workspace_bytes(B, L, H, d, binding._dtype_code(Vs[0])) + 256, dtype=torch.uint8, device="cuda")
+        it = [0]
+
+        def call():
+            i = it[0] % nbuf
+            binding.mix_forward(Vs[i], g, out=outs[i], ws=ws)
+            it[0] += 1
+        reps = max(args.steps, min(200, int(2e9 // max(nbytes, 1)) + 1))
+        ms = time_loop(call, reps, 3)
+        it[0] = 0
+        ms_hot = time_loop(lambda: binding.mix_forward(Vs[0], g, out=outs[0], ws=ws), reps, 3)
+        alg = 2 * nbytes + B * H * (L // 2 + 1) * 8
+        print(json.dumps({"workload": name, "B": B, "H": H, "L": L, "d": d, "io": c["io"], "ms": ms,
+                          "tokens_per_s": B * L / (ms * 1e-3), "algorithmic_bytes": alg,
+                          "hbm_frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "buffers_rotated": nbuf,
+                          "ms_cache_resident": ms_hot}), flush=True)
+        del Vs, outs, g, ws
+        torch.cuda.empty_cache()
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -105,6 +145,11 @@ def main():
         sys.exit(2)
     import torch
     from paper_2502_18394_amd import binding, synth
+    if args.sweep:
+        torch.cuda.set_device(0)
+        binding.lib()
+        sweep(args)
+        return
 
     cfg = dict(synth.CONFIGS[args.workload])
     if args.L:

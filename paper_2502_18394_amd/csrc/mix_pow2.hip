@@ -108,23 +108,38 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const float2 *__restrict_
 // base-16 digit-reversed order out), inverse passes undo them in reverse, so the gate is
 // applied in digit-reversed order (the expanded gate is stored that way) and no reordering
 // pass exists.  Pass q (0-based) has stride S = 16^(P-1-q): lane tau owns positions
-// (tau / S) * 16 S + tau % S + S * j, j = 0..15.
-__device__ __forceinline__ int lds_pad(int p) { return p + (p >> 4); }
-
+// (tau / S) * 16 S + tau % S + S * j, j = 0..15.  LDS positions are padded by one element per
+// 16 (p -> p + p/16); for S >= 16 that keeps a lane's 16 positions an arithmetic sequence.
+//
+// Only the exchange between passes 0 and 1 of a 4096-point column crosses waves; every other
+// exchange stays inside a group of 16 lanes that own the same 256-position block, and needs no
+// workgroup barrier because the LDS operations of one wave complete in issue order.  The forward
+// and the inverse cross-wave exchange use two different buffers, so one barrier each suffices.
 template <int P, int Q>
-__device__ __forceinline__ int pass_pos(int tau, int j) {
+__device__ __forceinline__ int pad_base(int tau) {
     constexpr int S = 1 << (4 * (P - 1 - Q));
-    return (tau / S) * (16 * S) + (tau % S) + S * j;
+    if (S == 1) return 17 * tau;
+    const int p = (tau / S) * (16 * S) + (tau % S);
+    return p + (p >> 4);
+}
+template <int P, int Q>
+__device__ constexpr int pad_stride() {
+    constexpr int S = 1 << (4 * (P - 1 - Q));
+    return S == 1 ? 1 : S + S / 16;
 }
 
-template <int P, int QFROM, int QTO>
-__device__ __forceinline__ void exchange(float2 (&x)[16], float2 *ldc, int tau) {
+// write at pass QFROM's positions, read at pass QTO's.  CROSS: other waves take part.
+template <int P, int QFROM, int QTO, bool CROSS>
+__device__ __forceinline__ void exchange(float2 (&x)[16], float2 *buf, int tau) {
+    float2 *w = buf + pad_base<P, QFROM>(tau);
+    const float2 *r = buf + pad_base<P, QTO>(tau);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) ldc[lds_pad(pass_pos<P, QFROM>(tau, j))] = x[j];
-    __syncthreads();
+    for (int j = 0; j < 16; ++j) w[j * pad_stride<P, QFROM>()] = x[j];
+    if (CROSS) __syncthreads();
+    else __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int j = 0; j < 16; ++j) x[j] = ldc[lds_pad(pass_pos<P, QTO>(tau, j))];
-    __syncthreads();
+    for (int j = 0; j < 16; ++j) x[j] = r[j * pad_stride<P, QTO>()];
+    if (!CROSS) __builtin_amdgcn_wave_barrier();
 }
 
 template <int P, int MODE>
@@ -132,6 +147,7 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
                                              const float2 *__restrict__ twN1, int N2, int ppw, int bh0) {
     static_assert(P == 2 || P == 3, "N1 is 256 or 4096");
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
+    constexpr bool kCross = (P == 3);                // does the pass 0 <-> 1 exchange span waves?
     extern __shared__ float2 lds_big[];
     const int tid = threadIdx.x, tau = tid % TPC, ci = tid / TPC;
     const int groups = 32 / ppw;
@@ -139,7 +155,8 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
     const int pg = blk % groups;
     blk /= groups;
     const int k2 = blk % N2, bhl = blk / N2;
-    float2 *ldc = lds_big + ci * COLW;
+    float2 *buf_f = lds_big + ci * COLW;             // forward exchanges
+    float2 *buf_i = kCross ? buf_f + CPI * COLW : buf_f;   // inverse cross-wave exchange
 
     float2 tw[P - 1][15];
 #pragma unroll
@@ -156,26 +173,32 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
         for (int j = 0; j < 16; ++j) G[j] = gsrc[j * TPC + tau];
     }
 
-    for (int c = ci; c < ppw; c += CPI) {
-        float2 *col = scr + (((size_t)bhl * N2 + k2) * 32 + pg * ppw + c) * N1;
-        float2 x[16];
-        if (MODE != 2) {
+    float2 *col = scr + (((size_t)bhl * N2 + k2) * 32 + pg * ppw + ci) * N1;
+    const int in_off = (MODE != 2) ? tau : 16 * tau, in_step = (MODE != 2) ? TPC : 1;
+    float2 nx[16];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) x[j] = col[tau + TPC * j];
+    for (int j = 0; j < 16; ++j) nx[j] = col[in_off + in_step * j];
+    for (int c = ci; c < ppw; c += CPI) {
+        float2 x[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) x[j] = nx[j];
+        if (c + CPI < ppw) {                          // next column's loads fly during this one's passes
+            const float2 *ncol = col + (size_t)CPI * N1;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) nx[j] = ncol[in_off + in_step * j];
+        }
+        if (MODE != 2) {
             dft<16, false>(x);
 #pragma unroll
             for (int u = 1; u < 16; ++u) x[u] = cmul(x[u], tw[0][u - 1]);
-            exchange<P, 0, 1>(x, ldc, tau);
+            exchange<P, 0, 1, kCross>(x, buf_f, tau);
             dft<16, false>(x);
             if constexpr (P == 3) {
 #pragma unroll
-                for (int u = 1; u < 16; ++u) x[u] = cmul(x[u], tw[P - 2][u - 1]);
-                exchange<P, P - 2, P - 1>(x, ldc, tau);
+                for (int u = 1; u < 16; ++u) x[u] = cmul(x[u], tw[1][u - 1]);
+                exchange<P, 1, 2, false>(x, buf_f, tau);
                 dft<16, false>(x);
             }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 16; ++j) x[j] = col[16 * tau + j];
         }
         if (MODE == 0) {
 #pragma unroll
@@ -184,21 +207,24 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
         if (MODE == 1) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) col[16 * tau + j] = x[j];
-            continue;
-        }
-        dft<16, true>(x);
-        if constexpr (P == 3) {
-            exchange<P, P - 1, P - 2>(x, ldc, tau);
-#pragma unroll
-            for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[P - 2][u - 1]);
+            if (kCross) __syncthreads();              // buf_f is rewritten by the next column
+        } else {
             dft<16, true>(x);
+            if constexpr (P == 3) {
+                exchange<P, 2, 1, false>(x, buf_f, tau);
+#pragma unroll
+                for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[1][u - 1]);
+                dft<16, true>(x);
+            }
+            exchange<P, 1, 0, kCross>(x, buf_i, tau);
+#pragma unroll
+            for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[0][u - 1]);
+            dft<16, true>(x);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) col[tau + TPC * j] = x[j];
+            if (MODE == 2 && kCross) __syncthreads(); // single cross exchange per column: guard buf_i
         }
-        exchange<P, 1, 0>(x, ldc, tau);
-#pragma unroll
-        for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[0][u - 1]);
-        dft<16, true>(x);
-#pragma unroll
-        for (int j = 0; j < 16; ++j) col[tau + TPC * j] = x[j];
+        col += (size_t)CPI * N1;
     }
 }
 
@@ -297,7 +323,7 @@ hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, v
 template <int P, int MODE>
 static hipError_t big_t(const Pow2Plan &pl, float2 *scr, const float2 *gp, int bh0, int nbh, hipStream_t st) {
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
-    const size_t lds = (size_t)CPI * COLW * sizeof(float2);
+    const size_t lds = (size_t)CPI * COLW * sizeof(float2) * (P == 3 ? 2 : 1);
     const int ppw = (P == 2) ? 16 : 4;   // pairs per workgroup; a multiple of CPI dividing 32
     auto kern = k_big<P, MODE>;
     hipError_t e = allow_lds(kern, lds);

@@ -153,6 +153,18 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
     const int bh = blockIdx.x, b = bh / H, h = bh % H;
     const int F = L / 2 + 1;
 
+    // rows l = (tid/32) + 8 i.  Eight loads are put in flight before any is consumed; the first
+    // batch flies while the gate table below is being built.
+    const int lp_in = tid & 31;
+    const typename IO::pair_t *src = v + (((size_t)b * L) * H + h) * 32 + lp_in;
+    const size_t rs = (size_t)H * 32;
+    typename IO::pair_t val[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int l = (tid >> 5) + 8 * i;
+        val[i] = (l < L) ? src[(size_t)l * rs] : IO::zero();
+    }
+
     // roots of unity and the gate in position order: position p = sum_q u_q S_q holds bin
     // k = sum_q u_q (R_1 ... R_{q-1}); full-length Hermitian extension, 1/L folded in.
     for (int p = tid; p < L; p += 256) {
@@ -173,10 +185,22 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
         const float sc = 1.0f / (float)L;
         gpos[p] = make_float2(val.x * sc, val.y * sc);
     }
-    {
-        const int lp = tid & 31;
-        const typename IO::pair_t *src = v + (((size_t)b * L) * H + h) * 32 + lp;
-        for (int l = tid >> 5; l < L; l += 8) slab[l * 32 + lp] = IO::unpack(src[(size_t)l * H * 32]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int l = (tid >> 5) + 8 * i;
+        if (l < L) slab[l * 32 + lp_in] = IO::unpack(val[i]);
+    }
+    for (int l0 = (tid >> 5) + 64; l0 < L; l0 += 64) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int l = l0 + 8 * i;
+            val[i] = (l < L) ? src[(size_t)l * rs] : IO::zero();
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int l = l0 + 8 * i;
+            if (l < L) slab[l * 32 + lp_in] = IO::unpack(val[i]);
+        }
     }
     __syncthreads();
     int n = L;
