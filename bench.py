@@ -20,6 +20,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+# L2<->fabric bytes per spectre_mix_forward call at llama1b_128k from the rocprofv3 FETCH_SIZE + WRITE_SIZE passes
+# summarised in profiles/bench_llama1b_128k_and_decode_32k.md (scaled by the plain-copy factors given there)
+MIX_TRAFFIC_BYTES_128K = 5.48 * 2 ** 30
+DECODE_SWEEP_TRAFFIC_BYTES = (2122.1 + 2056.2) * 2 ** 20
 # fp32 vector peak without packed math: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s
 VALU_PEAK_GINSTR = 256 * 4 * 16 * 2.4
 
@@ -34,6 +38,7 @@ def parse():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=32)
+    ap.add_argument("--no-membw", action="store_true", help="skip the streaming-bandwidth probe")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline line, print one JSON line per configuration (mixer only): the "
                          "length sweep at the Llama head shape, config 1 and the ViT shape")
@@ -98,6 +103,25 @@ def cpu_baseline(cfg, L):
     full = dt * (cfg["B"] * H / Hs)
     return {"value": cfg["B"] * L / full, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"gate+mix_forward of {Hs} of {cfg['B'] * H} heads at L={L} took {dt:.2f} s, scaled to all heads"}
+
+
+def membw_probe():
+    """Measured streaming bandwidth of this GPU (child process: paper_2502_18394_amd/membw_probe)."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2502_18394_amd", "membw_probe")
+    if not os.path.exists(exe):
+        return None
+    try:
+        out = subprocess.run([exe, "128", "4096"], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True,
+                             timeout=120).stdout
+    except Exception as e:   # the probe is informative only
+        return {"error": str(e)}
+    res = {"unit": "GB/s", "what": "grid-stride float4 kernels; read, write, in-place read+write, copy"}
+    for line in out.splitlines():
+        f = line.split()
+        if len(f) == 5 and f[0].isdigit():
+            res[f"{f[0]}MB"] = dict(zip(("read", "write", "rw", "copy"), (float(x) for x in f[1:])))
+    return res
 
 
 def sweep(args):
@@ -205,7 +229,8 @@ def main():
                    "global_batch": B, "seq_len": L, "parallelism": "single GPU"},
         "roofline": {"bound": "hbm", "kernel": "spectre_mix_forward (gate_expand + per head group: small_fwd, big, small_inv)",
                      "achieved": mix_bytes / (ms_mix * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": mix_bytes / (ms_mix * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "frac": mix_bytes / (ms_mix * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": MIX_TRAFFIC_BYTES_128K if (args.workload == "llama1b_128k" and not args.L) else None,
                      "algorithmic_bytes": mix_bytes, "ms": ms_mix},
         "roofline_alu": {"bound": "alu", "achieved": mix_flops_instr / (ms_mix * 1e-3) / 1e9, "peak": VALU_PEAK_GINSTR,
                          "unit": "G lane-instr/s", "frac": mix_flops_instr / (ms_mix * 1e-3) / 1e9 / VALU_PEAK_GINSTR},
@@ -242,10 +267,12 @@ def main():
                          "tokens_per_s": Bd / (ms_dec * 1e-3), "ms_per_step": ms_dec, "steps": args.decode_steps,
                          "roofline": {"bound": "hbm", "kernel": "k_sweep<update,read>", "achieved": sweep_bytes / (ms_dec * 1e-3) / 1e9,
                                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sweep_bytes / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                      "algorithmic_bytes": sweep_bytes}}
+                                      "traffic": DECODE_SWEEP_TRAFFIC_BYTES, "algorithmic_bytes": sweep_bytes}}
         del cache, Pd
         torch.cuda.empty_cache()
 
+    if not args.no_membw:
+        res["membw_probe"] = membw_probe()
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_baseline(cfg, L)
     print(json.dumps(res), flush=True)

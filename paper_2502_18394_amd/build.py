@@ -10,6 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspectre_hip.so")
+PROBE = os.path.join(HERE, "membw_probe")            # stand-alone bandwidth probe (not part of the library)
 SOURCES = ["api.hip", "mix_pow2.hip", "mix_slab.hip", "gate.hip", "prefix.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -27,6 +28,12 @@ def build(verbose=False, extra=()):
         raise RuntimeError("hipcc failed:\n" + res.stdout)
     if verbose and out:
         print(out)
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
+           os.path.join(CSRC, "membw_probe.hip"), "-o", PROBE]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed (membw_probe):\n" + res.stdout)
     return LIB
 
 
