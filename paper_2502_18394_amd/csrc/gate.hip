@@ -117,6 +117,7 @@ __global__ __launch_bounds__(256) void k_gate_hidden(const double *__restrict__ 
 // Row r means (b, h): r = b for per-head weights (head = blockIdx.y), r = b*H + h for shared.
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kTileStride = 66;   // floats per staged row: 64 + 2, conflict-free for 8-byte row reads
+constexpr int kHalfStride = 34;   // same for the 32-wide half rows of the d_g = 64 fast path
 
 template <bool VEC>
 __device__ __forceinline__ float4 load4(const float *__restrict__ p, int j, int dg, bool ok) {
@@ -144,6 +145,31 @@ __device__ __forceinline__ void gate_mfma4(floatx4 (&acc)[RG], const float *arow
     }
 }
 
+// 64 consecutive rows of W2 (d_g = 64) as sixteen 16-byte loads per lane: loads 0..7 cover hidden
+// indices 0..31 of rows 8s + lane/8, loads 8..15 indices 32..63 (a wave instruction reads 8 half rows
+// of 128 B)
+__device__ __forceinline__ void gate_load_tile(float4 (&a)[16], const float *__restrict__ w2h, int tile, int lr,
+                                               int lc, int twoF) {
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+        const int n = tile * 64 + 8 * (s & 7) + lr;
+        a[s] = (n < twoF) ? *reinterpret_cast<const float4 *>(w2h + (size_t)n * 64 + 32 * (s >> 3) + lc)
+                          : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+// modReLU (Sec. 3.2 step 3c) of one bin and its store
+__device__ __forceinline__ void gate_store_bin(float2 *dst, float re, float im, bool act_on, float mb) {
+    if (act_on) {
+        const float mag = sqrtf(re * re + im * im);
+        const float act = fmaxf(mag + mb, 0.0f);
+        const float sc = (mag > 0.0f) ? act / mag : 0.0f;
+        re *= sc;
+        im *= sc;
+    }
+    *dst = make_float2(re, im);
+}
+
 template <bool VEC, int RG>   // VEC: d_g % 4 == 0 and 16-byte aligned rows; RG: row groups of 4
 __global__ __launch_bounds__(256) void k_gate_out(const float *__restrict__ hid, const float *__restrict__ W2,
                                                   const float *__restrict__ b2,
@@ -167,8 +193,72 @@ __global__ __launch_bounds__(256) void k_gate_out(const float *__restrict__ hid,
     const int ntiles = (twoF + 63) / 64;
     // per-wave staging tile [64 rows][kTileStride floats]: filled with fully coalesced 16-byte
     // loads (a wave instruction covers 4 whole rows of 64 weights), read back one row per lane
-    float *tile_w = hs + 4 * RG * dgs + wave * (64 * kTileStride);
+    float *tile_w = hs + 4 * RG * dgs + wave * (64 * ((VEC && dg == 64) ? kHalfStride : kTileStride));
     const float *w2h = W2 + (size_t)hp * twoF * dg;
+    if (VEC && dg == 64) {
+        // fast path (one 64-wide slab per tile), software pipelined: the next tile's weights and this
+        // tile's bias terms are in flight while the matrix cores work on the staged tile
+        const int lr = lane >> 3, lc = 4 * (lane & 7);
+        const int tstep = gridDim.x * 4;
+        int tile = blockIdx.x * 4 + wave;
+        float4 a[16];
+        if (tile < ntiles) gate_load_tile(a, w2h, tile, lr, lc, twoF);
+        for (; tile < ntiles; tile += tstep) {
+            floatx4 acc[RG];
+#pragma unroll
+            for (int q = 0; q < RG; ++q) acc[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+            const float *arow = tile_w + lane * kHalfStride;
+            const float *hrow = hs + jrow * dgs;
+            // first half of the hidden indices through the staging tile
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                float2 *dst = reinterpret_cast<float2 *>(tile_w + (8 * s + lr) * kHalfStride + lc);
+                dst[0] = make_float2(a[s].x, a[s].y);
+                dst[1] = make_float2(a[s].z, a[s].w);
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int jj = 0; jj < 32; jj += 4) gate_mfma4<RG>(acc, arow + jj, hrow + jj, dgs);
+            __builtin_amdgcn_wave_barrier();
+            // second half; after its copy to LDS the registers are free for the next tile's loads
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                float2 *dst = reinterpret_cast<float2 *>(tile_w + (8 * s + lr) * kHalfStride + lc);
+                dst[0] = make_float2(a[8 + s].x, a[8 + s].y);
+                dst[1] = make_float2(a[8 + s].z, a[8 + s].w);
+            }
+            if (tile + tstep < ntiles) gate_load_tile(a, w2h, tile + tstep, lr, lc, twoF);
+            const int n4 = tile * 64 + (lane & ~3);
+            const bool e_ok = n4 < twoF;                      // twoF is even and n4 a multiple of 4
+            const bool e_ok2 = n4 + 2 < twoF;
+            float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            float2 mb2 = make_float2(0.f, 0.f);
+            if (e_ok) {
+                const float *bp = b2 + (size_t)hp * twoF + n4;
+                bias4.x = bp[0]; bias4.y = bp[1];
+                if (e_ok2) { bias4.z = bp[2]; bias4.w = bp[3]; }
+                if (mbias) {
+                    const float *mp = mbias + (size_t)hp * F + (n4 >> 1);
+                    mb2.x = mp[0];
+                    if (e_ok2) mb2.y = mp[1];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int jj = 0; jj < 32; jj += 4) gate_mfma4<RG>(acc, arow + jj, hrow + 32 + jj, dgs);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int q = 0; q < RG; ++q) {
+                const int r = r_base + 4 * q + jrow;
+                if (r >= M || !e_ok) continue;
+                const int bh = (Hg == 1) ? r : r * H + hsel;
+                gate_store_bin(g + (size_t)bh * F + (n4 >> 1), acc[q][0] + bias4.x, acc[q][1] + bias4.y, mbias != nullptr, mb2.x);
+                if (e_ok2)
+                    gate_store_bin(g + (size_t)bh * F + (n4 >> 1) + 1, acc[q][2] + bias4.z, acc[q][3] + bias4.w, mbias != nullptr, mb2.y);
+            }
+        }
+        return;
+    }
     for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
         floatx4 acc[RG];
 #pragma unroll
@@ -178,28 +268,12 @@ __global__ __launch_bounds__(256) void k_gate_out(const float *__restrict__ hid,
             const int lpr = width / 4;                     // lanes per row
             const int rows_per_instr = 64 / lpr;
             const int lr = lane / lpr, lc = 4 * (lane % lpr);
-            if (VEC && lpr == 16) {
-                float4 a[16];
-#pragma unroll
-                for (int s = 0; s < 16; ++s) {
-                    const int n = tile * 64 + 4 * s + lr;
-                    a[s] = (n < twoF) ? *reinterpret_cast<const float4 *>(w2h + (size_t)n * dg + j0 + lc)
-                                      : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-#pragma unroll
-                for (int s = 0; s < 16; ++s) {
-                    float2 *dst = reinterpret_cast<float2 *>(tile_w + (4 * s + lr) * kTileStride + lc);
-                    dst[0] = make_float2(a[s].x, a[s].y);
-                    dst[1] = make_float2(a[s].z, a[s].w);
-                }
-            } else {
-                for (int r0 = 0; r0 < 64; r0 += rows_per_instr) {
-                    const int row = r0 + lr, n = tile * 64 + row;
-                    if (row < 64) {
-                        const float4 v = load4<VEC>(w2h + (size_t)(n < twoF ? n : 0) * dg, j0 + lc, dg, n < twoF);
-                        float *dst = tile_w + row * kTileStride + lc;
-                        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
-                    }
+            for (int r0 = 0; r0 < 64; r0 += rows_per_instr) {
+                const int row = r0 + lr, n = tile * 64 + row;
+                if (row < 64) {
+                    const float4 v = load4<VEC>(w2h + (size_t)(n < twoF ? n : 0) * dg, j0 + lc, dg, n < twoF);
+                    float *dst = tile_w + row * kTileStride + lc;
+                    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
                 }
             }
             // LDS operations of one wave complete in issue order, so the reads below see the writes
@@ -207,12 +281,7 @@ __global__ __launch_bounds__(256) void k_gate_out(const float *__restrict__ hid,
             __builtin_amdgcn_wave_barrier();
             const float *arow = tile_w + lane * kTileStride;
             const float *hrow = hs + jrow * dgs + j0;
-            if (width == 64) {
-#pragma unroll
-                for (int jj = 0; jj < 64; jj += 4) gate_mfma4<RG>(acc, arow + jj, hrow + jj, dgs);
-            } else {
-                for (int jj = 0; jj < width; jj += 4) gate_mfma4<RG>(acc, arow + jj, hrow + jj, dgs);
-            }
+            for (int jj = 0; jj < width; jj += 4) gate_mfma4<RG>(acc, arow + jj, hrow + jj, dgs);
             __builtin_amdgcn_wave_barrier();
         }
         // epilogue: this lane holds reals n4 .. n4+3 (two bins) of row r for every row group
@@ -227,16 +296,9 @@ __global__ __launch_bounds__(256) void k_gate_out(const float *__restrict__ hid,
                 const int nn = n4 + 2 * half;
                 if (nn >= twoF) continue;
                 const int k = nn >> 1;
-                float re = acc[q][2 * half] + b2[(size_t)hp * twoF + nn];
-                float im = acc[q][2 * half + 1] + b2[(size_t)hp * twoF + nn + 1];
-                if (mbias) {
-                    const float mag = sqrtf(re * re + im * im);
-                    const float act = fmaxf(mag + mbias[(size_t)hp * F + k], 0.0f);
-                    const float sc = (mag > 0.0f) ? act / mag : 0.0f;
-                    re *= sc;
-                    im *= sc;
-                }
-                g[(size_t)bh * F + k] = make_float2(re, im);
+                gate_store_bin(g + (size_t)bh * F + k, acc[q][2 * half] + b2[(size_t)hp * twoF + nn],
+                               acc[q][2 * half + 1] + b2[(size_t)hp * twoF + nn + 1], mbias != nullptr,
+                               mbias ? mbias[(size_t)hp * F + k] : 0.0f);
             }
         }
     }
@@ -292,13 +354,18 @@ hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev 
     const int gy = P.Hg == 1 ? 1 : H;
     int gx = (1024 + gy - 1) / gy;                 // about 4 workgroups per compute unit in total
     if (gx > (ntiles + 3) / 4) gx = (ntiles + 3) / 4;
+    {   // shrink the grid to the smallest one with the same number of tiles per wave (no ragged last round)
+        const int iters = (ntiles + 4 * gx - 1) / (4 * gx);
+        gx = (ntiles + 4 * iters - 1) / (4 * iters);
+    }
     dim3 grid(gx, gy);
     const bool vec = (P.d_g % 4 == 0) && (reinterpret_cast<uintptr_t>(P.W2) & 15) == 0;
     const int dgp = (P.d_g + 3) & ~3;
     for (int r_base = 0; r_base < M; r_base += 32) {
         const int rows = (M - r_base < 32) ? M - r_base : 32;
         const int rg = (rows + 3) / 4;            // 1..8 row groups in this pass
-        const size_t lds = ((size_t)4 * (rg <= 1 ? 1 : rg <= 2 ? 2 : rg <= 4 ? 4 : 8) * (dgp + 4) + 4 * 64 * 66) * sizeof(float);
+        const size_t lds = ((size_t)4 * (rg <= 1 ? 1 : rg <= 2 ? 2 : rg <= 4 ? 4 : 8) * (dgp + 4) +
+                            4 * 64 * ((vec && P.d_g == 64) ? kHalfStride : kTileStride)) * sizeof(float);
 #define SPECTRE_GATE_OUT(V, R) k_gate_out<V, R><<<grid, 256, lds, st>>>(hid, P.W2, P.b2, P.modrelu_bias, g, B, H, P.Hg, P.d_g, F, r_base)
         if (vec) {
             if (rg <= 1) SPECTRE_GATE_OUT(true, 1); else if (rg <= 2) SPECTRE_GATE_OUT(true, 2);

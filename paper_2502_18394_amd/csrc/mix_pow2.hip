@@ -144,14 +144,22 @@ __device__ __forceinline__ void exchange(float2 (&x)[16], float2 *buf, int tau) 
 
 template <int P, int MODE>
 __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const float2 *__restrict__ gp,
-                                             const float2 *__restrict__ twN1, int N2, int ppw, int bh0) {
+                                             const float2 *__restrict__ twN1, int N2, int ppw, int bh0,
+                                             int nplanes_xcd) {
     static_assert(P == 2 || P == 3, "N1 is 256 or 4096");
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
     constexpr bool kCross = (P == 3);                // does the pass 0 <-> 1 exchange span waves?
     extern __shared__ float2 lds_big[];
     const int tid = threadIdx.x, tau = tid % TPC, ci = tid / TPC;
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  The 32/ppw workgroups
+    // that share one (head, k2) plane of the expanded gate are given ids 8 apart, so they run on
+    // the same XCD and the plane is fetched into one L2 instead of eight.
     const int groups = 32 / ppw;
     int blk = blockIdx.x;
+    if (nplanes_xcd > 0) {
+        const int xcd = blk & 7, idx = blk >> 3;
+        blk = ((idx / groups) * 8 + xcd) * groups + idx % groups;
+    }
     const int pg = blk % groups;
     blk /= groups;
     const int k2 = blk % N2, bhl = blk / N2;
@@ -329,7 +337,8 @@ static hipError_t big_t(const Pow2Plan &pl, float2 *scr, const float2 *gp, int b
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)nbh * pl.N2 * (32 / ppw);
-    kern<<<dim3(grid), dim3(256), lds, st>>>(scr, gp, pl.twN1, pl.N2, ppw, bh0);
+    const int planes = nbh * pl.N2;                    // remapping needs the plane count to split 8 ways
+    kern<<<dim3(grid), dim3(256), lds, st>>>(scr, gp, pl.twN1, pl.N2, ppw, bh0, planes % 8 == 0 ? planes : 0);
     return hipGetLastError();
 }
 
