@@ -89,6 +89,8 @@ typedef struct {
     const float *W2;           /* [Hg, 2F, d_g]   u[n] = sum_j hid[j] W2[n][j] + b2[n]        */
     const float *b2;           /* [Hg, 2F]                                                    */
     const float *modrelu_bias; /* [Hg, F] real bias of modReLU, or NULL to skip the activation */
+    const float *toeplitz;     /* complex64 [Hg, 2r+1] taps t_{-r..r} (tap m at index m+r) of the   */
+    int toeplitz_r;            /* optional low-rank update of step 3b, or NULL / 0 to skip it       */
 } spectre_gate_params;
 
 size_t spectre_gate_workspace_bytes(int B, int L, int H, const spectre_gate_params *P /*host*/);
@@ -101,6 +103,8 @@ size_t spectre_gate_workspace_bytes(int B, int L, int H, const spectre_gate_para
  *   qbar   = ln_gamma * (x - mean(x)) / sqrt(var(x) + ln_eps) + ln_beta
  *   hid    = GELU(qbar W1 + b1)                 (exact erf form)
  *   u      = W2 hid + b2,   g_k = u[2k] + j u[2k+1],  k = 0..F-1
+ *   g     <- g + (t * g),  (t * g)_k = sum_{m=-r..r} t_m g_{k-m} with g = 0 outside 0..F-1
+ *                                                      (Sec. 3.2 step 3b; skipped if toeplitz NULL)
  *   g_k   <- max(|g_k| + bias_k, 0) * g_k / |g_k|      (0 where |g_k| = 0; skipped if bias NULL)
  *   g_k   <- g_k * exp(+j 2 pi ((k * phase_pos) mod n_fft) / n_fft)    (skipped if phase_pos = 0)
  *

@@ -33,7 +33,9 @@
  *     real transform keeps their real parts only (equivalently: extend the gated
  *     half spectrum by Hermitian symmetry and take the real part);
  *   - positional phase multiplies bin k by exp(+j 2 pi k p / n) for one scalar
- *     position p per call.
+ *     position p per call;
+ *   - the optional Toeplitz update of step 3b is a zero-padded "same" convolution
+ *     along the frequency axis of the F stored bins.
  *
  * Complex arrays are interleaved (re, im) doubles.  Tensors are row-major with
  * the index order written in each comment.  No function here keeps state.
@@ -234,18 +236,21 @@ int so_irfft(int n, const double *Y, double *x, int method) {
  *   sum_q   [B,H,d]      sum of the query rows (caller pools, or cache state)
  *   x = inv_count * sum_q;  qbar = gamma*(x-mean)/sqrt(var+eps)+beta
  *   hid = GELU(qbar W1 + b1);  u = hid W2 + b2;  g_k = u[2k] + j u[2k+1]
+ *   g   <- g + (t * g): (t * g)_k = sum_{m=-r..r} t_m g_{k-m}, g taken as 0 outside 0..F-1
+ *          (step 3b, optional; taps == NULL: skipped)
  *   g_k <- max(|g_k| + bias_k, 0) g_k/|g_k|      (bias == NULL: left as is)
  *   g_k <- g_k exp(+j 2 pi ((k p) mod n)/n)      (p == 0: no phase)
  *
  * Parameters are per head when Hg == H and shared by all heads when Hg == 1:
  *   gamma, beta [Hg,d]; W1 [Hg,d,dg]; b1 [Hg,dg]; W2 [Hg,dg,2F]; b2 [Hg,2F];
- *   bias [Hg,F] or NULL.   F = n/2+1.   g_out [B,H,F] complex. */
+ *   bias [Hg,F] or NULL; taps [Hg,2r+1] complex (tap m at index m+r) or NULL.
+ *   F = n/2+1.   g_out [B,H,F] complex. */
 int so_gate(int B, int H, int d, int dg, int n, int Hg,
             const double *sum_q, double inv_count,
             const double *gamma, const double *beta, double eps,
             const double *W1, const double *b1,
             const double *W2, const double *b2,
-            const double *bias, long long p, double *g_out) {
+            const double *bias, const double *taps, int r, long long p, double *g_out) {
     if (!(Hg == H || Hg == 1) || n < 1 || d < 1 || dg < 1) return -1;
     int F = n / 2 + 1;
     cplx *g = (cplx *)g_out;
@@ -271,6 +276,7 @@ int so_gate(int B, int H, int d, int dg, int n, int Hg,
             for (int i = 0; i < d; ++i) a += qbar[i] * W1[((size_t)hp * d + i) * dg + j];
             hid[j] = 0.5 * a * (1.0 + erf(a / sqrt(2.0)));
         }
+        cplx *raw = g + ((size_t)b * H + h) * F;   /* MLP output, then updated in place */
         for (int k = 0; k < F; ++k) {
             cplx u;
             u.re = b2[(size_t)hp * 2 * F + 2 * k];
@@ -280,6 +286,28 @@ int so_gate(int B, int H, int d, int dg, int n, int Hg,
                 u.re += hid[j] * w[0];
                 u.im += hid[j] * w[1];
             }
+            raw[k] = u;
+        }
+        if (taps) {
+            const cplx *t = (const cplx *)taps + (size_t)hp * (2 * r + 1);
+            cplx *upd = (cplx *)malloc(sizeof(cplx) * (size_t)F);
+            if (!upd) { free(qbar); return -2; }
+            for (int k = 0; k < F; ++k) {
+                cplx acc = raw[k];
+                for (int m = -r; m <= r; ++m) {
+                    int src = k - m;
+                    if (src < 0 || src >= F) continue;
+                    cplx pr = c_mul(t[m + r], raw[src]);
+                    acc.re += pr.re;
+                    acc.im += pr.im;
+                }
+                upd[k] = acc;
+            }
+            memcpy(raw, upd, sizeof(cplx) * (size_t)F);
+            free(upd);
+        }
+        for (int k = 0; k < F; ++k) {
+            cplx u = raw[k];
             if (bias) {
                 double mag = sqrt(u.re * u.re + u.im * u.im);
                 if (mag == 0.0) { u.re = 0.0; u.im = 0.0; }
@@ -294,7 +322,7 @@ int so_gate(int B, int H, int d, int dg, int n, int Hg,
                 long long pm = p % n; if (pm < 0) pm += n;
                 u = c_mul(u, root_of_unity((long long)k * pm, n, +1));
             }
-            g[((size_t)b * H + h) * F + k] = u;
+            raw[k] = u;
         }
     }
     free(qbar);

@@ -105,7 +105,7 @@ def pool_q(Q):
 def gate(sum_q, inv_count, params, n, phase_pos=0):
     """Gate from a pooled query sum.  ``params`` is a dict with ln_gamma, ln_beta
     [Hg,d], ln_eps, W1 [Hg,d,dg], b1 [Hg,dg], W2 [Hg,dg,2F], b2 [Hg,2F],
-    modrelu_bias [Hg,F] or None."""
+    modrelu_bias [Hg,F] or None, toeplitz [Hg,2r+1] complex or None (tap m at index m+r)."""
     sum_q = _f64(sum_q)
     B, H, d = sum_q.shape
     W1 = _f64(params["W1"])
@@ -121,11 +121,17 @@ def gate(sum_q, inv_count, params, n, phase_pos=0):
     if bias is not None:
         bias = _f64(bias)
         assert bias.shape == (Hg, F)
+    taps = params.get("toeplitz")
+    r = 0
+    if taps is not None:
+        taps = _c128(taps)
+        assert taps.ndim == 2 and taps.shape[0] == Hg and taps.shape[1] % 2 == 1
+        r = taps.shape[1] // 2
     out = np.empty((B, H, F), dtype=np.complex128)
     rc = _L().so_gate(ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(dg),
                       ctypes.c_int(n), ctypes.c_int(Hg), _p(sum_q), ctypes.c_double(inv_count),
                       _p(gam), _p(bet), ctypes.c_double(float(params["ln_eps"])),
-                      _p(W1), _p(b1), _p(W2), _p(b2), _p(bias),
+                      _p(W1), _p(b1), _p(W2), _p(b2), _p(bias), _p(taps), ctypes.c_int(r),
                       ctypes.c_longlong(int(phase_pos)), _p(out))
     if rc:
         raise RuntimeError(f"so_gate rc={rc}")

@@ -30,7 +30,7 @@ class GateParamsC(ctypes.Structure):
     _fields_ = [("Hg", ctypes.c_int), ("d", ctypes.c_int), ("d_g", ctypes.c_int), ("n_fft", ctypes.c_int),
                 ("ln_gamma", ctypes.c_void_p), ("ln_beta", ctypes.c_void_p), ("ln_eps", ctypes.c_float),
                 ("W1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("W2", ctypes.c_void_p), ("b2", ctypes.c_void_p),
-                ("modrelu_bias", ctypes.c_void_p)]
+                ("modrelu_bias", ctypes.c_void_p), ("toeplitz", ctypes.c_void_p), ("toeplitz_r", ctypes.c_int)]
 
 
 class PrefixCacheC(ctypes.Structure):
@@ -136,9 +136,15 @@ class GateParams:
         self.t["W2"] = w2.transpose(1, 2).contiguous()
         del w2
         self.Hg, self.d, self.d_g, self.F = Hg, d, d_g, F
+        taps = params.get("toeplitz")
+        self.t["toeplitz"], r = None, 0
+        if taps is not None:
+            taps = torch.as_tensor(taps).to(torch.complex64).to(device).contiguous()
+            assert taps.ndim == 2 and taps.shape[0] == Hg and taps.shape[1] % 2 == 1
+            self.t["toeplitz"], r = taps, taps.shape[1] // 2
         p = lambda k: None if self.t[k] is None else ctypes.c_void_p(self.t[k].data_ptr())
         self.c = GateParamsC(Hg, d, d_g, self.n_fft, p("ln_gamma"), p("ln_beta"), float(params["ln_eps"]),
-                             p("W1"), p("b1"), p("W2"), p("b2"), p("modrelu_bias"))
+                             p("W1"), p("b1"), p("W2"), p("b2"), p("modrelu_bias"), p("toeplitz"), r)
 
 
 def gate_workspace_bytes(B, L, H, P):

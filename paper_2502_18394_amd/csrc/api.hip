@@ -204,6 +204,8 @@ static int check_gate_params(const spectre_gate_params *P, int H, const char *wh
     if (!P->ln_gamma || !P->ln_beta || !P->W1 || !P->b1 || !P->W2 || !P->b2)
         return fail(SPECTRE_EINVAL, "%s: null parameter array", who);
     if (!(P->ln_eps >= 0.0f)) return fail(SPECTRE_EINVAL, "%s: ln_eps must be >= 0", who);
+    if (P->toeplitz && (P->toeplitz_r < 0 || P->toeplitz_r > 64))
+        return fail(SPECTRE_EUNSUPPORTED, "%s: toeplitz_r=%d not in 0..64", who, P->toeplitz_r);
     return SPECTRE_OK;
 }
 
@@ -212,13 +214,20 @@ static GateDev gate_dev(const spectre_gate_params *P) {
     g.Hg = P->Hg; g.d = P->d; g.d_g = P->d_g; g.n_fft = P->n_fft;
     g.ln_gamma = P->ln_gamma; g.ln_beta = P->ln_beta; g.ln_eps = P->ln_eps;
     g.W1 = P->W1; g.b1 = P->b1; g.W2 = P->W2; g.b2 = P->b2; g.modrelu_bias = P->modrelu_bias;
+    g.toeplitz = reinterpret_cast<const float2 *>(P->toeplitz);
+    g.toeplitz_r = P->toeplitz ? P->toeplitz_r : 0;
     return g;
+}
+
+// scratch for the un-activated MLP output, needed only with the Toeplitz update
+static size_t gate_raw_bytes(int B, int H, const spectre_gate_params *P) {
+    return P->toeplitz ? align256((size_t)B * H * (P->n_fft / 2 + 1) * sizeof(float2)) : 0;
 }
 
 size_t spectre_gate_workspace_bytes(int B, int L, int H, const spectre_gate_params *P) {
     if (!P || B < 1 || L < 1 || H < 1 || P->d < 2 || P->d_g < 1) return 0;
     return align256(gate_partial_bytes(B, L, H, P->d)) + align256((size_t)B * H * P->d * sizeof(double)) +
-           align256((size_t)B * H * P->d_g * sizeof(float));
+           align256((size_t)B * H * P->d_g * sizeof(float)) + gate_raw_bytes(B, H, P);
 }
 
 int spectre_gate(const void *q, int q_is_pooled, spectre_dtype q_dtype, double inv_count,
@@ -243,13 +252,15 @@ int spectre_gate(const void *q, int q_is_pooled, spectre_dtype q_dtype, double i
     double *sum_ws = reinterpret_cast<double *>(w);
     w += align256((size_t)B * H * P->d * sizeof(double));
     float *hid = reinterpret_cast<float *>(w);
+    w += align256((size_t)B * H * P->d_g * sizeof(float));
+    float2 *raw = reinterpret_cast<float2 *>(w);
     const double *sum_q = static_cast<const double *>(q);
     if (!q_is_pooled) {
         hipError_t e = launch_pool((int)q_dtype, q, partial, sum_ws, B, L, H, P->d, st);
         if (e != hipSuccess) return fail_hip(e, "pool");
         sum_q = sum_ws;
     }
-    hipError_t e = launch_gate_mlp(sum_q, inv_count, gate_dev(P), hid, B, H, phase_pos % P->n_fft,
+    hipError_t e = launch_gate_mlp(sum_q, inv_count, gate_dev(P), hid, raw, B, H, phase_pos % P->n_fft,
                                    static_cast<float2 *>(g_out), st);
     if (e != hipSuccess) return fail_hip(e, "gate_mlp");
     return SPECTRE_OK;
@@ -426,7 +437,8 @@ size_t spectre_prefix_step_workspace_bytes(const spectre_prefix_cache *c, const 
     if (!c || !P || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 2 || P->d_g < 1) return 0;
     const int BH = c->B * c->H, F = c->N_max / 2 + 1;
     return align256((size_t)BH * c->d * sizeof(float)) + align256((size_t)BH * P->d_g * sizeof(float)) +
-           align256((size_t)BH * F * sizeof(float2)) + align256((size_t)BH * sweep_chunks(F) * c->d * sizeof(float));
+           align256((size_t)BH * F * sizeof(float2)) + align256((size_t)BH * sweep_chunks(F) * c->d * sizeof(float)) +
+           gate_raw_bytes(c->B, c->H, P);
 }
 
 int spectre_prefix_step(spectre_prefix_cache *c, const void *v_t, const void *q_t, const spectre_gate_params *P,
@@ -451,11 +463,13 @@ int spectre_prefix_step(spectre_prefix_cache *c, const void *v_t, const void *q_
     float2 *g = reinterpret_cast<float2 *>(w);
     w += align256((size_t)BH * F * sizeof(float2));
     float *partial = reinterpret_cast<float *>(w);
+    w += align256((size_t)BH * sweep_chunks(F) * d * sizeof(float));
+    float2 *raw = reinterpret_cast<float2 *>(w);
     const int slot = (int)(c->t % N), evict = c->t >= N ? 1 : 0;
     hipError_t e = launch_ring_update((int)io, v_t, q_t, 1, 0, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf),
                                       static_cast<double *>(c->sum_q), delta, B, H, d, N, slot, evict, st);
     if (e != hipSuccess) return fail_hip(e, "ring_update");
-    e = launch_gate_mlp(static_cast<const double *>(c->sum_q), 1.0 / (double)N, gate_dev(P), hid, B, H, 0, g, st);
+    e = launch_gate_mlp(static_cast<const double *>(c->sum_q), 1.0 / (double)N, gate_dev(P), hid, raw, B, H, 0, g, st);
     if (e != hipSuccess) return fail_hip(e, "gate_mlp");
     e = launch_sweep(true, true, static_cast<float2 *>(c->prefix_fft), delta, static_cast<const float2 *>(c->twiddle), g,
                      partial, BH, F, N, slot, st);

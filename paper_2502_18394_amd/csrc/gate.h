@@ -12,6 +12,8 @@ struct GateDev {                 // device pointers; layout as in the public par
     const float *ln_gamma, *ln_beta;
     float ln_eps;
     const float *W1, *b1, *W2, *b2, *modrelu_bias;
+    const float2 *toeplitz;      // [Hg, 2r+1] or nullptr
+    int toeplitz_r;
 };
 
 // Bytes of the pooling partial sums for query rows [B, L, H, d].
@@ -21,8 +23,9 @@ size_t gate_partial_bytes(int B, int L, int H, int d);
 hipError_t launch_pool(int io, const void *q, double *partial, double *sum_q, int B, int L, int H, int d,
                        hipStream_t st);
 
-// g [B,H,F] from sum_q; hid is scratch [B,H,d_g]; phase already reduced modulo n_fft.
-hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev &P, float *hid, int B, int H,
-                           long long phase, float2 *g, hipStream_t st);
+// g [B,H,F] from sum_q; hid is scratch [B,H,d_g]; raw is scratch [B,H,F] complex, only used when
+// P.toeplitz is set; phase already reduced modulo n_fft.
+hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev &P, float *hid, float2 *raw,
+                           int B, int H, long long phase, float2 *g, hipStream_t st);
 
 }  // namespace spectre

@@ -304,6 +304,29 @@ __global__ __launch_bounds__(256) void k_gate_out(const float *__restrict__ hid,
     }
 }
 
+// Toeplitz low-rank update (Sec. 3.2 step 3b) followed by modReLU (step 3c):
+//   g_k = act( raw_k + sum_{m=-r..r} t_m raw_{k-m} ),  raw = 0 outside 0..F-1.   One lane per bin.
+__global__ __launch_bounds__(256) void k_gate_toeplitz(const float2 *__restrict__ raw, const float2 *__restrict__ taps,
+                                                       const float *__restrict__ mbias, float2 *__restrict__ g,
+                                                       int H, int Hg, int F, int r, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int k = (int)(idx % F);
+    const size_t bh = idx / F;
+    const int hp = (Hg == 1) ? 0 : (int)(bh % H);
+    const float2 *t = taps + (size_t)hp * (2 * r + 1) + r;
+    const float2 *row = raw + bh * F;
+    float2 acc = row[k];
+    for (int m = -r; m <= r; ++m) {
+        const int src = k - m;
+        if (src < 0 || src >= F) continue;
+        const float2 pr = cmul(t[m], row[src]);
+        acc.x += pr.x;
+        acc.y += pr.y;
+    }
+    gate_store_bin(g + idx, acc.x, acc.y, mbias != nullptr, mbias ? mbias[(size_t)hp * F + k] : 0.0f);
+}
+
 // positional phase: g[bh][k] *= exp(+j 2 pi ((k p) mod n)/n), angle reduced in integers and
 // evaluated in fp64.  One lane per gate entry; only launched when p != 0.
 __global__ __launch_bounds__(256) void k_gate_phase(float2 *__restrict__ g, int F, int n_fft, long long phase,
@@ -342,8 +365,8 @@ hipError_t launch_pool(int io, const void *q, double *partial, double *sum_q, in
     return hipGetLastError();
 }
 
-hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev &P, float *hid, int B, int H,
-                           long long phase, float2 *g, hipStream_t st) {
+hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev &P, float *hid, float2 *raw,
+                           int B, int H, long long phase, float2 *g, hipStream_t st) {
     k_gate_hidden<<<B * H, 256, 0, st>>>(sum_q, inv_count, P.ln_gamma, P.ln_beta, P.ln_eps, P.W1, P.b1, hid, H,
                                          P.Hg, P.d, P.d_g);
     hipError_t e = hipGetLastError();
@@ -361,12 +384,15 @@ hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev 
     dim3 grid(gx, gy);
     const bool vec = (P.d_g % 4 == 0) && (reinterpret_cast<uintptr_t>(P.W2) & 15) == 0;
     const int dgp = (P.d_g + 3) & ~3;
+    // with the Toeplitz update the MLP output goes to `raw` un-activated and a second pass finishes it
+    const float *out_bias = P.toeplitz ? nullptr : P.modrelu_bias;
+    float2 *out_g = P.toeplitz ? raw : g;
     for (int r_base = 0; r_base < M; r_base += 32) {
         const int rows = (M - r_base < 32) ? M - r_base : 32;
         const int rg = (rows + 3) / 4;            // 1..8 row groups in this pass
         const size_t lds = ((size_t)4 * (rg <= 1 ? 1 : rg <= 2 ? 2 : rg <= 4 ? 4 : 8) * (dgp + 4) +
                             4 * 64 * ((vec && P.d_g == 64) ? kHalfStride : kTileStride)) * sizeof(float);
-#define SPECTRE_GATE_OUT(V, R) k_gate_out<V, R><<<grid, 256, lds, st>>>(hid, P.W2, P.b2, P.modrelu_bias, g, B, H, P.Hg, P.d_g, F, r_base)
+#define SPECTRE_GATE_OUT(V, R) k_gate_out<V, R><<<grid, 256, lds, st>>>(hid, P.W2, P.b2, out_bias, out_g, B, H, P.Hg, P.d_g, F, r_base)
         if (vec) {
             if (rg <= 1) SPECTRE_GATE_OUT(true, 1); else if (rg <= 2) SPECTRE_GATE_OUT(true, 2);
             else if (rg <= 4) SPECTRE_GATE_OUT(true, 4); else SPECTRE_GATE_OUT(true, 8);
@@ -378,9 +404,13 @@ hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev 
         hipError_t e2 = hipGetLastError();
         if (e2 != hipSuccess) return e2;
     }
+    const size_t total = (size_t)B * H * F;
+    if (P.toeplitz) {
+        k_gate_toeplitz<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(raw, P.toeplitz, P.modrelu_bias, g, H, P.Hg, F,
+                                                                         P.toeplitz_r, total);
+    }
     e = hipGetLastError();
     if (e != hipSuccess || phase == 0) return e;
-    const size_t total = (size_t)B * H * F;
     k_gate_phase<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(g, F, P.n_fft, phase, total);
     return hipGetLastError();
 }

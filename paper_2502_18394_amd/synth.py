@@ -69,6 +69,13 @@ def gate_params(seed, Hg, d, n_fft, d_g=D_GATE, modrelu=True, std=0.02):
     return p
 
 
+def toeplitz_taps(seed, Hg, r, std=0.02):
+    """Complex taps t_{-r..r} ~ N(0, std) for the optional low-rank gate update, complex64 [Hg, 2r+1]."""
+    rng = np.random.default_rng(seed)
+    t = std * rng.standard_normal((Hg, 2 * r + 1, 2), dtype=np.float32)
+    return np.ascontiguousarray(t[..., 0] + 1j * t[..., 1]).astype(np.complex64)
+
+
 def random_gate(seed, B, H, n_fft):
     """A stand-alone complex gate [B,H,F] with O(1) entries (for mixer-only tests)."""
     rng = np.random.default_rng(seed)

@@ -68,3 +68,28 @@ def test_pooling_of_long_sequence_is_accurate(oracle):
     """128k rows: the pooled mean is ~0.003 and LayerNorm rescales it to O(1), so the sum must be tight."""
     got, want = run_gate(oracle, 1, 131072, 2, 64, 64, 1024, "bf16", seed=21)
     assert rel_l2(got, want) <= 1e-5
+
+
+@pytest.mark.parametrize("B,L,H,r,shared,modrelu", [(2, 512, 3, 2, False, True), (1, 196, 4, 8, True, True),
+                                                     (3, 1024, 2, 0, False, False), (1, 8192, 32, 4, False, True)])
+def test_gate_with_toeplitz_update(oracle, B, L, H, r, shared, modrelu):
+    """Sec. 3.2 step 3b between the MLP and modReLU."""
+    from paper_2502_18394_amd import binding
+    d, dg = 64, 64
+    Hg = 1 if shared else H
+    p = synth.gate_params(50 + r, Hg, d, L, d_g=dg, modrelu=modrelu, std=0.1)
+    p["toeplitz"] = synth.toeplitz_taps(60 + r, Hg, r, std=0.3)
+    vals, store = synth.tokens(70 + r, (B, L, H, d), "f32")
+    P = binding.GateParams(p)
+    g = binding.gate(to_device(store, "f32"), P, 1.0 / L, phase_pos=5 if r == 2 else 0)
+    torch.cuda.synchronize()
+    p64 = f64(p)
+    p64["toeplitz"] = p["toeplitz"].astype(np.complex128)
+    want = oracle.gate(oracle.pool_q(vals.astype(np.float64)), 1.0 / L, p64, L, 5 if r == 2 else 0)
+    err = rel_l2(g.cpu().numpy(), want)
+    print(f"  r={r} rel_l2={err:.3e}", flush=True)
+    assert err <= 1e-5
+    # and it does something: differs from the gate without taps
+    p_plain = {k: v for k, v in p64.items() if k != "toeplitz"}
+    plain = oracle.gate(oracle.pool_q(vals.astype(np.float64)), 1.0 / L, p_plain, L, 5 if r == 2 else 0)
+    assert rel_l2(want, plain) > 1e-3

@@ -219,3 +219,60 @@ def test_phase_is_periodic_and_shifts_the_output(oracle):
 def test_pool_q(oracle):
     Q = _rng(12).standard_normal((2, 37, 3, 5))
     np.testing.assert_allclose(oracle.pool_q(Q), Q.sum(axis=1), atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- Toeplitz update (step 3b)
+def _gate_no_act(oracle, taps, n=32, seed=20, Hg=1, H=1):
+    d, dg = 4, 4
+    p = synth.gate_params(seed, Hg, d, n, d_g=dg, std=0.5, modrelu=False)
+    sq = _rng(seed + 1).standard_normal((1, H, d))
+    raw = oracle.gate(sq, 1.0, p, n)
+    upd = oracle.gate(sq, 1.0, dict(p, toeplitz=taps), n)
+    return raw, upd, p, sq
+
+
+def test_toeplitz_centre_tap_scales_the_gate(oracle):
+    """r = 0: g + t_0 g = (1 + t_0) g."""
+    t0 = 0.3 - 0.7j
+    raw, upd, _, _ = _gate_no_act(oracle, np.array([[t0]]))
+    np.testing.assert_allclose(upd, (1 + t0) * raw, atol=1e-14)
+
+
+@pytest.mark.parametrize("m0", [-2, -1, 1, 2])
+def test_toeplitz_single_off_centre_tap_shifts_along_frequency(oracle, m0):
+    """t_m = delta(m - m0): (t * g)_k = g_{k - m0}, zero where k - m0 leaves 0..F-1."""
+    r = 2
+    taps = np.zeros((1, 2 * r + 1), complex)
+    taps[0, m0 + r] = 1.0
+    raw, upd, _, _ = _gate_no_act(oracle, taps)
+    F = raw.shape[-1]
+    shifted = np.zeros(F, complex)
+    for k in range(F):
+        if 0 <= k - m0 < F:
+            shifted[k] = raw[0, 0, k - m0]
+    np.testing.assert_allclose(upd[0, 0], raw[0, 0] + shifted, atol=1e-14)
+
+
+def test_toeplitz_equals_library_convolution_and_precedes_modrelu(oracle):
+    """General taps: numpy's zero-padded 'same' convolution; modReLU acts on the updated gate."""
+    r = 3
+    rng = _rng(30)
+    taps = (rng.standard_normal((2, 2 * r + 1)) + 1j * rng.standard_normal((2, 2 * r + 1))) * 0.3
+    n, d, dg, H = 40, 4, 4, 2
+    p = synth.gate_params(31, H, d, n, d_g=dg, std=0.5, modrelu=False)
+    sq = rng.standard_normal((2, H, d))
+    raw = oracle.gate(sq, 1.0, p, n)
+    upd = oracle.gate(sq, 1.0, dict(p, toeplitz=taps), n)
+    for b in range(2):
+        for h in range(H):
+            want = raw[b, h] + np.convolve(raw[b, h], taps[h], mode="same")
+            np.testing.assert_allclose(upd[b, h], want, atol=1e-13)
+    F = n // 2 + 1
+    bias = rng.standard_normal((H, F)) * 0.3
+    act = oracle.gate(sq, 1.0, dict(p, toeplitz=taps, modrelu_bias=bias), n)
+    np.testing.assert_allclose(np.abs(act), np.maximum(np.abs(upd) + bias[None], 0), atol=1e-13)
+
+
+def test_toeplitz_zero_taps_change_nothing(oracle):
+    raw, upd, _, _ = _gate_no_act(oracle, np.zeros((1, 5), complex))
+    np.testing.assert_array_equal(raw, upd)
