@@ -88,18 +88,21 @@ __device__ __forceinline__ void dft_any(float2 (&x)[R]) {
 // S = n / R its stride; roots[m] = exp(-j 2 pi m / L).  Forward: butterfly then twiddle (and
 // the gate, when GATE, which makes this the last forward pass).  Inverse: conjugate twiddle then
 // inverse butterfly.
-template <int R, bool INV, bool GATE>
+template <int R, bool INV, bool GATE, int PP>
 __device__ __forceinline__ void slab_pass(float2 *__restrict__ slab, const float2 *__restrict__ roots,
                                           const float2 *__restrict__ gpos, int L, int n, int tid, int nthreads) {
+    constexpr int kShift = (PP == 32) ? 5 : 4;
     const int S = n / R, tstep = L / n;
-    const int nb = (L / R) * 32;
+    const int nb = (L / R) * PP;
+    // bi / S by a multiply and shift: exact while bi * S < 2^20 (bi < L/R <= 256, S <= 256)
+    const unsigned inv_s = ((1u << 20) + (unsigned)S - 1) / (unsigned)S;
     for (int w = tid; w < nb; w += nthreads) {
-        const int col = w & 31, bi = w >> 5;
-        const int i = bi % S, blk = bi / S;
+        const int col = w & (PP - 1), bi = w >> kShift;
+        const int blk = (int)(((unsigned)bi * inv_s) >> 20), i = bi - blk * S;
         const int base = blk * n + i;
         float2 x[R];
 #pragma unroll
-        for (int j = 0; j < R; ++j) x[j] = slab[(base + S * j) * 32 + col];
+        for (int j = 0; j < R; ++j) x[j] = slab[(base + S * j) * PP + col];
         if (INV) {
 #pragma unroll
             for (int u = 1; u < R; ++u) x[u] = cmulc(x[u], roots[i * u * tstep]);
@@ -114,21 +117,21 @@ __device__ __forceinline__ void slab_pass(float2 *__restrict__ slab, const float
             }
         }
 #pragma unroll
-        for (int j = 0; j < R; ++j) slab[(base + S * j) * 32 + col] = x[j];
+        for (int j = 0; j < R; ++j) slab[(base + S * j) * PP + col] = x[j];
     }
 }
 
-template <bool INV, bool GATE>
+template <bool INV, bool GATE, int PP>
 __device__ __forceinline__ void slab_pass_dispatch(int R, float2 *slab, const float2 *roots, const float2 *gpos,
                                                    int L, int n, int tid, int nthreads) {
     switch (R) {
-        case 2: slab_pass<2, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 3: slab_pass<3, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 4: slab_pass<4, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 5: slab_pass<5, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 7: slab_pass<7, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 8: slab_pass<8, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 16: slab_pass<16, INV, GATE>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 2: slab_pass<2, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 3: slab_pass<3, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 4: slab_pass<4, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 5: slab_pass<5, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 7: slab_pass<7, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 8: slab_pass<8, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 16: slab_pass<16, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
         default: break;
     }
 }
@@ -138,8 +141,10 @@ struct SlabRadices {
     int r[10];
 };
 
-// grid = B*H workgroups of 256 lanes.  LDS: slab [L][32] float2, roots [L], gpos [L].
-template <typename IO>
+// grid = B*H*(32/PP) workgroups of 256 lanes, PP channel pairs each (a whole head, or half a head
+// when rows are fp32: still full 128-byte row segments, half the LDS, twice the workgroups per CU).
+// LDS: slab [L][PP] float2, roots [L], gpos [L].
+template <typename IO, int PP>
 __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__restrict__ v,
                                                   const float2 *__restrict__ g,
                                                   typename IO::pair_t *__restrict__ out,
@@ -147,21 +152,22 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
                                                   SlabRadices rad) {
     extern __shared__ float2 lds_slab[];
     float2 *slab = lds_slab;
-    float2 *roots = slab + (size_t)L * 32;
+    float2 *roots = slab + (size_t)L * PP;
     float2 *gpos = roots + L;
+    constexpr int kParts = 32 / PP, kRows = 256 / PP;      // workgroups per head; rows covered per sweep
     const int tid = threadIdx.x;
-    const int bh = blockIdx.x, b = bh / H, h = bh % H;
+    const int bh = blockIdx.x / kParts, part = blockIdx.x % kParts, b = bh / H, h = bh % H;
     const int F = L / 2 + 1;
 
     // rows l = (tid/32) + 8 i.  Eight loads are put in flight before any is consumed; the first
     // batch flies while the gate table below is being built.
-    const int lp_in = tid & 31;
-    const typename IO::pair_t *src = v + (((size_t)b * L) * H + h) * 32 + lp_in;
+    const int lp_in = tid & (PP - 1), row_in = tid / PP;
+    const typename IO::pair_t *src = v + (((size_t)b * L) * H + h) * 32 + part * PP + lp_in;
     const size_t rs = (size_t)H * 32;
     typename IO::pair_t val[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int l = (tid >> 5) + 8 * i;
+        const int l = row_in + kRows * i;
         val[i] = (l < L) ? src[(size_t)l * rs] : IO::zero();
     }
 
@@ -187,38 +193,37 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int l = (tid >> 5) + 8 * i;
-        if (l < L) slab[l * 32 + lp_in] = IO::unpack(val[i]);
+        const int l = row_in + kRows * i;
+        if (l < L) slab[l * PP + lp_in] = IO::unpack(val[i]);
     }
-    for (int l0 = (tid >> 5) + 64; l0 < L; l0 += 64) {
+    for (int l0 = row_in + 8 * kRows; l0 < L; l0 += 8 * kRows) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int l = l0 + 8 * i;
+            const int l = l0 + kRows * i;
             val[i] = (l < L) ? src[(size_t)l * rs] : IO::zero();
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int l = l0 + 8 * i;
-            if (l < L) slab[l * 32 + lp_in] = IO::unpack(val[i]);
+            const int l = l0 + kRows * i;
+            if (l < L) slab[l * PP + lp_in] = IO::unpack(val[i]);
         }
     }
     __syncthreads();
     int n = L;
     for (int q = 0; q < rad.count; ++q) {
-        if (q == rad.count - 1) slab_pass_dispatch<false, true>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
-        else slab_pass_dispatch<false, false>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        if (q == rad.count - 1) slab_pass_dispatch<false, true, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        else slab_pass_dispatch<false, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
         n /= rad.r[q];
         __syncthreads();
     }
     for (int q = rad.count - 1; q >= 0; --q) {
         n *= rad.r[q];
-        slab_pass_dispatch<true, false>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        slab_pass_dispatch<true, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
         __syncthreads();
     }
     {
-        const int lp = tid & 31;
-        typename IO::pair_t *dst = out + (((size_t)b * L) * H + h) * 32 + lp;
-        for (int l = tid >> 5; l < L; l += 8) dst[(size_t)l * H * 32] = IO::pack(slab[l * 32 + lp]);
+        typename IO::pair_t *dst = out + (((size_t)b * L) * H + h) * 32 + part * PP + lp_in;
+        for (int l = row_in; l < L; l += kRows) dst[(size_t)l * rs] = IO::pack(slab[l * PP + lp_in]);
     }
 }
 
@@ -244,29 +249,26 @@ static SlabRadices slab_radices(int L) {
     return r;
 }
 
+template <typename IO, int PP>
+static hipError_t mix_slab_t(const void *v, const float2 *g, void *out, const float2 *roots, int B, int L, int H,
+                             hipStream_t st) {
+    const size_t lds = ((size_t)L * PP + 2 * (size_t)L) * sizeof(float2);
+    const SlabRadices rad = slab_radices(L);
+    auto kern = k_mix_slab<IO, PP>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    kern<<<dim3(B * H * (32 / PP)), dim3(256), lds, st>>>(static_cast<const typename IO::pair_t *>(v), g,
+                                                         static_cast<typename IO::pair_t *>(out), roots, L, H, rad);
+    return hipGetLastError();
+}
+
 hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, const float2 *roots, int B, int L,
                            int H, hipStream_t st) {
-    const size_t lds = ((size_t)L * 32 + 2 * (size_t)L) * sizeof(float2);
-    const SlabRadices rad = slab_radices(L);
-    hipError_t e;
-    if (io) {
-        auto kern = k_mix_slab<IoBf16>;
-        if (lds > 48 * 1024) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        kern<<<dim3(B * H), dim3(256), lds, st>>>(static_cast<const uint32_t *>(v), g, static_cast<uint32_t *>(out),
-                                                  roots, L, H, rad);
-    } else {
-        auto kern = k_mix_slab<IoF32>;
-        if (lds > 48 * 1024) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        kern<<<dim3(B * H), dim3(256), lds, st>>>(static_cast<const float2 *>(v), g, static_cast<float2 *>(out), roots,
-                                                  L, H, rad);
-    }
-    return hipGetLastError();
+    if (io) return mix_slab_t<IoBf16, 32>(v, g, out, roots, B, L, H, st);
+    return mix_slab_t<IoF32, 16>(v, g, out, roots, B, L, H, st);
 }
 
 }  // namespace spectre
