@@ -238,7 +238,22 @@ def main():
         "gate_only": {"ms": ms_gate, "algorithmic_bytes": gate_bytes,
                       "hbm_frac": gate_bytes / (ms_gate * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
-    del V, Q, out, g, ws_mix, ws_gate, P
+    # token projection (next-row item): X -> V and the pooled query, X read once
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 8)
+    Wq = 0.125 * torch.randn((H, d, d), generator=gen, device="cuda", dtype=torch.float32)
+    Wv = 0.125 * torch.randn((H, d, d), generator=gen, device="cuda", dtype=torch.float32)
+    ws_proj = torch.empty(int(binding.lib().spectre_project_workspace_bytes(B, L, H, d)) + 256, dtype=torch.uint8, device="cuda")
+    ms_proj = time_loop(lambda: binding.project(Q, Wq, Wv, ws=ws_proj), args.steps, 2)
+    proj_bytes = 2 * tokens * H * d * esize
+    proj_flops = 2.0 * tokens * H * d * d
+    res["project"] = {"ms": ms_proj, "algorithmic_bytes": proj_bytes,
+                      "hbm_frac": proj_bytes / (ms_proj * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "tflops": proj_flops / (ms_proj * 1e-3) / 1e12,
+                      "what": "spectre_project: V = X W_v per head + pooled query in one pass over X (bf16 rows: "
+                              "32x32x16 bf16 MFMA with two-term weights; fp32 rows: 32x32x2 fp32 MFMA); includes "
+                              "allocating the outputs"}
+    del V, Q, out, g, ws_mix, ws_gate, P, Wq, Wv, ws_proj
     torch.cuda.empty_cache()
 
     if args.copy_calib:

@@ -122,6 +122,24 @@ int spectre_gate(const void *q, int q_is_pooled, spectre_dtype q_dtype, double i
                  long long phase_pos, void *g_out, void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * spectre_project - token projection, Sec. 3.2 step 1 (Eq. 2), per head: every head h multiplies its
+ * own d channels of the token rows by its d x d matrices,
+ *        V[b, l, h, :] = X[b, l, h, :] W^(v)_h        Q[b, l, h, :] = X[b, l, h, :] W^(q)_h .
+ * The mixing layer needs V and only the sum of the query rows; since pooling commutes with the
+ * projection the call reads X once, writes V and returns sum_q = (sum_l X[b, l, h, :]) W^(q)_h.
+ *
+ *   x       [B, L, H, d] of dtype io (d = 64)
+ *   Wq, Wv  fp32 [Hw, d, d], input-major (row i, column j: out_j = sum_i x_i W[i][j]); Hw = H or 1
+ *   v_out   [B, L, H, d] of dtype io; must not overlap x
+ *   q_out   [B, L, H, d] of dtype io, or NULL when the query rows themselves are not needed
+ *   sum_q   double [B, H, d], or NULL; ready to be passed to spectre_gate with q_is_pooled = 1
+ */
+size_t spectre_project_workspace_bytes(int B, int L, int H, int d);
+int spectre_project(const void *x, const float *Wq, const float *Wv, int Hw, int B, int L, int H, int d,
+                    spectre_dtype io, void *v_out, void *q_out, void *sum_q, void *ws, size_t ws_bytes,
+                    void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * spectre_mix_forward - the mixing layer, Sec. 3.2 steps 2 and 4 (Eq. 3, Eq. 4): for every
  * sequence b, head h and channel c
  *        out[b, :, h, c] = irfft_L( g[b, h, :] * rfft_L( v[b, :, h, c] ) ).

@@ -329,6 +329,29 @@ int so_gate(int B, int H, int d, int dg, int n, int Hg,
     return 0;
 }
 
+/* Token projection, Sec. 3.2 step 1 (Eq. 2), read per head: every head owns d x d matrices W^(q), W^(v)
+ * and projects its own d channels of the token rows,  Q[b,l,h,:] = X[b,l,h,:] W^(q)_h,  V likewise.
+ * X, Q, V [B,L,H,d]; Wq, Wv [Hw,d,d] with Hw = H (per head) or 1 (shared), input-major (row i, column j). */
+int so_project(int B, int L, int H, int d, int Hw, const double *X, const double *Wq, const double *Wv,
+               double *Q, double *V) {
+    if (!(Hw == H || Hw == 1)) return -1;
+    for (int b = 0; b < B; ++b) for (int l = 0; l < L; ++l) for (int h = 0; h < H; ++h) {
+        const double *x = X + (((size_t)b * L + l) * H + h) * d;
+        const double *wq = Wq + (size_t)(Hw == 1 ? 0 : h) * d * d;
+        const double *wv = Wv + (size_t)(Hw == 1 ? 0 : h) * d * d;
+        for (int j = 0; j < d; ++j) {
+            double aq = 0.0, av = 0.0;
+            for (int i = 0; i < d; ++i) {
+                aq += x[i] * wq[(size_t)i * d + j];
+                av += x[i] * wv[(size_t)i * d + j];
+            }
+            Q[(((size_t)b * L + l) * H + h) * d + j] = aq;
+            V[(((size_t)b * L + l) * H + h) * d + j] = av;
+        }
+    }
+    return 0;
+}
+
 /* sum_q[b,h,c] = sum_l Q[b,l,h,c]   (Q is [B,L,H,d]) */
 void so_pool_q(int B, int L, int H, int d, const double *Q, double *sum_q) {
     for (int b = 0; b < B; ++b) for (int h = 0; h < H; ++h) for (int c = 0; c < d; ++c) {

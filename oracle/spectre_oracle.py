@@ -94,6 +94,20 @@ def irfft(Y, n, method=FAST):
     return out
 
 
+def project(X, Wq, Wv):
+    """Q = X W^(q), V = X W^(v) per head (Eq. 2); X [B,L,H,d], Wq/Wv [Hw,d,d]."""
+    X, Wq, Wv = _f64(X), _f64(Wq), _f64(Wv)
+    B, L, H, d = X.shape
+    Hw = Wq.shape[0]
+    assert Wq.shape == (Hw, d, d) and Wv.shape == (Hw, d, d)
+    Q, V = np.empty_like(X), np.empty_like(X)
+    rc = _L().so_project(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(Hw),
+                         _p(X), _p(Wq), _p(Wv), _p(Q), _p(V))
+    if rc:
+        raise RuntimeError(f"so_project rc={rc}")
+    return Q, V
+
+
 def pool_q(Q):
     Q = _f64(Q)
     B, L, H, d = Q.shape

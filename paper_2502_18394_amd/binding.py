@@ -49,10 +49,10 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.spectre_last_error.restype = ctypes.c_char_p
         for name in ("spectre_gate_workspace_bytes", "spectre_mix_workspace_bytes", "spectre_prefix_bytes",
+                     "spectre_project_workspace_bytes",
                      "spectre_prefix_update_workspace_bytes", "spectre_prefix_readout_workspace_bytes",
                      "spectre_prefix_step_workspace_bytes"):
-            if hasattr(L, name):
-                getattr(L, name).restype = ctypes.c_size_t
+            getattr(L, name).restype = ctypes.c_size_t
         _lib = L
     return _lib
 
@@ -114,6 +114,26 @@ def mix_forward(v, g, out=None, ws=None, stream=None):
     _check(lib().spectre_mix_forward(_dev(v, "v"), _dev(g, "g"), _dev(out, "out"), ctypes.c_int(B), ctypes.c_int(L),
                                      ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(io), wsp, wsn, _stream(stream)))
     return out
+
+
+def project(x, Wq, Wv, want_q=False, want_sum_q=True, ws=None, stream=None):
+    """Per-head token projection (Eq. 2).  x [B,L,H,64] f32/bf16; Wq, Wv float32 [Hw,64,64] (Hw = H or 1).
+    Returns (v, q or None, sum_q float64 [B,H,64] or None)."""
+    B, L, H, d = x.shape
+    io = _dtype_code(x)
+    for w in (Wq, Wv):
+        if w.dtype != torch.float32 or tuple(w.shape[1:]) != (d, d) or w.shape[0] != Wq.shape[0]:
+            raise ValueError("Wq, Wv must be float32 [Hw,d,d]")
+    v = torch.empty_like(x)
+    q = torch.empty_like(x) if want_q else None
+    sq = torch.empty((B, H, d), dtype=torch.float64, device=x.device) if want_sum_q else None
+    need = lib().spectre_project_workspace_bytes(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.c_int(d))
+    ws, wsp, wsn = _workspace(need, x.device, ws)
+    _check(lib().spectre_project(_dev(x, "x"), _dev(Wq, "Wq"), _dev(Wv, "Wv"), ctypes.c_int(Wq.shape[0]),
+                                 ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(io),
+                                 _dev(v, "v"), None if q is None else _dev(q, "q"),
+                                 None if sq is None else _dev(sq, "sum_q"), wsp, wsn, _stream(stream)))
+    return v, q, sq
 
 
 class GateParams:

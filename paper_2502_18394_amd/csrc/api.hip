@@ -18,6 +18,7 @@
 #include "internal.h"
 #include "mix_slab.h"
 #include "prefix.h"
+#include "project.h"
 
 namespace spectre {
 
@@ -263,6 +264,46 @@ int spectre_gate(const void *q, int q_is_pooled, spectre_dtype q_dtype, double i
     hipError_t e = launch_gate_mlp(sum_q, inv_count, gate_dev(P), hid, raw, B, H, phase_pos % P->n_fft,
                                    static_cast<float2 *>(g_out), st);
     if (e != hipSuccess) return fail_hip(e, "gate_mlp");
+    return SPECTRE_OK;
+}
+
+// ------------------------------------------------------------------------------------------ projection
+size_t spectre_project_workspace_bytes(int B, int L, int H, int d) {
+    if (B < 1 || L < 1 || H < 1 || d != 64) return 0;
+    return align256((size_t)B * project_chunks(L) * H * d * sizeof(double)) + align256((size_t)B * H * d * sizeof(double));
+}
+
+int spectre_project(const void *x, const float *Wq, const float *Wv, int Hw, int B, int L, int H, int d,
+                    spectre_dtype io, void *v_out, void *q_out, void *sum_q, void *ws, size_t ws_bytes, void *stream) {
+    if (!x || !Wq || !Wv || !v_out) return fail(SPECTRE_EINVAL, "project: null pointer");
+    if (B < 1 || L < 1 || H < 1 || d < 1) return fail(SPECTRE_EINVAL, "project: non-positive size");
+    if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "project: bad dtype");
+    if (!(Hw == H || Hw == 1)) return fail(SPECTRE_EINVAL, "project: Hw must be H or 1");
+    if (d != 64) return fail(SPECTRE_EUNSUPPORTED, "project: d=%d (only 64 is built)", d);
+    if (H > 65535 || B > 65535) return fail(SPECTRE_EUNSUPPORTED, "project: H or B above 65535");
+    const size_t bytes = (size_t)B * L * H * d * (io == SPECTRE_BF16 ? 2 : 4);
+    const char *xb = static_cast<const char *>(x);
+    for (const void *o : {static_cast<const void *>(v_out), static_cast<const void *>(q_out)}) {
+        const char *ob = static_cast<const char *>(o);
+        if (ob && xb < ob + bytes && ob < xb + bytes) return fail(SPECTRE_EINVAL, "project: output overlaps x");
+    }
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(v_out) | reinterpret_cast<uintptr_t>(q_out)) & 15)
+        return fail(SPECTRE_EINVAL, "project: tensors must be 16-byte aligned");
+    const size_t need = spectre_project_workspace_bytes(B, L, H, d);
+    if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "project: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "project: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    double *partial = static_cast<double *>(ws);
+    double *sum_x = reinterpret_cast<double *>(static_cast<char *>(ws) +
+                                               align256((size_t)B * project_chunks(L) * H * d * sizeof(double)));
+    hipError_t e = launch_project((int)io, x, Wq, Wv, Hw, v_out, q_out, partial, B, L, H, st);
+    if (e != hipSuccess) return fail_hip(e, "project");
+    if (sum_q) {
+        e = launch_pool_final(partial, sum_x, B, H * d, project_chunks(L), st);
+        if (e != hipSuccess) return fail_hip(e, "pool_final");
+        e = launch_project_pooled(sum_x, Wq, Hw, B, H, static_cast<double *>(sum_q), st);
+        if (e != hipSuccess) return fail_hip(e, "project_pooled");
+    }
     return SPECTRE_OK;
 }
 

@@ -23,6 +23,9 @@ size_t gate_partial_bytes(int B, int L, int H, int d);
 hipError_t launch_pool(int io, const void *q, double *partial, double *sum_q, int B, int L, int H, int d,
                        hipStream_t st);
 
+// sum [B][row] = sum over chunks of partial [B][nchunks][row], added in a fixed order in fp64.
+hipError_t launch_pool_final(const double *partial, double *sum, int B, int row, int nchunks, hipStream_t st);
+
 // g [B,H,F] from sum_q; hid is scratch [B,H,d_g]; raw is scratch [B,H,F] complex, only used when
 // P.toeplitz is set; phase already reduced modulo n_fft.
 hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev &P, float *hid, float2 *raw,

@@ -365,6 +365,11 @@ hipError_t launch_pool(int io, const void *q, double *partial, double *sum_q, in
     return hipGetLastError();
 }
 
+hipError_t launch_pool_final(const double *partial, double *sum, int B, int row, int nchunks, hipStream_t st) {
+    k_pool_final<<<dim3((row + 31) / 32, B), 256, 0, st>>>(partial, sum, row, nchunks);
+    return hipGetLastError();
+}
+
 hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev &P, float *hid, float2 *raw,
                            int B, int H, long long phase, float2 *g, hipStream_t st) {
     k_gate_hidden<<<B * H, 256, 0, st>>>(sum_q, inv_count, P.ln_gamma, P.ln_beta, P.ln_eps, P.W1, P.b1, hid, H,

@@ -276,3 +276,44 @@ def test_toeplitz_equals_library_convolution_and_precedes_modrelu(oracle):
 def test_toeplitz_zero_taps_change_nothing(oracle):
     raw, upd, _, _ = _gate_no_act(oracle, np.zeros((1, 5), complex))
     np.testing.assert_array_equal(raw, upd)
+
+
+# ----------------------------------------------------------------------------- token projection (Eq. 2)
+def test_projection_against_library_matmul(oracle):
+    r = _rng(40)
+    B, L, H, d = 2, 5, 3, 4
+    X = r.standard_normal((B, L, H, d))
+    for Hw in (H, 1):
+        Wq, Wv = r.standard_normal((Hw, d, d)), r.standard_normal((Hw, d, d))
+        Q, V = oracle.project(X, Wq, Wv)
+        for h in range(H):
+            hw = 0 if Hw == 1 else h
+            np.testing.assert_allclose(Q[:, :, h], X[:, :, h] @ Wq[hw], atol=1e-13)
+            np.testing.assert_allclose(V[:, :, h], X[:, :, h] @ Wv[hw], atol=1e-13)
+
+
+def test_projection_identity_and_column_routing(oracle):
+    """W = I copies the rows; a one-hot W[i0, j0] routes input channel i0 to output channel j0 only."""
+    B, L, H, d = 1, 3, 2, 4
+    X = _rng(41).standard_normal((B, L, H, d))
+    eye = np.broadcast_to(np.eye(d), (H, d, d)).copy()
+    Q, V = oracle.project(X, eye, 2.0 * eye)
+    np.testing.assert_array_equal(Q, X)
+    np.testing.assert_array_equal(V, 2.0 * X)
+    W = np.zeros((H, d, d))
+    W[1, 2, 0] = 1.0                      # head 1: input channel 2 -> output channel 0
+    Q, _ = oracle.project(X, W, W)
+    want = np.zeros_like(X)
+    want[:, :, 1, 0] = X[:, :, 1, 2]
+    np.testing.assert_array_equal(Q, want)
+
+
+def test_pooled_projection_is_projection_of_pooled_rows(oracle):
+    """Linearity the GPU path relies on: sum_l (x_l W) = (sum_l x_l) W."""
+    r = _rng(42)
+    B, L, H, d = 2, 50, 3, 8
+    X, Wq = r.standard_normal((B, L, H, d)), r.standard_normal((H, d, d))
+    Q, _ = oracle.project(X, Wq, Wq)
+    lhs = oracle.pool_q(Q)
+    rhs = np.einsum("bhi,hij->bhj", X.sum(axis=1), Wq)
+    np.testing.assert_allclose(lhs, rhs, atol=1e-11)
