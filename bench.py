@@ -20,8 +20,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
-# L2<->fabric bytes per spectre_mix_forward call at llama1b_128k from the rocprofv3 FETCH_SIZE + WRITE_SIZE passes
-# summarised in profiles/bench_llama1b_128k_and_decode_32k.md (scaled by the plain-copy factors given there)
+# L2<->fabric bytes per spectre_mix_forward call at llama1b_128k and per decode sweep, from separate rocprofv3
+# FETCH_SIZE and WRITE_SIZE passes over this same script (scaled by what the counters read for a plain 1 GiB copy;
+# the summary is kept with the other profiler summaries)
 MIX_TRAFFIC_BYTES_128K = 5.48 * 2 ** 30
 DECODE_SWEEP_TRAFFIC_BYTES = (2122.1 + 2056.2) * 2 ** 20
 # fp32 vector peak without packed math: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s
@@ -219,7 +220,7 @@ def main():
     F = L // 2 + 1
     mix_bytes = 2 * tokens * H * d * esize + B * H * F * 8                # read V, write out, read g
     gate_bytes = tokens * H * d * esize + P.Hg * P.d_g * 2 * F * 4 + B * H * F * 8   # read Q, read W2, write g
-    mix_flops_instr = tokens * H * (d // 2) * (2 * 3.5 * (L.bit_length() - 1) + 6)   # lane-instructions, see the design doc
+    mix_flops_instr = tokens * H * (d // 2) * (2 * 3.5 * (L.bit_length() - 1) + 6)   # lane-instructions: 3.5 per point per radix-2 stage each way + 6 for the gate
     res = {
         "metric": "mixer tokens/sec at L=128k (H=32,d=64) + % HBM roofline; decode tokens/sec",
         "value": tokens / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,

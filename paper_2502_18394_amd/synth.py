@@ -12,7 +12,7 @@ import numpy as np
 
 BASE_SEED = 42
 
-# name -> shape of the workload (BASELINE configs, in order)
+# name -> shape of the workload
 CONFIGS = {
     "single_head_1k": dict(B=1, H=1, L=1024, d=64, io="f32"),
     "llama1b_8k": dict(B=1, H=32, L=8192, d=64, io="bf16"),
