@@ -1,0 +1,86 @@
+"""Runtime behaviour of the library on the GPU: streams, determinism, table cache, error paths."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import rel_l2, to_device
+from paper_2502_18394_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def test_calls_follow_the_callers_stream(oracle):
+    """Work is enqueued on the stream passed in, not on the default one."""
+    from paper_2502_18394_amd import binding
+    B, L, H, d = 1, 2048, 2, 64
+    vals, store = synth.tokens(1, (B, L, H, d), "f32")
+    g = synth.random_gate(2, B, H, L)
+    s = torch.cuda.Stream()
+    v = to_device(store, "f32")
+    gd = torch.from_numpy(g).cuda()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        out = binding.mix_forward(v, gd, stream=s)
+    s.synchronize()
+    want = oracle.mix_forward(vals.astype(np.float64), g.astype(np.complex128))
+    assert rel_l2(out.cpu().numpy(), want) <= 1e-5
+
+
+def test_decode_step_is_bitwise_reproducible():
+    from paper_2502_18394_amd import binding
+    B, H, d, N = 2, 3, 64, 1024
+    p = synth.gate_params(3, H, d, N)
+    P = binding.GateParams(p)
+    _, v0 = synth.tokens(4, (B, N, H, d), "f32")
+    _, q0 = synth.tokens(5, (B, N, H, d), "f32")
+    _, vt = synth.tokens(6, (B, 8, H, d), "f32")
+    _, qt = synth.tokens(7, (B, 8, H, d), "f32")
+    runs = []
+    for _ in range(2):
+        c = binding.PrefixCache(B, H, d, N)
+        c.update(to_device(v0, "f32"), to_device(q0, "f32"))
+        outs = [c.step(to_device(np.ascontiguousarray(vt[:, i:i + 1]), "f32"),
+                       to_device(np.ascontiguousarray(qt[:, i:i + 1]), "f32"), P).clone() for i in range(8)]
+        torch.cuda.synchronize()
+        runs.append((torch.stack(outs), c.prefix_fft.clone()))
+    assert torch.equal(runs[0][0], runs[1][0]) and torch.equal(runs[0][1].view(torch.float32), runs[1][1].view(torch.float32))
+
+
+def test_shutdown_frees_tables_and_library_recovers(oracle):
+    from paper_2502_18394_amd import binding
+    vals, store = synth.tokens(8, (1, 512, 1, 64), "f32")
+    g = synth.random_gate(9, 1, 1, 512)
+    a = binding.mix_forward(to_device(store, "f32"), torch.from_numpy(g).cuda()).cpu()
+    torch.cuda.synchronize()
+    binding.lib().spectre_shutdown()
+    binding.lib().spectre_shutdown()
+    b = binding.mix_forward(to_device(store, "f32"), torch.from_numpy(g).cuda()).cpu()
+    assert torch.equal(a, b)
+
+
+def test_error_paths_launch_nothing():
+    from paper_2502_18394_amd import binding
+    v = torch.zeros((1, 1024, 1, 64), device="cuda")
+    g = torch.zeros((1, 1, 513), dtype=torch.complex64, device="cuda")
+    L = binding.lib()
+    small = torch.empty(512, dtype=torch.uint8, device="cuda")
+    off = (-small.data_ptr()) % 256
+    rc = L.spectre_mix_forward(ctypes.c_void_p(v.data_ptr()), ctypes.c_void_p(g.data_ptr()), ctypes.c_void_p(v.data_ptr()),
+                               1, 1024, 1, 64, 0, ctypes.c_void_p(small.data_ptr() + off), ctypes.c_size_t(256), None)
+    assert rc == binding.EINVAL                                  # out overlaps v
+    out = torch.empty_like(v)
+    rc = L.spectre_mix_forward(ctypes.c_void_p(v.data_ptr()), ctypes.c_void_p(g.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                               1, 1024, 1, 64, 0, ctypes.c_void_p(small.data_ptr() + off), ctypes.c_size_t(256), None)
+    assert rc == binding.EWORKSPACE and b"workspace" in L.spectre_last_error()
+    c = binding.PrefixCache(1, 1, 64, 256)
+    with pytest.raises(binding.SpectreError) as e:
+        c.readout(torch.zeros((1, 1, 129), dtype=torch.complex64, device="cuda"))
+    assert e.value.code == binding.EINVAL                        # empty cache
+    big = torch.zeros((1, 300, 1, 64), device="cuda")
+    with pytest.raises(binding.SpectreError) as e:
+        c.update(big, big)
+    assert e.value.code == binding.EINVAL and c.t == 0           # prompt longer than the window
+    with pytest.raises(binding.SpectreError):
+        binding.PrefixCache(1, 1, 64, 1000)                      # window length without a plan
