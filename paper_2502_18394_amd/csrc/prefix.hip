@@ -81,13 +81,13 @@ __global__ __launch_bounds__(256) void k_sweep(float4 *__restrict__ X, const flo
     for (int k = k0 + row; k < k1; k += 8) {
         const unsigned m = ((unsigned)k * (unsigned)slot) & (unsigned)(N - 1);
         const float2 w = tw[m];
-        float4 x = Xp[(size_t)k * 32];
+        float4 x = stream_load(Xp + (size_t)k * 32);
         if (UPDATE) {
             x.x = fmaf(dl.x, w.x, x.x);
             x.y = fmaf(dl.x, w.y, x.y);
             x.z = fmaf(dl.y, w.x, x.z);
             x.w = fmaf(dl.y, w.y, x.w);
-            Xp[(size_t)k * 32] = x;
+            stream_store(Xp + (size_t)k * 32, x);
         }
         if (READ) {
             const float2 gk = g[(size_t)bh * F + k];
