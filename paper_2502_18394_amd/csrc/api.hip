@@ -93,7 +93,7 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // cache between the three kernels of a group.
 int mix_chunk_heads(int BH, int L, int d) {
     size_t per_head = (size_t)L * (size_t)(d / 2) * sizeof(float2);
-    size_t budget = (size_t)136 << 20;
+    size_t budget = (size_t)204 << 20;
     if (const char *e = getenv("SPECTRE_CHUNK_MB")) {
         long mb = atol(e);
         if (mb > 0) budget = (size_t)mb << 20;

@@ -47,6 +47,8 @@ struct IoF32 {
     __device__ static __forceinline__ float2 unpack(pair_t p) { return p; }
     __device__ static __forceinline__ pair_t pack(float2 v) { return v; }
     __device__ static __forceinline__ pair_t zero() { return make_float2(0.f, 0.f); }
+    __device__ static __forceinline__ pair_t load_stream(const pair_t *p) { return stream_load(p); }
+    __device__ static __forceinline__ void store_stream(pair_t *p, pair_t v) { stream_store(p, v); }
 };
 struct IoBf16 {
     typedef uint32_t pair_t;
@@ -60,6 +62,8 @@ struct IoBf16 {
         return __builtin_bit_cast(uint32_t, b);
     }
     __device__ static __forceinline__ pair_t zero() { return 0u; }
+    __device__ static __forceinline__ pair_t load_stream(const pair_t *p) { return __builtin_nontemporal_load(p); }
+    __device__ static __forceinline__ void store_stream(pair_t *p, pair_t v) { __builtin_nontemporal_store(v, p); }
 };
 
 }  // namespace spectre

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
 #pragma unroll
         for (int t2 = 0; t2 < N2; ++t2) {
             const int l = t1_0 + r + N1 * t2;
-            val[t2] = (l < rows) ? v[(((size_t)b * rows + l) * H + h) * 32 + lp] : IO::zero();
+            val[t2] = (l < rows) ? IO::load_stream(v + (((size_t)b * rows + l) * H + h) * 32 + lp) : IO::zero();
         }
 #pragma unroll
         for (int t2 = 0; t2 < N2; ++t2) lds[(t2 * TT + r) * S + lp] = val[t2];
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const float2 *__restrict_
     for (int t2 = 0; t2 < N2; ++t2) {
         const int orow = t1_0 + r + N1 * t2 - row0;
         if (orow >= 0 && orow < out_rows)
-            out[(((size_t)b * out_rows + orow) * H + h) * 32 + lp] = lds[(t2 * TT + r) * S + lp];
+            IO::store_stream(out + (((size_t)b * out_rows + orow) * H + h) * 32 + lp, lds[(t2 * TT + r) * S + lp]);
     }
 }
 
