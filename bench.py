@@ -23,8 +23,8 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 # L2<->fabric bytes per spectre_mix_forward call at llama1b_128k and per decode sweep, from separate rocprofv3
 # FETCH_SIZE and WRITE_SIZE passes over this same script (scaled by what the counters read for a plain 1 GiB copy;
 # the summary is kept with the other profiler summaries)
-MIX_TRAFFIC_BYTES_128K = 5.48 * 2 ** 30
-DECODE_SWEEP_TRAFFIC_BYTES = (2122.1 + 2056.2) * 2 ** 20
+MIX_TRAFFIC_BYTES_128K = 5.21 * 2 ** 30
+DECODE_SWEEP_TRAFFIC_BYTES = (2085.8 + 2056.2) * 2 ** 20
 # fp32 vector peak without packed math: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s
 VALU_PEAK_GINSTR = 256 * 4 * 16 * 2.4
 
