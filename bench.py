@@ -133,6 +133,9 @@ def sweep(args):
     cases = [("single_head_1k", synth.CONFIGS["single_head_1k"])]
     cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in synth.SWEEP_L]
     cases += [("vit_196", synth.CONFIGS["vit_196"])]
+    # lengths with neither a power-of-two nor an in-LDS plan (padded power-of-two convolution)
+    cases += [("vit_197_cls", dict(B=256, H=12, L=197, d=64, io="f32"))]
+    cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in (1000, 12288, 50000)]
     for name, c in cases:
         B, H, L, d = c["B"], c["H"], c["L"], c["d"]
         dtype = torch.bfloat16 if c["io"] == "bf16" else torch.float32

@@ -31,9 +31,12 @@
  *     launch) and spectre_last_error() describes the reason.  The library never
  *     aborts or throws.
  *   - Supported shapes.  Mixer and cache: d = 64 channels per head.  Transform
- *     lengths: every n <= 512 whose prime factors are 2, 3, 5 or 7 (196 = 4*7*7
- *     among them) and every power of two from 256 to 131072 for the mixer; a power
- *     of two from 256 to 131072 for the cache window N_max.  The gate takes any
+ *     lengths of the mixer: every n <= 512 whose prime factors are 2, 3, 5 or 7
+ *     (196 = 4*7*7 among them) and every power of two from 256 to 131072 have
+ *     their own kernels; every other n <= 65536 is computed exactly as well, as a
+ *     zero-padded power-of-two convolution (2.5 to 5 times the cost of a power of
+ *     two of similar size).  The cache window N_max is a power of two from 256 to
+ *     131072.  The gate takes any
  *     d <= 256, d_g <= 256 and any n_fft >= 2.  spectre_length_supported() answers
  *     for the mixer; anything else returns SPECTRE_EUNSUPPORTED.
  */

@@ -16,6 +16,7 @@
 
 #include "gate.h"
 #include "internal.h"
+#include "mix_chirp.h"
 #include "mix_slab.h"
 #include "prefix.h"
 #include "project.h"
@@ -41,6 +42,7 @@ int fail_hip(hipError_t e, const char *what) {
 // ---------------------------------------------------------------- per-device tables
 struct DeviceTables {
     std::map<int, float2 *> roots;   // n -> device array [n] of exp(-j 2 pi m / n)
+    std::map<int, float2 *> chirp;   // L -> device array: chirp [L], then its filter spectrum [M]
 };
 static std::mutex g_mu;
 static std::map<int, DeviceTables> g_tables;
@@ -75,6 +77,32 @@ int get_roots(int n, const float2 **out) {
         it = t.roots.emplace(n, d).first;
     }
     *out = it->second;
+    return SPECTRE_OK;
+}
+
+// Chirp tables of an arbitrary length L (padded length M): *w [L], *filt [M].
+static int get_chirp(int L, const Pow2Plan &pl, const float2 **w, const float2 **filt) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    std::lock_guard<std::mutex> lk(g_mu);
+    DeviceTables &t = g_tables[dev];
+    auto it = t.chirp.find(L);
+    if (it == t.chirp.end()) {
+        std::vector<float2> h((size_t)L + pl.L);
+        chirp_tables_host(L, pl.L, pl.N1, pl.N2, pl.P, h.data(), h.data() + L);
+        float2 *d = nullptr;
+        e = hipMalloc(reinterpret_cast<void **>(&d), sizeof(float2) * h.size());
+        if (e != hipSuccess) return fail_hip(e, "hipMalloc(chirp)");
+        e = hipMemcpy(d, h.data(), sizeof(float2) * h.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(d);
+            return fail_hip(e, "hipMemcpy(chirp)");
+        }
+        it = t.chirp.emplace(L, d).first;
+    }
+    *w = it->second;
+    *filt = it->second + L;
     return SPECTRE_OK;
 }
 
@@ -115,13 +143,87 @@ const char *spectre_last_error(void) { return g_err.c_str(); }
 
 int spectre_version(void) { return 100; }
 
-// 0 = no kernel, 1 = whole slab in LDS, 2 = four-step power-of-two path.
+// 0 = no kernel, 1 = whole slab in LDS, 2 = four-step power-of-two path, 3 = any other length
+// through a padded power-of-two convolution.
 static int mix_route(int BH, int L, int d) {
     if (d != 64) return 0;
     int N1, N2, P;
     const bool p2 = pow2_split(L, &N1, &N2, &P), sl = slab_supported(L);
     if (sl && (!p2 || BH >= 256)) return 1;
-    return p2 ? 2 : 0;
+    if (p2) return 2;
+    return chirp_padded_length(L) ? 3 : 0;
+}
+
+// Workspace sections of the arbitrary-length route.
+struct ChirpLayout {
+    int M, nph;
+    size_t gp, scr, t1, t2;      // byte sizes
+    size_t total() const { return gp + scr + t1 + t2; }
+};
+static ChirpLayout chirp_layout(int BH, int L, int d) {
+    ChirpLayout c;
+    c.M = chirp_padded_length(L);
+    c.nph = (BH + 31) / 32;
+    c.gp = align256((size_t)BH * c.M * sizeof(float2));
+    c.scr = align256((size_t)mix_chunk_heads(BH, c.M, d) * c.M * (d / 2) * sizeof(float2));
+    c.t1 = align256((size_t)L * c.nph * 32 * sizeof(float2));
+    c.t2 = align256((size_t)c.M * c.nph * 32 * sizeof(float2));
+    return c;
+}
+
+static int mix_chirp(const void *v, const float2 *g, void *out, int B, int L, int H, int d, spectre_dtype io,
+                     void *ws, hipStream_t st) {
+    const int BH = B * H;
+    const ChirpLayout c = chirp_layout(BH, L, d);
+    Pow2Plan pl;
+    int rc = get_pow2_plan(c.M, &pl);
+    if (rc) return rc;
+    const float2 *w = nullptr, *filt = nullptr;
+    rc = get_chirp(L, pl, &w, &filt);
+    if (rc) return rc;
+    char *base = static_cast<char *>(ws);
+    float2 *gp = reinterpret_cast<float2 *>(base);
+    float2 *scr = reinterpret_cast<float2 *>(base + c.gp);
+    float2 *t1 = reinterpret_cast<float2 *>(base + c.gp + c.scr);
+    float2 *t2 = reinterpret_cast<float2 *>(base + c.gp + c.scr + c.t1);
+    const int nph = c.nph, phchunk = mix_chunk_heads(nph, c.M, d);
+
+    // per-head convolution kernel kappa = irfft_L(gate), all heads at once as pseudo-head columns
+    hipError_t e = launch_chirp_pre(g, w, t1, BH, L, nph, st);
+    if (e != hipSuccess) return fail_hip(e, "chirp_pre");
+    for (int ph0 = 0; ph0 < nph; ph0 += phchunk) {
+        const int n = (nph - ph0 < phchunk) ? nph - ph0 : phchunk;
+        e = launch_small_fwd(pl, SPECTRE_F32, t1, scr, L, nph, ph0, n, st);
+        if (e != hipSuccess) return fail_hip(e, "small_fwd(chirp)");
+        e = launch_big(pl, scr, filt, 0, n, 0, st, true);
+        if (e != hipSuccess) return fail_hip(e, "big(chirp)");
+        e = launch_small_inv(pl, SPECTRE_F32, scr, t1, 0, L, nph, ph0, n, st);
+        if (e != hipSuccess) return fail_hip(e, "small_inv(chirp)");
+    }
+    // its periodic extension around index 0 of the padded length, transformed: the data pass's gate
+    e = launch_chirp_post(t1, w, t2, L, c.M, nph, st);
+    if (e != hipSuccess) return fail_hip(e, "chirp_post");
+    for (int ph0 = 0; ph0 < nph; ph0 += phchunk) {
+        const int n = (nph - ph0 < phchunk) ? nph - ph0 : phchunk;
+        e = launch_small_fwd(pl, SPECTRE_F32, t2, scr, c.M, nph, ph0, n, st);
+        if (e != hipSuccess) return fail_hip(e, "small_fwd(kernel)");
+        e = launch_big(pl, scr, nullptr, 0, n, 1, st);
+        if (e != hipSuccess) return fail_hip(e, "big(kernel)");
+        e = launch_chirp_gate(scr, gp, BH, c.M, pl.N1, pl.N2, ph0, n, st);
+        if (e != hipSuccess) return fail_hip(e, "chirp_gate");
+    }
+    // the data: zero-padded to M, first L rows of the result kept
+    const int chunk = mix_chunk_heads(BH, c.M, d);
+    for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
+        const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
+        e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, st);
+        if (e != hipSuccess) return fail_hip(e, "small_fwd");
+        e = launch_big(pl, scr, gp, bh0, nbh, 0, st);
+        if (e != hipSuccess) return fail_hip(e, "big");
+        e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, st);
+        if (e != hipSuccess) return fail_hip(e, "small_inv");
+    }
+    return SPECTRE_OK;
 }
 
 int spectre_length_supported(int n, int d) { return mix_route(1, n, d) != 0; }
@@ -133,6 +235,7 @@ void spectre_shutdown(void) {
     for (auto &kv : g_tables) {
         (void)hipSetDevice(kv.first);
         for (auto &r : kv.second.roots) (void)hipFree(r.second);
+        for (auto &r : kv.second.chirp) (void)hipFree(r.second);
     }
     g_tables.clear();
     (void)hipSetDevice(cur);
@@ -145,6 +248,7 @@ size_t spectre_mix_workspace_bytes(int B, int L, int H, int d, spectre_dtype io)
     const int route = mix_route(BH, L, d);
     if (route == 0) return 0;
     if (route == 1) return 256;
+    if (route == 3) return chirp_layout(BH, L, d).total();
     const int chunk = mix_chunk_heads(BH, L, d);
     return align256((size_t)BH * L * sizeof(float2)) + align256((size_t)chunk * L * (d / 2) * sizeof(float2));
 }
@@ -175,6 +279,7 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         if (e != hipSuccess) return fail_hip(e, "mix_slab");
         return SPECTRE_OK;
     }
+    if (mix_route(BH, L, d) == 3) return mix_chirp(v, static_cast<const float2 *>(g), out, B, L, H, d, io, ws, st);
     Pow2Plan pl;
     int rc = get_pow2_plan(L, &pl);
     if (rc) return rc;

@@ -25,13 +25,14 @@ bool pow2_split(int L, int *N1, int *N2, int *P);
 // Launchers (enqueue only).  `pairs` = d/2 must be 32.  All return hipError_t.
 //   small_fwd : rows of v (tensor [B, rows, H, d], zero beyond `rows`) -> scratch[bh_local][k2][pair][t1]
 //   big       : in-place N1-point transforms on scratch; mode 0 = forward, gate, inverse;
-//               1 = forward only; 2 = inverse only.  gp = expanded gate for mode 0.
+//               1 = forward only; 2 = inverse only.  gp = expanded gate for mode 0, one
+//               [N2][N1] block per head from head bh0 on, or (shared_gate) one block for all.
 //   small_inv : scratch -> rows [row0, row0 + out_rows) of the inverse transform into
 //               out (tensor [B, out_rows, H, d])
 hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
                             int bh0, int nbh, hipStream_t st);
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
-                      hipStream_t st);
+                      hipStream_t st, bool shared_gate = false);
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
                             int out_rows, int H, int bh0, int nbh, hipStream_t st);
 // g [BH, L/2+1] -> gp [BH][N2][N1] in the big kernel's register order, scaled by 1/L and

@@ -145,7 +145,7 @@ __device__ __forceinline__ void exchange(float2 (&x)[16], float2 *buf, int tau) 
 template <int P, int MODE>
 __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const float2 *__restrict__ gp,
                                              const float2 *__restrict__ twN1, int N2, int ppw, int bh0,
-                                             int nplanes_xcd) {
+                                             int nplanes_xcd, int g_step) {
     static_assert(P == 2 || P == 3, "N1 is 256 or 4096");
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
     constexpr bool kCross = (P == 3);                // does the pass 0 <-> 1 exchange span waves?
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
     }
     float2 G[16];
     if (MODE == 0) {
-        const float2 *gsrc = gp + ((size_t)(bh0 + bhl) * N2 + k2) * N1;
+        const float2 *gsrc = gp + ((size_t)(bh0 + bhl * g_step) * N2 + k2) * N1;   // g_step 0: one gate for all
 #pragma unroll
         for (int j = 0; j < 16; ++j) G[j] = gsrc[j * TPC + tau];
     }
@@ -329,7 +329,8 @@ hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, v
 }
 
 template <int P, int MODE>
-static hipError_t big_t(const Pow2Plan &pl, float2 *scr, const float2 *gp, int bh0, int nbh, hipStream_t st) {
+static hipError_t big_t(const Pow2Plan &pl, float2 *scr, const float2 *gp, int bh0, int nbh, bool shared_gate,
+                        hipStream_t st) {
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
     const size_t lds = (size_t)CPI * COLW * sizeof(float2) * (P == 3 ? 2 : 1);
     const int ppw = (P == 2) ? 16 : 4;   // pairs per workgroup; a multiple of CPI dividing 32
@@ -338,20 +339,21 @@ static hipError_t big_t(const Pow2Plan &pl, float2 *scr, const float2 *gp, int b
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)nbh * pl.N2 * (32 / ppw);
     const int planes = nbh * pl.N2;                    // remapping needs the plane count to split 8 ways
-    kern<<<dim3(grid), dim3(256), lds, st>>>(scr, gp, pl.twN1, pl.N2, ppw, bh0, planes % 8 == 0 ? planes : 0);
+    kern<<<dim3(grid), dim3(256), lds, st>>>(scr, gp, pl.twN1, pl.N2, ppw, bh0, planes % 8 == 0 ? planes : 0,
+                                             shared_gate ? 0 : 1);
     return hipGetLastError();
 }
 
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
-                      hipStream_t st) {
+                      hipStream_t st, bool shared_gate) {
     if (pl.P == 2) {
-        if (mode == 0) return big_t<2, 0>(pl, scratch, gp, bh0, nbh, st);
-        if (mode == 1) return big_t<2, 1>(pl, scratch, gp, bh0, nbh, st);
-        if (mode == 2) return big_t<2, 2>(pl, scratch, gp, bh0, nbh, st);
+        if (mode == 0) return big_t<2, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st);
+        if (mode == 1) return big_t<2, 1>(pl, scratch, gp, bh0, nbh, shared_gate, st);
+        if (mode == 2) return big_t<2, 2>(pl, scratch, gp, bh0, nbh, shared_gate, st);
     } else if (pl.P == 3) {
-        if (mode == 0) return big_t<3, 0>(pl, scratch, gp, bh0, nbh, st);
-        if (mode == 1) return big_t<3, 1>(pl, scratch, gp, bh0, nbh, st);
-        if (mode == 2) return big_t<3, 2>(pl, scratch, gp, bh0, nbh, st);
+        if (mode == 0) return big_t<3, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st);
+        if (mode == 1) return big_t<3, 1>(pl, scratch, gp, bh0, nbh, shared_gate, st);
+        if (mode == 2) return big_t<3, 2>(pl, scratch, gp, bh0, nbh, shared_gate, st);
     }
     return hipErrorInvalidValue;
 }

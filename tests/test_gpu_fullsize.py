@@ -49,6 +49,25 @@ def test_headline_shape_fp32_io(oracle):
     assert err <= TOL["f32"]
 
 
+@pytest.mark.parametrize("L,H,io", [(50000, 32, "bf16"), (65535, 3, "f32"), (40000, 40, "f32")])
+def test_long_lengths_without_a_power_of_two_plan(oracle, L, H, io):
+    """The largest padded transforms (131072 points) of the arbitrary-length route, several scratch groups
+    and a partly filled pseudo-head of gate sequences (H = 40)."""
+    from paper_2502_18394_amd import binding
+    B, d = 1, 64
+    print(f"case L={L} H={H} io={io}", flush=True)
+    vals, store = synth.tokens(synth.BASE_SEED + L, (B, L, H, d), io)
+    g = synth.random_gate(synth.BASE_SEED + L + 1, B, H, L)
+    out = binding.mix_forward(to_device(store, io), torch.from_numpy(g).cuda())
+    torch.cuda.synchronize()
+    heads = sorted({0, H // 2, H - 1})
+    got = from_device(out[:, :, heads, :].contiguous())
+    want = oracle.mix_forward(vals[:, :, heads, :].astype(np.float64), g[:, heads].astype(np.complex128))
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL[io]
+
+
 def test_gate_plus_mixer_end_to_end_128k(oracle):
     """The benchmark's step: gate from the query rows (per-head weights, F = 65537), then the mixer."""
     from paper_2502_18394_amd import binding

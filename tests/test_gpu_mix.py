@@ -104,10 +104,34 @@ def test_vit_config_full_size(oracle):
     assert err <= 1e-5
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,L,H", [(1, 11, 1), (2, 197, 3), (1, 1, 2), (1, 1000, 2), (1, 1031, 1), (2, 3000, 2),
+                                   (1, 12289, 1), (3, 640, 40), (1, 3 * 4096, 2)])
+def test_any_other_length(oracle, B, L, H, io):
+    """Lengths with neither a power-of-two nor an in-LDS plan (primes, 197 = 14*14 patches + a class
+    token, 1000, 3*2^k): padded power-of-two convolution with a chirp-z evaluated kernel."""
+    print(f"case B={B} L={L} H={H} io={io}", flush=True)
+    got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 11 * L + H)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL[io]
+
+
+def test_any_other_length_identity_and_shift(oracle):
+    B, L, H, d, s = 1, 1000, 2, 64, 333
+    k = np.arange(L // 2 + 1)
+    g = np.ones((B, H, L // 2 + 1), np.complex64)
+    got, want, vals = run_case(oracle, B, L, H, d, "f32", seed=9, gate=g)
+    assert rel_l2(got, vals) <= 1e-5
+    g = np.broadcast_to(np.exp(-2j * np.pi * ((k * s) % L) / L), (B, H, L // 2 + 1)).astype(np.complex64)
+    got, want, vals = run_case(oracle, B, L, H, d, "f32", seed=10, gate=np.ascontiguousarray(g))
+    assert rel_l2(got, np.roll(vals, s, axis=1)) <= 1e-5
+
+
 def test_unsupported_lengths_are_refused():
     from paper_2502_18394_amd import binding
-    v = torch.zeros((1, 11, 1, 64), device="cuda")
-    g = torch.zeros((1, 1, 6), dtype=torch.complex64, device="cuda")
+    v = torch.zeros((1, 65537, 1, 64), device="cuda")
+    g = torch.zeros((1, 1, 32769), dtype=torch.complex64, device="cuda")
     with pytest.raises(binding.SpectreError) as e:
         binding.mix_forward(v, g)
     assert e.value.code == binding.EUNSUPPORTED
