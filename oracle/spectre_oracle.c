@@ -35,7 +35,15 @@
  *   - positional phase multiplies bin k by exp(+j 2 pi k p / n) for one scalar
  *     position p per call;
  *   - the optional Toeplitz update of step 3b is a zero-padded "same" convolution
- *     along the frequency axis of the F stored bins.
+ *     along the frequency axis of the F stored bins;
+ *   - wavelet refinement (Sec. 3.5; the wavelet family, the depth and the shape of
+ *     the gates are not given): the orthonormal Haar transform, J <= (number of
+ *     times 2 divides n) levels, coefficients stored coarse to fine; the MLP emits
+ *     one gate per band and channel ("channel-wise level gates", (J+1) x d values:
+ *     band 0 = the coarse approximation, band l = the details of level l, level 1
+ *     the finest) which every coefficient of that band shares; the gates are the
+ *     MLP output as is (no squashing); the controller that skips the module is the
+ *     caller's business.
  *
  * Complex arrays are interleaved (re, im) doubles.  Tensors are row-major with
  * the index order written in each comment.  No function here keeps state.
@@ -522,6 +530,135 @@ int so_prefix_readout_window(int B, int H, int d, int N, int Lw, const double *s
         if (so_irfft(N, (double *)Y, x, method)) fail = 1;
         for (int i = 0; i < Lw; ++i)
             out[(((size_t)b * Lw + i) * H + h) * d + c] = x[N - Lw + i];
+        free(x);
+    }
+    return fail ? -2 : 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Wavelet Refinement Module, Sec. 3.5 steps (a)-(d), under the reading in this
+ * file's header.
+ *
+ * Orthonormal Haar analysis of J levels along one column of n values (2^J must
+ * divide n).  One level maps a run c[0..len) to averages a[i] = (c[2i] +
+ * c[2i+1])/sqrt 2 and details d[i] = (c[2i] - c[2i+1])/sqrt 2; the averages are
+ * analysed again.  Output order: [a_J | d_J | d_(J-1) | ... | d_1], i.e. the
+ * details of level l sit at indices n/2^l .. n/2^(l-1) - 1. */
+int so_haar_fwd(int n, int J, const double *x, double *w) {
+    if (n < 1 || J < 0 || (J > 0 && (n % (1 << J)) != 0)) return -1;
+    double *cur = (double *)malloc(sizeof(double) * (size_t)n);
+    if (!cur) return -2;
+    memcpy(cur, x, sizeof(double) * (size_t)n);
+    memcpy(w, x, sizeof(double) * (size_t)n);
+    int len = n;
+    for (int l = 1; l <= J; ++l) {
+        int half = len / 2;
+        for (int i = 0; i < half; ++i) {
+            w[i] = (cur[2 * i] + cur[2 * i + 1]) / sqrt(2.0);
+            w[half + i] = (cur[2 * i] - cur[2 * i + 1]) / sqrt(2.0);
+        }
+        memcpy(cur, w, sizeof(double) * (size_t)half);
+        len = half;
+    }
+    free(cur);
+    return 0;
+}
+
+/* Synthesis: the inverse of so_haar_fwd (the transform is orthogonal, so this is
+ * its transpose): c[2i] = (a[i] + d[i])/sqrt 2, c[2i+1] = (a[i] - d[i])/sqrt 2,
+ * from the coarsest level up. */
+int so_haar_inv(int n, int J, const double *w, double *x) {
+    if (n < 1 || J < 0 || (J > 0 && (n % (1 << J)) != 0)) return -1;
+    double *cur = (double *)malloc(sizeof(double) * (size_t)n);
+    if (!cur) return -2;
+    memcpy(x, w, sizeof(double) * (size_t)n);
+    int len = n >> J;
+    for (int l = J; l >= 1; --l) {
+        for (int i = 0; i < len; ++i) {
+            cur[2 * i] = (x[i] + x[len + i]) / sqrt(2.0);
+            cur[2 * i + 1] = (x[i] - x[len + i]) / sqrt(2.0);
+        }
+        memcpy(x, cur, sizeof(double) * (size_t)(2 * len));
+        len *= 2;
+    }
+    free(cur);
+    return 0;
+}
+
+/* Band of coefficient i in so_haar_fwd's output order: 0 for the approximation,
+ * l for a detail of level l. */
+static int haar_band(int i, int n, int J) {
+    if (i < (n >> J)) return 0;
+    int l = J;
+    while (i >= (n >> (l - 1))) --l;
+    return l;
+}
+
+/* Step (b): level gates from the pooled query.  qbar as in so_gate; hid =
+ * GELU(qbar W1 + b1); s = hid W2 + b2, read as [J+1 bands][d channels].
+ *   gamma, beta [Hg,d]; W1 [Hg,d,dw]; b1 [Hg,dw]; W2 [Hg,dw,(J+1)*d]; b2 [Hg,(J+1)*d].
+ *   s_out [B,H,J+1,d]. */
+int so_wrm_gates(int B, int H, int d, int dw, int J, int Hg,
+                 const double *sum_q, double inv_count,
+                 const double *gamma, const double *beta, double eps,
+                 const double *W1, const double *b1,
+                 const double *W2, const double *b2, double *s_out) {
+    if (!(Hg == H || Hg == 1) || d < 1 || dw < 1 || J < 0) return -1;
+    int nout = (J + 1) * d;
+    double *qbar = (double *)malloc(sizeof(double) * (size_t)(d + dw));
+    if (!qbar) return -2;
+    double *hid = qbar + d;
+    for (int b = 0; b < B; ++b) for (int h = 0; h < H; ++h) {
+        int hp = (Hg == 1) ? 0 : h;
+        const double *sq = sum_q + ((size_t)b * H + h) * d;
+        double mean = 0.0, var = 0.0;
+        for (int i = 0; i < d; ++i) mean += inv_count * sq[i];
+        mean /= d;
+        for (int i = 0; i < d; ++i) {
+            double c = inv_count * sq[i] - mean;
+            var += c * c;
+        }
+        var /= d;
+        for (int i = 0; i < d; ++i)
+            qbar[i] = gamma[(size_t)hp * d + i] * (inv_count * sq[i] - mean) / sqrt(var + eps)
+                    + beta[(size_t)hp * d + i];
+        for (int j = 0; j < dw; ++j) {
+            double a = b1[(size_t)hp * dw + j];
+            for (int i = 0; i < d; ++i) a += qbar[i] * W1[((size_t)hp * d + i) * dw + j];
+            hid[j] = 0.5 * a * (1.0 + erf(a / sqrt(2.0)));
+        }
+        double *s = s_out + ((size_t)b * H + h) * nout;
+        for (int o = 0; o < nout; ++o) {
+            double a = b2[(size_t)hp * nout + o];
+            for (int j = 0; j < dw; ++j) a += hid[j] * W2[((size_t)hp * dw + j) * nout + o];
+            s[o] = a;
+        }
+    }
+    free(qbar);
+    return 0;
+}
+
+/* Steps (a), (c), (d): for every column, analyse, scale every coefficient by the
+ * gate of its band and channel, synthesise, and add the result to the input.
+ *   V, out [B,L,H,d];  s [B,H,J+1,d]. */
+int so_wrm_apply(int B, int L, int H, int d, int J, const double *V, const double *s, double *out) {
+    if (L < 1 || J < 0 || (J > 0 && (L % (1 << J)) != 0)) return -1;
+    long long ncol = (long long)B * H * d;
+    int fail = 0;
+#pragma omp parallel for schedule(static)
+    for (long long col = 0; col < ncol; ++col) {
+        int c = (int)(col % d);
+        int h = (int)((col / d) % H);
+        int b = (int)(col / ((long long)d * H));
+        double *x = (double *)malloc(sizeof(double) * 3 * (size_t)L);
+        if (!x) { fail = 1; continue; }
+        double *w = x + L, *ref = w + L;
+        for (int t = 0; t < L; ++t) x[t] = V[(((size_t)b * L + t) * H + h) * d + c];
+        if (so_haar_fwd(L, J, x, w)) fail = 1;
+        const double *sb = s + ((size_t)b * H + h) * (size_t)(J + 1) * d;
+        for (int i = 0; i < L; ++i) w[i] *= sb[(size_t)haar_band(i, L, J) * d + c];
+        if (so_haar_inv(L, J, w, ref)) fail = 1;
+        for (int t = 0; t < L; ++t) out[(((size_t)b * L + t) * H + h) * d + c] = x[t] + ref[t];
         free(x);
     }
     return fail ? -2 : 0;

@@ -165,6 +165,61 @@ def mix_forward(V, g, method=FAST):
     return out
 
 
+def haar_fwd(x, J):
+    """Orthonormal Haar analysis of a 1-D array, J levels, output [a_J | d_J | ... | d_1] (Sec. 3.5 step a)."""
+    x = _f64(x)
+    w = np.empty_like(x)
+    rc = _L().so_haar_fwd(ctypes.c_int(x.shape[0]), ctypes.c_int(J), _p(x), _p(w))
+    if rc:
+        raise RuntimeError(f"so_haar_fwd rc={rc}")
+    return w
+
+
+def haar_inv(w, J):
+    w = _f64(w)
+    x = np.empty_like(w)
+    rc = _L().so_haar_inv(ctypes.c_int(w.shape[0]), ctypes.c_int(J), _p(w), _p(x))
+    if rc:
+        raise RuntimeError(f"so_haar_inv rc={rc}")
+    return x
+
+
+def wrm_gates(sum_q, inv_count, params, J):
+    """Level gates s [B,H,J+1,d] (Sec. 3.5 step b).  ``params``: ln_gamma, ln_beta [Hg,d], ln_eps,
+    W1 [Hg,d,dw], b1 [Hg,dw], W2 [Hg,dw,(J+1)*d], b2 [Hg,(J+1)*d]."""
+    sum_q = _f64(sum_q)
+    B, H, d = sum_q.shape
+    W1 = _f64(params["W1"])
+    Hg, d_, dw = W1.shape
+    assert d_ == d
+    nout = (J + 1) * d
+    W2, b1, b2 = _f64(params["W2"]), _f64(params["b1"]), _f64(params["b2"])
+    gam, bet = _f64(params["ln_gamma"]), _f64(params["ln_beta"])
+    assert W2.shape == (Hg, dw, nout) and b2.shape == (Hg, nout) and b1.shape == (Hg, dw)
+    assert gam.shape == (Hg, d) and bet.shape == (Hg, d)
+    out = np.empty((B, H, J + 1, d), dtype=np.float64)
+    rc = _L().so_wrm_gates(ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(dw), ctypes.c_int(J),
+                           ctypes.c_int(Hg), _p(sum_q), ctypes.c_double(inv_count), _p(gam), _p(bet),
+                           ctypes.c_double(float(params["ln_eps"])), _p(W1), _p(b1), _p(W2), _p(b2), _p(out))
+    if rc:
+        raise RuntimeError(f"so_wrm_gates rc={rc}")
+    return out
+
+
+def wrm_apply(V, s, J):
+    """V + iDWT(s * DWT(V)) along the sequence axis (Sec. 3.5 steps a, c, d); V [B,L,H,d], s [B,H,J+1,d]."""
+    V = _f64(V)
+    s = _f64(s)
+    B, L, H, d = V.shape
+    assert s.shape == (B, H, J + 1, d)
+    out = np.empty_like(V)
+    rc = _L().so_wrm_apply(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(J),
+                           _p(V), _p(s), _p(out))
+    if rc:
+        raise RuntimeError(f"so_wrm_apply rc={rc}")
+    return out
+
+
 class PrefixCache:
     """State of Algorithm 1 for B*H heads; ``t`` counts the tokens appended."""
 

@@ -69,6 +69,31 @@ def gate_params(seed, Hg, d, n_fft, d_g=D_GATE, modrelu=True, std=0.02):
     return p
 
 
+def wrm_params(seed, Hg, d, levels, d_w=D_GATE, std=0.02, gate_std=0.5):
+    """Wavelet-refinement MLP (Sec. 3.5 step b): W1, b1 ~ N(0, std), LayerNorm as for the gate; the output
+    layer ~ N(0, gate_std) so that the level gates are O(1) and every band visibly matters.
+    W2 [Hg, d_w, (levels+1)*d], b2 [Hg, (levels+1)*d], float32."""
+    rng = np.random.default_rng(seed)
+    nout = (levels + 1) * d
+
+    def nrm(sd, *s):
+        return (sd * rng.standard_normal(s, dtype=np.float32)).astype(np.float32)
+
+    return dict(Hg=Hg, d=d, d_w=d_w, levels=levels, ln_eps=LN_EPS,
+                ln_gamma=(1.0 + nrm(std, Hg, d)).astype(np.float32), ln_beta=nrm(std, Hg, d),
+                W1=nrm(std, Hg, d, d_w), b1=nrm(std, Hg, d_w),
+                W2=nrm(gate_std, Hg, d_w, nout), b2=nrm(gate_std, Hg, nout))
+
+
+def max_wavelet_levels(n):
+    """How many times 2 divides n: the deepest Haar analysis of an n-point column."""
+    J = 0
+    while n > 1 and n % 2 == 0:
+        n //= 2
+        J += 1
+    return J
+
+
 def toeplitz_taps(seed, Hg, r, std=0.02):
     """Complex taps t_{-r..r} ~ N(0, std) for the optional low-rank gate update, complex64 [Hg, 2r+1]."""
     rng = np.random.default_rng(seed)
