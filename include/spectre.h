@@ -143,6 +143,40 @@ int spectre_project(const void *x, const float *Wq, const float *Wv, int Hw, int
                     void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Wavelet refinement, Sec. 3.5 steps (a)-(d): out = v + iDWT( s * DWT(v) ) along the sequence axis
+ * of every (b, h, channel) column.  The section names neither the wavelet nor the shape of the
+ * gates; this library implements the orthonormal Haar wavelet with `levels` = J analysis levels
+ * (2^J must divide L) and one real gate per band and channel: s [B, H, J+1, d], band 0 = the
+ * coarse approximation (L / 2^J coefficients per column), band l = 1..J the details of level l
+ * (level 1 = differences of adjacent rows).  The learned controller that skips the module is the
+ * caller's: skipping means not calling.
+ *
+ * spectre_wrm_gates - step (b): s = W2' GELU(qbar W1 + b1) + b2 with qbar the LayerNorm of the pooled
+ * query exactly as in spectre_gate (same q / q_is_pooled / inv_count arguments).
+ *   P->W1 [Hg, d, d_w], b1 [Hg, d_w], W2 [Hg, d_w, (J+1)*d] (input-major), b2 [Hg, (J+1)*d],
+ *   ln_gamma, ln_beta [Hg, d]; Hg = H or 1; d <= 256, d_w <= 256, levels <= 30.
+ *   s_out  float [B, H, J+1, d].
+ *
+ * spectre_wrm_apply - steps (a), (c), (d) for v, out [B, L, H, d] of dtype io, d = 64.  out may be v
+ * itself (in place) but must not overlap it otherwise.  One pass over v when J <= 8; above that one
+ * extra read of v (sums of 256-row tiles for the coarse levels).
+ */
+typedef struct {
+    int Hg, d, d_w, levels;
+    const float *ln_gamma, *ln_beta;
+    float ln_eps;
+    const float *W1, *b1, *W2, *b2;
+} spectre_wrm_params;
+
+size_t spectre_wrm_gates_workspace_bytes(int B, int L, int H, const spectre_wrm_params *P /*host*/);
+int spectre_wrm_gates(const void *q, int q_is_pooled, spectre_dtype q_dtype, double inv_count,
+                      const spectre_wrm_params *P /*host*/, int B, int L, int H, void *s_out, void *ws,
+                      size_t ws_bytes, void *stream);
+size_t spectre_wrm_apply_workspace_bytes(int B, int L, int H, int d, int levels);
+int spectre_wrm_apply(const void *v, const void *s, void *out, int B, int L, int H, int d, int levels,
+                      spectre_dtype io, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * spectre_mix_forward - the mixing layer, Sec. 3.2 steps 2 and 4 (Eq. 3, Eq. 4): for every
  * sequence b, head h and channel c
  *        out[b, :, h, c] = irfft_L( g[b, h, :] * rfft_L( v[b, :, h, c] ) ).

@@ -33,6 +33,12 @@ class GateParamsC(ctypes.Structure):
                 ("modrelu_bias", ctypes.c_void_p), ("toeplitz", ctypes.c_void_p), ("toeplitz_r", ctypes.c_int)]
 
 
+class WrmParamsC(ctypes.Structure):
+    _fields_ = [("Hg", ctypes.c_int), ("d", ctypes.c_int), ("d_w", ctypes.c_int), ("levels", ctypes.c_int),
+                ("ln_gamma", ctypes.c_void_p), ("ln_beta", ctypes.c_void_p), ("ln_eps", ctypes.c_float),
+                ("W1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("W2", ctypes.c_void_p), ("b2", ctypes.c_void_p)]
+
+
 class PrefixCacheC(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("d", ctypes.c_int), ("N_max", ctypes.c_int),
                 ("t", ctypes.c_longlong),
@@ -49,7 +55,8 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.spectre_last_error.restype = ctypes.c_char_p
         for name in ("spectre_gate_workspace_bytes", "spectre_mix_workspace_bytes", "spectre_prefix_bytes",
-                     "spectre_project_workspace_bytes",
+                     "spectre_project_workspace_bytes", "spectre_wrm_gates_workspace_bytes",
+                     "spectre_wrm_apply_workspace_bytes",
                      "spectre_prefix_update_workspace_bytes", "spectre_prefix_readout_workspace_bytes",
                      "spectre_prefix_step_workspace_bytes"):
             getattr(L, name).restype = ctypes.c_size_t
@@ -192,6 +199,65 @@ def gate(q, P, inv_count, pooled=False, phase_pos=0, g_out=None, ws=None, stream
                               ctypes.c_int(H), ctypes.c_longlong(int(phase_pos)), _dev(g_out, "g_out"),
                               wsp, wsn, _stream(stream)))
     return g_out
+
+
+class WrmParams:
+    """Device copies of the wavelet-refinement MLP (Sec. 3.5 step b) plus the C parameter block.
+    W1 [Hg,d,d_w], b1 [Hg,d_w], W2 [Hg,d_w,(levels+1)*d], b2 [Hg,(levels+1)*d]."""
+
+    def __init__(self, params, device="cuda"):
+        self.t = {k: torch.as_tensor(params[k], dtype=torch.float32).to(device).contiguous()
+                  for k in ("ln_gamma", "ln_beta", "W1", "b1", "W2", "b2")}
+        Hg, d, d_w = self.t["W1"].shape
+        self.levels = int(params["levels"])
+        assert tuple(self.t["W2"].shape) == (Hg, d_w, (self.levels + 1) * d)
+        self.Hg, self.d, self.d_w = Hg, d, d_w
+        p = lambda k: ctypes.c_void_p(self.t[k].data_ptr())
+        self.c = WrmParamsC(Hg, d, d_w, self.levels, p("ln_gamma"), p("ln_beta"), float(params["ln_eps"]),
+                            p("W1"), p("b1"), p("W2"), p("b2"))
+
+
+def wrm_gates(q, P, inv_count, pooled=False, s_out=None, ws=None, stream=None):
+    """Level gates float32 [B,H,levels+1,d] from query rows [B,L,H,d] or (pooled=True) their float64 sum [B,H,d]."""
+    if pooled:
+        if q.dtype != torch.float64:
+            raise TypeError("pooled q must be float64 [B,H,d]")
+        B, H, d = q.shape
+        L, code = 1, F32
+    else:
+        B, L, H, d = q.shape
+        code = _dtype_code(q)
+    if d != P.d:
+        raise ValueError("d mismatch")
+    if s_out is None:
+        s_out = torch.empty((B, H, P.levels + 1, d), dtype=torch.float32, device=q.device)
+    need = lib().spectre_wrm_gates_workspace_bytes(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.byref(P.c))
+    ws, wsp, wsn = _workspace(need, q.device, ws)
+    _check(lib().spectre_wrm_gates(_dev(q, "q"), ctypes.c_int(1 if pooled else 0), ctypes.c_int(code),
+                                   ctypes.c_double(inv_count), ctypes.byref(P.c), ctypes.c_int(B), ctypes.c_int(L),
+                                   ctypes.c_int(H), _dev(s_out, "s_out"), wsp, wsn, _stream(stream)))
+    return s_out
+
+
+def wrm_apply_workspace_bytes(B, L, H, d, levels):
+    return int(lib().spectre_wrm_apply_workspace_bytes(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H),
+                                                       ctypes.c_int(d), ctypes.c_int(levels)))
+
+
+def wrm_apply(v, s, out=None, ws=None, stream=None):
+    """v + iDWT(s * DWT(v)) along the sequence axis (Sec. 3.5 steps a, c, d); v [B,L,H,d] f32/bf16,
+    s float32 [B,H,levels+1,d].  Pass out=v for in-place operation."""
+    B, L, H, d = v.shape
+    if s.dtype != torch.float32 or s.ndim != 4 or tuple(s.shape[:2]) != (B, H) or s.shape[3] != d:
+        raise ValueError("s must be float32 [B,H,levels+1,d]")
+    levels = s.shape[2] - 1
+    if out is None:
+        out = torch.empty_like(v)
+    ws, wsp, wsn = _workspace(wrm_apply_workspace_bytes(B, L, H, d, levels), v.device, ws)
+    _check(lib().spectre_wrm_apply(_dev(v, "v"), _dev(s, "s"), _dev(out, "out"), ctypes.c_int(B), ctypes.c_int(L),
+                                   ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(levels),
+                                   ctypes.c_int(_dtype_code(v)), wsp, wsn, _stream(stream)))
+    return out
 
 
 class PrefixCache:

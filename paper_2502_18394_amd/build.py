@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspectre_hip.so")
 PROBE = os.path.join(HERE, "membw_probe")            # stand-alone bandwidth probe (not part of the library)
-SOURCES = ["api.hip", "mix_pow2.hip", "mix_slab.hip", "mix_chirp.hip", "gate.hip", "prefix.hip", "project.hip"]
+SOURCES = ["api.hip", "mix_pow2.hip", "mix_slab.hip", "mix_chirp.hip", "gate.hip", "prefix.hip", "project.hip", "wrm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]

@@ -20,6 +20,7 @@
 #include "mix_slab.h"
 #include "prefix.h"
 #include "project.h"
+#include "wrm.h"
 
 namespace spectre {
 
@@ -409,6 +410,93 @@ int spectre_project(const void *x, const float *Wq, const float *Wv, int Hw, int
         e = launch_project_pooled(sum_x, Wq, Hw, B, H, static_cast<double *>(sum_q), st);
         if (e != hipSuccess) return fail_hip(e, "project_pooled");
     }
+    return SPECTRE_OK;
+}
+
+// ------------------------------------------------------------------------------------------ wavelet refinement
+static int check_wrm_params(const spectre_wrm_params *P, int H, const char *who) {
+    if (!P) return fail(SPECTRE_EINVAL, "%s: null parameters", who);
+    if (!(P->Hg == H || P->Hg == 1)) return fail(SPECTRE_EINVAL, "%s: Hg must be H or 1", who);
+    if (P->d < 1 || P->d > 256) return fail(SPECTRE_EUNSUPPORTED, "%s: d=%d not in 1..256", who, P->d);
+    if (P->d_w < 1 || P->d_w > 256) return fail(SPECTRE_EUNSUPPORTED, "%s: d_w=%d not in 1..256", who, P->d_w);
+    if (P->levels < 0 || P->levels > 30) return fail(SPECTRE_EINVAL, "%s: levels=%d not in 0..30", who, P->levels);
+    if (!P->ln_gamma || !P->ln_beta || !P->W1 || !P->b1 || !P->W2 || !P->b2)
+        return fail(SPECTRE_EINVAL, "%s: null parameter array", who);
+    if (!(P->ln_eps >= 0.0f)) return fail(SPECTRE_EINVAL, "%s: ln_eps must be >= 0", who);
+    return SPECTRE_OK;
+}
+
+size_t spectre_wrm_gates_workspace_bytes(int B, int L, int H, const spectre_wrm_params *P) {
+    if (!P || B < 1 || L < 1 || H < 1 || P->d < 1) return 0;
+    return align256(gate_partial_bytes(B, L, H, P->d)) + align256((size_t)B * H * P->d * sizeof(double));
+}
+
+int spectre_wrm_gates(const void *q, int q_is_pooled, spectre_dtype q_dtype, double inv_count,
+                      const spectre_wrm_params *P, int B, int L, int H, void *s_out, void *ws, size_t ws_bytes,
+                      void *stream) {
+    if (!q || !s_out) return fail(SPECTRE_EINVAL, "wrm_gates: null pointer");
+    if (B < 1 || H < 1 || (!q_is_pooled && L < 1)) return fail(SPECTRE_EINVAL, "wrm_gates: non-positive size");
+    if (!q_is_pooled && q_dtype != SPECTRE_F32 && q_dtype != SPECTRE_BF16)
+        return fail(SPECTRE_EINVAL, "wrm_gates: bad dtype");
+    if (!(inv_count == inv_count)) return fail(SPECTRE_EINVAL, "wrm_gates: inv_count is NaN");
+    int rc = check_wrm_params(P, H, "wrm_gates");
+    if (rc) return rc;
+    if (q_is_pooled) L = 1;
+    if ((long long)B * H * P->d > 0x7fffffffLL) return fail(SPECTRE_EUNSUPPORTED, "wrm_gates: B*H*d too large");
+    const size_t need = spectre_wrm_gates_workspace_bytes(B, L, H, P);
+    if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "wrm_gates: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "wrm_gates: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *w = static_cast<char *>(ws);
+    double *partial = reinterpret_cast<double *>(w);
+    w += align256(gate_partial_bytes(B, L, H, P->d));
+    double *sum_ws = reinterpret_cast<double *>(w);
+    const double *sum_q = static_cast<const double *>(q);
+    if (!q_is_pooled) {
+        hipError_t e = launch_pool((int)q_dtype, q, partial, sum_ws, B, L, H, P->d, st);
+        if (e != hipSuccess) return fail_hip(e, "pool");
+        sum_q = sum_ws;
+    }
+    WrmDev D;
+    D.Hg = P->Hg; D.d = P->d; D.d_w = P->d_w; D.levels = P->levels;
+    D.ln_gamma = P->ln_gamma; D.ln_beta = P->ln_beta; D.ln_eps = P->ln_eps;
+    D.W1 = P->W1; D.b1 = P->b1; D.W2 = P->W2; D.b2 = P->b2;
+    hipError_t e = launch_wrm_gates(sum_q, inv_count, D, B, H, static_cast<float *>(s_out), st);
+    if (e != hipSuccess) return fail_hip(e, "wrm_gates");
+    return SPECTRE_OK;
+}
+
+size_t spectre_wrm_apply_workspace_bytes(int B, int L, int H, int d, int levels) {
+    if (B < 1 || L < 1 || H < 1 || d != 64 || levels < 0 || levels > 30) return 0;
+    if (levels > 0 && (L % (1LL << levels)) != 0) return 0;
+    return 256 + 2 * align256(wrm_scratch_floats(B * H, L, levels) * sizeof(float));
+}
+
+int spectre_wrm_apply(const void *v, const void *s, void *out, int B, int L, int H, int d, int levels,
+                      spectre_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    if (!v || !s || !out) return fail(SPECTRE_EINVAL, "wrm_apply: null pointer");
+    if (B < 1 || L < 1 || H < 1 || d < 1) return fail(SPECTRE_EINVAL, "wrm_apply: non-positive size");
+    if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "wrm_apply: bad dtype");
+    if (levels < 0 || levels > 30) return fail(SPECTRE_EINVAL, "wrm_apply: levels=%d not in 0..30", levels);
+    if (levels > 0 && (L % (1LL << levels)) != 0)
+        return fail(SPECTRE_EINVAL, "wrm_apply: 2^%d does not divide L=%d", levels, L);
+    if (d != 64) return fail(SPECTRE_EUNSUPPORTED, "wrm_apply: d=%d (only 64 is built)", d);
+    if ((long long)B * H > 65535) return fail(SPECTRE_EUNSUPPORTED, "wrm_apply: B*H above 65535");
+    if (levels > kWrmTileLevels && L > 262144)
+        return fail(SPECTRE_EUNSUPPORTED, "wrm_apply: more than 8 levels needs L <= 262144");
+    const size_t bytes = (size_t)B * L * H * d * (io == SPECTRE_BF16 ? 2 : 4);
+    const char *vb = static_cast<const char *>(v), *ob = static_cast<const char *>(out);
+    if (vb != ob && vb < ob + bytes && ob < vb + bytes)
+        return fail(SPECTRE_EINVAL, "wrm_apply: out overlaps v without being v");
+    const size_t need = spectre_wrm_apply_workspace_bytes(B, L, H, d, levels);
+    if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "wrm_apply: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "wrm_apply: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t part = align256(wrm_scratch_floats(B * H, L, levels) * sizeof(float));
+    float *tile_sums = static_cast<float *>(ws);
+    float *upper = reinterpret_cast<float *>(static_cast<char *>(ws) + part);
+    hipError_t e = launch_wrm_apply((int)io, v, static_cast<const float *>(s), out, tile_sums, upper, B, L, H, levels, st);
+    if (e != hipSuccess) return fail_hip(e, "wrm_apply");
     return SPECTRE_OK;
 }
 

@@ -1,0 +1,106 @@
+"""GPU parity of the wavelet refinement (Sec. 3.5) against the fp64 oracle.
+
+The oracle analyses, scales and synthesises every column with the Haar transform; the library
+evaluates the same module through block means, so the two share no step."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import TOL, f64, from_device, rel_l2, to_device
+from paper_2502_18394_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def level_gates(seed, B, H, J, d=64):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((B, H, J + 1, d)).astype(np.float32)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,L,H,J", [(1, 1024, 1, 10), (2, 196, 3, 2), (1, 8192, 4, 13), (2, 512, 2, 9), (1, 256, 2, 8),
+                                     (1, 300, 2, 2), (3, 7, 2, 0), (1, 96, 1, 5), (2, 4096, 3, 6), (1, 2, 1, 1),
+                                     (1, 3 * 4096, 2, 12), (1, 1000, 2, 3), (1, 2048, 2, 4), (1, 131072, 2, 17)])
+def test_wrm_apply_matches_oracle(oracle, B, L, H, J, io):
+    from paper_2502_18394_amd import binding
+    print(f"case B={B} L={L} H={H} J={J} io={io}", flush=True)
+    vals, store = synth.tokens(300 + L + J, (B, L, H, 64), io)
+    s = level_gates(301 + L, B, H, J)
+    out = binding.wrm_apply(to_device(store, io), torch.from_numpy(s).cuda())
+    torch.cuda.synchronize()
+    want = oracle.wrm_apply(vals.astype(np.float64), s.astype(np.float64), J)
+    err = rel_l2(from_device(out), want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL[io]
+
+
+def test_wrm_special_gates_and_in_place(oracle):
+    from paper_2502_18394_amd import binding
+    B, L, H, J = 1, 2048, 2, 11
+    vals, store = synth.tokens(310, (B, L, H, 64), "f32")
+    v = to_device(store, "f32")
+    zero = torch.zeros((B, H, J + 1, 64), device="cuda")
+    assert torch.equal(binding.wrm_apply(v, zero), v)                         # gates 0: the module is skipped
+    assert rel_l2(from_device(binding.wrm_apply(v, zero + 1.0)), 2.0 * vals) <= 1e-6
+    s = zero.clone()
+    s[:, :, 0] = 1.0                                                           # coarsest band only: + column mean
+    got = from_device(binding.wrm_apply(v, s))
+    assert rel_l2(got, vals + vals.mean(axis=1, keepdims=True)) <= 1e-6
+    sr = torch.from_numpy(level_gates(311, B, H, J)).cuda()
+    ref = binding.wrm_apply(v, sr).clone()
+    w = v.clone()
+    binding.wrm_apply(w, sr, out=w)                                            # in place
+    torch.cuda.synchronize()
+    assert torch.equal(w, ref)
+
+
+@pytest.mark.parametrize("shared,pooled,io", [(False, False, "bf16"), (True, False, "f32"), (False, True, "f32")])
+def test_wrm_gates_match_oracle(oracle, shared, pooled, io):
+    from paper_2502_18394_amd import binding
+    B, L, H, d, J = 2, 1024, 3, 64, 10
+    p = synth.wrm_params(320, 1 if shared else H, d, J)
+    P = binding.WrmParams(p)
+    qv, qstore = synth.tokens(321, (B, L, H, d), io)
+    sum_q = oracle.pool_q(qv.astype(np.float64))
+    if pooled:
+        s = binding.wrm_gates(torch.from_numpy(sum_q).cuda(), P, 1.0 / L, pooled=True)
+    else:
+        s = binding.wrm_gates(to_device(qstore, io), P, 1.0 / L)
+    torch.cuda.synchronize()
+    want = oracle.wrm_gates(sum_q, 1.0 / L, f64(p), J)
+    err = rel_l2(s.cpu().numpy(), want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= 1e-5
+
+
+def test_mixer_then_refinement_end_to_end(oracle):
+    """Gate -> mixer -> level gates -> refinement on one query/value pair, against the oracle chain."""
+    from paper_2502_18394_amd import binding
+    B, L, H, d = 1, 4096, 2, 64
+    J = synth.max_wavelet_levels(L)
+    vals, vstore = synth.tokens(330, (B, L, H, d), "f32")
+    qv, qstore = synth.tokens(331, (B, L, H, d), "f32")
+    gp, wp = synth.gate_params(332, H, d, L), synth.wrm_params(333, H, d, J)
+    q = to_device(qstore, "f32")
+    g = binding.gate(q, binding.GateParams(gp), 1.0 / L)
+    mixed = binding.mix_forward(to_device(vstore, "f32"), g)
+    s = binding.wrm_gates(q, binding.WrmParams(wp), 1.0 / L)
+    out = binding.wrm_apply(mixed, s)
+    torch.cuda.synchronize()
+    sum_q = oracle.pool_q(qv.astype(np.float64))
+    g_o = oracle.gate(sum_q, 1.0 / L, f64(gp), L, 0)
+    want = oracle.wrm_apply(oracle.mix_forward(vals.astype(np.float64), g_o), oracle.wrm_gates(sum_q, 1.0 / L, f64(wp), J), J)
+    err = rel_l2(from_device(out), want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= 1e-5
+
+
+def test_wrm_rejects_bad_arguments():
+    from paper_2502_18394_amd import binding
+    v = torch.zeros((1, 96, 1, 64), device="cuda")
+    with pytest.raises(binding.SpectreError) as e:
+        binding.wrm_apply(v, torch.zeros((1, 1, 7, 64), device="cuda"))       # 2^6 does not divide 96
+    assert e.value.code == binding.EINVAL
+    with pytest.raises(binding.SpectreError) as e:
+        binding.wrm_apply(torch.zeros((1, 96, 1, 32), device="cuda"), torch.zeros((1, 1, 2, 32), device="cuda"))
+    assert e.value.code == binding.EUNSUPPORTED
