@@ -257,7 +257,17 @@ def main():
                       "what": "spectre_project: V = X W_v per head + pooled query in one pass over X (bf16 rows: "
                               "32x32x16 bf16 MFMA with two-term weights; fp32 rows: 32x32x2 fp32 MFMA); includes "
                               "allocating the outputs"}
-    del V, Q, out, g, ws_mix, ws_gate, P, Wq, Wv, ws_proj
+    # wavelet refinement (next-row item) applied to the mixer's output, full depth
+    J = synth.max_wavelet_levels(L)
+    s_lv = torch.randn((B, H, J + 1, d), generator=gen, device="cuda", dtype=torch.float32)
+    ws_wrm = torch.empty(binding.wrm_apply_workspace_bytes(B, L, H, d, J) + 256, dtype=torch.uint8, device="cuda")
+    wrm_out = torch.empty_like(out)
+    ms_wrm = time_loop(lambda: binding.wrm_apply(out, s_lv, out=wrm_out, ws=ws_wrm), args.steps, 2)
+    wrm_bytes = 2 * tokens * H * d * esize
+    res["wrm"] = {"ms": ms_wrm, "levels": J, "algorithmic_bytes": wrm_bytes,
+                  "hbm_frac": wrm_bytes / (ms_wrm * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                  "what": "spectre_wrm_apply: V + iDWT(s * DWT(V)), Haar, one gate per band and channel"}
+    del V, Q, out, g, ws_mix, ws_gate, P, Wq, Wv, ws_proj, s_lv, ws_wrm, wrm_out
     torch.cuda.empty_cache()
 
     if args.copy_calib:

@@ -481,7 +481,8 @@ int spectre_wrm_apply(const void *v, const void *s, void *out, int B, int L, int
     if (levels > 0 && (L % (1LL << levels)) != 0)
         return fail(SPECTRE_EINVAL, "wrm_apply: 2^%d does not divide L=%d", levels, L);
     if (d != 64) return fail(SPECTRE_EUNSUPPORTED, "wrm_apply: d=%d (only 64 is built)", d);
-    if ((long long)B * H > 65535) return fail(SPECTRE_EUNSUPPORTED, "wrm_apply: B*H above 65535");
+    if (B > 65535 || (L + kWrmTileRows - 1) / kWrmTileRows > 65535)
+        return fail(SPECTRE_EUNSUPPORTED, "wrm_apply: B or L/256 above 65535");
     if (levels > kWrmTileLevels && L > 262144)
         return fail(SPECTRE_EUNSUPPORTED, "wrm_apply: more than 8 levels needs L <= 262144");
     const size_t bytes = (size_t)B * L * H * d * (io == SPECTRE_BF16 ? 2 : 4);

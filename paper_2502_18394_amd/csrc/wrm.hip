@@ -52,6 +52,9 @@ __global__ __launch_bounds__(256) void k_wrm_gates(const double *__restrict__ su
 }
 
 // ------------------------------------------------------------------------------------------
+// Grids are (H, tiles, B) with the head index fastest: workgroups that run together then read all heads of
+// the same rows, i.e. whole contiguous token rows, and spread over every memory channel (one head's
+// 128-byte slices alone, 4 KB apart, sit on a fraction of them).
 // Row ownership inside a tile of 256 rows: thread (pair p = tid % 32, r = tid / 32) owns the 32
 // consecutive rows 32 r .. 32 r + 31 of channel pair p, so a row of a head is one coalesced
 // 128 B / 256 B segment across 32 lanes and levels 1..5 never leave the thread's registers.
@@ -62,17 +65,22 @@ __global__ __launch_bounds__(256) void k_wrm_tile_sums(const typename IO::pair_t
                                                        float2 *__restrict__ S, int L, int H, int ntiles) {
     __shared__ float2 part[8][32];
     const int tid = threadIdx.x, p = tid & 31, r = tid >> 5;
-    const int tile = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh % H;
+    const int h = blockIdx.x, tile = blockIdx.y, b = blockIdx.z, bh = b * H + h;
     const int row0 = tile * kWrmTileRows + r * 32;
-    float2 acc = make_float2(0.f, 0.f);
-#pragma unroll 8
+    // all 32 loads are issued before the first use (the raw words are kept; unpacking inside the guarded
+    // load would make every load wait for the previous one)
+    typename IO::pair_t raw[32];
+#pragma unroll
     for (int i = 0; i < 32; ++i) {
         const int l = row0 + i;
-        if (l < L) {
-            const float2 x = IO::unpack(v[(((size_t)b * L + l) * H + h) * 32 + p]);
-            acc.x += x.x;
-            acc.y += x.y;
-        }
+        raw[i] = (l < L) ? v[(((size_t)b * L + l) * H + h) * 32 + p] : IO::zero();
+    }
+    float2 acc = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        const float2 x = IO::unpack(raw[i]);
+        acc.x += x.x;
+        acc.y += x.y;
     }
     part[r][p] = acc;
     __syncthreads();
@@ -135,16 +143,21 @@ __global__ __launch_bounds__(256) void k_wrm_apply(const typename IO::pair_t *__
                                                    int ntiles) {
     __shared__ float2 part[8][33];
     const int tid = threadIdx.x, p = tid & 31, r = tid >> 5;
-    const int tile = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh % H;
+    const int h = blockIdx.x, tile = blockIdx.y, b = blockIdx.z, bh = b * H + h;
     const int row0 = tile * kWrmTileRows + r * 32;
     const float *sb = s + (size_t)bh * (J + 1) * 64;
     const int c0 = 2 * p;
 
     float2 x[32];
+    {   // issue all loads before the first unpack (see k_wrm_tile_sums)
+        typename IO::pair_t raw[32];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-        const int l = row0 + i;
-        x[i] = (l < L) ? IO::unpack(IO::load_stream(v + (((size_t)b * L + l) * H + h) * 32 + p)) : make_float2(0.f, 0.f);
+        for (int i = 0; i < 32; ++i) {
+            const int l = row0 + i;
+            raw[i] = (l < L) ? IO::load_stream(v + (((size_t)b * L + l) * H + h) * 32 + p) : IO::zero();
+        }
+#pragma unroll
+        for (int i = 0; i < 32; ++i) x[i] = IO::unpack(raw[i]);
     }
     // block sums of levels 1..5 inside the thread
     float2 s1[16], s2[8], s3[4], s4[2], s5;
@@ -242,7 +255,7 @@ hipError_t launch_wrm_apply(int io, const void *v, const float *s, void *out, fl
                             int B, int L, int H, int levels, hipStream_t st) {
     const int BH = B * H;
     const int ntiles = (L + kWrmTileRows - 1) / kWrmTileRows;
-    const dim3 grid(ntiles, BH);
+    const dim3 grid(H, ntiles, B);
     if (levels > kWrmTileLevels) {                      // then 2^levels divides L, so L is a multiple of 512
         if (io) k_wrm_tile_sums<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(v),
                                                               reinterpret_cast<float2 *>(tile_sums), L, H, ntiles);
