@@ -36,6 +36,13 @@
  *     position p per call;
  *   - the optional Toeplitz update of step 3b is a zero-padded "same" convolution
  *     along the frequency axis of the F stored bins;
+ *   - persistent memory (Sec. 3.4 concatenates an N_mem-point and an N_max-point
+ *     half spectrum, which is the spectrum of no signal): the N_mem memory rows are
+ *     the first rows of a window of n = N_mem + N_max rows whose other N_max rows
+ *     are the ring buffer; the cache is the n-point spectrum of that window, the
+ *     gate has n/2+1 bins, the inverse is n-point.  Memory rows are never evicted,
+ *     carry no query (they do not enter sum_q, whose divisor stays 1/N_max), and a
+ *     decode step updates ring slot N_mem + (t mod N_max) only;
  *   - wavelet refinement (Sec. 3.5; the wavelet family, the depth and the shape of
  *     the gates are not given): the orthonormal Haar transform, J <= (number of
  *     times 2 divides n) levels, coefficients stored coarse to fine; the MLP emits
@@ -530,6 +537,124 @@ int so_prefix_readout_window(int B, int H, int d, int N, int Lw, const double *s
         if (so_irfft(N, (double *)Y, x, method)) fail = 1;
         for (int i = 0; i < Lw; ++i)
             out[(((size_t)b * Lw + i) * H + h) * d + c] = x[N - Lw + i];
+        free(x);
+    }
+    return fail ? -2 : 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Persistent memory extension, Sec. 3.4, under the reading in this file's header.
+ * n = Nmem + Nmax; spec [B,H,n/2+1,d]; v_buf, q_buf [B,H,n,d] with rows 0..Nmem-1
+ * holding the memory (q_buf zero there); sum_q [B,H,d] over the live ring rows. */
+
+/* Set-up and pre-fill in one: the window [M ; V (T <= Nmax rows) ; 0] is laid
+ * down and transformed once.  M [B,H,Nmem,d]; V, Q [B,T,H,d] (T may be 0). */
+int so_memory_prefill(int B, int H, int d, int Nmem, int Nmax, int T, const double *M,
+                      const double *V, const double *Q,
+                      double *spec, double *v_buf, double *q_buf, double *sum_q, int method) {
+    if (T > Nmax || T < 0 || Nmem < 0 || Nmax < 1) return -1;
+    int n = Nmem + Nmax, F = n / 2 + 1;
+    long long ncol = (long long)B * H * d;
+    int fail = 0;
+    memset(v_buf, 0, sizeof(double) * (size_t)B * H * n * d);
+    memset(q_buf, 0, sizeof(double) * (size_t)B * H * n * d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long long col = 0; col < ncol; ++col) {
+        int c = (int)(col % d);
+        int h = (int)((col / d) % H);
+        int b = (int)(col / ((long long)d * H));
+        size_t bh = (size_t)b * H + h;
+        double *x = (double *)calloc((size_t)n + 2 * (size_t)F, sizeof(double));
+        if (!x) { fail = 1; continue; }
+        for (int m = 0; m < Nmem; ++m) {
+            x[m] = M[(bh * Nmem + m) * d + c];
+            v_buf[(bh * n + m) * d + c] = x[m];
+        }
+        double s = 0.0;
+        for (int l = 0; l < T; ++l) {
+            size_t src = (((size_t)b * T + l) * H + h) * d + c;
+            size_t dst = (bh * n + Nmem + l) * d + c;
+            x[Nmem + l] = V[src];
+            v_buf[dst] = V[src];
+            q_buf[dst] = Q[src];
+            s += Q[src];
+        }
+        sum_q[bh * d + c] = s;
+        if (so_rfft(n, x, x + n, method)) fail = 1;
+        for (int k = 0; k < F; ++k) {
+            size_t o = ((bh * F + k) * d + c) * 2;
+            spec[o] = x[n + 2 * k];
+            spec[o + 1] = x[n + 2 * k + 1];
+        }
+        free(x);
+    }
+    return fail ? -2 : 0;
+}
+
+/* Decode step with memory: token number t goes to row s = Nmem + (t mod Nmax) of
+ * the window, replacing the token of Nmax steps ago once the ring is full; Eq. (5)
+ * with the n-point root exp(-j 2 pi k s / n).  Memory rows are never touched. */
+void so_memory_update(int B, int H, int d, int Nmem, int Nmax, long long t,
+                      const double *v_t, const double *q_t,
+                      double *spec, double *v_buf, double *q_buf, double *sum_q) {
+    int n = Nmem + Nmax, F = n / 2 + 1;
+    long long s = Nmem + t % Nmax;
+    double *delta = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!delta) return;
+    for (int b = 0; b < B; ++b) for (int h = 0; h < H; ++h) {
+        size_t bh = (size_t)b * H + h;
+        for (int c = 0; c < d; ++c) {
+            size_t slot = (bh * n + (size_t)s) * d + c;
+            double v_old = (t >= Nmax) ? v_buf[slot] : 0.0;
+            double q_old = (t >= Nmax) ? q_buf[slot] : 0.0;
+            double vn = v_t[bh * d + c], qn = q_t[bh * d + c];
+            delta[c] = vn - v_old;
+            v_buf[slot] = vn;
+            q_buf[slot] = qn;
+            sum_q[bh * d + c] += qn - q_old;
+        }
+        for (int k = 0; k < F; ++k) {
+            cplx w = root_of_unity((long long)k * s, n, -1);
+            for (int c = 0; c < d; ++c) {
+                size_t o = ((bh * F + k) * d + c) * 2;
+                spec[o] += delta[c] * w.re;
+                spec[o + 1] += delta[c] * w.im;
+            }
+        }
+    }
+    free(delta);
+}
+
+/* Window readout with memory: z = irfft_n(g * spec); the Lw = min(t, Nmax) live
+ * tokens are returned oldest first, out[b,i,h,:] = z[Nmem + ((t - Lw + i) mod Nmax)]
+ * (t = tokens appended so far).  g carries no positional phase here: a circular
+ * shift would move the pinned memory rows as well. */
+int so_memory_readout_window(int B, int H, int d, int Nmem, int Nmax, long long t,
+                             const double *spec, const double *g, double *out, int method) {
+    int n = Nmem + Nmax, F = n / 2 + 1;
+    int Lw = (int)(t < Nmax ? t : Nmax);
+    long long ncol = (long long)B * H * d;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long long col = 0; col < ncol; ++col) {
+        int c = (int)(col % d);
+        int h = (int)((col / d) % H);
+        int b = (int)(col / ((long long)d * H));
+        size_t bh = (size_t)b * H + h;
+        double *x = (double *)malloc(sizeof(double) * ((size_t)n + 2 * (size_t)F));
+        if (!x) { fail = 1; continue; }
+        cplx *Y = (cplx *)(x + n);
+        const cplx *gg = (const cplx *)g + bh * F;
+        for (int k = 0; k < F; ++k) {
+            size_t o = ((bh * F + k) * d + c) * 2;
+            cplx X = { spec[o], spec[o + 1] };
+            Y[k] = c_mul(gg[k], X);
+        }
+        if (so_irfft(n, (double *)Y, x, method)) fail = 1;
+        for (int i = 0; i < Lw; ++i) {
+            long long tok = t - Lw + i;
+            out[(((size_t)b * Lw + i) * H + h) * d + c] = x[Nmem + tok % Nmax];
+        }
         free(x);
     }
     return fail ? -2 : 0;

@@ -274,3 +274,70 @@ class PrefixCache:
         if rc:
             raise RuntimeError(f"so_prefix_readout_window rc={rc}")
         return out
+
+
+class MemoryPrefixCache:
+    """Prefix-FFT cache with a persistent memory bank (Sec. 3.4): a window of n = N_mem + N_max rows whose
+    first N_mem rows are the memory M [B,H,N_mem,d] and whose other rows are the ring buffer."""
+
+    def __init__(self, B, H, d, N_mem, N_max):
+        self.B, self.H, self.d, self.N_mem, self.N_max = B, H, d, N_mem, N_max
+        self.n = N_mem + N_max
+        self.F = self.n // 2 + 1
+        self.t = 0
+        self.spec = np.zeros((B, H, self.F, d), dtype=np.complex128)
+        self.v_buf = np.zeros((B, H, self.n, d), dtype=np.float64)
+        self.q_buf = np.zeros((B, H, self.n, d), dtype=np.float64)
+        self.sum_q = np.zeros((B, H, d), dtype=np.float64)
+
+    def _dims(self):
+        return (ctypes.c_int(self.B), ctypes.c_int(self.H), ctypes.c_int(self.d), ctypes.c_int(self.N_mem),
+                ctypes.c_int(self.N_max))
+
+    def prefill(self, M, V=None, Q=None, method=FAST):
+        """Lay down the memory and (optionally) a prompt V, Q [B,T,H,d], transform once."""
+        M = _f64(M)
+        assert M.shape == (self.B, self.H, self.N_mem, self.d) and self.t == 0
+        if V is None:
+            V = np.zeros((self.B, 0, self.H, self.d))
+            Q = V
+        V, Q = _f64(V), _f64(Q)
+        T = V.shape[1]
+        assert V.shape == (self.B, T, self.H, self.d) and Q.shape == V.shape
+        rc = _L().so_memory_prefill(*self._dims(), ctypes.c_int(T), _p(M), _p(V), _p(Q), _p(self.spec),
+                                    _p(self.v_buf), _p(self.q_buf), _p(self.sum_q), ctypes.c_int(method))
+        if rc:
+            raise RuntimeError(f"so_memory_prefill rc={rc}")
+        self.t = T
+
+    def update(self, v_t, q_t):
+        v_t = _f64(v_t).reshape(self.B, self.H, self.d)
+        q_t = _f64(q_t).reshape(self.B, self.H, self.d)
+        _L().so_memory_update(*self._dims(), ctypes.c_longlong(self.t), _p(v_t), _p(q_t), _p(self.spec),
+                              _p(self.v_buf), _p(self.q_buf), _p(self.sum_q))
+        self.t += 1
+
+    def newest_slot(self):
+        return self.N_mem + (self.t - 1) % self.N_max
+
+    def readout_row(self, g, m):
+        g = _c128(g)
+        assert g.shape == (self.B, self.H, self.F)
+        out = np.empty((self.B, self.H, self.d), dtype=np.float64)
+        _L().so_prefix_readout_row(ctypes.c_int(self.B), ctypes.c_int(self.H), ctypes.c_int(self.d),
+                                   ctypes.c_int(self.n), ctypes.c_longlong(int(m)), _p(self.spec), _p(g), _p(out))
+        return out
+
+    def readout_newest(self, g):
+        return self.readout_row(g, self.newest_slot()).reshape(self.B, 1, self.H, self.d)
+
+    def readout_window(self, g, method=FAST):
+        """The live tokens' rows of irfft_n(g * spec), oldest first; [B, min(t, N_max), H, d]."""
+        g = _c128(g)
+        Lw = min(self.t, self.N_max)
+        out = np.empty((self.B, Lw, self.H, self.d), dtype=np.float64)
+        rc = _L().so_memory_readout_window(*self._dims(), ctypes.c_longlong(self.t), _p(self.spec), _p(g), _p(out),
+                                           ctypes.c_int(method))
+        if rc:
+            raise RuntimeError(f"so_memory_readout_window rc={rc}")
+        return out
