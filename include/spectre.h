@@ -195,33 +195,56 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
  * Prefix-FFT cache, Sec. 3.3 and Algorithm 1.  One cache serves B*H heads that advance in
  * lock-step (one token counter).  The caller allocates the five device arrays (sizes from
  * spectre_prefix_bytes), fills in the dimensions, and calls spectre_prefix_init once.
+ *
+ * Persistent memory, Sec. 3.4 (N_mem > 0).  The section's literal concatenation of an N_mem-point and
+ * an N_max-point half spectrum is the spectrum of no signal; the reading implemented here: the memory
+ * rows M are the first N_mem rows of a window of n = N_mem + N_max rows whose other N_max rows are the
+ * ring buffer, the cache is the n-point half spectrum of that window, the gate has F = n/2 + 1 bins and
+ * the inverse is n-point.  Memory rows are never evicted and never updated by a decode step, carry no
+ * query (they do not enter sum_q; the descriptor's divisor stays 1/N_max), and token t lives in row
+ * N_mem + (t mod N_max).  With N_mem = 0 everything below reduces to Sec. 3.3 as printed.
  */
 typedef struct {
-    int B, H, d, N_max;   /* N_max: window length = transform length, a supported power of two  */
+    int B, H, d;
+    int N_max;            /* ring capacity: the live window of Sec. 3.3                          */
+    int N_mem;            /* persistent memory rows in front of the ring (0 = none)              */
+                          /* n = N_mem + N_max is the transform length, a supported power of two */
     long long t;          /* HOST field: tokens appended so far; advanced by update/step        */
-    void *prefix_fft;     /* complex64 [B, H, F, d]: half spectrum of the ring buffer           */
-    void *v_buf;          /* float [B, H, N_max, d]: ring buffer of values, slot = index mod N  */
-    void *q_buf;          /* float [B, H, N_max, d]: ring buffer of queries                     */
+    void *prefix_fft;     /* complex64 [B, H, F, d]: n-point half spectrum of the window, F=n/2+1*/
+    void *v_buf;          /* float [B, H, n, d]: memory rows, then the ring of values            */
+    void *q_buf;          /* float [B, H, n, d]: zeros, then the ring of queries                 */
     void *sum_q;          /* double [B, H, d]: running sum of the live queries                  */
-    void *twiddle;        /* complex64 [N_max]: exp(-j 2 pi m / N_max), the pre-cached factors  */
+    void *twiddle;        /* complex64 [n]: exp(-j 2 pi m / n), the pre-cached factors          */
 } spectre_prefix_cache;
 
 enum { SPECTRE_PREFIX_FFT = 0, SPECTRE_PREFIX_VBUF = 1, SPECTRE_PREFIX_QBUF = 2,
        SPECTRE_PREFIX_SUMQ = 3, SPECTRE_PREFIX_TWIDDLE = 4 };
-/* Bytes of cache field `which` (one of the enumerators above); 0 on bad arguments. */
-size_t spectre_prefix_bytes(int B, int H, int d, int N_max, int which);
+/* Bytes of cache field `which` (one of the enumerators above) for a window of n = N_mem + N_max
+ * rows; 0 on bad arguments. */
+size_t spectre_prefix_bytes(int B, int H, int d, int n, int which);
 
 /* Zeroes the state, fills the twiddle table (computed in fp64, rounded once), sets t = 0. */
 int spectre_prefix_init(spectre_prefix_cache *cache /*host*/, void *stream);
 
 /*
+ * spectre_prefix_set_memory - Sec. 3.4: lay the memory rows down and transform the window once
+ * ("store the transform of the memory once").  Only on an empty cache (t = 0), right after init,
+ * for a cache with N_mem > 0.   mem  float [mem_batch, H, N_mem, d], mem_batch = 1 (shared by all
+ * sequences) or B.
+ */
+size_t spectre_prefix_set_memory_workspace_bytes(const spectre_prefix_cache *cache /*host*/);
+int spectre_prefix_set_memory(spectre_prefix_cache *cache /*host*/, const float *mem, int mem_batch,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/*
  * spectre_prefix_update - append T tokens.  v_new, q_new are [B, T, H, d] of dtype `io`.
  *   cache->t == 0 and T > 1 : pre-fill (Algorithm 1, PreFill): one N_max-point real transform of
  *        the prompt zero-padded at the tail, ring buffers filled, sum_q = sum of the prompt's
- *        queries.  Requires T <= N_max.
+ *        queries.  Requires T <= N_max.  (With memory rows: the prompt goes behind them and the
+ *        whole window is transformed.)
  *   otherwise : T successive decode updates (Algorithm 1, DecodeStep up to the gate; Eq. 5):
- *        s = t mod N_max;  delta = v_t - [t >= N_max] v_buf[s];
- *        prefix_fft[k, :] += delta * exp(-j 2 pi ((k s) mod N_max)/N_max)   for every bin k;
+ *        s = N_mem + t mod N_max;  delta = v_t - [t >= N_max] v_buf[s];
+ *        prefix_fft[k, :] += delta * exp(-j 2 pi ((k s) mod n)/n)   for every bin k;
  *        sum_q += q_t - [t >= N_max] q_buf[s];  v_buf[s] = v_t;  q_buf[s] = q_t;  t += 1.
  * On success cache->t has advanced by T.
  */
@@ -232,13 +255,16 @@ int spectre_prefix_update(spectre_prefix_cache *cache /*host*/, const void *v_ne
 
 /*
  * spectre_prefix_readout - Algorithm 1's last three lines, z = irfft_N( g * prefix_fft ).
- *   mode SPECTRE_READ_NEWEST : out [B, 1, H, d] = row (t-1) mod N_max of z, the newest token's row,
+ *   mode SPECTRE_READ_NEWEST : out [B, 1, H, d] = row N_mem + (t-1) mod N_max of z, the newest token's row,
  *        evaluated as a direct sum over the bins (the O(N_max/2 d) per-step cost Sec. 3.3 quotes);
  *        pass the gate WITHOUT positional phase.
  *   mode SPECTRE_READ_WINDOW : out [B, L', H, d] = rows N_max-L' .. N_max-1 of z, L' = min(t, N_max)
  *        (a full inverse transform).  With a gate built with phase_pos = t these rows are the live
  *        tokens in chronological order, the last one equal to the NEWEST readout.
- *   g     complex64 [B, H, F], F = N_max/2 + 1.   Requires t >= 1.
+ *        With memory rows (N_mem > 0) a circular shift would move the pinned rows too: pass the
+ *        gate WITHOUT phase; the L' live tokens' rows of z are gathered from their ring slots and
+ *        returned oldest first.
+ *   g     complex64 [B, H, F], F = n/2 + 1.   Requires t >= 1.
  */
 enum { SPECTRE_READ_NEWEST = 0, SPECTRE_READ_WINDOW = 1 };
 size_t spectre_prefix_readout_workspace_bytes(const spectre_prefix_cache *cache /*host*/, int mode,
@@ -251,7 +277,7 @@ int spectre_prefix_readout(const spectre_prefix_cache *cache /*host*/, const voi
  *   spectre_prefix_update(T = 1), spectre_gate(sum_q, 1/N_max, phase 0), spectre_prefix_readout(NEWEST)
  * but a single sweep over the cache (each cache entry is read once and written once).
  *   v_t, q_t  [B, 1, H, d] of dtype io       out  [B, 1, H, d] of dtype io
- *   P         gate parameters with P->n_fft == N_max
+ *   P         gate parameters with P->n_fft == n = N_mem + N_max
  */
 size_t spectre_prefix_step_workspace_bytes(const spectre_prefix_cache *cache /*host*/,
                                            const spectre_gate_params *P /*host*/);

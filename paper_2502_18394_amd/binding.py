@@ -41,7 +41,7 @@ class WrmParamsC(ctypes.Structure):
 
 class PrefixCacheC(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("d", ctypes.c_int), ("N_max", ctypes.c_int),
-                ("t", ctypes.c_longlong),
+                ("N_mem", ctypes.c_int), ("t", ctypes.c_longlong),
                 ("prefix_fft", ctypes.c_void_p), ("v_buf", ctypes.c_void_p), ("q_buf", ctypes.c_void_p),
                 ("sum_q", ctypes.c_void_p), ("twiddle", ctypes.c_void_p)]
 
@@ -58,7 +58,7 @@ def lib():
                      "spectre_project_workspace_bytes", "spectre_wrm_gates_workspace_bytes",
                      "spectre_wrm_apply_workspace_bytes",
                      "spectre_prefix_update_workspace_bytes", "spectre_prefix_readout_workspace_bytes",
-                     "spectre_prefix_step_workspace_bytes"):
+                     "spectre_prefix_step_workspace_bytes", "spectre_prefix_set_memory_workspace_bytes"):
             getattr(L, name).restype = ctypes.c_size_t
         _lib = L
     return _lib
@@ -263,25 +263,36 @@ def wrm_apply(v, s, out=None, ws=None, stream=None):
 class PrefixCache:
     """Caller-owned Prefix-FFT cache state (Algorithm 1) in device memory."""
 
-    def __init__(self, B, H, d, N_max, device="cuda"):
+    def __init__(self, B, H, d, N_max, N_mem=0, device="cuda"):
+        """N_max = ring capacity; N_mem = persistent memory rows (Sec. 3.4); n = N_mem + N_max is the transform length."""
         L = lib()
-        self.B, self.H, self.d, self.N = B, H, d, N_max
-        self.F = N_max // 2 + 1
-        nb = [int(L.spectre_prefix_bytes(ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(N_max),
+        n = N_max + N_mem
+        self.B, self.H, self.d, self.N, self.N_mem, self.n = B, H, d, N_max, N_mem, n
+        self.F = n // 2 + 1
+        nb = [int(L.spectre_prefix_bytes(ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(n),
                                          ctypes.c_int(w))) for w in range(5)]
         if min(nb) == 0:
-            raise SpectreError(EUNSUPPORTED, f"no prefix cache for B={B} H={H} d={d} N_max={N_max}")
+            raise SpectreError(EUNSUPPORTED, f"no prefix cache for B={B} H={H} d={d} N_mem+N_max={n}")
         self.prefix_fft = torch.empty((B, H, self.F, d), dtype=torch.complex64, device=device)
-        self.v_buf = torch.empty((B, H, N_max, d), dtype=torch.float32, device=device)
-        self.q_buf = torch.empty((B, H, N_max, d), dtype=torch.float32, device=device)
+        self.v_buf = torch.empty((B, H, n, d), dtype=torch.float32, device=device)
+        self.q_buf = torch.empty((B, H, n, d), dtype=torch.float32, device=device)
         self.sum_q = torch.empty((B, H, d), dtype=torch.float64, device=device)
-        self.twiddle = torch.empty((N_max,), dtype=torch.complex64, device=device)
-        for t, n in zip((self.prefix_fft, self.v_buf, self.q_buf, self.sum_q, self.twiddle), nb):
-            assert t.numel() * t.element_size() == n, (t.shape, n)
-        self.c = PrefixCacheC(B, H, d, N_max, 0, self.prefix_fft.data_ptr(), self.v_buf.data_ptr(),
+        self.twiddle = torch.empty((n,), dtype=torch.complex64, device=device)
+        for t, nbytes in zip((self.prefix_fft, self.v_buf, self.q_buf, self.sum_q, self.twiddle), nb):
+            assert t.numel() * t.element_size() == nbytes, (t.shape, nbytes)
+        self.c = PrefixCacheC(B, H, d, N_max, N_mem, 0, self.prefix_fft.data_ptr(), self.v_buf.data_ptr(),
                               self.q_buf.data_ptr(), self.sum_q.data_ptr(), self.twiddle.data_ptr())
         self._ws = None
         _check(L.spectre_prefix_init(ctypes.byref(self.c), _stream(None)))
+
+    def set_memory(self, mem, stream=None):
+        """mem float32 [1 or B, H, N_mem, d]: the persistent memory rows; call once, before any token."""
+        if mem.dtype != torch.float32 or mem.ndim != 4 or tuple(mem.shape[1:]) != (self.H, self.N_mem, self.d):
+            raise ValueError("mem must be float32 [1 or B, H, N_mem, d]")
+        need = lib().spectre_prefix_set_memory_workspace_bytes(ctypes.byref(self.c))
+        self._ws, wsp, wsn = _workspace(need, mem.device, self._ws)
+        _check(lib().spectre_prefix_set_memory(ctypes.byref(self.c), _dev(mem, "mem"), ctypes.c_int(mem.shape[0]),
+                                               wsp, wsn, _stream(stream)))
 
     @property
     def t(self):

@@ -142,7 +142,7 @@ extern "C" {
 
 const char *spectre_last_error(void) { return g_err.c_str(); }
 
-int spectre_version(void) { return 100; }
+int spectre_version(void) { return 110; }
 
 // 0 = no kernel, 1 = whole slab in LDS, 2 = four-step power-of-two path, 3 = any other length
 // through a padded power-of-two convolution.
@@ -507,11 +507,15 @@ static bool prefix_length_ok(int N, int d) {
     return d == 64 && pow2_split(N, &N1, &N2, &P);
 }
 
+// Transform length of a cache: the pinned memory rows followed by the ring (Sec. 3.4).
+static inline int window_len(const spectre_prefix_cache *c) { return c->N_max + c->N_mem; }
+
 static int check_cache(const spectre_prefix_cache *c, const char *who) {
     if (!c) return fail(SPECTRE_EINVAL, "%s: null cache", who);
-    if (c->B < 1 || c->H < 1 || c->d < 1 || c->N_max < 2) return fail(SPECTRE_EINVAL, "%s: bad cache dimensions", who);
-    if (!prefix_length_ok(c->N_max, c->d))
-        return fail(SPECTRE_EUNSUPPORTED, "%s: no kernel for N_max=%d, d=%d", who, c->N_max, c->d);
+    if (c->B < 1 || c->H < 1 || c->d < 1 || c->N_max < 1 || c->N_mem < 0 || c->N_max > (1 << 30) || c->N_mem > (1 << 30))
+        return fail(SPECTRE_EINVAL, "%s: bad cache dimensions", who);
+    if (!prefix_length_ok(window_len(c), c->d))
+        return fail(SPECTRE_EUNSUPPORTED, "%s: no kernel for N_mem+N_max=%d, d=%d", who, window_len(c), c->d);
     if (!c->prefix_fft || !c->v_buf || !c->q_buf || !c->sum_q || !c->twiddle)
         return fail(SPECTRE_EINVAL, "%s: null cache array", who);
     if (c->t < 0) return fail(SPECTRE_EINVAL, "%s: negative token counter", who);
@@ -541,10 +545,10 @@ int spectre_prefix_init(spectre_prefix_cache *c, void *stream) {
     const int which[4] = {SPECTRE_PREFIX_FFT, SPECTRE_PREFIX_VBUF, SPECTRE_PREFIX_QBUF, SPECTRE_PREFIX_SUMQ};
     for (int i = 0; i < 4; ++i) {
         if (reinterpret_cast<uintptr_t>(arr[i]) & 15) return fail(SPECTRE_EINVAL, "prefix_init: cache array not 16-byte aligned");
-        hipError_t e = launch_fill_zero(arr[i], spectre_prefix_bytes(c->B, c->H, c->d, c->N_max, which[i]), st);
+        hipError_t e = launch_fill_zero(arr[i], spectre_prefix_bytes(c->B, c->H, c->d, window_len(c), which[i]), st);
         if (e != hipSuccess) return fail_hip(e, "fill_zero");
     }
-    hipError_t e = launch_fill_twiddle(static_cast<float2 *>(c->twiddle), c->N_max, st);
+    hipError_t e = launch_fill_twiddle(static_cast<float2 *>(c->twiddle), window_len(c), st);
     if (e != hipSuccess) return fail_hip(e, "fill_twiddle");
     c->t = 0;
     return SPECTRE_OK;
@@ -554,12 +558,32 @@ static size_t scratch_bytes(int BH, int N, int d) {
     return align256((size_t)mix_chunk_heads(BH, N, d) * N * (d / 2) * sizeof(float2));
 }
 
+// prefix_fft = n-point half spectra of the rows now in v_buf ([B*H, n, d] fp32, read as B*H sequences of
+// one head each); scr holds scratch_bytes(...).
+static int transform_window(const spectre_prefix_cache *c, float2 *scr, hipStream_t st) {
+    const int N = window_len(c), BH = c->B * c->H;
+    Pow2Plan pl;
+    int rc = get_pow2_plan(N, &pl);
+    if (rc) return rc;
+    const int chunk = mix_chunk_heads(BH, N, c->d);
+    for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
+        const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
+        hipError_t e = launch_small_fwd(pl, SPECTRE_F32, c->v_buf, scr, N, 1, bh0, nbh, st);
+        if (e != hipSuccess) return fail_hip(e, "small_fwd(window)");
+        e = launch_big(pl, scr, nullptr, bh0, nbh, 1, st);
+        if (e != hipSuccess) return fail_hip(e, "big(forward)");
+        e = launch_untangle(scr, static_cast<float2 *>(c->prefix_fft), N, pl.N1, pl.N2, pl.P, bh0, nbh, st);
+        if (e != hipSuccess) return fail_hip(e, "untangle");
+    }
+    return SPECTRE_OK;
+}
+
 size_t spectre_prefix_update_workspace_bytes(const spectre_prefix_cache *c, int T, spectre_dtype io) {
     (void)io;
-    if (!c || T < 1 || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 2) return 0;
+    if (!c || T < 1 || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 1 || c->N_mem < 0) return 0;
     const int BH = c->B * c->H;
     return align256((size_t)BH * c->d * sizeof(float)) + align256(gate_partial_bytes(c->B, T, c->H, c->d)) +
-           scratch_bytes(BH, c->N_max, c->d);
+           scratch_bytes(BH, window_len(c), c->d);
 }
 
 int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void *q_new, int T, spectre_dtype io,
@@ -573,7 +597,7 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
     if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_update: workspace %zu < %zu bytes", ws_bytes, need);
     if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_update: ws not 256-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int B = c->B, H = c->H, d = c->d, N = c->N_max, BH = B * H, F = N / 2 + 1;
+    const int B = c->B, H = c->H, d = c->d, N = window_len(c), W = c->N_max, M0 = c->N_mem, BH = B * H, F = N / 2 + 1;
     char *w = static_cast<char *>(ws);
     float *delta = reinterpret_cast<float *>(w);
     w += align256((size_t)BH * d * sizeof(float));
@@ -583,14 +607,21 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
     float2 *X = static_cast<float2 *>(c->prefix_fft);
     hipError_t e;
     if (c->t == 0 && T > 1) {
-        if (T > N) return fail(SPECTRE_EINVAL, "prefix_update: prompt of %d tokens exceeds N_max=%d", T, N);
-        Pow2Plan pl;
-        rc = get_pow2_plan(N, &pl);
-        if (rc) return rc;
-        e = launch_fill_ring((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), B, T, H, N, st);
+        if (T > W) return fail(SPECTRE_EINVAL, "prefix_update: prompt of %d tokens exceeds N_max=%d", T, W);
+        e = launch_fill_ring((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), B, T, H, N,
+                             M0, st);
         if (e != hipSuccess) return fail_hip(e, "fill_ring");
         e = launch_pool((int)io, q_new, partial, static_cast<double *>(c->sum_q), B, T, H, d, st);
         if (e != hipSuccess) return fail_hip(e, "pool");
+        if (M0 > 0) {                       // the window starts with the memory rows: transform the ring buffer itself
+            rc = transform_window(c, scr, st);
+            if (rc) return rc;
+            c->t = T;
+            return SPECTRE_OK;
+        }
+        Pow2Plan pl;
+        rc = get_pow2_plan(N, &pl);
+        if (rc) return rc;
         const int chunk = mix_chunk_heads(BH, N, d);
         for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
             const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
@@ -605,7 +636,7 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
         return SPECTRE_OK;
     }
     for (int ti = 0; ti < T; ++ti) {
-        const int slot = (int)(c->t % N), evict = c->t >= N ? 1 : 0;
+        const int slot = M0 + (int)(c->t % W), evict = c->t >= W ? 1 : 0;
         e = launch_ring_update((int)io, v_new, q_new, T, ti, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf),
                                static_cast<double *>(c->sum_q), delta, B, H, d, N, slot, evict, st);
         if (e != hipSuccess) return fail_hip(e, "ring_update");
@@ -616,12 +647,34 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
     return SPECTRE_OK;
 }
 
+size_t spectre_prefix_set_memory_workspace_bytes(const spectre_prefix_cache *c) {
+    if (!c || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 1 || c->N_mem < 0) return 0;
+    return scratch_bytes(c->B * c->H, window_len(c), c->d);
+}
+
+int spectre_prefix_set_memory(spectre_prefix_cache *c, const float *mem, int mem_batch, void *ws, size_t ws_bytes,
+                              void *stream) {
+    int rc = check_cache(c, "prefix_set_memory");
+    if (rc) return rc;
+    if (!mem) return fail(SPECTRE_EINVAL, "prefix_set_memory: null pointer");
+    if (c->N_mem < 1) return fail(SPECTRE_EINVAL, "prefix_set_memory: the cache has no memory rows (N_mem = 0)");
+    if (c->t != 0) return fail(SPECTRE_EINVAL, "prefix_set_memory: only on an empty cache (t = 0), right after init");
+    if (mem_batch != 1 && mem_batch != c->B) return fail(SPECTRE_EINVAL, "prefix_set_memory: mem_batch must be 1 or B");
+    const size_t need = spectre_prefix_set_memory_workspace_bytes(c);
+    if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_set_memory: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_set_memory: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_set_memory(mem, mem_batch, static_cast<float *>(c->v_buf), c->B, c->H, window_len(c), c->N_mem, st);
+    if (e != hipSuccess) return fail_hip(e, "set_memory");
+    return transform_window(c, static_cast<float2 *>(ws), st);
+}
+
 size_t spectre_prefix_readout_workspace_bytes(const spectre_prefix_cache *c, int mode, spectre_dtype io) {
     (void)io;
-    if (!c || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 2) return 0;
-    const int BH = c->B * c->H, F = c->N_max / 2 + 1;
+    if (!c || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 1 || c->N_mem < 0) return 0;
+    const int BH = c->B * c->H, F = window_len(c) / 2 + 1;
     if (mode == SPECTRE_READ_NEWEST) return align256((size_t)BH * sweep_chunks(F) * c->d * sizeof(float));
-    if (mode == SPECTRE_READ_WINDOW) return scratch_bytes(BH, c->N_max, c->d);
+    if (mode == SPECTRE_READ_WINDOW) return scratch_bytes(BH, window_len(c), c->d);
     return 0;
 }
 
@@ -637,13 +690,13 @@ int spectre_prefix_readout(const spectre_prefix_cache *c, const void *g, int mod
     if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_readout: workspace %zu < %zu bytes", ws_bytes, need);
     if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_readout: ws not 256-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int B = c->B, H = c->H, d = c->d, N = c->N_max, BH = B * H, F = N / 2 + 1;
+    const int B = c->B, H = c->H, d = c->d, N = window_len(c), W = c->N_max, M0 = c->N_mem, BH = B * H, F = N / 2 + 1;
     float2 *X = static_cast<float2 *>(c->prefix_fft);
     const float2 *gg = static_cast<const float2 *>(g);
     hipError_t e;
     if (mode == SPECTRE_READ_NEWEST) {
         float *partial = static_cast<float *>(ws);
-        const int slot = (int)((c->t - 1) % N);
+        const int slot = M0 + (int)((c->t - 1) % W);
         e = launch_sweep(false, true, X, nullptr, static_cast<const float2 *>(c->twiddle), gg, partial, BH, F, N, slot, st);
         if (e != hipSuccess) return fail_hip(e, "sweep(read)");
         e = launch_readout_final((int)io, partial, out, BH, F, st);
@@ -654,7 +707,7 @@ int spectre_prefix_readout(const spectre_prefix_cache *c, const void *g, int mod
     rc = get_pow2_plan(N, &pl);
     if (rc) return rc;
     float2 *scr = static_cast<float2 *>(ws);
-    const int Lw = (int)(c->t < N ? c->t : N);
+    const int Lw = (int)(c->t < W ? c->t : W);
     const int chunk = mix_chunk_heads(BH, N, d);
     for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
         const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
@@ -662,15 +715,17 @@ int spectre_prefix_readout(const spectre_prefix_cache *c, const void *g, int mod
         if (e != hipSuccess) return fail_hip(e, "tangle");
         e = launch_big(pl, scr, nullptr, bh0, nbh, 2, st);
         if (e != hipSuccess) return fail_hip(e, "big(inverse)");
-        e = launch_small_inv(pl, (int)io, scr, out, N - Lw, Lw, H, bh0, nbh, st);
+        // with memory rows the live tokens are gathered from their ring slots, oldest first
+        if (M0 > 0) e = launch_small_inv(pl, (int)io, scr, out, 0, Lw, H, bh0, nbh, st, M0, W, (int)((c->t - 1) % W));
+        else e = launch_small_inv(pl, (int)io, scr, out, N - Lw, Lw, H, bh0, nbh, st);
         if (e != hipSuccess) return fail_hip(e, "small_inv");
     }
     return SPECTRE_OK;
 }
 
 size_t spectre_prefix_step_workspace_bytes(const spectre_prefix_cache *c, const spectre_gate_params *P) {
-    if (!c || !P || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 2 || P->d_g < 1) return 0;
-    const int BH = c->B * c->H, F = c->N_max / 2 + 1;
+    if (!c || !P || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 1 || c->N_mem < 0 || P->d_g < 1) return 0;
+    const int BH = c->B * c->H, F = window_len(c) / 2 + 1;
     return align256((size_t)BH * c->d * sizeof(float)) + align256((size_t)BH * P->d_g * sizeof(float)) +
            align256((size_t)BH * F * sizeof(float2)) + align256((size_t)BH * sweep_chunks(F) * c->d * sizeof(float)) +
            gate_raw_bytes(c->B, c->H, P);
@@ -684,12 +739,13 @@ int spectre_prefix_step(spectre_prefix_cache *c, const void *v_t, const void *q_
     if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "prefix_step: bad dtype");
     rc = check_gate_params(P, c->H, "prefix_step");
     if (rc) return rc;
-    if (P->n_fft != c->N_max || P->d != c->d) return fail(SPECTRE_EINVAL, "prefix_step: gate is for n_fft=%d, d=%d", P->n_fft, P->d);
+    if (P->n_fft != window_len(c) || P->d != c->d)
+        return fail(SPECTRE_EINVAL, "prefix_step: gate is for n_fft=%d, d=%d", P->n_fft, P->d);
     const size_t need = spectre_prefix_step_workspace_bytes(c, P);
     if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_step: workspace %zu < %zu bytes", ws_bytes, need);
     if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_step: ws not 256-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int B = c->B, H = c->H, d = c->d, N = c->N_max, BH = B * H, F = N / 2 + 1;
+    const int B = c->B, H = c->H, d = c->d, N = window_len(c), W = c->N_max, M0 = c->N_mem, BH = B * H, F = N / 2 + 1;
     char *w = static_cast<char *>(ws);
     float *delta = reinterpret_cast<float *>(w);
     w += align256((size_t)BH * d * sizeof(float));
@@ -700,11 +756,11 @@ int spectre_prefix_step(spectre_prefix_cache *c, const void *v_t, const void *q_
     float *partial = reinterpret_cast<float *>(w);
     w += align256((size_t)BH * sweep_chunks(F) * d * sizeof(float));
     float2 *raw = reinterpret_cast<float2 *>(w);
-    const int slot = (int)(c->t % N), evict = c->t >= N ? 1 : 0;
+    const int slot = M0 + (int)(c->t % W), evict = c->t >= W ? 1 : 0;
     hipError_t e = launch_ring_update((int)io, v_t, q_t, 1, 0, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf),
                                       static_cast<double *>(c->sum_q), delta, B, H, d, N, slot, evict, st);
     if (e != hipSuccess) return fail_hip(e, "ring_update");
-    e = launch_gate_mlp(static_cast<const double *>(c->sum_q), 1.0 / (double)N, gate_dev(P), hid, raw, B, H, 0, g, st);
+    e = launch_gate_mlp(static_cast<const double *>(c->sum_q), 1.0 / (double)W, gate_dev(P), hid, raw, B, H, 0, g, st);
     if (e != hipSuccess) return fail_hip(e, "gate_mlp");
     e = launch_sweep(true, true, static_cast<float2 *>(c->prefix_fft), delta, static_cast<const float2 *>(c->twiddle), g,
                      partial, BH, F, N, slot, st);

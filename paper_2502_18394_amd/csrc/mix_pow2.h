@@ -28,13 +28,16 @@ bool pow2_split(int L, int *N1, int *N2, int *P);
 //               1 = forward only; 2 = inverse only.  gp = expanded gate for mode 0, one
 //               [N2][N1] block per head from head bh0 on, or (shared_gate) one block for all.
 //   small_inv : scratch -> rows [row0, row0 + out_rows) of the inverse transform into
-//               out (tensor [B, out_rows, H, d])
+//               out (tensor [B, out_rows, H, d]); with ring_w > 0 instead the out_rows newest
+//               entries, oldest first, of a ring buffer in rows ring0 .. ring0+ring_w-1 whose
+//               newest entry is row ring0+newest
 hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
                             int bh0, int nbh, hipStream_t st);
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
                       hipStream_t st, bool shared_gate = false);
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
-                            int out_rows, int H, int bh0, int nbh, hipStream_t st);
+                            int out_rows, int H, int bh0, int nbh, hipStream_t st, int ring0 = 0, int ring_w = 0,
+                            int newest = 0);
 // g [BH, L/2+1] -> gp [BH][N2][N1] in the big kernel's register order, scaled by 1/L and
 // extended to all L bins by Hermitian symmetry (real parts only at DC and Nyquist).
 hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st);

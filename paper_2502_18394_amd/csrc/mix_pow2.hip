@@ -67,12 +67,15 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
 }
 
 // small_inv: mirror image.  Rows l of the inverse transform with row0 <= l < row0+out_rows
-// are written to row l-row0 of out [B, out_rows, H, d].
+// are written to row l-row0 of out [B, out_rows, H, d].  With ring_w > 0 the rows are instead
+// gathered from a ring buffer that occupies rows ring0 .. ring0+ring_w-1 and whose newest entry
+// sits at ring0+newest: the out_rows newest entries are written oldest first.
 template <int N2, int TT, typename IO>
 __global__ __launch_bounds__(32 * TT) void k_small_inv(const float2 *__restrict__ scr,
                                                        typename IO::pair_t *__restrict__ out,
                                                        const float2 *__restrict__ twL, int row0,
-                                                       int out_rows, int H, int N1, int bh0) {
+                                                       int out_rows, int H, int N1, int bh0, int ring0,
+                                                       int ring_w, int newest) {
     typedef typename IO::pair_t pair_t;
     constexpr int S = TileStride<IO>::value;
     extern __shared__ unsigned char smem_raw[];
@@ -96,7 +99,13 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const float2 *__restrict_
     const int lp = tid & 31, r = tid >> 5;
 #pragma unroll
     for (int t2 = 0; t2 < N2; ++t2) {
-        const int orow = t1_0 + r + N1 * t2 - row0;
+        const int l = t1_0 + r + N1 * t2;
+        int orow = l - row0;
+        if (ring_w > 0) {
+            int age = newest - (l - ring0);            // 0 = newest entry of the ring
+            if (age < 0) age += ring_w;
+            orow = (l >= ring0) ? out_rows - 1 - age : -1;
+        }
         if (orow >= 0 && orow < out_rows)
             IO::store_stream(out + (((size_t)b * out_rows + orow) * H + h) * 32 + lp, lds[(t2 * TT + r) * S + lp]);
     }
@@ -297,13 +306,13 @@ static hipError_t small_fwd_t(const Pow2Plan &pl, const void *v, float2 *scr, in
 
 template <int N2, int TT, typename IO>
 static hipError_t small_inv_t(const Pow2Plan &pl, const float2 *scr, void *out, int row0, int out_rows,
-                              int H, int bh0, int nbh, hipStream_t st) {
+                              int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w, int newest) {
     const size_t lds = (size_t)N2 * TT * TileStride<IO>::value * sizeof(typename IO::pair_t);
     auto kern = k_small_inv<N2, TT, IO>;
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
     kern<<<dim3(pl.N1 / TT, nbh), dim3(32 * TT), lds, st>>>(
-        scr, static_cast<typename IO::pair_t *>(out), pl.twL, row0, out_rows, H, pl.N1, bh0);
+        scr, static_cast<typename IO::pair_t *>(out), pl.twL, row0, out_rows, H, pl.N1, bh0, ring0, ring_w, newest);
     return hipGetLastError();
 }
 
@@ -324,8 +333,9 @@ hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *s
 }
 
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
-                            int out_rows, int H, int bh0, int nbh, hipStream_t st) {
-    SPECTRE_DISPATCH_N2(small_inv_t, pl, scratch, out, row0, out_rows, H, bh0, nbh, st)
+                            int out_rows, int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w,
+                            int newest) {
+    SPECTRE_DISPATCH_N2(small_inv_t, pl, scratch, out, row0, out_rows, H, bh0, nbh, st, ring0, ring_w, newest)
 }
 
 template <int P, int MODE>

@@ -142,17 +142,19 @@ __global__ __launch_bounds__(256) void k_readout_final(const float *__restrict__
 
 // ------------------------------------------------------------------------------------------
 // pre-fill helpers.
-// Ring buffers from the prompt: v_buf[bh][l][c] = V[b][l][h][c] for l < T, 0 beyond.
+// Ring buffers from the prompt: v_buf[bh][row0 + l][c] = V[b][l][h][c] for l < T, 0 beyond; rows below
+// row0 (the persistent memory of Sec. 3.4) are left as they are.
 template <typename IO>
 __global__ __launch_bounds__(256) void k_fill_ring(const typename IO::pair_t *__restrict__ V,
                                                    const typename IO::pair_t *__restrict__ Q,
                                                    float2 *__restrict__ v_buf, float2 *__restrict__ q_buf, int T,
-                                                   int H, int N, size_t total) {
+                                                   int H, int N, int row0, size_t total) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int p = (int)(idx % 32);
     const size_t r = idx / 32;
-    const int l = (int)(r % N);
+    const int l = (int)(r % N) - row0;
+    if (l < 0) return;
     const size_t bh = r / N;
     const int h = (int)(bh % H);
     const size_t b = bh / H;
@@ -164,6 +166,19 @@ __global__ __launch_bounds__(256) void k_fill_ring(const typename IO::pair_t *__
     }
     v_buf[idx] = v;
     q_buf[idx] = q;
+}
+
+// Memory rows (Sec. 3.4): v_buf[bh][m][c] = mem[b or 0][h][m][c], m < Nmem.  One lane per element.
+__global__ __launch_bounds__(256) void k_set_memory(const float *__restrict__ mem, float *__restrict__ v_buf, int H,
+                                                    int N, int Nmem, int d, int per_batch, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int c = (int)(idx % d);
+    const size_t r = idx / d;
+    const int m = (int)(r % Nmem);
+    const size_t bh = r / Nmem;
+    const size_t src_bh = per_batch ? bh : bh % H;
+    v_buf[(bh * N + m) * d + c] = mem[(src_bh * Nmem + m) * d + c];
 }
 
 __device__ __forceinline__ int digit_reverse16p(int k1, int P) {
@@ -279,18 +294,26 @@ hipError_t launch_readout_final(int io, const float *partial, void *out, int BH,
     return hipGetLastError();
 }
 
+hipError_t launch_set_memory(const float *mem, int mem_batch, float *v_buf, int B, int H, int N, int Nmem,
+                             hipStream_t st) {
+    const size_t total = (size_t)B * H * Nmem * 64;
+    k_set_memory<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(mem, v_buf, H, N, Nmem, 64, mem_batch == B ? 1 : 0,
+                                                                  total);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_ring(int io, const void *V, const void *Q, float *v_buf, float *q_buf, int B, int T, int H,
-                            int N, hipStream_t st) {
+                            int N, int row0, hipStream_t st) {
     const size_t total = (size_t)B * H * N * 32;
     const unsigned grid = (unsigned)((total + 255) / 256);
     if (io)
         k_fill_ring<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(V), static_cast<const uint32_t *>(Q),
                                                   reinterpret_cast<float2 *>(v_buf),
-                                                  reinterpret_cast<float2 *>(q_buf), T, H, N, total);
+                                                  reinterpret_cast<float2 *>(q_buf), T, H, N, row0, total);
     else
         k_fill_ring<IoF32><<<grid, 256, 0, st>>>(static_cast<const float2 *>(V), static_cast<const float2 *>(Q),
                                                  reinterpret_cast<float2 *>(v_buf), reinterpret_cast<float2 *>(q_buf),
-                                                 T, H, N, total);
+                                                 T, H, N, row0, total);
     return hipGetLastError();
 }
 
