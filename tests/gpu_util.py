@@ -26,4 +26,8 @@ def from_device(t):
 
 
 def f64(params):
-    return {k: (np.asarray(v, np.float64) if isinstance(v, np.ndarray) else v) for k, v in params.items()}
+    def up(v):
+        if not isinstance(v, np.ndarray):
+            return v
+        return v.astype(np.complex128 if np.iscomplexobj(v) else np.float64)
+    return {k: up(v) for k, v in params.items()}
