@@ -246,34 +246,48 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
 }
 
 // ------------------------------------------------------------------------------------------
-// gate_expand: one lane per expanded entry.
-__device__ __forceinline__ int digit_reverse16(int pos, int P) {
-    return P == 2 ? (((pos & 15) << 4) | (pos >> 4))
-                  : (((pos & 15) << 8) | (pos & 0xF0) | (pos >> 8));
-}
-
+// gate_expand: g [BH][L/2+1] -> gp [BH][N2][N1] with gp[bh][k2][j*TPC + tau] = ext(g)[k2 + N2*k1] / L,
+// k1 = digit_reverse16(16*tau + j) (the bin a lane of the big kernel holds in register j after the
+// forward passes) and ext = Hermitian extension with real DC and Nyquist bins.
+//
+// A block of 256*N2 consecutive bins k = k0 + q*N2 + k2 (q < 256) is exactly what 256 consecutive
+// entries r of every one of the N2 planes need: for N1 = 4096, r = 256 j + 16 b + a reads
+// q = 16 a + b (k0 = 256 N2 j); for N1 = 256 the order is the same on both sides (r = q).  One
+// workgroup per block loads the bins in order, turns them in LDS and stores whole 2 KB runs.
+// LDS strides keep the 16 x 2 lanes of a half wave on distinct banks for N2 = 32.
 __global__ __launch_bounds__(256) void k_gate_expand(const float2 *__restrict__ g, float2 *__restrict__ gp,
-                                                     int L, int N1, int N2, int P, size_t total) {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int TPC = N1 / 16;
-    const int F = L / 2 + 1;
-    const size_t bh = idx / L;
-    const int rem = (int)(idx % L);
-    const int k2 = rem / N1, r = rem % N1;
-    const int j = r / TPC, tau = r % TPC;
-    const int k1 = digit_reverse16(16 * tau + j, P);
-    const int k = k2 + N2 * k1;
+                                                     int L, int N1, int N2, int P) {
+    extern __shared__ float2 lds_ge[];
+    const int tid = threadIdx.x, bh = blockIdx.y, F = L / 2 + 1;
+    const int k0 = blockIdx.x * 256 * N2;
+    const int SB = (P == 3) ? N2 + 16 : N2 + 1, SA = (P == 3) ? 16 * SB + 1 : 16 * SB;
     const float scale = 1.0f / (float)L;
-    float2 val;
-    if (k == 0 || 2 * k == L) {
-        val = make_float2(g[bh * F + k].x, 0.0f);
-    } else if (2 * k < L) {
-        val = g[bh * F + k];
-    } else {
-        val = cconj(g[bh * F + (L - k)]);
+    const float2 *gh = g + (size_t)bh * F;
+    for (int m0 = tid; m0 < 256 * N2; m0 += 256 * 8) {   // eight independent loads in flight per lane
+        float2 raw[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int m = m0 + 256 * u, k = k0 + m;
+            raw[u] = (m < 256 * N2) ? gh[2 * k <= L ? k : L - k] : make_float2(0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int m = m0 + 256 * u, k = k0 + m;
+            if (m < 256 * N2) {
+                float2 val = raw[u];
+                if (2 * k > L) val.y = -val.y;
+                if (k == 0 || 2 * k == L) val.y = 0.0f;
+                const int q = m / N2, k2 = m % N2;
+                lds_ge[(q >> 4) * SA + (q & 15) * SB + k2] = make_float2(val.x * scale, val.y * scale);
+            }
+        }
     }
-    gp[idx] = make_float2(val.x * scale, val.y * scale);
+    __syncthreads();
+    const int q = (P == 3) ? (((tid & 15) << 4) | (tid >> 4)) : tid;
+    const float2 *src = lds_ge + (q >> 4) * SA + (q & 15) * SB;
+    float2 *dst = gp + (size_t)bh * L + blockIdx.x * 256 + tid;
+#pragma unroll 8
+    for (int k2 = 0; k2 < N2; ++k2) dst[(size_t)k2 * N1] = src[k2];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -369,10 +383,19 @@ hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int
 }
 
 hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st) {
-    const size_t total = (size_t)BH * pl.L;
-    const unsigned grid = (unsigned)((total + 255) / 256);
-    k_gate_expand<<<dim3(grid), dim3(256), 0, st>>>(g, gp, pl.L, pl.N1, pl.N2, pl.P, total);
-    return hipGetLastError();
+    const int SB = (pl.P == 3) ? pl.N2 + 16 : pl.N2 + 1, SA = (pl.P == 3) ? 16 * SB + 1 : 16 * SB;
+    const size_t lds = (size_t)16 * SA * sizeof(float2);
+    hipError_t e = allow_lds(k_gate_expand, lds);
+    if (e != hipSuccess) return e;
+    for (int bh0 = 0; bh0 < BH; bh0 += 65535) {         // grid.y limit
+        const int n = (BH - bh0 < 65535) ? BH - bh0 : 65535;
+        const int F = pl.L / 2 + 1;
+        k_gate_expand<<<dim3(pl.N1 / 256, n), dim3(256), lds, st>>>(g + (size_t)bh0 * F, gp + (size_t)bh0 * pl.L,
+                                                                    pl.L, pl.N1, pl.N2, pl.P);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace spectre
