@@ -44,6 +44,7 @@ int fail_hip(hipError_t e, const char *what) {
 struct DeviceTables {
     std::map<int, float2 *> roots;   // n -> device array [n] of exp(-j 2 pi m / n)
     std::map<int, float2 *> chirp;   // L -> device array: chirp [L], then its filter spectrum [M]
+    std::map<int, int *> slab_order; // L -> device array [L]: bin held by each position of the in-LDS transform
 };
 static std::mutex g_mu;
 static std::map<int, DeviceTables> g_tables;
@@ -76,6 +77,30 @@ int get_roots(int n, const float2 **out) {
             return fail_hip(e, "hipMemcpy(roots)");
         }
         it = t.roots.emplace(n, d).first;
+    }
+    *out = it->second;
+    return SPECTRE_OK;
+}
+
+static int get_slab_order(int L, const int **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    std::lock_guard<std::mutex> lk(g_mu);
+    DeviceTables &t = g_tables[dev];
+    auto it = t.slab_order.find(L);
+    if (it == t.slab_order.end()) {
+        std::vector<int> h((size_t)L);
+        slab_bin_order(L, h.data());
+        int *d = nullptr;
+        e = hipMalloc(reinterpret_cast<void **>(&d), sizeof(int) * h.size());
+        if (e != hipSuccess) return fail_hip(e, "hipMalloc(slab order)");
+        e = hipMemcpy(d, h.data(), sizeof(int) * h.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(d);
+            return fail_hip(e, "hipMemcpy(slab order)");
+        }
+        it = t.slab_order.emplace(L, d).first;
     }
     *out = it->second;
     return SPECTRE_OK;
@@ -237,6 +262,7 @@ void spectre_shutdown(void) {
         (void)hipSetDevice(kv.first);
         for (auto &r : kv.second.roots) (void)hipFree(r.second);
         for (auto &r : kv.second.chirp) (void)hipFree(r.second);
+        for (auto &r : kv.second.slab_order) (void)hipFree(r.second);
     }
     g_tables.clear();
     (void)hipSetDevice(cur);
@@ -276,7 +302,10 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         const float2 *roots = nullptr;
         int rc = get_roots(L, &roots);
         if (rc) return rc;
-        hipError_t e = launch_mix_slab((int)io, v, static_cast<const float2 *>(g), out, roots, B, L, H, st);
+        const int *order = nullptr;
+        rc = get_slab_order(L, &order);
+        if (rc) return rc;
+        hipError_t e = launch_mix_slab((int)io, v, static_cast<const float2 *>(g), out, roots, order, B, L, H, st);
         if (e != hipSuccess) return fail_hip(e, "mix_slab");
         return SPECTRE_OK;
     }

@@ -88,7 +88,8 @@ __device__ __forceinline__ void dft_any(float2 (&x)[R]) {
 // S = n / R its stride; roots[m] = exp(-j 2 pi m / L).  Forward: butterfly then twiddle (and
 // the gate, when GATE, which makes this the last forward pass).  Inverse: conjugate twiddle then
 // inverse butterfly.
-template <int R, bool INV, bool GATE, int PP>
+// UNIT: n == R, every twiddle is 1 and is skipped.
+template <int R, bool INV, bool GATE, bool UNIT, int PP>
 __device__ __forceinline__ void slab_pass(float2 *__restrict__ slab, const float2 *__restrict__ roots,
                                           const float2 *__restrict__ gpos, int L, int n, int tid, int nthreads) {
     constexpr int kShift = (PP == 32) ? 5 : 4;
@@ -103,14 +104,16 @@ __device__ __forceinline__ void slab_pass(float2 *__restrict__ slab, const float
         float2 x[R];
 #pragma unroll
         for (int j = 0; j < R; ++j) x[j] = slab[(base + S * j) * PP + col];
-        if (INV) {
+        if (INV && !UNIT) {
 #pragma unroll
             for (int u = 1; u < R; ++u) x[u] = cmulc(x[u], roots[i * u * tstep]);
         }
         dft_any<R, INV>(x);
         if (!INV) {
+            if (!UNIT) {
 #pragma unroll
-            for (int u = 1; u < R; ++u) x[u] = cmul(x[u], roots[i * u * tstep]);
+                for (int u = 1; u < R; ++u) x[u] = cmul(x[u], roots[i * u * tstep]);
+            }
             if (GATE) {
 #pragma unroll
                 for (int u = 0; u < R; ++u) x[u] = cmul(x[u], gpos[base + S * u]);
@@ -121,17 +124,17 @@ __device__ __forceinline__ void slab_pass(float2 *__restrict__ slab, const float
     }
 }
 
-template <bool INV, bool GATE, int PP>
+template <bool INV, bool GATE, bool UNIT, int PP>
 __device__ __forceinline__ void slab_pass_dispatch(int R, float2 *slab, const float2 *roots, const float2 *gpos,
                                                    int L, int n, int tid, int nthreads) {
     switch (R) {
-        case 2: slab_pass<2, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 3: slab_pass<3, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 4: slab_pass<4, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 5: slab_pass<5, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 7: slab_pass<7, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 8: slab_pass<8, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
-        case 16: slab_pass<16, INV, GATE, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 2: slab_pass<2, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 3: slab_pass<3, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 4: slab_pass<4, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 5: slab_pass<5, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 7: slab_pass<7, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 8: slab_pass<8, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 16: slab_pass<16, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
         default: break;
     }
 }
@@ -148,7 +151,8 @@ template <typename IO, int PP>
 __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__restrict__ v,
                                                   const float2 *__restrict__ g,
                                                   typename IO::pair_t *__restrict__ out,
-                                                  const float2 *__restrict__ roots_g, int L, int H,
+                                                  const float2 *__restrict__ roots_g,
+                                                  const int *__restrict__ bin_of_pos, int L, int H,
                                                   SlabRadices rad) {
     extern __shared__ float2 lds_slab[];
     float2 *slab = lds_slab;
@@ -159,31 +163,24 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
     const int bh = blockIdx.x / kParts, part = blockIdx.x % kParts, b = bh / H, h = bh % H;
     const int F = L / 2 + 1;
 
-    // rows l = (tid/32) + 8 i.  Eight loads are put in flight before any is consumed; the first
-    // batch flies while the gate table below is being built.
+    // rows l = tid/PP + kRows i.  Sixteen loads are put in flight before any is consumed (all 196 rows of
+    // the ViT grid at once for fp32 half heads); the first batch flies while the gate table below is built.
     const int lp_in = tid & (PP - 1), row_in = tid / PP;
     const typename IO::pair_t *src = v + (((size_t)b * L) * H + h) * 32 + part * PP + lp_in;
     const size_t rs = (size_t)H * 32;
-    typename IO::pair_t val[8];
+    constexpr int kBatch = 16;
+    typename IO::pair_t val[kBatch];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < kBatch; ++i) {
         const int l = row_in + kRows * i;
         val[i] = (l < L) ? src[(size_t)l * rs] : IO::zero();
     }
 
-    // roots of unity and the gate in position order: position p = sum_q u_q S_q holds bin
-    // k = sum_q u_q (R_1 ... R_{q-1}); full-length Hermitian extension, 1/L folded in.
+    // roots of unity and the gate in position order (bin_of_pos[p] = the bin that position p holds after
+    // the last forward pass); full-length Hermitian extension, 1/L folded in.
     for (int p = tid; p < L; p += 256) {
         roots[p] = roots_g[p];
-        int rem = p, n = L, k = 0, w = 1;
-        for (int q = 0; q < rad.count; ++q) {
-            const int S = n / rad.r[q];
-            const int u = rem / S;
-            rem -= u * S;
-            k += u * w;
-            w *= rad.r[q];
-            n = S;
-        }
+        const int k = bin_of_pos[p];
         float2 val;
         if (k == 0 || 2 * k == L) val = make_float2(g[(size_t)bh * F + k].x, 0.f);
         else if (2 * k < L) val = g[(size_t)bh * F + k];
@@ -192,18 +189,18 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
         gpos[p] = make_float2(val.x * sc, val.y * sc);
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < kBatch; ++i) {
         const int l = row_in + kRows * i;
         if (l < L) slab[l * PP + lp_in] = IO::unpack(val[i]);
     }
-    for (int l0 = row_in + 8 * kRows; l0 < L; l0 += 8 * kRows) {
+    for (int l0 = row_in + kBatch * kRows; l0 < L; l0 += kBatch * kRows) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < kBatch; ++i) {
             const int l = l0 + kRows * i;
             val[i] = (l < L) ? src[(size_t)l * rs] : IO::zero();
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < kBatch; ++i) {
             const int l = l0 + kRows * i;
             if (l < L) slab[l * PP + lp_in] = IO::unpack(val[i]);
         }
@@ -211,14 +208,15 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
     __syncthreads();
     int n = L;
     for (int q = 0; q < rad.count; ++q) {
-        if (q == rad.count - 1) slab_pass_dispatch<false, true, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
-        else slab_pass_dispatch<false, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        if (q == rad.count - 1) slab_pass_dispatch<false, true, true, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        else slab_pass_dispatch<false, false, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
         n /= rad.r[q];
         __syncthreads();
     }
     for (int q = rad.count - 1; q >= 0; --q) {
         n *= rad.r[q];
-        slab_pass_dispatch<true, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        if (q == rad.count - 1) slab_pass_dispatch<true, false, true, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        else slab_pass_dispatch<true, false, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
         __syncthreads();
     }
     {
@@ -249,9 +247,27 @@ static SlabRadices slab_radices(int L) {
     return r;
 }
 
+// Position p = sum_q u_q S_q (S_q = stride of pass q) holds bin k = sum_q u_q (R_1 ... R_(q-1)) after the
+// forward passes: mixed-radix digit reversal.
+void slab_bin_order(int L, int *bin_of_pos) {
+    const SlabRadices rad = slab_radices(L);
+    for (int p = 0; p < L; ++p) {
+        int rem = p, n = L, k = 0, w = 1;
+        for (int q = 0; q < rad.count; ++q) {
+            const int S = n / rad.r[q];
+            const int u = rem / S;
+            rem -= u * S;
+            k += u * w;
+            w *= rad.r[q];
+            n = S;
+        }
+        bin_of_pos[p] = k;
+    }
+}
+
 template <typename IO, int PP>
-static hipError_t mix_slab_t(const void *v, const float2 *g, void *out, const float2 *roots, int B, int L, int H,
-                             hipStream_t st) {
+static hipError_t mix_slab_t(const void *v, const float2 *g, void *out, const float2 *roots, const int *bin_of_pos,
+                             int B, int L, int H, hipStream_t st) {
     const size_t lds = ((size_t)L * PP + 2 * (size_t)L) * sizeof(float2);
     const SlabRadices rad = slab_radices(L);
     auto kern = k_mix_slab<IO, PP>;
@@ -261,14 +277,15 @@ static hipError_t mix_slab_t(const void *v, const float2 *g, void *out, const fl
         if (e != hipSuccess) return e;
     }
     kern<<<dim3(B * H * (32 / PP)), dim3(256), lds, st>>>(static_cast<const typename IO::pair_t *>(v), g,
-                                                         static_cast<typename IO::pair_t *>(out), roots, L, H, rad);
+                                                         static_cast<typename IO::pair_t *>(out), roots, bin_of_pos, L, H,
+                                                         rad);
     return hipGetLastError();
 }
 
-hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, const float2 *roots, int B, int L,
-                           int H, hipStream_t st) {
-    if (io) return mix_slab_t<IoBf16, 32>(v, g, out, roots, B, L, H, st);
-    return mix_slab_t<IoF32, 16>(v, g, out, roots, B, L, H, st);
+hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, const float2 *roots,
+                           const int *bin_of_pos, int B, int L, int H, hipStream_t st) {
+    if (io) return mix_slab_t<IoBf16, 32>(v, g, out, roots, bin_of_pos, B, L, H, st);
+    return mix_slab_t<IoF32, 16>(v, g, out, roots, bin_of_pos, B, L, H, st);
 }
 
 }  // namespace spectre
