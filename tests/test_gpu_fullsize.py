@@ -129,3 +129,63 @@ def test_decode_config_sampled_heads(oracle):
                 print(f"  step {i} (b,h)=({b},{h}): out {e_out:.3e} spec {e_spec:.3e} sum_q {e_sum:.3e}", flush=True)
                 assert e_out <= 1e-5 and e_spec <= 1e-5 and e_sum <= 1e-12
     assert cache.t == N + steps
+
+
+def test_wavelet_refinement_at_the_headline_shape(oracle):
+    """The benchmark's refinement row: B=1, H=32, L=131072, bf16, all 17 Haar levels; sampled heads."""
+    from paper_2502_18394_amd import binding
+    B, H, d, L = 1, 32, 64, 131072
+    J = synth.max_wavelet_levels(L)
+    vals, store = synth.tokens(synth.BASE_SEED + 40, (B, L, H, d), "bf16")
+    s = np.random.default_rng(synth.BASE_SEED + 41).standard_normal((B, H, J + 1, d)).astype(np.float32)
+    out = binding.wrm_apply(to_device(store, "bf16"), torch.from_numpy(s).cuda())
+    torch.cuda.synchronize()
+    heads = [0, 11, 31]
+    got = from_device(out[:, :, heads, :].contiguous())
+    want = oracle.wrm_apply(vals[:, :, heads, :].astype(np.float64), s[:, heads].astype(np.float64), J)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+
+
+def test_decode_with_memory_bank_sampled_heads(oracle):
+    """Config 4's cache with 64 of its 32768 rows pinned as persistent memory (Sec. 3.4): the ring of 32704
+    rows is pre-filled to the brim, then fused decode steps; sampled (b,h) against the oracle."""
+    from paper_2502_18394_amd import binding
+    B, H, d, N_mem, N_max, steps = 8, 32, 64, 64, 32704, 24
+    n = N_mem + N_max
+    sample = [(0, 0), (6, 19)]
+    rng = np.random.default_rng(synth.BASE_SEED + 50)
+    M = rng.standard_normal((1, H, N_mem, d), dtype=np.float32)
+    cache = binding.PrefixCache(B, H, d, N_max, N_mem=N_mem)
+    cache.set_memory(torch.from_numpy(M).cuda())
+    p = synth.gate_params(synth.BASE_SEED + 51, H, d, n)
+    P = binding.GateParams(p)
+    V = rng.standard_normal((B, N_max, H, d), dtype=np.float32)
+    Q = rng.standard_normal((B, N_max, H, d), dtype=np.float32)
+    cache.update(torch.from_numpy(V).cuda(), torch.from_numpy(Q).cuda())
+    ocs = []
+    for (b, h) in sample:
+        oc = oracle.MemoryPrefixCache(1, 1, d, N_mem, N_max)
+        oc.prefill(M[:, h:h + 1].astype(np.float64), V[b:b + 1, :, h:h + 1].astype(np.float64),
+                   Q[b:b + 1, :, h:h + 1].astype(np.float64))
+        ocs.append(oc)
+    del V, Q
+    vt = rng.standard_normal((steps, B, 1, H, d), dtype=np.float32)
+    qt = rng.standard_normal((steps, B, 1, H, d), dtype=np.float32)
+    vt_d, qt_d = torch.from_numpy(vt).cuda(), torch.from_numpy(qt).cuda()
+    for i in range(steps):
+        out = cache.step(vt_d[i], qt_d[i], P)
+        for (b, h), oc in zip(sample, ocs):
+            oc.update(vt[i, b:b + 1, :, h:h + 1].astype(np.float64), qt[i, b:b + 1, :, h:h + 1].astype(np.float64))
+        if i in (0, steps - 1):
+            torch.cuda.synchronize()
+            for (b, h), oc in zip(sample, ocs):
+                sub = {k: (np.asarray(v[h:h + 1], np.float64) if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+                want = oc.readout_newest(oracle.gate(oc.sum_q, 1.0 / N_max, sub, n, 0))
+                e_out = rel_l2(out[b, 0, h].cpu().numpy(), want[0, 0, 0])
+                e_spec = rel_l2(cache.prefix_fft[b, h].cpu().numpy(), oc.spec[0, 0])
+                print(f"  step {i} (b,h)=({b},{h}): out {e_out:.3e} spec {e_spec:.3e}", flush=True)
+                assert e_out <= 1e-5 and e_spec <= 1e-5
+                assert np.array_equal(cache.v_buf[b, h, :N_mem].cpu().numpy(), M[0, h])
+    assert cache.t == N_max + steps
