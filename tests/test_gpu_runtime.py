@@ -84,3 +84,51 @@ def test_error_paths_launch_nothing():
     assert e.value.code == binding.EINVAL and c.t == 0           # prompt longer than the window
     with pytest.raises(binding.SpectreError):
         binding.PrefixCache(1, 1, 64, 1000)                      # window length without a plan
+
+
+def test_forward_path_replays_from_a_hip_graph(oracle):
+    """gate -> mixer -> level gates -> refinement captured once in a HIP graph (tables warmed, buffers
+    preallocated: nothing allocates or synchronises inside the calls) and replayed on fresh inputs, with eager
+    work and synchronisations between the replays; every replay must equal the eager result bit for bit."""
+    from paper_2502_18394_amd import binding
+    B, L, H, d = 1, 4096, 4, 64
+    J = synth.max_wavelet_levels(L)
+    P = binding.GateParams(synth.gate_params(40, H, d, L))
+    W = binding.WrmParams(synth.wrm_params(41, H, d, J))
+
+    def inputs(seed):
+        _, vs = synth.tokens(seed, (B, L, H, d), "bf16")
+        _, qs = synth.tokens(seed + 1, (B, L, H, d), "bf16")
+        return to_device(vs, "bf16"), to_device(qs, "bf16")
+
+    def eager(v, q):
+        g = binding.gate(q, P, 1.0 / L)
+        return binding.wrm_apply(binding.mix_forward(v, g), binding.wrm_gates(q, W, 1.0 / L))
+
+    v0, q0 = inputs(42)
+    want0 = eager(v0, q0).clone()                       # also warms the per-length tables
+    torch.cuda.synchronize()
+    v_s, q_s = v0.clone(), q0.clone()                   # static graph inputs
+    g_s = torch.empty((B, H, L // 2 + 1), dtype=torch.complex64, device="cuda")
+    s_s = torch.empty((B, H, J + 1, d), dtype=torch.float32, device="cuda")
+    mix_s, out_s = torch.empty_like(v_s), torch.empty_like(v_s)
+    ws = [torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+          for n in (binding.gate_workspace_bytes(B, L, H, P), binding.mix_workspace_bytes(B, L, H, d, binding.BF16),
+                    binding.gate_workspace_bytes(B, L, H, P), binding.wrm_apply_workspace_bytes(B, L, H, d, J))]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.gate(q_s, P, 1.0 / L, g_out=g_s, ws=ws[0])
+        binding.mix_forward(v_s, g_s, out=mix_s, ws=ws[1])
+        binding.wrm_gates(q_s, W, 1.0 / L, s_out=s_s, ws=ws[2])
+        binding.wrm_apply(mix_s, s_s, out=out_s, ws=ws[3])
+    for r, seed in enumerate((42, 50, 60)):
+        v, q = inputs(seed)
+        want = eager(v, q).clone()                      # eager work between replays
+        torch.cuda.synchronize()
+        v_s.copy_(v)
+        q_s.copy_(q)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_s.view(torch.int16), want.view(torch.int16)), f"replay {r}"
+        if r == 0:
+            assert torch.equal(out_s.view(torch.int16), want0.view(torch.int16))
