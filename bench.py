@@ -63,6 +63,19 @@ def time_loop(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def time_each(fn, n):
+    """(median, min) milliseconds of n calls timed one by one with their own HIP event pairs."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in ev)
+    return t[len(t) // 2], t[0]
+
+
 def device_tokens(shape, seed, dtype):
     import torch
     gen = torch.Generator(device="cuda")
@@ -133,9 +146,11 @@ def sweep(args):
     cases = [("single_head_1k", synth.CONFIGS["single_head_1k"])]
     cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in synth.SWEEP_L]
     cases += [("vit_196", synth.CONFIGS["vit_196"])]
-    # lengths with neither a power-of-two nor an in-LDS plan (padded power-of-two convolution)
+    # four-step lengths with an odd factor (3 * 4096, 24 * 4096), then lengths with no plan of their own
+    # (padded power-of-two convolution)
+    cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in (12288, 98304)]
     cases += [("vit_197_cls", dict(B=256, H=12, L=197, d=64, io="f32"))]
-    cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in (1000, 12288, 50000)]
+    cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in (1000, 50000)]
     for name, c in cases:
         B, H, L, d = c["B"], c["H"], c["L"], c["d"]
         dtype = torch.bfloat16 if c["io"] == "bf16" else torch.float32
@@ -226,6 +241,7 @@ def main():
 
     ms_mix = time_loop(mix_only, args.steps, 2)
     ms_gate = time_loop(gate_only, args.steps, 2)
+    mix_med, mix_min = time_each(mix_only, max(args.steps, 50))
 
     tokens = B * L
     F = L // 2 + 1
@@ -246,7 +262,8 @@ def main():
                      "algorithmic_bytes": mix_bytes, "ms": ms_mix},
         "roofline_alu": {"bound": "alu", "achieved": mix_flops_instr / (ms_mix * 1e-3) / 1e9, "peak": VALU_PEAK_GINSTR,
                          "unit": "G lane-instr/s", "frac": mix_flops_instr / (ms_mix * 1e-3) / 1e9 / VALU_PEAK_GINSTR},
-        "mix_only": {"tokens_per_s": tokens / (ms_mix * 1e-3), "ms": ms_mix},
+        "mix_only": {"tokens_per_s": tokens / (ms_mix * 1e-3), "ms": ms_mix, "ms_median_of_single_calls": mix_med,
+                     "ms_min_of_single_calls": mix_min},
         "gate_only": {"ms": ms_gate, "algorithmic_bytes": gate_bytes,
                       "hbm_frac": gate_bytes / (ms_gate * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }

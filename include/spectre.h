@@ -32,11 +32,12 @@
  *     aborts or throws.
  *   - Supported shapes.  Mixer and cache: d = 64 channels per head.  Transform
  *     lengths of the mixer: every n <= 512 whose prime factors are 2, 3, 5 or 7
- *     (196 = 4*7*7 among them) and every power of two from 256 to 131072 have
- *     their own kernels; every other n <= 65536 is computed exactly as well, as a
- *     zero-padded power-of-two convolution (2.5 to 5 times the cost of a power of
- *     two of similar size).  The cache window N_max is a power of two from 256 to
- *     131072.  The gate takes any
+ *     (196 = 4*7*7 among them) and every n = N1 * N2 with N1 = 256 or 4096 and
+ *     N2 <= 32 of the form {1, 3, 5, 7} * 2^a (all powers of two from 256 to 131072,
+ *     768, 12288 = 3 * 4096, 98304 = 24 * 4096, ...) have their own kernels; every
+ *     other n <= 65536 is computed exactly as well, as a zero-padded power-of-two
+ *     convolution (2.5 to 5 times the cost of a power of two of similar size).  The
+ *     cache window n = N_mem + N_max is one of the N1 * N2 lengths above.  The gate takes any
  *     d <= 256, d_g <= 256 and any n_fft >= 2.  spectre_length_supported() answers
  *     for the mixer; anything else returns SPECTRE_EUNSUPPORTED.
  */

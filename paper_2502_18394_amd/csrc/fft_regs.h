@@ -5,6 +5,10 @@
 // outputs in natural order.  R is a power of two up to 32.  After full unrolling
 // every array index and every root of unity is a compile-time constant, so the
 // arrays live in VGPRs and the constants are instruction literals.
+//
+// dft_odd<R, INV> does the same for R = 3, 5, 7 and small_dft<N, INV> for every
+// N = M * Q <= 32 with M in {1, 3, 5, 7} and Q a power of two, by the prime-factor
+// index maps (M and Q are coprime, so no twiddles arise between the two stages).
 #pragma once
 #include "common.h"
 
@@ -84,6 +88,116 @@ __host__ __device__ __forceinline__ void dft(float2 (&x)[R]) {
             dft<R2, INV>(t);
 #pragma unroll
             for (int u2 = 0; u2 < R2; ++u2) x[u1 + 4 * u2] = t[u2];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// odd prime radices: X_0 = x_0 + sum a_j;  X_k, X_{R-k} = (x_0 + sum_j cos(2 pi jk/R) a_j)
+//   -/+ j sum_j sin(2 pi jk/R) b_j  with a_j = x_j + x_{R-j}, b_j = x_j - x_{R-j}.
+template <int R> struct OddRoots;
+template <> struct OddRoots<3> {
+    static constexpr float c[1] = {-0.5f};
+    static constexpr float s[1] = {0.86602540378443864676f};
+};
+template <> struct OddRoots<5> {
+    static constexpr float c[2] = {0.30901699437494742410f, -0.80901699437494742410f};
+    static constexpr float s[2] = {0.95105651629515357212f, 0.58778525229247312917f};
+};
+template <> struct OddRoots<7> {
+    static constexpr float c[3] = {0.62348980185873353053f, -0.22252093395631440429f, -0.90096886790241912624f};
+    static constexpr float s[3] = {0.78183148246802980871f, 0.97492791218182360702f, 0.43388373911755812048f};
+};
+
+template <int R>
+__device__ constexpr float odd_cos(int m) {   // cos(2 pi m / R)
+    m %= R;
+    if (m == 0) return 1.0f;
+    if (m > R / 2) m = R - m;
+    return OddRoots<R>::c[m - 1];
+}
+template <int R>
+__device__ constexpr float odd_sin(int m) {   // sin(2 pi m / R)
+    m %= R;
+    if (m == 0) return 0.0f;
+    if (m > R / 2) return -OddRoots<R>::s[R - m - 1];
+    return OddRoots<R>::s[m - 1];
+}
+
+template <int R, bool INV>
+__device__ __forceinline__ void dft_odd(float2 (&x)[R]) {
+    constexpr int Hf = R / 2;
+    float2 a[Hf], b[Hf];
+#pragma unroll
+    for (int j = 1; j <= Hf; ++j) {
+        a[j - 1] = x[j] + x[R - j];
+        b[j - 1] = x[j] - x[R - j];
+    }
+    float2 x0 = x[0];
+    float2 sum = x0;
+#pragma unroll
+    for (int j = 0; j < Hf; ++j) sum = sum + a[j];
+    x[0] = sum;
+#pragma unroll
+    for (int k = 1; k <= Hf; ++k) {
+        float2 cr = x0, si = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int j = 1; j <= Hf; ++j) {
+            const float c = odd_cos<R>(j * k), s = odd_sin<R>(j * k);
+            cr.x = fmaf(c, a[j - 1].x, cr.x);
+            cr.y = fmaf(c, a[j - 1].y, cr.y);
+            si.x = fmaf(s, b[j - 1].x, si.x);
+            si.y = fmaf(s, b[j - 1].y, si.y);
+        }
+        // forward: X_k = cr - j si, X_{R-k} = cr + j si  (j*si = (-si.y, si.x)); inverse swaps
+        const float2 jsi = make_float2(-si.y, si.x);
+        x[k] = INV ? cr + jsi : cr - jsi;
+        x[R - k] = INV ? cr - jsi : cr + jsi;
+    }
+}
+
+// Odd part of n (n with its factors of two removed), and a^-1 mod m for coprime a, m (1 if m = 1).
+__host__ __device__ constexpr int odd_part(int n) { return (n % 2 == 0) ? odd_part(n / 2) : n; }
+__host__ __device__ constexpr int inverse_mod(int a, int m) {
+    for (int i = 1; i < m; ++i)
+        if ((a * i) % m == 1) return i;
+    return 1;
+}
+__host__ __device__ constexpr bool small_dft_supported(int n) {
+    return n >= 1 && n <= 32 && (odd_part(n) == 1 || odd_part(n) == 3 || odd_part(n) == 5 || odd_part(n) == 7);
+}
+
+// N = M * Q, M odd prime (or 1), Q a power of two.  Prime-factor algorithm: input index
+// n = (Q n1 + M n2) mod N, output index k = (Q (Q^-1 mod M) k1 + M (M^-1 mod Q) k2) mod N, so that
+// exp(-j 2 pi n k / N) = exp(-j 2 pi n1 k1 / M) exp(-j 2 pi n2 k2 / Q).
+template <int N, bool INV>
+__device__ __forceinline__ void small_dft(float2 (&x)[N]) {
+    static_assert(small_dft_supported(N), "length");
+    constexpr int M = odd_part(N), Q = N / M;
+    if constexpr (M == 1) {
+        dft<N, INV>(x);
+    } else if constexpr (Q == 1) {
+        dft_odd<N, INV>(x);
+    } else {
+        constexpr int eM = Q * inverse_mod(Q % M, M), eQ = M * inverse_mod(M % Q, Q);
+        float2 y[N];
+#pragma unroll
+        for (int n1 = 0; n1 < M; ++n1) {
+            float2 t[Q];
+#pragma unroll
+            for (int n2 = 0; n2 < Q; ++n2) t[n2] = x[(Q * n1 + M * n2) % N];
+            dft<Q, INV>(t);
+#pragma unroll
+            for (int k2 = 0; k2 < Q; ++k2) y[n1 * Q + k2] = t[k2];
+        }
+#pragma unroll
+        for (int k2 = 0; k2 < Q; ++k2) {
+            float2 t[M];
+#pragma unroll
+            for (int n1 = 0; n1 < M; ++n1) t[n1] = y[n1 * Q + k2];
+            dft_odd<M, INV>(t);
+#pragma unroll
+            for (int k1 = 0; k1 < M; ++k1) x[(eM * k1 + eQ * k2) % N] = t[k1];
         }
     }
 }

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
     float2 x[N2];
 #pragma unroll
     for (int t2 = 0; t2 < N2; ++t2) x[t2] = IO::unpack(lds[(t2 * TT + tl) * S + p]);
-    dft<N2, false>(x);
+    small_dft<N2, false>(x);
     float2 *dst = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
 #pragma unroll
     for (int k2 = 0; k2 < N2; ++k2) {
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const float2 *__restrict_
         for (int k2 = 0; k2 < N2; ++k2) y[k2] = src[(size_t)k2 * 32 * N1];
 #pragma unroll
         for (int k2 = 1; k2 < N2; ++k2) y[k2] = cmulc(y[k2], twL[t1 * k2]);
-        dft<N2, true>(y);
+        small_dft<N2, true>(y);
 #pragma unroll
         for (int t2 = 0; t2 < N2; ++t2) lds[(t2 * TT + tl) * S + p] = IO::pack(y[t2]);
     }
@@ -292,9 +292,13 @@ __global__ __launch_bounds__(256) void k_gate_expand(const float2 *__restrict__ 
 
 // ------------------------------------------------------------------------------------------
 bool pow2_split(int L, int *N1, int *N2, int *P) {
-    if (L < 256 || (L & (L - 1)) != 0 || L > 131072) return false;
-    if (L <= 8192) { *N1 = 256; *P = 2; }
-    else { *N1 = 4096; *P = 3; }
+    if (L < 256 || L > 131072) return false;
+    const bool by256 = (L % 256 == 0) && small_dft_supported(L / 256);
+    const bool by4096 = (L % 4096 == 0) && small_dft_supported(L / 4096);
+    // the in-register small transform is the cheaper place for stages, so N2 is made as large as 32 allows
+    if (by256) { *N1 = 256; *P = 2; }
+    else if (by4096) { *N1 = 4096; *P = 3; }
+    else return false;
     *N2 = L / *N1;
     return true;
 }
@@ -330,14 +334,16 @@ static hipError_t small_inv_t(const Pow2Plan &pl, const float2 *scr, void *out, 
     return hipGetLastError();
 }
 
+#define SPECTRE_N2_CASE(FN, N, ...) \
+    case N: return io ? FN<N, 16, IoBf16>(__VA_ARGS__) : FN<N, 8, IoF32>(__VA_ARGS__);
 #define SPECTRE_DISPATCH_N2(FN, ...)                                         \
     switch (pl.N2) {                                                         \
-        case 1: return io ? FN<1, 16, IoBf16>(__VA_ARGS__) : FN<1, 8, IoF32>(__VA_ARGS__);   \
-        case 2: return io ? FN<2, 16, IoBf16>(__VA_ARGS__) : FN<2, 8, IoF32>(__VA_ARGS__);   \
-        case 4: return io ? FN<4, 16, IoBf16>(__VA_ARGS__) : FN<4, 8, IoF32>(__VA_ARGS__);   \
-        case 8: return io ? FN<8, 16, IoBf16>(__VA_ARGS__) : FN<8, 8, IoF32>(__VA_ARGS__);   \
-        case 16: return io ? FN<16, 16, IoBf16>(__VA_ARGS__) : FN<16, 8, IoF32>(__VA_ARGS__); \
-        case 32: return io ? FN<32, 16, IoBf16>(__VA_ARGS__) : FN<32, 8, IoF32>(__VA_ARGS__); \
+        SPECTRE_N2_CASE(FN, 1, __VA_ARGS__) SPECTRE_N2_CASE(FN, 2, __VA_ARGS__) SPECTRE_N2_CASE(FN, 3, __VA_ARGS__)    \
+        SPECTRE_N2_CASE(FN, 4, __VA_ARGS__) SPECTRE_N2_CASE(FN, 5, __VA_ARGS__) SPECTRE_N2_CASE(FN, 6, __VA_ARGS__)    \
+        SPECTRE_N2_CASE(FN, 7, __VA_ARGS__) SPECTRE_N2_CASE(FN, 8, __VA_ARGS__) SPECTRE_N2_CASE(FN, 10, __VA_ARGS__)   \
+        SPECTRE_N2_CASE(FN, 12, __VA_ARGS__) SPECTRE_N2_CASE(FN, 14, __VA_ARGS__) SPECTRE_N2_CASE(FN, 16, __VA_ARGS__) \
+        SPECTRE_N2_CASE(FN, 20, __VA_ARGS__) SPECTRE_N2_CASE(FN, 24, __VA_ARGS__) SPECTRE_N2_CASE(FN, 28, __VA_ARGS__) \
+        SPECTRE_N2_CASE(FN, 32, __VA_ARGS__)                                 \
         default: return hipErrorInvalidValue;                                \
     }
 

@@ -14,70 +14,6 @@
 
 namespace spectre {
 
-// ------------------------------------------------------------------------------------------
-// odd prime radices: X_0 = x_0 + sum a_j;  X_k, X_{R-k} = (x_0 + sum_j cos(2 pi jk/R) a_j)
-//   -/+ j sum_j sin(2 pi jk/R) b_j  with a_j = x_j + x_{R-j}, b_j = x_j - x_{R-j}.
-template <int R> struct OddRoots;
-template <> struct OddRoots<3> {
-    static constexpr float c[1] = {-0.5f};
-    static constexpr float s[1] = {0.86602540378443864676f};
-};
-template <> struct OddRoots<5> {
-    static constexpr float c[2] = {0.30901699437494742410f, -0.80901699437494742410f};
-    static constexpr float s[2] = {0.95105651629515357212f, 0.58778525229247312917f};
-};
-template <> struct OddRoots<7> {
-    static constexpr float c[3] = {0.62348980185873353053f, -0.22252093395631440429f, -0.90096886790241912624f};
-    static constexpr float s[3] = {0.78183148246802980871f, 0.97492791218182360702f, 0.43388373911755812048f};
-};
-
-template <int R>
-__device__ constexpr float odd_cos(int m) {   // cos(2 pi m / R)
-    m %= R;
-    if (m == 0) return 1.0f;
-    if (m > R / 2) m = R - m;
-    return OddRoots<R>::c[m - 1];
-}
-template <int R>
-__device__ constexpr float odd_sin(int m) {   // sin(2 pi m / R)
-    m %= R;
-    if (m == 0) return 0.0f;
-    if (m > R / 2) return -OddRoots<R>::s[R - m - 1];
-    return OddRoots<R>::s[m - 1];
-}
-
-template <int R, bool INV>
-__device__ __forceinline__ void dft_odd(float2 (&x)[R]) {
-    constexpr int Hf = R / 2;
-    float2 a[Hf], b[Hf];
-#pragma unroll
-    for (int j = 1; j <= Hf; ++j) {
-        a[j - 1] = x[j] + x[R - j];
-        b[j - 1] = x[j] - x[R - j];
-    }
-    float2 x0 = x[0];
-    float2 sum = x0;
-#pragma unroll
-    for (int j = 0; j < Hf; ++j) sum = sum + a[j];
-    x[0] = sum;
-#pragma unroll
-    for (int k = 1; k <= Hf; ++k) {
-        float2 cr = x0, si = make_float2(0.f, 0.f);
-#pragma unroll
-        for (int j = 1; j <= Hf; ++j) {
-            const float c = odd_cos<R>(j * k), s = odd_sin<R>(j * k);
-            cr.x = fmaf(c, a[j - 1].x, cr.x);
-            cr.y = fmaf(c, a[j - 1].y, cr.y);
-            si.x = fmaf(s, b[j - 1].x, si.x);
-            si.y = fmaf(s, b[j - 1].y, si.y);
-        }
-        // forward: X_k = cr - j si, X_{R-k} = cr + j si  (j*si = (-si.y, si.x)); inverse swaps
-        const float2 jsi = make_float2(-si.y, si.x);
-        x[k] = INV ? cr + jsi : cr - jsi;
-        x[R - k] = INV ? cr - jsi : cr + jsi;
-    }
-}
-
 template <int R, bool INV>
 __device__ __forceinline__ void dft_any(float2 (&x)[R]) {
     if constexpr (R == 3 || R == 5 || R == 7) dft_odd<R, INV>(x);

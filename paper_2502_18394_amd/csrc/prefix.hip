@@ -78,8 +78,16 @@ __global__ __launch_bounds__(256) void k_sweep(float4 *__restrict__ X, const flo
     const float invN = 1.0f / (float)N;
     float acc0 = 0.f, acc1 = 0.f;
     float4 *Xp = X + ((size_t)bh * F) * 32 + lane;
-    for (int k = k0 + row; k < k1; k += 8) {
-        const unsigned m = ((unsigned)k * (unsigned)slot) & (unsigned)(N - 1);
+    // (k * slot) mod N for k = k0 + row, k0 + row + 8, ...: exact for any N, one 64-bit remainder per lane
+    unsigned step, m;
+    if ((N & (N - 1)) == 0) {            // power of two: the wrap of 32-bit products is harmless
+        step = (8u * (unsigned)slot) & (unsigned)(N - 1);
+        m = ((unsigned)(k0 + row) * (unsigned)slot) & (unsigned)(N - 1);
+    } else {
+        step = (unsigned)((8ull * (unsigned)slot) % (unsigned)N);
+        m = (unsigned)(((unsigned long long)(k0 + row) * (unsigned)slot) % (unsigned)N);
+    }
+    for (int k = k0 + row; k < k1; k += 8, m = (m + step >= (unsigned)N) ? m + step - (unsigned)N : m + step) {
         const float2 w = tw[m];
         float4 x = stream_load(Xp + (size_t)k * 32);
         if (UPDATE) {

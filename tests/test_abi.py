@@ -49,7 +49,9 @@ def test_version_and_supported_lengths(lib):
     # any other length up to 65536 goes through a padded power-of-two convolution
     for n in (1, 11, 26, 197, 1022, 1031, 3 * 4096, 65535, 65536):
         assert lib.spectre_length_supported(n, 64) == 1, n
-    for n in (0, -4, 65537, 3 * 32768, 262144):
+    # 3 * 32768 = 24 * 4096 has a four-step plan with an odd factor; 5 * 32768 = 40 * 4096 has none
+    assert lib.spectre_length_supported(3 * 32768, 64) == 1
+    for n in (0, -4, 65537, 5 * 32768, 262144):
         assert lib.spectre_length_supported(n, 64) == 0, n
     assert lib.spectre_length_supported(1024, 48) == 0
 
@@ -57,7 +59,7 @@ def test_version_and_supported_lengths(lib):
 def test_workspace_queries(lib):
     assert lib.spectre_mix_workspace_bytes(1, 131072, 32, 64, 1) > 32 * 131072 * 8
     assert lib.spectre_mix_workspace_bytes(256, 196, 12, 64, 0) == 256          # slab path needs no scratch
-    assert lib.spectre_mix_workspace_bytes(1, 3 * 32768, 1, 64, 0) == 0         # unsupported
+    assert lib.spectre_mix_workspace_bytes(1, 5 * 32768, 1, 64, 0) == 0         # unsupported
     # L=11: padded length 256; gate planes + scratch + two staging tensors of one pseudo-head
     assert lib.spectre_mix_workspace_bytes(1, 11, 1, 64, 0) == 256 * 8 + 256 * 32 * 8 + 11 * 32 * 8 + 256 * 32 * 8
     F = 32768 // 2 + 1
@@ -78,7 +80,7 @@ def test_bad_arguments_fail_on_the_host(lib):
     rc = lib.spectre_mix_forward(fake, fake, fake, 1, 1024, 1, 64, 0, fake, ctypes.c_size_t(1 << 30), None)
     assert rc == 1 and b"overlap" in lib.spectre_last_error()
     far = ctypes.c_void_p(1 << 40)
-    rc = lib.spectre_mix_forward(fake, fake, far, 1, 3 * 32768, 1, 64, 0, fake, ctypes.c_size_t(1 << 30), None)
+    rc = lib.spectre_mix_forward(fake, fake, far, 1, 5 * 32768, 1, 64, 0, fake, ctypes.c_size_t(1 << 30), None)
     assert rc == 2                                                                # unsupported length
     rc = lib.spectre_mix_forward(fake, fake, far, 1, 1024, 1, 32, 0, fake, ctypes.c_size_t(1 << 30), None)
     assert rc == 2                                                                # unsupported d

@@ -117,6 +117,20 @@ def test_any_other_length(oracle, B, L, H, io):
     assert err <= TOL[io]
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,L,H", [(1, 768, 2), (2, 1280, 1), (1, 1792, 3), (1, 1536, 2), (1, 2560, 1), (2, 3072, 2),
+                                   (1, 3584, 1), (1, 5120, 2), (1, 6144, 3), (1, 7168, 1), (1, 12288, 2), (1, 20480, 1),
+                                   (1, 28672, 2), (1, 49152, 1), (1, 98304, 1), (1, 114688, 1)])
+def test_four_step_with_an_odd_factor(oracle, B, L, H, io):
+    """L = N1 * N2 with N1 = 256 or 4096 and N2 = 3, 5, 7 times a power of two (<= 28): the same four-step
+    kernels as the power-of-two lengths, the small in-register transform by the prime-factor algorithm."""
+    print(f"case B={B} L={L} H={H} io={io}", flush=True)
+    got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 13 * L + H)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL[io]
+
+
 def test_any_other_length_identity_and_shift(oracle):
     B, L, H, d, s = 1, 1000, 2, 64, 333
     k = np.arange(L // 2 + 1)

@@ -24,6 +24,7 @@ def _assert_state(c, oc, tag):
 
 
 @pytest.mark.parametrize("N,T0,steps,io", [(256, 100, 560, "f32"), (256, 0, 300, "bf16"), (512, 512, 40, "f32"),
+                                           (768, 500, 300, "f32"), (12288, 12000, 300, "bf16"),
                                            (4096, 1000, 20, "bf16"), (16384, 16384, 6, "f32")])
 def test_prefill_then_updates_track_the_oracle(oracle, N, T0, steps, io):
     from paper_2502_18394_amd import binding
@@ -62,7 +63,8 @@ def test_multi_token_append_equals_single_steps(oracle):
     _assert_state(c, oc, "after 1 + 299 tokens")
 
 
-@pytest.mark.parametrize("N,T,io", [(256, 90, "f32"), (256, 700, "f32"), (1024, 1024, "bf16"), (16384, 300, "f32")])
+@pytest.mark.parametrize("N,T,io", [(256, 90, "f32"), (256, 700, "f32"), (1024, 1024, "bf16"), (16384, 300, "f32"),
+                                    (1280, 1500, "f32"), (7168, 7000, "bf16")])
 def test_readouts_match_oracle(oracle, N, T, io):
     from paper_2502_18394_amd import binding
     B, H, d = 2, 3, 64
