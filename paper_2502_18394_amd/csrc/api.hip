@@ -134,7 +134,7 @@ static int get_chirp(int L, const Pow2Plan &pl, const float2 **w, const float2 *
 
 int get_pow2_plan(int L, Pow2Plan *pl) {
     int N1, N2, P;
-    if (!pow2_split(L, &N1, &N2, &P)) return fail(SPECTRE_EUNSUPPORTED, "no power-of-two plan for length %d", L);
+    if (!pow2_split(L, &N1, &N2, &P)) return fail(SPECTRE_EUNSUPPORTED, "no four-step plan for length %d", L);
     pl->L = L; pl->N1 = N1; pl->N2 = N2; pl->P = P;
     int rc = get_roots(L, &pl->twL);
     if (rc) return rc;

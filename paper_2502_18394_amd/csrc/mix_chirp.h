@@ -1,10 +1,10 @@
-// Mixing layer for sequence lengths with no power-of-two or in-LDS plan (Sec. 3.2 steps 2-4).
+// Mixing layer for sequence lengths with no four-step or in-LDS plan (Sec. 3.2 steps 2-4).
 //
 // By App. B the layer is a circular convolution of every channel with one real kernel per head,
 // kappa = irfft_L(gate).  A length-L circular convolution equals the first L outputs of a
-// length-M circular convolution (M a power of two >= 2L-1) of the zero-padded signal with the
+// length-M circular convolution (M >= 2L-1 a length the four-step kernels serve) of the zero-padded signal with the
 // periodic extension kk of kappa laid out around index 0, so the data go through the
-// power-of-two kernels once, with rfft_M(kk) as their gate.  kappa itself, one sequence per
+// four-step kernels once, with rfft_M(kk) as their gate.  kappa itself, one sequence per
 // head, is an L-point inverse DFT of arbitrary L; it is evaluated by the chirp-z identity
 //   exp(+j 2 pi k m / L) = w_k w_m conj(w_{m-k}),  w_n = exp(+j pi n^2 / L)
 // which turns it into one more length-M circular convolution, with a fixed chirp filter.
@@ -16,7 +16,7 @@
 
 namespace spectre {
 
-// Smallest usable power of two M >= max(2L-1, 256); 0 if it exceeds the power-of-two path.
+// Smallest four-step length M >= max(2L-1, 256); 0 if there is none (L > 65536).
 int chirp_padded_length(int L);
 
 // A[k][ph][p] = ext(g[bh])[k] * w_k, bh = 32 ph + p (zero for bh >= BH); ext = Hermitian extension

@@ -1,5 +1,5 @@
-// Arbitrary-length mixing through the power-of-two kernels: chirp-z evaluation of the per-head
-// convolution kernel and its embedding in a padded power-of-two convolution.
+// Arbitrary-length mixing through the four-step kernels: chirp-z evaluation of the per-head
+// convolution kernel and its embedding in a padded convolution of a four-step length.
 #include "mix_chirp.h"
 
 #include <cmath>
@@ -7,14 +7,21 @@
 #include <vector>
 
 #include "common.h"
+#include "mix_pow2.h"
 
 namespace spectre {
 
 int chirp_padded_length(int L) {
     if (L < 1 || L > 65536) return 0;
-    int M = 256;
-    while (M < 2 * L - 1) M <<= 1;
-    return M <= 131072 ? M : 0;
+    const int need = 2 * L - 1;
+    int best = 0;
+    for (int N1 : {256, 4096})
+        for (int N2 = 1; N2 <= 32; ++N2) {
+            const int M = N1 * N2;
+            int a, b, c;
+            if (M >= need && (best == 0 || M < best) && pow2_split(M, &a, &b, &c)) best = M;
+        }
+    return best;
 }
 
 __global__ __launch_bounds__(256) void k_chirp_pre(const float2 *__restrict__ g, const float2 *__restrict__ w,
@@ -90,23 +97,27 @@ hipError_t launch_chirp_gate(const float2 *scr, float2 *gp, int BH, int M, int N
 }
 
 // ------------------------------------------------------------------------------------------ host tables
-static void fft_host(std::vector<std::complex<double>> &a) {      // in-place radix-2, forward sign
-    const size_t n = a.size();
-    for (size_t i = 1, j = 0; i < n; ++i) {
-        size_t bit = n >> 1;
-        for (; j & bit; bit >>= 1) j ^= bit;
-        j ^= bit;
-        if (i < j) std::swap(a[i], a[j]);
+// Forward DFT of n = 2^a 3^b 5^c 7^d points (decimation in time, smallest prime factor first), out of place.
+// root[j] = exp(-j 2 pi j / top) for the top-level length, of which n is a divisor.
+static void fft_host(const std::complex<double> *in, size_t stride, size_t n, std::complex<double> *out,
+                     const std::vector<std::complex<double>> &root) {
+    if (n == 1) {
+        out[0] = in[0];
+        return;
     }
-    for (size_t len = 2; len <= n; len <<= 1) {
-        std::vector<std::complex<double>> root(len / 2);
-        for (size_t m = 0; m < len / 2; ++m) root[m] = std::polar(1.0, -2.0 * M_PI * (double)m / (double)len);
-        for (size_t i = 0; i < n; i += len)
-            for (size_t m = 0; m < len / 2; ++m) {
-                const std::complex<double> u = a[i + m], t = a[i + m + len / 2] * root[m];
-                a[i + m] = u + t;
-                a[i + m + len / 2] = u - t;
-            }
+    const size_t top = root.size();
+    size_t p = 2;
+    while (n % p != 0) ++p;
+    const size_t m = n / p;
+    for (size_t r = 0; r < p; ++r) fft_host(in + r * stride, stride * p, m, out + r * m, root);
+    std::complex<double> col[7];
+    for (size_t k = 0; k < m; ++k) {
+        for (size_t r = 0; r < p; ++r) col[r] = out[r * m + k] * root[(r * k) * (top / n)];
+        for (size_t q = 0; q < p; ++q) {
+            std::complex<double> acc = col[0];
+            for (size_t r = 1; r < p; ++r) acc += col[r] * root[((r * q) % p) * (top / p)];
+            out[k + q * m] = acc;
+        }
     }
 }
 
@@ -121,9 +132,12 @@ void chirp_tables_host(int L, int M, int N1, int N2, int P, float2 *w, float2 *f
         wd[n] = std::polar(1.0, M_PI * (double)sq / (double)L);
         w[n] = make_float2((float)wd[n].real(), (float)wd[n].imag());
     }
-    f[0] = std::conj(wd[0]);
-    for (int i = 1; i < L; ++i) f[i] = f[M - i] = std::conj(wd[i]);
-    fft_host(f);
+    std::vector<std::complex<double>> ft(M, std::complex<double>(0.0, 0.0));
+    ft[0] = std::conj(wd[0]);
+    for (int i = 1; i < L; ++i) ft[i] = ft[M - i] = std::conj(wd[i]);
+    std::vector<std::complex<double>> root(M);
+    for (int j = 0; j < M; ++j) root[j] = std::polar(1.0, -2.0 * M_PI * (double)j / (double)M);
+    fft_host(ft.data(), 1, (size_t)M, f.data(), root);
     const int TPC = N1 / 16;
     for (int k2 = 0; k2 < N2; ++k2)
         for (int r = 0; r < N1; ++r) {

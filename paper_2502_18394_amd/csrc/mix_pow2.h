@@ -1,4 +1,5 @@
-// Power-of-two transform path: host-side plan and launch declarations.
+// Four-step transform path (power-of-two lengths and power-of-two lengths times 3, 5 or 7): host-side plan and
+// launch declarations.
 //
 // An L-point transform (L = N1 * N2) of the channel pairs of one head is split the
 // four-step way: N2-point DFTs over the far index inside single lanes ("small"
@@ -13,13 +14,13 @@ namespace spectre {
 
 struct Pow2Plan {
     int L = 0;            // transform length
-    int N1 = 0, N2 = 0;   // L = N1 * N2; N1 = 16^P
+    int N1 = 0, N2 = 0;   // L = N1 * N2; N1 = 16^P, N2 <= 32 of the form {1,3,5,7} * 2^a
     int P = 0;
     const float2 *twL = nullptr;   // [L]  exp(-j 2 pi m / L), device
     const float2 *twN1 = nullptr;  // [N1] exp(-j 2 pi m / N1), device
 };
 
-// Decomposition rule; returns false if L has no power-of-two plan.
+// Decomposition rule; returns false if L has no such plan.
 bool pow2_split(int L, int *N1, int *N2, int *P);
 
 // Launchers (enqueue only).  `pairs` = d/2 must be 32.  All return hipError_t.

@@ -1,5 +1,6 @@
-// Power-of-two transform path of the SPECTRE mixing layer (Sec. 3.2 steps 2-4,
-// Eq. 3 and Eq. 4) for gfx950.
+// Four-step transform path of the SPECTRE mixing layer (Sec. 3.2 steps 2-4,
+// Eq. 3 and Eq. 4) for gfx950: L = N1 * N2 with N1 = 256 or 4096 and N2 <= 32 of the
+// form {1, 3, 5, 7} * 2^a.
 //
 // Two adjacent channels of a head are transformed together as one complex
 // sequence z = v_even + j v_odd.  Because the gate is extended to all L bins by
