@@ -31,7 +31,7 @@
  *     launch) and spectre_last_error() describes the reason.  The library never
  *     aborts or throws.
  *   - Supported shapes.  Mixer and cache: d = 64 channels per head.  Transform
- *     lengths of the mixer: every n <= 512 whose prime factors are 2, 3, 5 or 7
+ *     lengths of the mixer: every n <= 2048 whose prime factors are 2, 3, 5 or 7
  *     (196 = 4*7*7 among them) and every n = N1 * N2 with N1 = 256 or 4096 and
  *     N2 <= 32 of the form {1, 3, 5, 7} * 2^a (all powers of two from 256 to 131072,
  *     768, 12288 = 3 * 4096, 98304 = 24 * 4096, ...) have their own kernels; every

@@ -175,7 +175,9 @@ static int mix_route(int BH, int L, int d) {
     if (d != 64) return 0;
     int N1, N2, P;
     const bool p2 = pow2_split(L, &N1, &N2, &P), sl = slab_supported(L);
-    if (sl && (!p2 || BH >= 256)) return 1;
+    // the in-LDS kernel is one launch: it wins when the length has no four-step plan, when there are many short
+    // slabs, and when the whole call is small enough to be bound by the four-step path's dependent launches
+    if (sl && (!p2 || (L <= 512 && BH >= 256) || (long long)BH * L <= 65536)) return 1;
     if (p2) return 2;
     return chirp_padded_length(L) ? 3 : 0;
 }

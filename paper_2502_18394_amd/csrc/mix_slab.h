@@ -4,7 +4,7 @@
 
 namespace spectre {
 
-constexpr int kSlabMaxL = 512;
+constexpr int kSlabMaxL = 2048;
 
 // True if L <= kSlabMaxL and L = 2^a 3^b 5^c 7^d.
 bool slab_supported(int L);

@@ -28,10 +28,11 @@ __device__ __forceinline__ void dft_any(float2 (&x)[R]) {
 template <int R, bool INV, bool GATE, bool UNIT, int PP>
 __device__ __forceinline__ void slab_pass(float2 *__restrict__ slab, const float2 *__restrict__ roots,
                                           const float2 *__restrict__ gpos, int L, int n, int tid, int nthreads) {
-    constexpr int kShift = (PP == 32) ? 5 : 4;
+    constexpr int kShift = (PP == 32) ? 5 : (PP == 16) ? 4 : (PP == 8) ? 3 : 2;
+    static_assert(PP == 32 || PP == 16 || PP == 8 || PP == 4, "pairs per workgroup");
     const int S = n / R, tstep = L / n;
     const int nb = (L / R) * PP;
-    // bi / S by a multiply and shift: exact while bi * S < 2^20 (bi < L/R <= 256, S <= 256)
+    // bi / S by a multiply and shift: exact while bi * S < 2^20 (bi < L/R <= 1024, S <= L/R)
     const unsigned inv_s = ((1u << 20) + (unsigned)S - 1) / (unsigned)S;
     for (int w = tid; w < nb; w += nthreads) {
         const int col = w & (PP - 1), bi = w >> kShift;
@@ -80,8 +81,10 @@ struct SlabRadices {
     int r[10];
 };
 
-// grid = B*H*(32/PP) workgroups of 256 lanes, PP channel pairs each (a whole head, or half a head
-// when rows are fp32: still full 128-byte row segments, half the LDS, twice the workgroups per CU).
+// grid = B*H*(32/PP) workgroups of 256 lanes, PP channel pairs each: a whole head, half a head when rows
+// are fp32 (still full 128-byte row segments, half the LDS, twice the workgroups per CU), or as little as
+// 4 pairs when there are few heads (then the call is one launch over every compute unit instead of four
+// dependent ones) or the sequence is long (the slab must fit in LDS).
 // LDS: slab [L][PP] float2, roots [L], gpos [L].
 template <typename IO, int PP>
 __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__restrict__ v,
@@ -113,16 +116,35 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
     }
 
     // roots of unity and the gate in position order (bin_of_pos[p] = the bin that position p holds after
-    // the last forward pass); full-length Hermitian extension, 1/L folded in.
-    for (int p = tid; p < L; p += 256) {
-        roots[p] = roots_g[p];
-        const int k = bin_of_pos[p];
-        float2 val;
-        if (k == 0 || 2 * k == L) val = make_float2(g[(size_t)bh * F + k].x, 0.f);
-        else if (2 * k < L) val = g[(size_t)bh * F + k];
-        else val = cconj(g[(size_t)bh * F + (L - k)]);
+    // the last forward pass); full-length Hermitian extension, 1/L folded in.  The two dependent loads
+    // (bin, then gate) are issued for all of a lane's positions at once: L <= 2048 = 8 * 256.
+    {
+        constexpr int kPos = kSlabMaxL / 256;
+        int kbin[kPos];
+        float2 gv[kPos], rv[kPos];
+#pragma unroll
+        for (int i = 0; i < kPos; ++i) {
+            const int p = tid + 256 * i;
+            kbin[i] = (p < L) ? bin_of_pos[p] : 0;
+            rv[i] = (p < L) ? roots_g[p] : make_float2(0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < kPos; ++i) {
+            const int k = kbin[i];
+            gv[i] = (tid + 256 * i < L) ? g[(size_t)bh * F + (2 * k <= L ? k : L - k)] : make_float2(0.f, 0.f);
+        }
         const float sc = 1.0f / (float)L;
-        gpos[p] = make_float2(val.x * sc, val.y * sc);
+#pragma unroll
+        for (int i = 0; i < kPos; ++i) {
+            const int p = tid + 256 * i, k = kbin[i];
+            if (p < L) {
+                float2 val = gv[i];
+                if (2 * k > L) val.y = -val.y;
+                if (k == 0 || 2 * k == L) val.y = 0.f;
+                roots[p] = rv[i];
+                gpos[p] = make_float2(val.x * sc, val.y * sc);
+            }
+        }
     }
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
@@ -218,10 +240,28 @@ static hipError_t mix_slab_t(const void *v, const float2 *g, void *out, const fl
     return hipGetLastError();
 }
 
+// Pairs per workgroup: as many as fit in LDS (slab L*PP + two tables of L complex numbers), no more than keeps
+// every compute unit busy (B*H*32/PP >= 256 workgroups), at most a whole head (half a head for fp32 rows).
+int slab_pairs_per_workgroup(int io, int BH, int L) {
+    int pp = io ? 32 : 16;
+    while (pp > 4 && (size_t)L * (pp + 2) * sizeof(float2) > (size_t)72 * 1024) pp /= 2;   // two workgroups per CU
+    while (pp > 4 && (long long)BH * (32 / pp) < 256) pp /= 2;
+    return pp;
+}
+
 hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, const float2 *roots,
                            const int *bin_of_pos, int B, int L, int H, hipStream_t st) {
-    if (io) return mix_slab_t<IoBf16, 32>(v, g, out, roots, bin_of_pos, B, L, H, st);
-    return mix_slab_t<IoF32, 16>(v, g, out, roots, bin_of_pos, B, L, H, st);
+    const int pp = slab_pairs_per_workgroup(io, B * H, L);
+    if ((size_t)L * (pp + 2) * sizeof(float2) > (size_t)160 * 1024) return hipErrorInvalidValue;
+#define SPECTRE_SLAB_CASE(PPV)                                                                       \
+    case PPV:                                                                                       \
+        return io ? mix_slab_t<IoBf16, PPV>(v, g, out, roots, bin_of_pos, B, L, H, st)              \
+                  : mix_slab_t<IoF32, PPV>(v, g, out, roots, bin_of_pos, B, L, H, st);
+    switch (pp) {
+        SPECTRE_SLAB_CASE(4) SPECTRE_SLAB_CASE(8) SPECTRE_SLAB_CASE(16) SPECTRE_SLAB_CASE(32)
+        default: return hipErrorInvalidValue;
+    }
+#undef SPECTRE_SLAB_CASE
 }
 
 }  // namespace spectre

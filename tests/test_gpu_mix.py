@@ -85,9 +85,12 @@ def test_run_to_run_bitwise_identical():
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
 @pytest.mark.parametrize("B,L,H", [(2, 196, 3), (1, 2, 1), (3, 4, 2), (2, 8, 2), (1, 49, 2), (2, 60, 1), (1, 105, 3),
-                                   (2, 128, 2), (1, 360, 2), (1, 500, 1), (1, 175, 2), (16, 256, 16), (8, 512, 32)])
+                                   (2, 128, 2), (1, 360, 2), (1, 500, 1), (1, 175, 2), (16, 256, 16), (8, 512, 32),
+                                   (1, 2048, 32), (4, 2000, 8), (1, 1920, 3), (50, 700, 6), (1, 1024, 64), (3, 1215, 2),
+                                   (2, 1029, 40), (1, 2048, 1)])
 def test_short_and_mixed_radix_lengths(oracle, B, L, H, io):
-    """Whole-slab path: non-power-of-two lengths (4*7*7 = 196 of the ViT grid, odd lengths) and short ones."""
+    """Whole-slab path: non-power-of-two lengths (4*7*7 = 196 of the ViT grid, odd lengths), short ones, and
+    lengths up to 2048 with few heads (4 to 32 channel pairs per workgroup)."""
     print(f"case B={B} L={L} H={H} io={io}", flush=True)
     got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 7 * L + H)
     err = rel_l2(got, want)
