@@ -10,14 +10,15 @@
 // forward ones in reverse, so nothing is ever reordered.
 #include "mix_slab.h"
 
+#include <vector>
+
 #include "fft_regs.h"
 
 namespace spectre {
 
 template <int R, bool INV>
 __device__ __forceinline__ void dft_any(float2 (&x)[R]) {
-    if constexpr (R == 3 || R == 5 || R == 7) dft_odd<R, INV>(x);
-    else dft<R, INV>(x);
+    small_dft<R, INV>(x);
 }
 
 // One in-place pass over all 32 columns of the slab.  n = current sub-transform length,
@@ -69,8 +70,12 @@ __device__ __forceinline__ void slab_pass_dispatch(int R, float2 *slab, const fl
         case 3: slab_pass<3, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
         case 4: slab_pass<4, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
         case 5: slab_pass<5, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 6: slab_pass<6, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
         case 7: slab_pass<7, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
         case 8: slab_pass<8, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 10: slab_pass<10, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 12: slab_pass<12, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
+        case 14: slab_pass<14, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
         case 16: slab_pass<16, INV, GATE, UNIT, PP>(slab, roots, gpos, L, n, tid, nthreads); break;
         default: break;
     }
@@ -192,16 +197,35 @@ bool slab_supported(int L) {
     return n == 1;
 }
 
+// Fewest passes with radices from {16, 14, 12, 10, 8, 7, 6, 5, 4, 3, 2} (each a power of two times at most one
+// of 3, 5, 7, which the in-register transform handles without twiddles); larger radices first.
+static int slab_best_count(int n, int *memo) {
+    if (n == 1) return 0;
+    if (memo[n] != 0) return memo[n];
+    int best = 1 << 20;
+    for (int r : {16, 14, 12, 10, 8, 7, 6, 5, 4, 3, 2})
+        if (n % r == 0) {
+            const int c = 1 + slab_best_count(n / r, memo);
+            if (c < best) best = c;
+        }
+    return memo[n] = best;
+}
+
 static SlabRadices slab_radices(int L) {
     SlabRadices r;
     r.count = 0;
+    std::vector<int> memo((size_t)L + 1, 0);
     int n = L;
-    for (int p : {7, 5, 3})
-        while (n % p == 0) { r.r[r.count++] = p; n /= p; }
-    while (n % 16 == 0) { r.r[r.count++] = 16; n /= 16; }
-    if (n % 8 == 0) { r.r[r.count++] = 8; n /= 8; }
-    if (n % 4 == 0) { r.r[r.count++] = 4; n /= 4; }
-    if (n % 2 == 0) { r.r[r.count++] = 2; n /= 2; }
+    while (n > 1 && r.count < 10) {
+        const int want = slab_best_count(n, memo.data());
+        if (want >= (1 << 20)) break;                      // not smooth: callers check slab_supported first
+        for (int c : {16, 14, 12, 10, 8, 7, 6, 5, 4, 3, 2})
+            if (n % c == 0 && 1 + slab_best_count(n / c, memo.data()) == want) {
+                r.r[r.count++] = c;
+                n /= c;
+                break;
+            }
+    }
     return r;
 }
 
