@@ -21,11 +21,15 @@
  *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and return without synchronising.  Inputs are never
  *     modified; outputs are fully overwritten; results are bitwise reproducible
- *     from run to run.
+ *     from run to run.  A long spectre_mix_forward call runs every other head group
+ *     on a helper stream of the library's own (default priority), forked from and
+ *     joined back into `stream` with events: to the caller the call still behaves
+ *     as work enqueued on `stream`, also under HIP graph capture.
  *   - The caller owns every buffer, including the scratch workspace `ws`, whose
  *     minimum size the matching *_workspace_bytes function returns.  The library
- *     itself only keeps small per-device read-only tables (roots of unity), built
- *     on first use of a transform length and kept until spectre_shutdown().
+ *     itself only keeps small per-device read-only tables (roots of unity) and a
+ *     helper stream with two events, created on first use and kept until
+ *     spectre_shutdown().
  *   - Every function returning int returns a spectre_status; on failure nothing
  *     has been enqueued (argument errors are detected on the host before any
  *     launch) and spectre_last_error() describes the reason.  The library never

@@ -41,10 +41,18 @@ int fail_hip(hipError_t e, const char *what) {
 }
 
 // ---------------------------------------------------------------- per-device tables
+// A helper stream on which every other head group of a long mixing call runs, so that the memory-bound
+// row kernels of one group overlap the arithmetic-heavy column kernel of the next; default priority.
+struct SideLane {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+
 struct DeviceTables {
     std::map<int, float2 *> roots;   // n -> device array [n] of exp(-j 2 pi m / n)
     std::map<int, float2 *> chirp;   // L -> device array: chirp [L], then its filter spectrum [M]
     std::map<int, int *> slab_order; // L -> device array [L]: bin held by each position of the in-LDS transform
+    std::vector<struct SideLane *> lanes;   // idle helper streams (with their fork/join events)
 };
 static std::mutex g_mu;
 static std::map<int, DeviceTables> g_tables;
@@ -106,6 +114,42 @@ static int get_slab_order(int L, const int **out) {
     return SPECTRE_OK;
 }
 
+// Helper lanes are pooled per device: a call takes one for the time it enqueues work and puts it back
+// (work already enqueued keeps its order; events may be re-recorded once the waits on them are enqueued).
+static int acquire_lane(int *dev_out, SideLane **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    *dev_out = dev;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        DeviceTables &t = g_tables[dev];
+        if (!t.lanes.empty()) {
+            *out = t.lanes.back();
+            t.lanes.pop_back();
+            return SPECTRE_OK;
+        }
+    }
+    SideLane *l = new SideLane;
+    e = hipStreamCreateWithFlags(&l->stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&l->fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&l->join, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        if (l->join) (void)hipEventDestroy(l->join);
+        if (l->fork) (void)hipEventDestroy(l->fork);
+        if (l->stream) (void)hipStreamDestroy(l->stream);
+        delete l;
+        return fail_hip(e, "helper stream");
+    }
+    *out = l;
+    return SPECTRE_OK;
+}
+
+static void release_lane(int dev, SideLane *l) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_tables[dev].lanes.push_back(l);
+}
+
 // Chirp tables of an arbitrary length L (padded length M): *w [L], *filt [M].
 static int get_chirp(int L, const Pow2Plan &pl, const float2 **w, const float2 **filt) {
     int dev = 0;
@@ -156,6 +200,21 @@ int mix_chunk_heads(int BH, int L, int d) {
     if (n < 1) n = 1;
     if (n > (size_t)BH) n = (size_t)BH;
     return (int)n;
+}
+
+// Long calls run their head groups on two lanes (the caller's stream and a helper stream), each with half the
+// scratch budget, when that still leaves at least two groups; *chunk = heads per group.
+static int mix_lanes(int BH, int L, int d, int *chunk) {
+    const int full = mix_chunk_heads(BH, L, d);
+    const int half = full / 2;
+    if (getenv("SPECTRE_ONE_LANE") || full >= BH || half < 1) {
+        *chunk = full;
+        return 1;
+    }
+    // an even number of equally sized groups, so that both lanes carry the same load
+    const int ngroups = 2 * ((BH + 2 * half - 1) / (2 * half));
+    *chunk = (BH + ngroups - 1) / ngroups;
+    return 2;
 }
 
 }  // namespace spectre
@@ -265,6 +324,13 @@ void spectre_shutdown(void) {
         for (auto &r : kv.second.roots) (void)hipFree(r.second);
         for (auto &r : kv.second.chirp) (void)hipFree(r.second);
         for (auto &r : kv.second.slab_order) (void)hipFree(r.second);
+        for (SideLane *l : kv.second.lanes) {
+            (void)hipStreamSynchronize(l->stream);
+            (void)hipEventDestroy(l->fork);
+            (void)hipEventDestroy(l->join);
+            (void)hipStreamDestroy(l->stream);
+            delete l;
+        }
     }
     g_tables.clear();
     (void)hipSetDevice(cur);
@@ -278,8 +344,9 @@ size_t spectre_mix_workspace_bytes(int B, int L, int H, int d, spectre_dtype io)
     if (route == 0) return 0;
     if (route == 1) return 256;
     if (route == 3) return chirp_layout(BH, L, d).total();
-    const int chunk = mix_chunk_heads(BH, L, d);
-    return align256((size_t)BH * L * sizeof(float2)) + align256((size_t)chunk * L * (d / 2) * sizeof(float2));
+    int chunk = 0;
+    const int lanes = mix_lanes(BH, L, d, &chunk);
+    return align256((size_t)BH * L * sizeof(float2)) + lanes * align256((size_t)chunk * L * (d / 2) * sizeof(float2));
 }
 
 int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, int H, int d,
@@ -316,19 +383,51 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
     int rc = get_pow2_plan(L, &pl);
     if (rc) return rc;
     float2 *gp = static_cast<float2 *>(ws);
-    float2 *scr = reinterpret_cast<float2 *>(static_cast<char *>(ws) + align256((size_t)BH * L * sizeof(float2)));
+    char *scr_base = static_cast<char *>(ws) + align256((size_t)BH * L * sizeof(float2));
     hipError_t e = launch_gate_expand(pl, static_cast<const float2 *>(g), gp, BH, st);
     if (e != hipSuccess) return fail_hip(e, "gate_expand");
-    const int chunk = mix_chunk_heads(BH, L, d);
-    for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
-        const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
-        e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, st);
-        if (e != hipSuccess) return fail_hip(e, "small_fwd");
-        e = launch_big(pl, scr, gp, bh0, nbh, 0, st);
-        if (e != hipSuccess) return fail_hip(e, "big");
-        e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, st);
-        if (e != hipSuccess) return fail_hip(e, "small_inv");
+    int chunk = 0;
+    const int lanes = mix_lanes(BH, L, d, &chunk);
+    const size_t lane_bytes = align256((size_t)chunk * L * (d / 2) * sizeof(float2));
+    SideLane *side = nullptr;
+    int dev = 0;
+    if (lanes == 2) {
+        rc = acquire_lane(&dev, &side);
+        if (rc) return rc;
+        // fork: the helper stream starts after the expanded gate (and everything before it on the caller's stream)
+        e = hipEventRecord(side->fork, st);
+        if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
+        if (e != hipSuccess) {
+            release_lane(dev, side);
+            return fail_hip(e, "fork to helper stream");
+        }
     }
+    int group = 0;
+    const char *what = nullptr;
+    for (int bh0 = 0; bh0 < BH && !what; bh0 += chunk, ++group) {
+        const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
+        const int lane = (lanes == 2) ? (group & 1) : 0;
+        hipStream_t ls = lane ? side->stream : st;
+        float2 *scr = reinterpret_cast<float2 *>(scr_base + (size_t)lane * lane_bytes);
+        e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, ls);
+        if (e != hipSuccess) { what = "small_fwd"; break; }
+        e = launch_big(pl, scr, gp, bh0, nbh, 0, ls);
+        if (e != hipSuccess) { what = "big"; break; }
+        e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls);
+        if (e != hipSuccess) { what = "small_inv"; break; }
+    }
+    if (lanes == 2) {
+        // join: the caller's stream continues after the helper stream's last kernel (also on a launch error,
+        // so that nothing of this call is left running unordered)
+        hipError_t ej = hipEventRecord(side->join, side->stream);
+        if (ej == hipSuccess) ej = hipStreamWaitEvent(st, side->join, 0);
+        release_lane(dev, side);
+        if (!what && ej != hipSuccess) {
+            e = ej;
+            what = "join from helper stream";
+        }
+    }
+    if (what) return fail_hip(e, what);
     return SPECTRE_OK;
 }
 
