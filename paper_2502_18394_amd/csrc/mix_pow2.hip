@@ -124,7 +124,11 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const float2 *__restrict_
 // Only the exchange between passes 0 and 1 of a 4096-point column crosses waves; every other
 // exchange stays inside a group of 16 lanes that own the same 256-position block, and needs no
 // workgroup barrier because the LDS operations of one wave complete in issue order.  The forward
-// and the inverse cross-wave exchange use two different buffers, so one barrier each suffices.
+// and the inverse cross-wave exchange share one buffer (35 KB per workgroup, which leaves room on a
+// compute unit for a row-transform workgroup of a neighbouring head group running on the other
+// stream).  Between the two, lanes only touch the 256-position block they own, so the only extra
+// barrier is at the end of a column: the next column's forward write lands on positions that
+// slower waves may still be reading for the inverse exchange.
 template <int P, int Q>
 __device__ __forceinline__ int pad_base(int tau) {
     constexpr int S = 1 << (4 * (P - 1 - Q));
@@ -174,7 +178,7 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
     blk /= groups;
     const int k2 = blk % N2, bhl = blk / N2;
     float2 *buf_f = lds_big + ci * COLW;             // forward exchanges
-    float2 *buf_i = kCross ? buf_f + CPI * COLW : buf_f;   // inverse cross-wave exchange
+    float2 *buf_i = buf_f;                           // inverse cross-wave exchange: same buffer
 
     float2 tw[P - 1][15];
 #pragma unroll
@@ -240,7 +244,7 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
             dft<16, true>(x);
 #pragma unroll
             for (int j = 0; j < 16; ++j) col[tau + TPC * j] = x[j];
-            if (MODE == 2 && kCross) __syncthreads(); // single cross exchange per column: guard buf_i
+            if (kCross) __syncthreads();              // the next column's forward write reuses the buffer
         }
         col += (size_t)CPI * N1;
     }
@@ -363,7 +367,7 @@ template <int P, int MODE>
 static hipError_t big_t(const Pow2Plan &pl, float2 *scr, const float2 *gp, int bh0, int nbh, bool shared_gate,
                         hipStream_t st) {
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
-    const size_t lds = (size_t)CPI * COLW * sizeof(float2) * (P == 3 ? 2 : 1);
+    const size_t lds = (size_t)CPI * COLW * sizeof(float2);
     const int ppw = (P == 2) ? 16 : 4;   // pairs per workgroup; a multiple of CPI dividing 32
     auto kern = k_big<P, MODE>;
     hipError_t e = allow_lds(kern, lds);
