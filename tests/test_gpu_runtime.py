@@ -86,12 +86,14 @@ def test_error_paths_launch_nothing():
         binding.PrefixCache(1, 1, 64, 1000)                      # window length without a plan
 
 
-def test_forward_path_replays_from_a_hip_graph(oracle):
+@pytest.mark.parametrize("L,H", [(4096, 4), (32768, 32)])
+def test_forward_path_replays_from_a_hip_graph(oracle, L, H):
     """gate -> mixer -> level gates -> refinement captured once in a HIP graph (tables warmed, buffers
     preallocated: nothing allocates or synchronises inside the calls) and replayed on fresh inputs, with eager
-    work and synchronisations between the replays; every replay must equal the eager result bit for bit."""
+    work and synchronisations between the replays; every replay must equal the eager result bit for bit.
+    The larger case runs its head groups on two streams (fork and join are captured as graph edges)."""
     from paper_2502_18394_amd import binding
-    B, L, H, d = 1, 4096, 4, 64
+    B, d = 1, 64
     J = synth.max_wavelet_levels(L)
     P = binding.GateParams(synth.gate_params(40, H, d, L))
     W = binding.WrmParams(synth.wrm_params(41, H, d, J))
@@ -132,3 +134,27 @@ def test_forward_path_replays_from_a_hip_graph(oracle):
         assert torch.equal(out_s.view(torch.int16), want.view(torch.int16)), f"replay {r}"
         if r == 0:
             assert torch.equal(out_s.view(torch.int16), want0.view(torch.int16))
+
+
+def test_two_stream_call_is_ordered_on_the_callers_stream():
+    """A long call runs half of its head groups on the library's helper stream; work enqueued on the
+    caller's stream right before and right after it must still see it as one ordered step."""
+    from paper_2502_18394_amd import binding
+    B, L, H, d = 1, 32768, 32, 64
+    _, store = synth.tokens(70, (B, L, H, d), "bf16")
+    g = torch.from_numpy(synth.random_gate(71, B, H, L)).cuda()
+    v_src = to_device(store, "bf16")
+    ref = binding.mix_forward(v_src, g).clone()
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    v = torch.zeros_like(v_src)
+    out = torch.zeros_like(v_src)
+    with torch.cuda.stream(s):
+        for _ in range(3):
+            v.copy_(v_src, non_blocking=True)          # producer on the caller's stream, just before the call
+            binding.mix_forward(v, g, out=out, stream=s)
+            snap = out.clone()                         # consumer on the caller's stream, just after the call
+            v.zero_()                                  # and a writer of the input, which must wait for the call
+            out.zero_()
+    s.synchronize()
+    assert torch.equal(snap.view(torch.int16), ref.view(torch.int16))
