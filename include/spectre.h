@@ -24,7 +24,10 @@
  *     from run to run.  A long spectre_mix_forward call runs every other head group
  *     on a helper stream of the library's own (default priority), forked from and
  *     joined back into `stream` with events: to the caller the call still behaves
- *     as work enqueued on `stream`, also under HIP graph capture.
+ *     as work enqueued on `stream`, also under HIP graph capture.  Two environment
+ *     variables exist for measurements: SPECTRE_ONE_LANE (any value) keeps every
+ *     group on `stream`; SPECTRE_CHUNK_MB=<n> sets the total size of the transform
+ *     scratch in flight (default 204, sized for the 256 MB memory-side cache).
  *   - The caller owns every buffer, including the scratch workspace `ws`, whose
  *     minimum size the matching *_workspace_bytes function returns.  The library
  *     itself only keeps small per-device read-only tables (roots of unity) and a
