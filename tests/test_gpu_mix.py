@@ -42,7 +42,7 @@ def run_case(oracle, B, L, H, d, io, seed, gate="random"):
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
 @pytest.mark.parametrize("B,L,H", [(1, 256, 1), (2, 512, 3), (1, 1024, 1), (1, 2048, 2), (2, 4096, 2),
-                                   (1, 8192, 3), (1, 16384, 1), (1, 32768, 2)])
+                                   (1, 8192, 3), (1, 16384, 1), (1, 32768, 2), (4, 8192, 32), (3, 16384, 11)])
 def test_mix_forward_matches_oracle(oracle, B, L, H, io):
     print(f"case B={B} L={L} H={H} io={io}", flush=True)
     got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + L + H)
