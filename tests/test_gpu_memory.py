@@ -23,7 +23,8 @@ def _assert_state(c, oc, tag):
 
 
 @pytest.mark.parametrize("N_mem,N_max,T0,steps,io,shared", [(16, 240, 100, 520, "f32", False), (64, 960, 0, 60, "bf16", True),
-                                                             (32, 480, 480, 30, "f32", True), (64, 4032, 1000, 12, "bf16", False)])
+                                                             (32, 480, 480, 30, "f32", True), (64, 4032, 1000, 12, "bf16", False),
+                                                             (255, 1, 0, 6, "f32", False), (0, 256, 100, 300, "f32", True)])
 def test_memory_cache_tracks_the_oracle(oracle, N_mem, N_max, T0, steps, io, shared):
     from paper_2502_18394_amd import binding
     B, H, d = 2, 2, 64
@@ -31,7 +32,8 @@ def test_memory_cache_tracks_the_oracle(oracle, N_mem, N_max, T0, steps, io, sha
     M = _memory(500 + N_mem, 1 if shared else B, H, N_mem)
     Mfull = np.broadcast_to(M, (B, H, N_mem, d)).astype(np.float64)
     c = binding.PrefixCache(B, H, d, N_max, N_mem=N_mem)
-    c.set_memory(torch.from_numpy(M).cuda())
+    if N_mem:                                   # N_mem = 0: the plain cache through the same code path
+        c.set_memory(torch.from_numpy(M).cuda())
     oc = oracle.MemoryPrefixCache(B, H, d, N_mem, N_max)
     seed = 510 + N_max
     if T0:

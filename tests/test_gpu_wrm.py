@@ -20,7 +20,8 @@ def level_gates(seed, B, H, J, d=64):
 @pytest.mark.parametrize("io", ["f32", "bf16"])
 @pytest.mark.parametrize("B,L,H,J", [(1, 1024, 1, 10), (2, 196, 3, 2), (1, 8192, 4, 13), (2, 512, 2, 9), (1, 256, 2, 8),
                                      (1, 300, 2, 2), (3, 7, 2, 0), (1, 96, 1, 5), (2, 4096, 3, 6), (1, 2, 1, 1),
-                                     (1, 3 * 4096, 2, 12), (1, 1000, 2, 3), (1, 2048, 2, 4), (1, 131072, 2, 17)])
+                                     (1, 3 * 4096, 2, 12), (1, 1000, 2, 3), (1, 2048, 2, 4), (1, 131072, 2, 17),
+                                     (2, 1, 1, 0), (70, 512, 1, 9), (1, 262144, 1, 18)])
 def test_wrm_apply_matches_oracle(oracle, B, L, H, J, io):
     from paper_2502_18394_amd import binding
     print(f"case B={B} L={L} H={H} J={J} io={io}", flush=True)
