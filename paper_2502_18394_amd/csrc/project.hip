@@ -76,7 +76,7 @@ __device__ __forceinline__ void proj_store(const floatx16 &acc0, const floatx16 
     __builtin_amdgcn_wave_barrier();
 }
 
-// grid (ceil(L / kProjRows), H, B); 256 lanes.
+// grid (H, ceil(L / kProjRows), B); 256 lanes.
 template <typename IO, bool WANT_Q>
 __global__ __launch_bounds__(256) void k_project(const void *__restrict__ x, const float *__restrict__ Wq,
                                                  const float *__restrict__ Wv, int Hw,
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void k_project(const void *__restrict__ x, con
     float *wq = wv + 64 * kWStride;                        // [64][kWStride], only filled when WANT_Q
     float *stage_all = wq + (WANT_Q ? 64 * kWStride : 0);  // 4 x [32][kOStride]; reused for the pooling
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;   // head fastest: whole token rows in flight
     const int hw = (Hw == 1) ? 0 : h;
     for (int idx = tid; idx < 64 * 64; idx += 256) {
         wv[(idx >> 6) * kWStride + (idx & 63)] = Wv[(size_t)hw * 4096 + idx];
@@ -186,7 +186,7 @@ __device__ __forceinline__ void proj_mfma_bf16(const uint4 (&a)[4], const uint4 
     }
 }
 
-// grid (ceil(L / kProjRows), H, B); 256 lanes.
+// grid (H, ceil(L / kProjRows), B); 256 lanes.
 template <bool WANT_Q>
 __global__ __launch_bounds__(256) void k_project_bf16(const uint16_t *__restrict__ x, const float *__restrict__ Wq,
                                                       const float *__restrict__ Wv, int Hw,
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256) void k_project_bf16(const uint16_t *__restrict
     uint4 *wq_lo = wq_hi + 512;
     float *stage_all = reinterpret_cast<float *>(WANT_Q ? wq_lo + 512 : wv_lo + 512);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;   // head fastest: whole token rows in flight
     const int hw = (Hw == 1) ? 0 : h;
     proj_fill_w_bf16(Wv + (size_t)hw * 4096, wv_hi, wv_lo, tid);
     if (WANT_Q) proj_fill_w_bf16(Wq + (size_t)hw * 4096, wq_hi, wq_lo, tid);
@@ -284,7 +284,7 @@ static hipError_t project_t(const void *x, const float *Wq, const float *Wv, int
         if (e != hipSuccess) return e;
     }
     const int nch = project_chunks(L);
-    kern<<<dim3(nch, H, B), dim3(256), lds, st>>>(x, Wq, Wv, Hw, static_cast<typename IO::pair_t *>(v_out),
+    kern<<<dim3(H, nch, B), dim3(256), lds, st>>>(x, Wq, Wv, Hw, static_cast<typename IO::pair_t *>(v_out),
                                                   static_cast<typename IO::pair_t *>(q_out), partial, L, H, nch);
     return hipGetLastError();
 }
@@ -295,7 +295,7 @@ hipError_t launch_project(int io, const void *x, const float *Wq, const float *W
         const size_t stage = (size_t)4 * 32 * kOStride, red = (size_t)4 * 64 * 33;
         const size_t lds = (size_t)512 * 16 * (q_out ? 4 : 2) + (stage > red ? stage : red) * sizeof(float);
         const int nch = project_chunks(L);
-        dim3 grid(nch, H, B);
+        dim3 grid(H, nch, B);
         if (q_out) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_project_bf16<true>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
