@@ -105,3 +105,48 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError):
         binding.lib()
+
+
+def _plan_rule(n):
+    """The documented rule, written out independently: in-LDS kernel for 2-3-5-7-smooth n <= 2048; four-step
+    for n = N1 * N2, N1 in {256, 4096}, N2 <= 32 of the form {1,3,5,7} * 2^a; else padded convolution up to 65536."""
+    if n < 1:
+        return False
+    m = n
+    for p in (2, 3, 5, 7):
+        while m % p == 0:
+            m //= p
+    if m == 1 and 2 <= n <= 2048:
+        return True
+    for n1 in (256, 4096):
+        if n % n1 == 0:
+            n2 = n // n1
+            odd = n2
+            while odd % 2 == 0:
+                odd //= 2
+            if n2 <= 32 and odd in (1, 3, 5, 7):
+                return True
+    return n <= 65536
+
+
+def test_supported_lengths_follow_the_documented_rule(lib):
+    for n in list(range(-2, 9000)) + list(range(65000, 66000)) + [k * 4096 for k in range(1, 40)] + [131072, 131073]:
+        assert bool(lib.spectre_length_supported(n, 64)) == _plan_rule(n), n
+        assert lib.spectre_length_supported(n, 32) == 0
+
+
+def test_workspace_sizes_are_consistent(lib):
+    """Every supported length reports a workspace; four-step lengths need the expanded gate plus scratch that never
+    exceeds the memory-side-cache budget by more than one head."""
+    for L in (256, 768, 4096, 12288, 32768, 98304, 131072):
+        for BH in (1, 8, 32, 256):
+            ws = lib.spectre_mix_workspace_bytes(1, L, BH, 64, 1)
+            per_head = L * 32 * 8
+            if BH * L <= 65536 and L <= 2048:
+                assert ws == 256                       # one in-LDS launch, no scratch
+                continue
+            gate = BH * L * 8
+            assert gate + per_head <= ws <= gate + max(per_head, 204 << 20) + 1024, (L, BH, ws)
+    assert lib.spectre_wrm_apply_workspace_bytes(1, 131072, 32, 64, 17) == 256 + 2 * 32 * 512 * 64 * 4
+    assert lib.spectre_wrm_apply_workspace_bytes(1, 131072, 32, 64, 8) == 256
+    assert lib.spectre_wrm_apply_workspace_bytes(1, 100, 1, 64, 3) == 0          # 8 does not divide 100
