@@ -100,40 +100,42 @@ __device__ __forceinline__ float wrm_coef(const float *__restrict__ sb, int l, i
     return (l < J) ? sb[(l + 1) * 64 + c] - sb[l * 64 + c] : sb[c] - sb[J * 64 + c];
 }
 
-// upper levels 9..J: one workgroup per (bh, group of 16 channels) builds the pyramid of block sums
+// upper levels 9..J: one workgroup per (bh, group of kUpCh channels) builds the pyramid of block sums
 // over the tiles in LDS, then walks it top-down accumulating coef_l * A_l; U[bh][tile][c] is the
-// sum of those terms for the blocks that contain the tile.
+// sum of those terms for the blocks that contain the tile.  256 lanes = kUpCh channels x kUpLanes tiles.
+constexpr int kUpCh = 4, kUpLanes = 256 / kUpCh;
 __global__ __launch_bounds__(256) void k_wrm_upper(const float *__restrict__ S, const float *__restrict__ s,
                                                    float *__restrict__ U, int ntiles, int J) {
-    extern __shared__ float pyr[];                     // levels 8, 9, ..., J back to back, 16 channels each
-    const int tid = threadIdx.x, cl = tid & 15, lane = tid >> 4;
-    const int bh = blockIdx.x, c = blockIdx.y * 16 + cl;
+    extern __shared__ float pyr[];                     // levels 8, 9, ..., J back to back, kUpCh channels each
+    const int tid = threadIdx.x, cl = tid % kUpCh, lane = tid / kUpCh;
+    const int bh = blockIdx.x, c = blockIdx.y * kUpCh + cl;
     const float *sb = s + (size_t)bh * (J + 1) * 64;
-    for (int i = lane; i < ntiles; i += 16) pyr[i * 16 + cl] = S[((size_t)bh * ntiles + i) * 64 + c];
+    for (int i = lane; i < ntiles; i += kUpLanes) pyr[i * kUpCh + cl] = S[((size_t)bh * ntiles + i) * 64 + c];
     __syncthreads();
     int off = 0, n = ntiles;
     for (int l = kWrmTileLevels + 1; l <= J; ++l) {    // up: block sums
         const int noff = off + n, nn = n >> 1;
-        for (int i = lane; i < nn; i += 16)
-            pyr[(noff + i) * 16 + cl] = pyr[(off + 2 * i) * 16 + cl] + pyr[(off + 2 * i + 1) * 16 + cl];
+        for (int i = lane; i < nn; i += kUpLanes)
+            pyr[(noff + i) * kUpCh + cl] = pyr[(off + 2 * i) * kUpCh + cl] + pyr[(off + 2 * i + 1) * kUpCh + cl];
         __syncthreads();
         off = noff;
         n = nn;
     }
     // down: entry i of level l becomes the correction shared by the rows of its block
-    for (int i = lane; i < n; i += 16) pyr[(off + i) * 16 + cl] *= wrm_coef(sb, J, J, c) * exp2f(-(float)J);
+    for (int i = lane; i < n; i += kUpLanes) pyr[(off + i) * kUpCh + cl] *= wrm_coef(sb, J, J, c) * exp2f(-(float)J);
     __syncthreads();
     for (int l = J - 1; l > kWrmTileLevels; --l) {
         const int poff = off, nn = n << 1;
         off -= nn;
         const float cf = wrm_coef(sb, l, J, c) * exp2f(-(float)l);
-        for (int i = lane; i < nn; i += 16)
-            pyr[(off + i) * 16 + cl] = pyr[(off + i) * 16 + cl] * cf + pyr[(poff + (i >> 1)) * 16 + cl];
+        for (int i = lane; i < nn; i += kUpLanes)
+            pyr[(off + i) * kUpCh + cl] = pyr[(off + i) * kUpCh + cl] * cf + pyr[(poff + (i >> 1)) * kUpCh + cl];
         __syncthreads();
         n = nn;
     }
     // now `off` is level 9's offset (= ntiles) and n its length
-    for (int i = lane; i < ntiles; i += 16) U[((size_t)bh * ntiles + i) * 64 + c] = pyr[(off + (i >> 1)) * 16 + cl];
+    for (int i = lane; i < ntiles; i += kUpLanes)
+        U[((size_t)bh * ntiles + i) * 64 + c] = pyr[(off + (i >> 1)) * kUpCh + cl];
 }
 
 template <typename IO>
@@ -263,13 +265,13 @@ hipError_t launch_wrm_apply(int io, const void *v, const float *s, void *out, fl
                                                           reinterpret_cast<float2 *>(tile_sums), L, H, ntiles);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        const size_t lds = (size_t)2 * ntiles * 16 * sizeof(float);
+        const size_t lds = (size_t)2 * ntiles * kUpCh * sizeof(float);
         if (lds > 48 * 1024) {
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_wrm_upper),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        k_wrm_upper<<<dim3(BH, 4), 256, lds, st>>>(tile_sums, s, upper, ntiles, levels);
+        k_wrm_upper<<<dim3(BH, 64 / kUpCh), 256, lds, st>>>(tile_sums, s, upper, ntiles, levels);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
