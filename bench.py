@@ -322,8 +322,26 @@ def main():
                          "roofline": {"bound": "hbm", "kernel": "k_sweep<update,read>", "achieved": sweep_bytes / (ms_dec * 1e-3) / 1e9,
                                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sweep_bytes / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                       "traffic": DECODE_SWEEP_TRAFFIC_BYTES, "algorithmic_bytes": sweep_bytes}}
-        del cache, Pd
+        del cache
         torch.cuda.empty_cache()
+        # the same steps with deferred updates: the cache is only read, every `cap` steps one sweep applies the
+        # pending rank-one updates (same outputs up to fp32 rounding; prefix_fft lags until the flush)
+        res["decode_deferred"] = {}
+        for cap in (16, 32):
+            cache = binding.PrefixCache(Bd, Hd, dd, N, defer=cap)
+            cache.update(device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 4, torch.float32),
+                         device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 5, torch.float32))
+            nsteps = max(cap, (args.decode_steps // cap) * cap)          # whole flush periods
+            ms_def = time_loop(lambda: cache.step(vt, qt, Pd, out=od), nsteps, cap)
+            own_bytes = 8 * Bd * Hd * Fd * dd * (1.0 + 1.0 / cap)    # cap - 1 reads, one read + write
+            res["decode_deferred"][f"cap{cap}"] = {
+                "tokens_per_s": Bd / (ms_def * 1e-3), "ms_per_step": ms_def, "steps": nsteps,
+                "bytes_per_step_of_this_schedule": own_bytes,
+                "hbm_frac_of_this_schedule": own_bytes / (ms_def * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "hbm_frac_vs_update_every_step": sweep_bytes / (ms_def * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            del cache
+            torch.cuda.empty_cache()
+        del Pd
 
     if not args.no_membw:
         res["membw_probe"] = membw_probe()

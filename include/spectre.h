@@ -223,7 +223,18 @@ typedef struct {
     void *q_buf;          /* float [B, H, n, d]: zeros, then the ring of queries                 */
     void *sum_q;          /* double [B, H, d]: running sum of the live queries                  */
     void *twiddle;        /* complex64 [n]: exp(-j 2 pi m / n), the pre-cached factors          */
+    /* Deferred updates (optional; pending == NULL or pending_cap == 0: every step updates the cache).
+     * Eq. 5 is linear, so spectre_prefix_step may leave the rank-one updates of the last tokens pending
+     * and only READ the cache: the newest row of irfft(g * X) for X = X_stale + sum_i Delta_i w^(k s_i) is
+     * that row for X_stale plus sum_i kappa[(s - s_i) mod n] Delta_i with kappa = irfft(g).  Every
+     * pending_cap steps one sweep applies all pending updates.  Outputs are the same up to fp32 rounding;
+     * prefix_fft lags behind until spectre_prefix_flush (or the flushing step). */
+    void *pending;        /* float [pending_cap, B, H, d]: Delta rows of the pending tokens, or NULL     */
+    int pending_cap;      /* 0 .. SPECTRE_MAX_PENDING                                                    */
+    int n_pending;        /* HOST field: tokens whose update is pending                                  */
+    int pending_slot[32]; /* HOST field: their window rows                                               */
 } spectre_prefix_cache;
+#define SPECTRE_MAX_PENDING 32
 
 enum { SPECTRE_PREFIX_FFT = 0, SPECTRE_PREFIX_VBUF = 1, SPECTRE_PREFIX_QBUF = 2,
        SPECTRE_PREFIX_SUMQ = 3, SPECTRE_PREFIX_TWIDDLE = 4 };
@@ -233,6 +244,11 @@ size_t spectre_prefix_bytes(int B, int H, int d, int n, int which);
 
 /* Zeroes the state, fills the twiddle table (computed in fp64, rounded once), sets t = 0. */
 int spectre_prefix_init(spectre_prefix_cache *cache /*host*/, void *stream);
+
+/* Applies the pending deferred updates (one sweep over the cache); a no-op when there are none.
+ * spectre_prefix_update and spectre_prefix_set_memory flush by themselves; spectre_prefix_readout takes a
+ * const cache and returns SPECTRE_EINVAL while updates are pending. */
+int spectre_prefix_flush(spectre_prefix_cache *cache /*host*/, void *stream);
 
 /*
  * spectre_prefix_set_memory - Sec. 3.4: lay the memory rows down and transform the window once

@@ -43,7 +43,9 @@ class PrefixCacheC(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("d", ctypes.c_int), ("N_max", ctypes.c_int),
                 ("N_mem", ctypes.c_int), ("t", ctypes.c_longlong),
                 ("prefix_fft", ctypes.c_void_p), ("v_buf", ctypes.c_void_p), ("q_buf", ctypes.c_void_p),
-                ("sum_q", ctypes.c_void_p), ("twiddle", ctypes.c_void_p)]
+                ("sum_q", ctypes.c_void_p), ("twiddle", ctypes.c_void_p),
+                ("pending", ctypes.c_void_p), ("pending_cap", ctypes.c_int), ("n_pending", ctypes.c_int),
+                ("pending_slot", ctypes.c_int * 32)]
 
 
 def lib():
@@ -263,8 +265,9 @@ def wrm_apply(v, s, out=None, ws=None, stream=None):
 class PrefixCache:
     """Caller-owned Prefix-FFT cache state (Algorithm 1) in device memory."""
 
-    def __init__(self, B, H, d, N_max, N_mem=0, device="cuda"):
-        """N_max = ring capacity; N_mem = persistent memory rows (Sec. 3.4); n = N_mem + N_max is the transform length."""
+    def __init__(self, B, H, d, N_max, N_mem=0, defer=0, device="cuda"):
+        """N_max = ring capacity; N_mem = persistent memory rows (Sec. 3.4); n = N_mem + N_max is the transform length.
+        defer > 0: step() leaves up to `defer` rank-one updates pending and only reads the cache (see spectre.h)."""
         L = lib()
         n = N_max + N_mem
         self.B, self.H, self.d, self.N, self.N_mem, self.n = B, H, d, N_max, N_mem, n
@@ -280,8 +283,10 @@ class PrefixCache:
         self.twiddle = torch.empty((n,), dtype=torch.complex64, device=device)
         for t, nbytes in zip((self.prefix_fft, self.v_buf, self.q_buf, self.sum_q, self.twiddle), nb):
             assert t.numel() * t.element_size() == nbytes, (t.shape, nbytes)
+        self.pending = torch.zeros((defer, B, H, d), dtype=torch.float32, device=device) if defer > 0 else None
         self.c = PrefixCacheC(B, H, d, N_max, N_mem, 0, self.prefix_fft.data_ptr(), self.v_buf.data_ptr(),
-                              self.q_buf.data_ptr(), self.sum_q.data_ptr(), self.twiddle.data_ptr())
+                              self.q_buf.data_ptr(), self.sum_q.data_ptr(), self.twiddle.data_ptr(),
+                              self.pending.data_ptr() if defer > 0 else None, defer, 0)
         self._ws = None
         _check(L.spectre_prefix_init(ctypes.byref(self.c), _stream(None)))
 
@@ -297,6 +302,14 @@ class PrefixCache:
     @property
     def t(self):
         return int(self.c.t)
+
+    @property
+    def n_pending(self):
+        return int(self.c.n_pending)
+
+    def flush(self, stream=None):
+        """Apply the pending deferred updates to prefix_fft."""
+        _check(lib().spectre_prefix_flush(ctypes.byref(self.c), _stream(stream)))
 
     def update(self, v_new, q_new, stream=None):
         B, T, H, d = v_new.shape

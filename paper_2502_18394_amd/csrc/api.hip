@@ -649,6 +649,9 @@ static int check_cache(const spectre_prefix_cache *c, const char *who) {
     if (!c->prefix_fft || !c->v_buf || !c->q_buf || !c->sum_q || !c->twiddle)
         return fail(SPECTRE_EINVAL, "%s: null cache array", who);
     if (c->t < 0) return fail(SPECTRE_EINVAL, "%s: negative token counter", who);
+    if (c->pending_cap < 0 || c->pending_cap > kMaxPending || (c->pending_cap > 0 && !c->pending) ||
+        c->n_pending < 0 || c->n_pending > c->pending_cap)
+        return fail(SPECTRE_EINVAL, "%s: bad deferred-update fields", who);
     if ((long long)c->B * c->H > 0x7fffffffLL / 64) return fail(SPECTRE_EUNSUPPORTED, "%s: B*H too large", who);
     return SPECTRE_OK;
 }
@@ -681,6 +684,20 @@ int spectre_prefix_init(spectre_prefix_cache *c, void *stream) {
     hipError_t e = launch_fill_twiddle(static_cast<float2 *>(c->twiddle), window_len(c), st);
     if (e != hipSuccess) return fail_hip(e, "fill_twiddle");
     c->t = 0;
+    c->n_pending = 0;
+    return SPECTRE_OK;
+}
+
+int spectre_prefix_flush(spectre_prefix_cache *c, void *stream) {
+    int rc = check_cache(c, "prefix_flush");
+    if (rc) return rc;
+    if (c->n_pending == 0) return SPECTRE_OK;
+    const int N = window_len(c), BH = c->B * c->H, F = N / 2 + 1;
+    hipError_t e = launch_sweep_lazy(true, false, static_cast<float2 *>(c->prefix_fft), static_cast<const float *>(c->pending),
+                                     static_cast<const float2 *>(c->twiddle), nullptr, nullptr, nullptr, BH, F, N, 0,
+                                     c->n_pending, c->pending_slot, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, "sweep(flush)");
+    c->n_pending = 0;
     return SPECTRE_OK;
 }
 
@@ -723,6 +740,8 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
     if (!v_new || !q_new) return fail(SPECTRE_EINVAL, "prefix_update: null pointer");
     if (T < 1) return fail(SPECTRE_EINVAL, "prefix_update: T < 1");
     if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "prefix_update: bad dtype");
+    rc = spectre_prefix_flush(c, stream);
+    if (rc) return rc;
     const size_t need = spectre_prefix_update_workspace_bytes(c, T, io);
     if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_update: workspace %zu < %zu bytes", ws_bytes, need);
     if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_update: ws not 256-byte aligned");
@@ -816,6 +835,8 @@ int spectre_prefix_readout(const spectre_prefix_cache *c, const void *g, int mod
     if (mode != SPECTRE_READ_NEWEST && mode != SPECTRE_READ_WINDOW) return fail(SPECTRE_EINVAL, "prefix_readout: bad mode");
     if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "prefix_readout: bad dtype");
     if (c->t < 1) return fail(SPECTRE_EINVAL, "prefix_readout: cache is empty");
+    if (c->n_pending > 0)
+        return fail(SPECTRE_EINVAL, "prefix_readout: %d deferred updates pending, call spectre_prefix_flush first", c->n_pending);
     const size_t need = spectre_prefix_readout_workspace_bytes(c, mode, io);
     if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_readout: workspace %zu < %zu bytes", ws_bytes, need);
     if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_readout: ws not 256-byte aligned");
@@ -858,7 +879,7 @@ size_t spectre_prefix_step_workspace_bytes(const spectre_prefix_cache *c, const 
     const int BH = c->B * c->H, F = window_len(c) / 2 + 1;
     return align256((size_t)BH * c->d * sizeof(float)) + align256((size_t)BH * P->d_g * sizeof(float)) +
            align256((size_t)BH * F * sizeof(float2)) + align256((size_t)BH * sweep_chunks(F) * c->d * sizeof(float)) +
-           gate_raw_bytes(c->B, c->H, P);
+           align256((size_t)BH * sweep_chunks(F) * 32 * sizeof(float)) + gate_raw_bytes(c->B, c->H, P);
 }
 
 int spectre_prefix_step(spectre_prefix_cache *c, const void *v_t, const void *q_t, const spectre_gate_params *P,
@@ -885,13 +906,39 @@ int spectre_prefix_step(spectre_prefix_cache *c, const void *v_t, const void *q_
     w += align256((size_t)BH * F * sizeof(float2));
     float *partial = reinterpret_cast<float *>(w);
     w += align256((size_t)BH * sweep_chunks(F) * d * sizeof(float));
+    float *kpart = reinterpret_cast<float *>(w);
+    w += align256((size_t)BH * sweep_chunks(F) * 32 * sizeof(float));
     float2 *raw = reinterpret_cast<float2 *>(w);
     const int slot = M0 + (int)(c->t % W), evict = c->t >= W ? 1 : 0;
+    const bool lazy = c->pending_cap > 0;
+    if (lazy) delta = static_cast<float *>(c->pending) + (size_t)c->n_pending * BH * d;   // this token's pending row
     hipError_t e = launch_ring_update((int)io, v_t, q_t, 1, 0, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf),
                                       static_cast<double *>(c->sum_q), delta, B, H, d, N, slot, evict, st);
     if (e != hipSuccess) return fail_hip(e, "ring_update");
     e = launch_gate_mlp(static_cast<const double *>(c->sum_q), 1.0 / (double)W, gate_dev(P), hid, raw, B, H, 0, g, st);
     if (e != hipSuccess) return fail_hip(e, "gate_mlp");
+    if (lazy) {
+        // the ring buffers and sum_q are already updated; from here on the token counts as appended
+        c->pending_slot[c->n_pending] = slot;
+        c->n_pending += 1;
+        c->t += 1;
+        const float *pend = static_cast<const float *>(c->pending);
+        const float2 *tw = static_cast<const float2 *>(c->twiddle);
+        if (c->n_pending == c->pending_cap) {          // the list is full: apply everything, read the updated cache
+            e = launch_sweep_lazy(true, true, static_cast<float2 *>(c->prefix_fft), pend, tw, g, partial, kpart, BH, F, N,
+                                  slot, c->n_pending, c->pending_slot, st);
+            if (e != hipSuccess) return fail_hip(e, "sweep(flush+read)");
+            c->n_pending = 0;
+            e = launch_readout_final((int)io, partial, out, BH, F, st);
+        } else {                                       // read the stale cache, add the pending tokens' share
+            e = launch_sweep_lazy(false, true, static_cast<float2 *>(c->prefix_fft), pend, tw, g, partial, kpart, BH, F, N,
+                                  slot, c->n_pending, c->pending_slot, st);
+            if (e != hipSuccess) return fail_hip(e, "sweep(read)");
+            e = launch_readout_final_lazy((int)io, partial, kpart, pend, out, BH, F, c->n_pending, st);
+        }
+        if (e != hipSuccess) return fail_hip(e, "readout_final");
+        return SPECTRE_OK;
+    }
     e = launch_sweep(true, true, static_cast<float2 *>(c->prefix_fft), delta, static_cast<const float2 *>(c->twiddle), g,
                      partial, BH, F, N, slot, st);
     if (e != hipSuccess) return fail_hip(e, "sweep(update+read)");

@@ -19,6 +19,16 @@ int sweep_chunks(int F);
 // update: Eq. (5) on every bin; read: partial sums of the newest row's readout with gate g.
 hipError_t launch_sweep(bool update, bool read, float2 *X, const float *delta, const float2 *tw, const float2 *g,
                         float *partial, int BH, int F, int N, int slot, hipStream_t st);
+// Deferred updates (the cache is only read by a decode step; pending rank-one updates are applied in one sweep
+// every few steps).  pending [cap][B*H][64] holds the tokens' Delta rows, slots[i] their ring rows.
+//   flush: apply all npend pending updates to X;  read: readout partials for the row `slot_new` with gate g;
+//   without flush the kappa partials kpart [BH][chunks][32] of the pending tokens are produced as well.
+constexpr int kMaxPending = 32;
+hipError_t launch_sweep_lazy(bool flush, bool read, float2 *X, const float *pending, const float2 *tw, const float2 *g,
+                             float *partial, float *kpart, int BH, int F, int N, int slot_new, int npend,
+                             const int *slots, hipStream_t st);
+hipError_t launch_readout_final_lazy(int io, const float *partial, const float *kpart, const float *pending, void *out,
+                                     int BH, int F, int npend, hipStream_t st);
 // out [B,1,H,d] (io dtype) from the sweep's partial sums.
 hipError_t launch_readout_final(int io, const float *partial, void *out, int BH, int F, hipStream_t st);
 

@@ -121,6 +121,290 @@ __global__ __launch_bounds__(256) void k_sweep(float4 *__restrict__ X, const flo
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Deferred updates.  Eq. (5) is linear, so the rank-one updates of the last few tokens need not be applied to
+// the cache before it is read: with X = X_stale + sum_i Delta_i w^(k s_i) over the pending tokens i, the newest
+// row of irfft(g * X) is the same row for X_stale plus sum_i kappa[(s - s_i) mod N] Delta_i, where
+// kappa = irfft(g) is the real convolution kernel of the gate (App. B) and s the newest slot.  A decode step
+// then only READS the cache; every `cap` steps one sweep applies all pending updates at once.
+//
+// k_sweep_lazy (the read-only step), grid and lanes as k_sweep: partial as in k_sweep<false, true> from the stale
+// cache, and kpart[bh][chunk][i] = the chunk's share of kappa[(slot_new - slot_i) mod N], accumulated by lane i of
+// every bin row (each of the 32 lanes of a row takes one pending token).
+// k_flush_mfma (the flush): X[k,:] += sum_i Delta_i tw[(k slot_i) mod N], stored; with READ the readout partials
+// are taken from the updated entries.
+struct PendingSlots {
+    int n;
+    int slot[kMaxPending];
+};
+
+__device__ __forceinline__ void index_walk(unsigned k_start, unsigned mult, int N, unsigned &m, unsigned &step) {
+    if ((N & (N - 1)) == 0) {
+        step = (8u * mult) & (unsigned)(N - 1);
+        m = (k_start * mult) & (unsigned)(N - 1);
+    } else {
+        step = (unsigned)((8ull * mult) % (unsigned)N);
+        m = (unsigned)(((unsigned long long)k_start * mult) % (unsigned)N);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_sweep_lazy(const float4 *__restrict__ X, const float2 *__restrict__ tw,
+                                                    const float2 *__restrict__ g, float *__restrict__ partial,
+                                                    float *__restrict__ kpart, int F, int N, int BH, int slot_new,
+                                                    PendingSlots ps, int nchunks) {
+    __shared__ float2 red[8][32];
+    __shared__ float kred[8][32];
+    const int lane = threadIdx.x & 31, row = threadIdx.x >> 5;
+    const int chunk = blockIdx.x, bh = blockIdx.y;
+    const int k0 = chunk * kSweepBins, k1 = min(F, k0 + kSweepBins);
+    unsigned m_new = 0, step_new = 0;
+    index_walk((unsigned)(k0 + row), (unsigned)slot_new, N, m_new, step_new);
+    const float invN = 1.0f / (float)N;
+    float acc0 = 0.f, acc1 = 0.f, kacc = 0.f;
+    const float4 *Xp = X + ((size_t)bh * F) * 32 + lane;
+    // lane i of every bin row follows pending token i: e_k = exp(-j 2 pi k j_i / N), j_i = (slot_new - slot_i)
+    // mod N, advanced by a fixed rotation per step of 8 bins and re-read from the table every 8th step
+    // (a walked index that runs past the chunk's end is still a valid table index)
+    const bool has = lane < ps.n;
+    const unsigned mult = has ? (unsigned)((slot_new - ps.slot[lane] + N) % N) : 0u;
+    unsigned m_item, step_item;
+    index_walk((unsigned)(k0 + row), mult, N, m_item, step_item);
+    const float2 rot = tw[step_item];
+    float2 e = tw[m_item];
+    constexpr int kU = 8;
+    // kU bin rows per trip, every load of the trip requested up front (addresses clamped into the chunk,
+    // rows past its end weighted with zero)
+    for (int kk = k0 + row; kk < k1; kk += 8 * kU) {
+        float4 x[kU];
+        float2 gk[kU], wn[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int kc = min(kk + 8 * u, k1 - 1);
+            x[u] = stream_load(Xp + (size_t)kc * 32);
+            gk[u] = g[(size_t)bh * F + kc];
+            wn[u] = tw[m_new];
+            m_new += step_new;
+            if (m_new >= (unsigned)N) m_new -= (unsigned)N;
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            m_item += step_item;
+            if (m_item >= (unsigned)N) m_item -= (unsigned)N;
+        }
+        const float2 e_next = tw[m_item];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int k = kk + 8 * u;
+            const float ck = k >= k1 ? 0.f : ((k == 0 || 2 * k == N) ? invN : 2.0f * invN);
+            const float2 r = cmulc(gk[u], wn[u]);    // g_k conj(w_k)
+            const float rr = r.x * ck, ri = r.y * ck;
+            acc0 = fmaf(rr, x[u].x, fmaf(-ri, x[u].y, acc0));
+            acc1 = fmaf(rr, x[u].z, fmaf(-ri, x[u].w, acc1));
+            kacc = fmaf(ck, fmaf(gk[u].x, e.x, gk[u].y * e.y), kacc);   // c_k/N Re(g_k conj(e_k))
+            e = cmul(e, rot);
+        }
+        e = e_next;
+    }
+    if (!has) kacc = 0.f;
+    red[row][lane] = make_float2(acc0, acc1);
+    kred[row][lane] = kacc;
+    __syncthreads();
+    if (row == 0) {
+        float2 s = red[0][lane];
+        float ks = kred[0][lane];
+#pragma unroll
+        for (int r = 1; r < 8; ++r) {
+            s.x += red[r][lane].x;
+            s.y += red[r][lane].y;
+            ks += kred[r][lane];
+        }
+        *reinterpret_cast<float2 *>(partial + ((size_t)bh * nchunks + chunk) * 64 + 2 * lane) = s;
+        kpart[((size_t)bh * nchunks + chunk) * 32 + lane] = ks;
+    }
+}
+
+// The flush as a matrix product on the matrix cores.  For one head, X[k, c] += sum_i w_i(k) Delta_i[c] is a
+// (bins x pending) by (pending x channels) product, once with Re w and once with Im w.  A wave owns a block of
+// 32 bins x 64 channels: four 32x32 accumulators (real and imaginary part for the even and for the odd
+// channels, so that a lane's four values of one bin are the 16 contiguous bytes of the cache entry), loaded
+// from the cache, advanced by CAP/2 v_mfma_f32_32x32x2f32 each (two pending tokens per instruction) and
+// stored back.  Operand layout of that instruction: A[i][k] in lane 32k + i, B[k][j] in lane 32k + j,
+// D[8(v/4) + 4(lane/32) + v%4][lane%32] in register v.
+// A workgroup takes kFlushChunks chunks of kSweepBins = 4 x 32 bins, one block per wave and chunk; partial as
+// in k_sweep.
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// (a b) mod N for a, b < N <= 2^17 without 64-bit division.
+__device__ __forceinline__ unsigned mul_mod(unsigned a, unsigned b, int N) {
+    if ((N & (N - 1)) == 0) return (a * b) & (unsigned)(N - 1);
+    return (((a * (b >> 9)) % (unsigned)N) * 512u + a * (b & 511u)) % (unsigned)N;
+}
+
+constexpr int kFlushChunks = 8;   // chunks of kSweepBins bins per workgroup
+
+template <bool READ, int CAP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_flush_mfma(
+    float4 *__restrict__ X, const float *__restrict__ pending, const float2 *__restrict__ tw,
+    const float2 *__restrict__ g, float *__restrict__ partial, int F, int N, int BH, int slot_new, PendingSlots ps,
+    int nchunks) {
+    static_assert(kSweepBins == 128, "one 32-bin block per wave and chunk");
+    __shared__ float2 red[kFlushChunks][4][32];
+    const int l = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = l & 31, half = l >> 5;
+    const int bh = blockIdx.y;
+    const int chunk_end = min(nchunks, ((int)blockIdx.x + 1) * kFlushChunks);
+
+    // operands that do not depend on the block, kept in LDS: the delta of token i at channels 2c and 2c + 1, and
+    // the factor's advance over a block's rows, tw[(c slot_i) mod N]; the block's own factor tw[(kb slot_i) mod N]
+    // is one address per half wave, so a block costs no scattered table reads
+    __shared__ float2 s_dl[CAP][32], s_adv[CAP][32];
+    __shared__ int s_slot[CAP];
+    if (threadIdx.x < CAP) s_slot[threadIdx.x] = ps.slot[threadIdx.x];
+#pragma unroll
+    for (int j = 0; j < CAP / 8; ++j) {
+        const int i = 8 * j + (threadIdx.x >> 5), c = threadIdx.x & 31;
+        float2 dl = make_float2(0.f, 0.f);
+        if (i < ps.n) dl = *reinterpret_cast<const float2 *>(pending + ((size_t)i * BH + bh) * 64 + 2 * c);
+        s_dl[i][c] = dl;
+        s_adv[i][c] = tw[mul_mod((unsigned)c, (unsigned)ps.slot[i], N)];
+    }
+    __syncthreads();
+    // software pipeline: the cache entries and the factors of the next block are requested before the matrix
+    // products of the current one start
+    // register v of a block <-> bin row 8(v/4) + 4 half + v%4
+    float4 xs[16];
+    float2 wbl;
+    auto request = [&](int chunk) {
+        const int kb = chunk * kSweepBins + 32 * wave;
+        const int k1 = min(F, chunk * kSweepBins + kSweepBins);
+        const float4 *Xp = X + ((size_t)bh * F + kb) * 32 + col;
+        // lane i < CAP fetches token i's factor at the block's first bin
+        wbl = tw[mul_mod((unsigned)kb, (unsigned)s_slot[l & (CAP - 1)], N)];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v / 4) + 4 * half + (v % 4);
+            xs[v] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (kb + r < k1) xs[v] = stream_load(Xp + (size_t)r * 32);
+        }
+    };
+    request(blockIdx.x * kFlushChunks);
+    for (int chunk = blockIdx.x * kFlushChunks; chunk < chunk_end; ++chunk) {
+        const int kb = chunk * kSweepBins + 32 * wave;
+        const int k1 = min(F, chunk * kSweepBins + kSweepBins);
+        float4 *Xp = X + ((size_t)bh * F + kb) * 32 + col;
+        floatx16 re0, im0, re1, im1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            re0[v] = xs[v].x;
+            im0[v] = xs[v].y;
+            re1[v] = xs[v].z;
+            im1[v] = xs[v].w;
+        }
+        const float2 wcur = wbl;
+        if (chunk + 1 < chunk_end) request(chunk + 1);
+#pragma unroll 2
+        for (int s = 0; s < CAP / 2; ++s) {
+            // token 2s + half: A = its factor at bin kb + col, B = its delta
+            const float2 wb = make_float2(__shfl(wcur.x, 2 * s + half), __shfl(wcur.y, 2 * s + half));
+            const float2 adv = s_adv[2 * s + half][col], dl = s_dl[2 * s + half][col];
+            const float ar = wb.x * adv.x - wb.y * adv.y, ai = wb.x * adv.y + wb.y * adv.x;
+            re0 = __builtin_amdgcn_mfma_f32_32x32x2f32(ar, dl.x, re0, 0, 0, 0);
+            im0 = __builtin_amdgcn_mfma_f32_32x32x2f32(ai, dl.x, im0, 0, 0, 0);
+            re1 = __builtin_amdgcn_mfma_f32_32x32x2f32(ar, dl.y, re1, 0, 0, 0);
+            im1 = __builtin_amdgcn_mfma_f32_32x32x2f32(ai, dl.y, im1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v / 4) + 4 * half + (v % 4);
+            if (kb + r < k1) stream_store(Xp + (size_t)r * 32, make_float4(re0[v], im0[v], re1[v], im1[v]));
+        }
+        if (READ) {
+            // lane col prepares the readout factor of bin kb + col; the rows a lane holds fetch theirs by shuffle
+            const int k = kb + col;
+            float rr = 0.f, ri = 0.f;
+            if (k < k1) {
+                const float invN = 1.0f / (float)N;
+                const float ck = (k == 0 || 2 * k == N) ? invN : 2.0f * invN;
+                const float2 r = cmulc(g[(size_t)bh * F + k], tw[mul_mod((unsigned)k, (unsigned)slot_new, N)]);
+                rr = r.x * ck;
+                ri = r.y * ck;
+            }
+            float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = 8 * (v / 4) + 4 * half + (v % 4);
+                const float a = __shfl(rr, r), b = __shfl(ri, r);
+                acc0 = fmaf(a, re0[v], fmaf(-b, im0[v], acc0));
+                acc1 = fmaf(a, re1[v], fmaf(-b, im1[v], acc1));
+            }
+            acc0 += __shfl_xor(acc0, 32);
+            acc1 += __shfl_xor(acc1, 32);
+            if (half == 0) red[chunk - blockIdx.x * kFlushChunks][wave][col] = make_float2(acc0, acc1);
+        }
+    }
+    if (READ) {
+        // the four waves' sums of every chunk, added in a fixed order
+        __syncthreads();
+        const int c = threadIdx.x >> 5, chunk = blockIdx.x * kFlushChunks + c;
+        static_assert(kFlushChunks == 8, "one chunk per 32 threads");
+        if (chunk < chunk_end) {
+            float2 t = red[c][0][col];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) {
+                t.x += red[c][w][col].x;
+                t.y += red[c][w][col].y;
+            }
+            *reinterpret_cast<float2 *>(partial + ((size_t)bh * nchunks + chunk) * 64 + 2 * col) = t;
+        }
+    }
+}
+
+// out[b, 0, h, c] = sum over chunks of partial + sum_i kappa_i Delta_i[c], kappa_i = sum over chunks of kpart.
+template <typename IO>
+__global__ __launch_bounds__(256) void k_readout_final_lazy(const float *__restrict__ partial,
+                                                            const float *__restrict__ kpart,
+                                                            const float *__restrict__ pending,
+                                                            typename IO::pair_t *__restrict__ out, int nchunks,
+                                                            int BH, int npend) {
+    __shared__ float2 red[8][32];
+    __shared__ float kred[8][32];
+    const int p = threadIdx.x & 31, grp = threadIdx.x >> 5, bh = blockIdx.x;
+    const float2 *src = reinterpret_cast<const float2 *>(partial + (size_t)bh * nchunks * 64) + p;
+    const float *ksrc = kpart + (size_t)bh * nchunks * 32 + p;
+    float2 s = make_float2(0.f, 0.f);
+    float ks = 0.f;
+    for (int c = grp; c < nchunks; c += 8) {
+        const float2 v = src[(size_t)c * 32];
+        s.x += v.x;
+        s.y += v.y;
+        ks += ksrc[(size_t)c * 32];
+    }
+    red[grp][p] = s;
+    kred[grp][p] = ks;
+    __syncthreads();
+    if (grp == 0) {
+        float kap = kred[0][p];
+#pragma unroll
+        for (int r = 1; r < 8; ++r) kap += kred[r][p];
+        kred[0][p] = kap;                     // kappa of pending token p
+    }
+    __syncthreads();
+    if (grp == 0) {
+        float2 t = red[0][p];
+#pragma unroll
+        for (int r = 1; r < 8; ++r) {
+            t.x += red[r][p].x;
+            t.y += red[r][p].y;
+        }
+        for (int i = 0; i < npend; ++i) {
+            const float2 dlt = *reinterpret_cast<const float2 *>(pending + ((size_t)i * BH + bh) * 64 + 2 * p);
+            t.x = fmaf(kred[0][i], dlt.x, t.x);
+            t.y = fmaf(kred[0][i], dlt.y, t.y);
+        }
+        out[(size_t)bh * 32 + p] = IO::pack(t);
+    }
+}
+
 // out[b, 0, h, c] = sum over chunks of partial.  One workgroup per head: 256 lanes = 32 channel
 // pairs x 8 chunk groups; group r adds chunks r, r+8, ... in order, then the 8 sums in order.
 template <typename IO>
@@ -293,6 +577,40 @@ hipError_t launch_sweep(bool update, bool read, float2 *X, const float *delta, c
     if (update && read) k_sweep<true, true><<<grid, 256, 0, st>>>(X4, delta, tw, g, partial, F, N, slot, nch);
     else if (update) k_sweep<true, false><<<grid, 256, 0, st>>>(X4, delta, tw, g, partial, F, N, slot, nch);
     else k_sweep<false, true><<<grid, 256, 0, st>>>(X4, delta, tw, g, partial, F, N, slot, nch);
+    return hipGetLastError();
+}
+
+hipError_t launch_sweep_lazy(bool flush, bool read, float2 *X, const float *pending, const float2 *tw, const float2 *g,
+                             float *partial, float *kpart, int BH, int F, int N, int slot_new, int npend,
+                             const int *slots, hipStream_t st) {
+    if (npend < 0 || npend > kMaxPending) return hipErrorInvalidValue;
+    PendingSlots ps;
+    ps.n = npend;
+    for (int i = 0; i < kMaxPending; ++i) ps.slot[i] = i < npend ? slots[i] : 0;
+    const int nch = sweep_chunks(F);
+    dim3 grid(nch, BH);
+    float4 *X4 = reinterpret_cast<float4 *>(X);
+    if (!flush) {
+        k_sweep_lazy<<<grid, 256, 0, st>>>(X4, tw, g, partial, kpart, F, N, BH, slot_new, ps, nch);
+        return hipGetLastError();
+    }
+    const dim3 fgrid((nch + kFlushChunks - 1) / kFlushChunks, BH);
+#define SPECTRE_FLUSH(RD, CAPV) \
+    k_flush_mfma<RD, CAPV><<<fgrid, 256, 0, st>>>(X4, pending, tw, g, partial, F, N, BH, slot_new, ps, nch)
+    if (read) {
+        if (npend <= 8) SPECTRE_FLUSH(true, 8); else if (npend <= 16) SPECTRE_FLUSH(true, 16); else SPECTRE_FLUSH(true, 32);
+    } else {
+        if (npend <= 8) SPECTRE_FLUSH(false, 8); else if (npend <= 16) SPECTRE_FLUSH(false, 16); else SPECTRE_FLUSH(false, 32);
+    }
+#undef SPECTRE_FLUSH
+    return hipGetLastError();
+}
+
+hipError_t launch_readout_final_lazy(int io, const float *partial, const float *kpart, const float *pending, void *out,
+                                     int BH, int F, int npend, hipStream_t st) {
+    const int nch = sweep_chunks(F);
+    if (io) k_readout_final_lazy<IoBf16><<<BH, 256, 0, st>>>(partial, kpart, pending, static_cast<uint32_t *>(out), nch, BH, npend);
+    else k_readout_final_lazy<IoF32><<<BH, 256, 0, st>>>(partial, kpart, pending, static_cast<float2 *>(out), nch, BH, npend);
     return hipGetLastError();
 }
 

@@ -90,15 +90,19 @@ def test_gate_plus_mixer_end_to_end_128k(oracle):
     assert e_gate <= 1e-5 and e_mix <= TOL["bf16"]
 
 
-def test_decode_config_sampled_heads(oracle):
+@pytest.mark.parametrize("defer", [0, 16, 32])
+def test_decode_config_sampled_heads(oracle, defer):
     """Config 4: B=8, H=32, d=64, N_max=32768 pre-filled to the brim, then fused decode steps (all take the
-    eviction branch of Eq. 5).  State and outputs of sampled (b,h) are compared at steps 0, 1, 128, 255."""
+    eviction branch of Eq. 5).  State and outputs of sampled (b,h) are compared at steps 0, 1, 128, 255.
+    With defer > 0 the cache applies its updates every `defer` steps (the oracle still applies Eq. 5 at every
+    token); its spectrum is compared after the pending ones have been flushed."""
     from paper_2502_18394_amd import binding
     c = synth.CONFIGS["decode_32k"]
     B, H, d, N, steps = c["B"], c["H"], c["d"], c["N_max"], c["steps"]
     sample = [(0, 0), (5, 17), (7, 31)]
     rng = np.random.default_rng(synth.BASE_SEED + 30)
-    cache = binding.PrefixCache(B, H, d, N)
+    print(f"case defer={defer}", flush=True)
+    cache = binding.PrefixCache(B, H, d, N, defer=defer)
     p = synth.gate_params(synth.BASE_SEED + 31, H, d, N)
     P = binding.GateParams(p)
     V = rng.standard_normal((B, N, H, d), dtype=np.float32)
@@ -119,6 +123,8 @@ def test_decode_config_sampled_heads(oracle):
         for (b, h), oc in zip(sample, ocs):
             oc.update(vt[i, b:b + 1, :, h:h + 1].astype(np.float64), qt[i, b:b + 1, :, h:h + 1].astype(np.float64))
         if i in check:
+            if defer:
+                cache.flush()
             torch.cuda.synchronize()
             for (b, h), oc in zip(sample, ocs):
                 sub = {k: (np.asarray(v[h:h + 1], np.float64) if isinstance(v, np.ndarray) else v) for k, v in p.items()}
