@@ -229,7 +229,7 @@ const char *spectre_last_error(void) { return g_err.c_str(); }
 int spectre_version(void) { return 110; }
 
 // 0 = no kernel, 1 = whole slab in LDS, 2 = four-step power-of-two path, 3 = any other length
-// through a padded power-of-two convolution.
+// through a padded power-of-two convolution, 4 = four-step path fused into one kernel (L = 4096).
 static int mix_route(int BH, int L, int d) {
     if (d != 64) return 0;
     int N1, N2, P;
@@ -237,6 +237,7 @@ static int mix_route(int BH, int L, int d) {
     // the in-LDS kernel is one launch: it wins when the length has no four-step plan, when there are many short
     // slabs, and when the whole call is small enough to be bound by the four-step path's dependent launches
     if (sl && (!p2 || (L <= 512 && BH >= 256) || (long long)BH * L <= 65536)) return 1;
+    if (fused_supported(L) && !getenv("SPECTRE_NO_FUSED")) return 4;
     if (p2) return 2;
     return chirp_padded_length(L) ? 3 : 0;
 }
@@ -344,6 +345,7 @@ size_t spectre_mix_workspace_bytes(int B, int L, int H, int d, spectre_dtype io)
     if (route == 0) return 0;
     if (route == 1) return 256;
     if (route == 3) return chirp_layout(BH, L, d).total();
+    if (route == 4) return 256;
     int chunk = 0;
     const int lanes = mix_lanes(BH, L, d, &chunk);
     return align256((size_t)BH * L * sizeof(float2)) + lanes * align256((size_t)chunk * L * (d / 2) * sizeof(float2));
@@ -379,6 +381,14 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         return SPECTRE_OK;
     }
     if (mix_route(BH, L, d) == 3) return mix_chirp(v, static_cast<const float2 *>(g), out, B, L, H, d, io, ws, st);
+    if (mix_route(BH, L, d) == 4) {
+        const float2 *tw = nullptr;
+        int rc = get_roots(4096, &tw);
+        if (rc) return rc;
+        hipError_t e = launch_fused((int)io, v, static_cast<const float2 *>(g), out, tw, L, H, BH, st);
+        if (e != hipSuccess) return fail_hip(e, "fused mixer");
+        return SPECTRE_OK;
+    }
     Pow2Plan pl;
     int rc = get_pow2_plan(L, &pl);
     if (rc) return rc;

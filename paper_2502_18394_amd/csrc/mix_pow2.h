@@ -43,4 +43,10 @@ hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, v
 // extended to all L bins by Hermitian symmetry (real parts only at DC and Nyquist).
 hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st);
 
+// One-kernel path for L = 4096 (a whole column fits in LDS): v, out = tensors [B, 4096, H, 64], g = gate
+// [B*H, 2049] as the caller passes it, tw4096 = device table of exp(-j 2 pi m / 4096).  No workspace.
+bool fused_supported(int L);
+hipError_t launch_fused(int io, const void *v, const float2 *g, void *out, const float2 *tw4096, int L, int H, int BH,
+                        hipStream_t st);
+
 }  // namespace spectre

@@ -251,6 +251,112 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
 }
 
 // ------------------------------------------------------------------------------------------
+// fused: L = 4096.  A column of this length (32 KB as complex fp32) fits in LDS, so the three kernels above and the
+// gate expansion collapse into one kernel and the tensor crosses HBM once each way.  A workgroup of 512 lanes owns
+// four adjacent channel pairs of one head (16 or 32 contiguous bytes of every row), each column with its own padded
+// exchange buffer (4 x 34 KB); its two groups of 256 lanes take two columns each, one after the other, with the big
+// kernel's lane layout and register budget.
+//   load : all lanes sweep the rows, lane pl = tid % 4 of a row reads pair pl into the buffer of column pl;
+//   core : the big kernel's passes (forward, gate, inverse) from and to the column's buffer; register j of lane
+//          tau holds bin 256 j + 16 (tau % 16) + tau / 16 after the forward passes (base-16 digit reversal), and
+//          the gate is read there directly, Hermitian extension and the 1/L of the inverse transform included;
+//   store: the mirror image of the load.
+// The eight workgroups of a head share its rows; their ids are 8 apart, so they run on the same XCD and a row is
+// fetched into one L2.  (The same construction for L = 8192, two columns per pair, leaves room for only two pairs
+// per workgroup, i.e. 8-byte pieces of every row, and measured slower than the three kernels.)
+template <typename IO>
+__global__ __launch_bounds__(512) void k_fused(const typename IO::pair_t *__restrict__ v,
+                                               const float2 *__restrict__ g,
+                                               typename IO::pair_t *__restrict__ out,
+                                               const float2 *__restrict__ twN1, int H, int BH) {
+    typedef typename IO::pair_t pair_t;
+    constexpr int P = 3, L = 4096, F = L / 2 + 1, COLW = L + L / 16, PP = 4, WPH = 32 / PP;
+    constexpr int RPS = 512 / PP, NS = L / RPS;     // rows per sweep of the workgroup, sweeps
+    constexpr int kBatch = 16;                      // sweeps whose loads are in flight together
+    extern __shared__ float2 lds_fused[];
+    const int tid = threadIdx.x, tau = tid & 255, grp = tid >> 8;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int bh = (idx / WPH) * 8 + xcd, part = idx % WPH;
+    if (bh >= BH) return;                           // whole workgroup: the grid is padded to 8 heads
+    const int b = bh / H, h = bh % H;
+    const int pl = tid % PP, r0 = tid / PP;
+    const size_t rs = (size_t)H * 32;
+    const size_t off = (((size_t)b * L) * H + h) * 32 + part * PP + pl;
+
+    for (int s0 = 0; s0 < NS; s0 += kBatch) {
+        pair_t raw[kBatch];
+#pragma unroll
+        for (int s = 0; s < kBatch; ++s) raw[s] = v[off + (size_t)(r0 + RPS * (s0 + s)) * rs];
+#pragma unroll
+        for (int s = 0; s < kBatch; ++s) {
+            const int r = r0 + RPS * (s0 + s);
+            lds_fused[pl * COLW + r + (r >> 4)] = IO::unpack(raw[s]);
+        }
+    }
+    __syncthreads();
+
+    float2 tw[P - 1][15];
+#pragma unroll
+    for (int u = 1; u < 16; ++u) {
+        tw[0][u - 1] = twN1[tau * u];
+        tw[1][u - 1] = twN1[(tau & 15) * 16 * u];
+    }
+    const float2 *gh = g + (size_t)bh * F;
+    const int kbase = 16 * (tau & 15) + (tau >> 4);
+    const float scale = 1.0f / (float)L;
+#pragma unroll 1
+    for (int c = grp; c < PP; c += 2) {
+        float2 *buf = lds_fused + c * COLW;
+        float2 *own = buf + pad_base<P, 0>(tau);     // the lane's pass-0 positions: rows tau + 256 j
+        float2 x[16], G[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int k = 256 * j + kbase;
+            G[j] = gh[2 * k <= L ? k : L - k];
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) x[j] = own[j * pad_stride<P, 0>()];
+        dft<16, false>(x);
+#pragma unroll
+        for (int u = 1; u < 16; ++u) x[u] = cmul(x[u], tw[0][u - 1]);
+        exchange<P, 0, 1, true>(x, buf, tau);
+        dft<16, false>(x);
+#pragma unroll
+        for (int u = 1; u < 16; ++u) x[u] = cmul(x[u], tw[1][u - 1]);
+        exchange<P, 1, 2, false>(x, buf, tau);
+        dft<16, false>(x);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int k = 256 * j + kbase;
+            float2 gv = make_float2(G[j].x * scale, G[j].y * scale);
+            if (2 * k > L) gv.y = -gv.y;
+            if (k == 0 || 2 * k == L) gv.y = 0.0f;
+            x[j] = cmul(x[j], gv);
+        }
+        dft<16, true>(x);
+        exchange<P, 2, 1, false>(x, buf, tau);
+#pragma unroll
+        for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[1][u - 1]);
+        dft<16, true>(x);
+        exchange<P, 1, 0, true>(x, buf, tau);
+#pragma unroll
+        for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[0][u - 1]);
+        dft<16, true>(x);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) own[j * pad_stride<P, 0>()] = x[j];   // nobody else touches these positions
+    }
+    __syncthreads();
+
+    for (int s0 = 0; s0 < NS; s0 += kBatch) {
+#pragma unroll
+        for (int s = 0; s < kBatch; ++s) {
+            const int r = r0 + RPS * (s0 + s);
+            out[off + (size_t)r * rs] = IO::pack(lds_fused[pl * COLW + r + (r >> 4)]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // gate_expand: g [BH][L/2+1] -> gp [BH][N2][N1] with gp[bh][k2][j*TPC + tau] = ext(g)[k2 + N2*k1] / L,
 // k1 = digit_reverse16(16*tau + j) (the bin a lane of the big kernel holds in register j after the
 // forward passes) and ext = Hermitian extension with real DC and Nyquist bins.
@@ -391,6 +497,29 @@ hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int
         if (mode == 2) return big_t<3, 2>(pl, scratch, gp, bh0, nbh, shared_gate, st);
     }
     return hipErrorInvalidValue;
+}
+
+bool fused_supported(int L) { return L == 4096; }
+
+template <typename IO>
+static hipError_t fused_t(const void *v, const float2 *g, void *out, const float2 *twN1, int H, int BH,
+                          hipStream_t st) {
+    constexpr int COLW = 4096 + 4096 / 16;
+    const size_t lds = (size_t)4 * COLW * sizeof(float2);
+    auto kern = k_fused<IO>;
+    hipError_t e = allow_lds(kern, lds);
+    if (e != hipSuccess) return e;
+    const long long grid = (long long)((BH + 7) / 8) * 8 * 8;   // heads padded to 8, 8 workgroups per head
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    kern<<<dim3((unsigned)grid), dim3(512), lds, st>>>(static_cast<const typename IO::pair_t *>(v), g,
+                                                       static_cast<typename IO::pair_t *>(out), twN1, H, BH);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused(int io, const void *v, const float2 *g, void *out, const float2 *tw4096, int L, int H, int BH,
+                        hipStream_t st) {
+    if (!fused_supported(L)) return hipErrorInvalidValue;
+    return io ? fused_t<IoBf16>(v, g, out, tw4096, H, BH, st) : fused_t<IoF32>(v, g, out, tw4096, H, BH, st);
 }
 
 hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st) {

@@ -56,6 +56,26 @@ def test_mix_forward_matches_oracle(oracle, B, L, H, io):
         assert np.all(np.abs(got - want) <= tol)
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H", [(3, 5), (1, 32), (1, 1)])
+def test_one_kernel_path_at_4096_and_the_three_kernel_path_behind_it(oracle, monkeypatch, B, H, io):
+    """L = 4096 runs as a single kernel (whole columns in LDS; head counts that are and are not multiples of the
+    eight workgroup slots per round).  With SPECTRE_NO_FUSED set the same call takes the three four-step kernels
+    (N1 = 256, N2 = 16), which keeps that plan covered by a mixer test; both must match the oracle."""
+    from paper_2502_18394_amd import binding
+    L = 4096
+    print(f"case B={B} H={H} io={io}", flush=True)
+    monkeypatch.delenv("SPECTRE_NO_FUSED", raising=False)
+    assert binding.mix_workspace_bytes(B, L, H, 64, binding.BF16) == 256
+    got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 11 * H)
+    monkeypatch.setenv("SPECTRE_NO_FUSED", "1")
+    assert binding.mix_workspace_bytes(B, L, H, 64, binding.BF16) > B * H * L * 8
+    got3, _, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 11 * H)
+    e1, e3 = rel_l2(got, want), rel_l2(got3, want)
+    print(f"  one kernel {e1:.3e}  three kernels {e3:.3e}", flush=True)
+    assert e1 <= TOL[io] and e3 <= TOL[io]
+
+
 def test_identity_gate_returns_input_on_gpu(oracle):
     B, L, H, d = 1, 4096, 2, 64
     g = np.ones((B, H, L // 2 + 1), np.complex64)

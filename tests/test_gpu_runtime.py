@@ -62,17 +62,17 @@ def test_shutdown_frees_tables_and_library_recovers(oracle):
 
 def test_error_paths_launch_nothing():
     from paper_2502_18394_amd import binding
-    v = torch.zeros((1, 4096, 1, 64), device="cuda")
-    g = torch.zeros((1, 1, 2049), dtype=torch.complex64, device="cuda")
+    v = torch.zeros((1, 8192, 1, 64), device="cuda")
+    g = torch.zeros((1, 1, 4097), dtype=torch.complex64, device="cuda")
     L = binding.lib()
     small = torch.empty(512, dtype=torch.uint8, device="cuda")
     off = (-small.data_ptr()) % 256
     rc = L.spectre_mix_forward(ctypes.c_void_p(v.data_ptr()), ctypes.c_void_p(g.data_ptr()), ctypes.c_void_p(v.data_ptr()),
-                               1, 4096, 1, 64, 0, ctypes.c_void_p(small.data_ptr() + off), ctypes.c_size_t(256), None)
+                               1, 8192, 1, 64, 0, ctypes.c_void_p(small.data_ptr() + off), ctypes.c_size_t(256), None)
     assert rc == binding.EINVAL                                  # out overlaps v
     out = torch.empty_like(v)
     rc = L.spectre_mix_forward(ctypes.c_void_p(v.data_ptr()), ctypes.c_void_p(g.data_ptr()), ctypes.c_void_p(out.data_ptr()),
-                               1, 4096, 1, 64, 0, ctypes.c_void_p(small.data_ptr() + off), ctypes.c_size_t(256), None)
+                               1, 8192, 1, 64, 0, ctypes.c_void_p(small.data_ptr() + off), ctypes.c_size_t(256), None)
     assert rc == binding.EWORKSPACE and b"workspace" in L.spectre_last_error()
     c = binding.PrefixCache(1, 1, 64, 256)
     with pytest.raises(binding.SpectreError) as e:
