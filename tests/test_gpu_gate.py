@@ -64,6 +64,26 @@ def test_gate_from_pooled_sum_decode_form(oracle):
         assert rel_l2(g.cpu().numpy(), want) <= 1e-5
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_pooling_kernels_agree_whatever_the_alignment(io):
+    """Rows that start on a 16-byte boundary are pooled with 16-byte loads, others pair by pair; both add the rows of
+    a channel in the same order, so the gates must be identical bit for bit."""
+    from paper_2502_18394_amd import binding
+    B, L, H, d = 2, 1000, 3, 64
+    P = binding.GateParams(synth.gate_params(31, H, d, L))
+    _, store = synth.tokens(32, (B, L, H, d), io)
+    q = to_device(store, io)
+    shift = 2                                             # elements: 8 bytes (fp32), 4 bytes (bf16)
+    flat = torch.empty(q.numel() + shift, dtype=q.dtype, device="cuda")
+    q_off = flat[shift:].view(B, L, H, d)
+    q_off.copy_(q)
+    assert q.data_ptr() % 16 == 0 and q_off.data_ptr() % 16 != 0
+    a = binding.gate(q, P, 1.0 / L)
+    b = binding.gate(q_off, P, 1.0 / L)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.view_as_real(a), torch.view_as_real(b))
+
+
 def test_pooling_of_long_sequence_is_accurate(oracle):
     """128k rows: the pooled mean is ~0.003 and LayerNorm rescales it to O(1), so the sum must be tight."""
     got, want = run_gate(oracle, 1, 131072, 2, 64, 64, 1024, "bf16", seed=21)
