@@ -208,7 +208,7 @@ __device__ __forceinline__ void gate_load_tile(float4 (&a)[16], const float *__r
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
         const int n = tile * 64 + 8 * (s & 7) + lr;
-        a[s] = (n < twoF) ? *reinterpret_cast<const float4 *>(w2h + (size_t)n * 64 + 32 * (s >> 3) + lc)
+        a[s] = (n < twoF) ? stream_load(reinterpret_cast<const float4 *>(w2h + (size_t)n * 64 + 32 * (s >> 3) + lc))
                           : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 }
@@ -226,7 +226,7 @@ __device__ __forceinline__ void gate_store_bin(float2 *dst, float re, float im, 
 }
 
 template <bool VEC, int RG>   // VEC: d_g % 4 == 0 and 16-byte aligned rows; RG: row groups of 4
-__global__ __launch_bounds__(256) void k_gate_out(const float *__restrict__ hid, const float *__restrict__ W2,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RG <= 2 ? 4 : 2))) void k_gate_out(const float *__restrict__ hid, const float *__restrict__ W2,
                                                   const float *__restrict__ b2,
                                                   const float *__restrict__ mbias, float2 *__restrict__ g,
                                                   int B, int H, int Hg, int dg, int F, int r_base) {
