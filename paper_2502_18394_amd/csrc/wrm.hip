@@ -95,6 +95,53 @@ __global__ __launch_bounds__(256) void k_wrm_tile_sums(const typename IO::pair_t
     }
 }
 
+// The same sums over whole token rows with 16-byte loads (four bf16 pairs or two fp32 pairs per lane, eight rows
+// in flight) for a 16-byte aligned tensor; every tile is full here (the levels that need the sums make L a multiple
+// of 512).  The additions follow the order of the kernel above: 32 rows in turn, then the eight partial sums in turn.
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_wrm_tile_sums_x16(const uint4 *__restrict__ v, float *__restrict__ S, int L,
+                                                           int H, int ntiles, int ppv) {
+    constexpr int NCH = BF16 ? 8 : 4;                 // channels per 16 bytes
+    typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+    const int pi = blockIdx.x * 256 + threadIdx.x;
+    if (pi >= ppv) return;
+    const int tile = blockIdx.y, b = blockIdx.z;
+    const uint4 *src = v + ((size_t)b * L + (size_t)tile * kWrmTileRows) * ppv + pi;
+    float tot[NCH];
+#pragma unroll 1
+    for (int grp = 0; grp < 8; ++grp) {
+        float acc[NCH];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) acc[c] = 0.f;
+#pragma unroll
+        for (int i0 = 0; i0 < 32; i0 += 8) {
+            u32x4_t w[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(src + (size_t)(i0 + i) * ppv));
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (BF16) {
+                    const float2 a = IoBf16::unpack(w[i].x), c = IoBf16::unpack(w[i].y), e = IoBf16::unpack(w[i].z),
+                                 f = IoBf16::unpack(w[i].w);
+                    acc[0] += a.x; acc[1] += a.y; acc[2] += c.x; acc[3] += c.y;
+                    acc[4 % NCH] += e.x; acc[5 % NCH] += e.y; acc[6 % NCH] += f.x; acc[7 % NCH] += f.y;
+                } else {
+                    acc[0] += __uint_as_float(w[i].x); acc[1] += __uint_as_float(w[i].y);
+                    acc[2] += __uint_as_float(w[i].z); acc[3] += __uint_as_float(w[i].w);
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) tot[c] = (grp == 0) ? acc[c] : tot[c] + acc[c];
+        src += (size_t)32 * ppv;
+    }
+    const int e0 = NCH * pi, h = e0 >> 6, c0 = e0 & 63;
+    float *dst = S + (((size_t)b * H + h) * ntiles + tile) * 64 + c0;
+#pragma unroll
+    for (int c = 0; c < NCH; c += 4) *reinterpret_cast<float4 *>(dst + c) = make_float4(tot[c], tot[c + 1], tot[c + 2], tot[c + 3]);
+}
+
 // coefficient of the level-l block mean in the closed form above
 __device__ __forceinline__ float wrm_coef(const float *__restrict__ sb, int l, int J, int c) {
     return (l < J) ? sb[(l + 1) * 64 + c] - sb[l * 64 + c] : sb[c] - sb[J * 64 + c];
@@ -259,7 +306,12 @@ hipError_t launch_wrm_apply(int io, const void *v, const float *s, void *out, fl
     const int ntiles = (L + kWrmTileRows - 1) / kWrmTileRows;
     const dim3 grid(H, ntiles, B);
     if (levels > kWrmTileLevels) {                      // then 2^levels divides L, so L is a multiple of 512
-        if (io) k_wrm_tile_sums<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(v),
+        if ((reinterpret_cast<uintptr_t>(v) & 15) == 0) {
+            const int ppv = H * 32 / (io ? 4 : 2);
+            const dim3 g16((ppv + 255) / 256, ntiles, B);
+            if (io) k_wrm_tile_sums_x16<true><<<g16, 256, 0, st>>>(static_cast<const uint4 *>(v), tile_sums, L, H, ntiles, ppv);
+            else k_wrm_tile_sums_x16<false><<<g16, 256, 0, st>>>(static_cast<const uint4 *>(v), tile_sums, L, H, ntiles, ppv);
+        } else if (io) k_wrm_tile_sums<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(v),
                                                               reinterpret_cast<float2 *>(tile_sums), L, H, ntiles);
         else k_wrm_tile_sums<IoF32><<<grid, 256, 0, st>>>(static_cast<const float2 *>(v),
                                                           reinterpret_cast<float2 *>(tile_sums), L, H, ntiles);

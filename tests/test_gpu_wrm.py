@@ -35,6 +35,24 @@ def test_wrm_apply_matches_oracle(oracle, B, L, H, J, io):
     assert err <= TOL[io]
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_wrm_tile_sums_agree_whatever_the_alignment(io):
+    """Above level 8 the tile sums are taken with 16-byte loads over whole rows when the tensor starts on a 16-byte
+    boundary and head by head otherwise; both add in the same order, so the outputs must be identical bit for bit."""
+    from paper_2502_18394_amd import binding
+    B, L, H, J = 2, 2048, 3, 11
+    _, store = synth.tokens(320, (B, L, H, 64), io)
+    s = torch.from_numpy(level_gates(321, B, H, J)).cuda()
+    v = to_device(store, io)
+    flat = torch.empty(v.numel() + 2, dtype=v.dtype, device="cuda")
+    v_off = flat[2:].view(B, L, H, 64)
+    v_off.copy_(v)
+    assert v.data_ptr() % 16 == 0 and v_off.data_ptr() % 16 != 0
+    a, b = binding.wrm_apply(v, s), binding.wrm_apply(v_off, s)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16 if io == "bf16" else torch.int32), b.view(torch.int16 if io == "bf16" else torch.int32))
+
+
 def test_wrm_special_gates_and_in_place(oracle):
     from paper_2502_18394_amd import binding
     B, L, H, J = 1, 2048, 2, 11
