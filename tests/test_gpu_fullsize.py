@@ -154,6 +154,44 @@ def test_wavelet_refinement_at_the_headline_shape(oracle):
     assert err <= TOL["bf16"]
 
 
+def test_decode_without_eviction_sampled_heads(oracle):
+    """The secondary decode row: config 4's 32768 tokens in a window of 65536 slots, so every step takes the branch
+    of Eq. 5 without eviction (the readout's divisor stays 1/N_max); sampled (b,h) against the oracle."""
+    from paper_2502_18394_amd import binding
+    B, H, d, T0, N, steps = 8, 32, 64, 32768, 65536, 12
+    sample = [(1, 3), (7, 30)]
+    rng = np.random.default_rng(synth.BASE_SEED + 60)
+    cache = binding.PrefixCache(B, H, d, N)
+    p = synth.gate_params(synth.BASE_SEED + 61, H, d, N)
+    P = binding.GateParams(p)
+    V = rng.standard_normal((B, T0, H, d), dtype=np.float32)
+    Q = rng.standard_normal((B, T0, H, d), dtype=np.float32)
+    cache.update(torch.from_numpy(V).cuda(), torch.from_numpy(Q).cuda())
+    ocs = []
+    for (b, h) in sample:
+        oc = oracle.PrefixCache(1, 1, d, N)
+        oc.prefill(V[b:b + 1, :, h:h + 1].astype(np.float64), Q[b:b + 1, :, h:h + 1].astype(np.float64))
+        ocs.append(oc)
+    del V, Q
+    vt = rng.standard_normal((steps, B, 1, H, d), dtype=np.float32)
+    qt = rng.standard_normal((steps, B, 1, H, d), dtype=np.float32)
+    vt_d, qt_d = torch.from_numpy(vt).cuda(), torch.from_numpy(qt).cuda()
+    for i in range(steps):
+        out = cache.step(vt_d[i], qt_d[i], P)
+        for (b, h), oc in zip(sample, ocs):
+            oc.update(vt[i, b:b + 1, :, h:h + 1].astype(np.float64), qt[i, b:b + 1, :, h:h + 1].astype(np.float64))
+        if i in (0, steps - 1):
+            torch.cuda.synchronize()
+            for (b, h), oc in zip(sample, ocs):
+                sub = {k: (np.asarray(v[h:h + 1], np.float64) if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+                want = oc.readout_newest(oracle.gate(oc.sum_q, 1.0 / N, sub, N, 0))
+                e_out = rel_l2(out[b, 0, h].cpu().numpy(), want[0, 0, 0])
+                e_spec = rel_l2(cache.prefix_fft[b, h].cpu().numpy(), oc.spec[0, 0])
+                print(f"  step {i} (b,h)=({b},{h}): out {e_out:.3e} spec {e_spec:.3e}", flush=True)
+                assert e_out <= 1e-5 and e_spec <= 1e-5
+    assert cache.t == T0 + steps
+
+
 def test_decode_with_memory_bank_sampled_heads(oracle):
     """Config 4's cache with 64 of its 32768 rows pinned as persistent memory (Sec. 3.4): the ring of 32704
     rows is pre-filled to the brim, then fused decode steps; sampled (b,h) against the oracle."""
