@@ -64,46 +64,63 @@ __global__ __launch_bounds__(256) void k_ring_update(const T *__restrict__ v_new
 // (the newest row of Cor. B.2's inverse; exp(+j 2 pi k slot/N) = conj(w_k)).
 constexpr int kSweepBins = 128;
 
+// (a b) mod N for a, b < N <= 2^17 without 64-bit division.
+__device__ __forceinline__ unsigned mul_mod(unsigned a, unsigned b, int N) {
+    if ((N & (N - 1)) == 0) return (a * b) & (unsigned)(N - 1);
+    return (((a * (b >> 9)) % (unsigned)N) * 512u + a * (b & 511u)) % (unsigned)N;
+}
+
+// The per-bin factors w_k and r_k of a chunk are prepared once by its first 128 lanes and kept in LDS; the rows
+// then cost one cache access each, four of them in flight per lane.
 template <bool UPDATE, bool READ>
 __global__ __launch_bounds__(256) void k_sweep(float4 *__restrict__ X, const float *__restrict__ delta,
                                                const float2 *__restrict__ tw, const float2 *__restrict__ g,
                                                float *__restrict__ partial, int F, int N, int slot,
                                                int nchunks) {
     __shared__ float2 red[8][32];
+    __shared__ float2 s_w[kSweepBins], s_r[kSweepBins];
     const int lane = threadIdx.x & 31, row = threadIdx.x >> 5;
     const int chunk = blockIdx.x, bh = blockIdx.y;
     const int k0 = chunk * kSweepBins, k1 = min(F, k0 + kSweepBins);
+    if (threadIdx.x < kSweepBins) {
+        const int k = min(k0 + (int)threadIdx.x, k1 - 1);
+        const float2 w = tw[mul_mod((unsigned)k, (unsigned)slot, N)];
+        s_w[threadIdx.x] = w;
+        if (READ) {
+            const float invN = 1.0f / (float)N;
+            const float ck = (k == 0 || 2 * k == N) ? invN : 2.0f * invN;
+            const float2 r = cmulc(g[(size_t)bh * F + k], w);   // g_k conj(w_k)
+            s_r[threadIdx.x] = make_float2(r.x * ck, r.y * ck);
+        }
+    }
     float2 dl = make_float2(0.f, 0.f);
     if (UPDATE) dl = *reinterpret_cast<const float2 *>(delta + (size_t)bh * 64 + 2 * lane);
-    const float invN = 1.0f / (float)N;
     float acc0 = 0.f, acc1 = 0.f;
     float4 *Xp = X + ((size_t)bh * F) * 32 + lane;
-    // (k * slot) mod N for k = k0 + row, k0 + row + 8, ...: exact for any N, one 64-bit remainder per lane
-    unsigned step, m;
-    if ((N & (N - 1)) == 0) {            // power of two: the wrap of 32-bit products is harmless
-        step = (8u * (unsigned)slot) & (unsigned)(N - 1);
-        m = ((unsigned)(k0 + row) * (unsigned)slot) & (unsigned)(N - 1);
-    } else {
-        step = (unsigned)((8ull * (unsigned)slot) % (unsigned)N);
-        m = (unsigned)(((unsigned long long)(k0 + row) * (unsigned)slot) % (unsigned)N);
-    }
-    for (int k = k0 + row; k < k1; k += 8, m = (m + step >= (unsigned)N) ? m + step - (unsigned)N : m + step) {
-        const float2 w = tw[m];
-        float4 x = stream_load(Xp + (size_t)k * 32);
-        if (UPDATE) {
-            x.x = fmaf(dl.x, w.x, x.x);
-            x.y = fmaf(dl.x, w.y, x.y);
-            x.z = fmaf(dl.y, w.x, x.z);
-            x.w = fmaf(dl.y, w.y, x.w);
-            stream_store(Xp + (size_t)k * 32, x);
-        }
-        if (READ) {
-            const float2 gk = g[(size_t)bh * F + k];
-            const float ck = (k == 0 || 2 * k == N) ? invN : 2.0f * invN;
-            const float2 r = cmulc(gk, w);   // g_k conj(w_k)
-            const float rr = r.x * ck, ri = r.y * ck;
-            acc0 = fmaf(rr, x.x, fmaf(-ri, x.y, acc0));
-            acc1 = fmaf(rr, x.z, fmaf(-ri, x.w, acc1));
+    __syncthreads();
+    constexpr int kU = 4;
+    for (int kk = k0 + row; kk < k1; kk += 8 * kU) {
+        float4 x[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) x[u] = stream_load(Xp + (size_t)min(kk + 8 * u, k1 - 1) * 32);
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int k = kk + 8 * u;
+            if (k < k1) {
+                if (UPDATE) {
+                    const float2 w = s_w[k - k0];
+                    x[u].x = fmaf(dl.x, w.x, x[u].x);
+                    x[u].y = fmaf(dl.x, w.y, x[u].y);
+                    x[u].z = fmaf(dl.y, w.x, x[u].z);
+                    x[u].w = fmaf(dl.y, w.y, x[u].w);
+                    stream_store(Xp + (size_t)k * 32, x[u]);
+                }
+                if (READ) {
+                    const float2 r = s_r[k - k0];
+                    acc0 = fmaf(r.x, x[u].x, fmaf(-r.y, x[u].y, acc0));
+                    acc1 = fmaf(r.x, x[u].z, fmaf(-r.y, x[u].w, acc1));
+                }
+            }
         }
     }
     if (READ) {
@@ -154,12 +171,24 @@ __global__ __launch_bounds__(256) void k_sweep_lazy(const float4 *__restrict__ X
                                                     PendingSlots ps, int nchunks) {
     __shared__ float2 red[8][32];
     __shared__ float kred[8][32];
+    __shared__ float2 s_r[kSweepBins], s_g[kSweepBins];   // per bin: c_k/N g_k conj(w_k), and c_k/N g_k
     const int lane = threadIdx.x & 31, row = threadIdx.x >> 5;
     const int chunk = blockIdx.x, bh = blockIdx.y;
     const int k0 = chunk * kSweepBins, k1 = min(F, k0 + kSweepBins);
-    unsigned m_new = 0, step_new = 0;
-    index_walk((unsigned)(k0 + row), (unsigned)slot_new, N, m_new, step_new);
-    const float invN = 1.0f / (float)N;
+    if (threadIdx.x < kSweepBins) {
+        const int k = k0 + threadIdx.x;
+        float2 r = make_float2(0.f, 0.f), gc = make_float2(0.f, 0.f);   // bins past the end carry no weight
+        if (k < k1) {
+            const float invN = 1.0f / (float)N;
+            const float ck = (k == 0 || 2 * k == N) ? invN : 2.0f * invN;
+            const float2 gk = g[(size_t)bh * F + k];
+            const float2 t = cmulc(gk, tw[mul_mod((unsigned)k, (unsigned)slot_new, N)]);   // g_k conj(w_k)
+            r = make_float2(t.x * ck, t.y * ck);
+            gc = make_float2(gk.x * ck, gk.y * ck);
+        }
+        s_r[threadIdx.x] = r;
+        s_g[threadIdx.x] = gc;
+    }
     float acc0 = 0.f, acc1 = 0.f, kacc = 0.f;
     const float4 *Xp = X + ((size_t)bh * F) * 32 + lane;
     // lane i of every bin row follows pending token i: e_k = exp(-j 2 pi k j_i / N), j_i = (slot_new - slot_i)
@@ -171,21 +200,14 @@ __global__ __launch_bounds__(256) void k_sweep_lazy(const float4 *__restrict__ X
     index_walk((unsigned)(k0 + row), mult, N, m_item, step_item);
     const float2 rot = tw[step_item];
     float2 e = tw[m_item];
+    __syncthreads();
     constexpr int kU = 8;
     // kU bin rows per trip, every load of the trip requested up front (addresses clamped into the chunk,
     // rows past its end weighted with zero)
     for (int kk = k0 + row; kk < k1; kk += 8 * kU) {
         float4 x[kU];
-        float2 gk[kU], wn[kU];
 #pragma unroll
-        for (int u = 0; u < kU; ++u) {
-            const int kc = min(kk + 8 * u, k1 - 1);
-            x[u] = stream_load(Xp + (size_t)kc * 32);
-            gk[u] = g[(size_t)bh * F + kc];
-            wn[u] = tw[m_new];
-            m_new += step_new;
-            if (m_new >= (unsigned)N) m_new -= (unsigned)N;
-        }
+        for (int u = 0; u < kU; ++u) x[u] = stream_load(Xp + (size_t)min(kk + 8 * u, k1 - 1) * 32);
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             m_item += step_item;
@@ -194,13 +216,13 @@ __global__ __launch_bounds__(256) void k_sweep_lazy(const float4 *__restrict__ X
         const float2 e_next = tw[m_item];
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-            const int k = kk + 8 * u;
-            const float ck = k >= k1 ? 0.f : ((k == 0 || 2 * k == N) ? invN : 2.0f * invN);
-            const float2 r = cmulc(gk[u], wn[u]);    // g_k conj(w_k)
-            const float rr = r.x * ck, ri = r.y * ck;
-            acc0 = fmaf(rr, x[u].x, fmaf(-ri, x[u].y, acc0));
-            acc1 = fmaf(rr, x[u].z, fmaf(-ri, x[u].w, acc1));
-            kacc = fmaf(ck, fmaf(gk[u].x, e.x, gk[u].y * e.y), kacc);   // c_k/N Re(g_k conj(e_k))
+            const int kl = min(kk + 8 * u - k0, kSweepBins - 1);
+            const bool live = kk + 8 * u < k1;
+            const float2 r = live ? s_r[kl] : make_float2(0.f, 0.f);
+            const float2 gc = live ? s_g[kl] : make_float2(0.f, 0.f);
+            acc0 = fmaf(r.x, x[u].x, fmaf(-r.y, x[u].y, acc0));
+            acc1 = fmaf(r.x, x[u].z, fmaf(-r.y, x[u].w, acc1));
+            kacc = fmaf(gc.x, e.x, fmaf(gc.y, e.y, kacc));   // c_k/N Re(g_k conj(e_k))
             e = cmul(e, rot);
         }
         e = e_next;
@@ -233,12 +255,6 @@ __global__ __launch_bounds__(256) void k_sweep_lazy(const float4 *__restrict__ X
 // A workgroup takes kFlushChunks chunks of kSweepBins = 4 x 32 bins, one block per wave and chunk; partial as
 // in k_sweep.
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-// (a b) mod N for a, b < N <= 2^17 without 64-bit division.
-__device__ __forceinline__ unsigned mul_mod(unsigned a, unsigned b, int N) {
-    if ((N & (N - 1)) == 0) return (a * b) & (unsigned)(N - 1);
-    return (((a * (b >> 9)) % (unsigned)N) * 512u + a * (b & 511u)) % (unsigned)N;
-}
 
 constexpr int kFlushChunks = 8;   // chunks of kSweepBins bins per workgroup
 
