@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=32)
     ap.add_argument("--no-membw", action="store_true", help="skip the streaming-bandwidth probe")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the secondary decode row (window of 65536 slots), e.g. under a profiler so that every\n"
+                         "cache kernel in the trace belongs to the decode_32k workload")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline line, print one JSON line per configuration (mixer only): the "
                          "length sweep at the Llama head shape, config 1 and the ViT shape")
@@ -343,22 +346,23 @@ def main():
             torch.cuda.empty_cache()
         del Pd
         torch.cuda.empty_cache()
-        # secondary row: a window of 65536 slots holding the same 32768 tokens, so the steps take the branch of
-        # Eq. 5 without eviction; twice the cache bytes per step
-        N2w = 2 * N
-        cache = binding.PrefixCache(Bd, Hd, dd, N2w)
-        Pw = device_gate_params(synth.BASE_SEED + 9, Hd, dd, N2w, synth.D_GATE, binding)
-        cache.update(device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 4, torch.float32),
-                     device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 5, torch.float32))
-        nst = max(4, args.decode_steps // 2)
-        ms_w = time_loop(lambda: cache.step(vt, qt, Pw, out=od), nst, 2)
-        wbytes = 2 * 8 * Bd * Hd * (N2w // 2 + 1) * dd
-        res["decode_no_eviction"] = {
-            "workload": f"fused Prefix-FFT step B={Bd} H={Hd} d={dd} N_max={N2w}, {N} tokens live (no eviction), fp32",
-            "tokens_per_s": Bd / (ms_w * 1e-3), "ms_per_step": ms_w, "steps": nst, "algorithmic_bytes": wbytes,
-            "hbm_frac": wbytes / (ms_w * 1e-3) / 1e9 / HBM_PEAK_GBS}
-        del cache, Pw
-        torch.cuda.empty_cache()
+        if not args.no_secondary:
+            # secondary row: a window of 65536 slots holding the same 32768 tokens, so the steps take the branch of
+            # Eq. 5 without eviction; twice the cache bytes per step
+            N2w = 2 * N
+            cache = binding.PrefixCache(Bd, Hd, dd, N2w)
+            Pw = device_gate_params(synth.BASE_SEED + 9, Hd, dd, N2w, synth.D_GATE, binding)
+            cache.update(device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 4, torch.float32),
+                         device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 5, torch.float32))
+            nst = max(4, args.decode_steps // 2)
+            ms_w = time_loop(lambda: cache.step(vt, qt, Pw, out=od), nst, 2)
+            wbytes = 2 * 8 * Bd * Hd * (N2w // 2 + 1) * dd
+            res["decode_no_eviction"] = {
+                "workload": f"fused Prefix-FFT step B={Bd} H={Hd} d={dd} N_max={N2w}, {N} tokens live (no eviction), fp32",
+                "tokens_per_s": Bd / (ms_w * 1e-3), "ms_per_step": ms_w, "steps": nst, "algorithmic_bytes": wbytes,
+                "hbm_frac": wbytes / (ms_w * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            del cache, Pw
+            torch.cuda.empty_cache()
 
     if not args.no_membw:
         res["membw_probe"] = membw_probe()
