@@ -233,3 +233,51 @@ def test_decode_with_memory_bank_sampled_heads(oracle):
                 assert e_out <= 1e-5 and e_spec <= 1e-5
                 assert np.array_equal(cache.v_buf[b, h, :N_mem].cpu().numpy(), M[0, h])
     assert cache.t == N_max + steps
+
+
+def test_tensors_with_more_than_2_31_elements(oracle):
+    """B=17 sequences of the headline shape: 4.6e9 elements (2.3e9 channel pairs, 9.1 GB) per tensor, so neither
+    element nor pair offsets of the last sequence fit 31 bits.  Pooling + gate, mixer, refinement and projection run
+    on the whole tensors; the first and the very last (b,h) slab are compared with the oracle."""
+    from paper_2502_18394_amd import binding
+    B, H, d, L = 17, 32, 64, 131072
+    assert B * L * H * d // 2 > 2 ** 31
+    J = synth.max_wavelet_levels(L)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 70)
+    v = torch.empty((B, L, H, d), device="cuda", dtype=torch.bfloat16)
+    for b in range(B):
+        v[b] = torch.randn((L, H, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    p = synth.gate_params(synth.BASE_SEED + 71, H, d, L)
+    P = binding.GateParams(p)
+    s_lv = np.random.default_rng(synth.BASE_SEED + 72).standard_normal((B, H, J + 1, d)).astype(np.float32)
+    rng = np.random.default_rng(synth.BASE_SEED + 73)
+    Wq = (0.125 * rng.standard_normal((H, d, d))).astype(np.float32)
+    Wv = (0.125 * rng.standard_normal((H, d, d))).astype(np.float32)
+    print("  gate", flush=True)
+    g = binding.gate(v, P, 1.0 / L)
+    print("  mixer", flush=True)
+    mixed = binding.mix_forward(v, g)
+    print("  refinement", flush=True)
+    refined = binding.wrm_apply(mixed, torch.from_numpy(s_lv).cuda())
+    print("  projection", flush=True)
+    pv, _, psum = binding.project(v, torch.from_numpy(Wq).cuda(), torch.from_numpy(Wv).cuda())
+    torch.cuda.synchronize()
+    for (b, h) in [(0, 0), (B - 1, H - 1)]:
+        x = v[b:b + 1, :, h:h + 1, :].float().cpu().numpy().astype(np.float64)
+        sub = {k: (np.asarray(a[h:h + 1], np.float64) if isinstance(a, np.ndarray) else a) for k, a in p.items()}
+        sub["Hg"] = 1
+        og = oracle.gate(oracle.pool_q(x), 1.0 / L, sub, L, 0)
+        e_gate = rel_l2(g[b:b + 1, h:h + 1].cpu().numpy(), og)
+        om = oracle.mix_forward(x, og)
+        e_mix = rel_l2(from_device(mixed[b:b + 1, :, h:h + 1, :].contiguous()), om)
+        # the refinement is checked on its own input (the mixer's rounded output), like the benchmark's row
+        m_in = mixed[b:b + 1, :, h:h + 1, :].float().cpu().numpy().astype(np.float64)
+        ow = oracle.wrm_apply(m_in, s_lv[b:b + 1, h:h + 1].astype(np.float64), J)
+        e_wrm = rel_l2(from_device(refined[b:b + 1, :, h:h + 1, :].contiguous()), ow)
+        Qo, Vo = oracle.project(x, Wq[h:h + 1].astype(np.float64), Wv[h:h + 1].astype(np.float64))
+        e_pv = rel_l2(from_device(pv[b:b + 1, :, h:h + 1, :].contiguous()), Vo)
+        e_ps = rel_l2(psum[b:b + 1, h:h + 1].cpu().numpy(), oracle.pool_q(Qo))
+        print(f"  (b,h)=({b},{h}): gate {e_gate:.3e} mixer {e_mix:.3e} refinement {e_wrm:.3e} "
+              f"projection {e_pv:.3e} pooled {e_ps:.3e}", flush=True)
+        assert e_gate <= 1e-5 and e_mix <= TOL["bf16"] and e_wrm <= TOL["bf16"] and e_pv <= TOL["bf16"] and e_ps <= 1e-5
