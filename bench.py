@@ -325,7 +325,34 @@ def main():
                          "roofline": {"bound": "hbm", "kernel": "k_sweep<update,read>", "achieved": sweep_bytes / (ms_dec * 1e-3) / 1e9,
                                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sweep_bytes / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                       "traffic": DECODE_SWEEP_TRAFFIC_BYTES, "algorithmic_bytes": sweep_bytes}}
-        del cache
+        # one-time rows of the same cache: pre-fill from 32768 tokens (Alg. 1 PreFill) and the literal full-window
+        # readout (inverse transform of the gated cache, all live rows)
+        Vp = device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 4, torch.float32)
+        Qp = device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 5, torch.float32)
+
+        def timed(fn, prep, n):
+            ts = []
+            for _ in range(n):
+                prep()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn()
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            return min(ts)
+        ms_pre = timed(lambda: cache.update(Vp, Qp), cache.reset, 3)
+        pre_bytes = 5 * 4 * Bd * Hd * N * dd                    # V, Q in; two ring buffers and the spectrum out
+        gw = binding.gate(cache.sum_q, Pd, 1.0 / N, pooled=True, phase_pos=cache.t)
+        ms_win = timed(lambda: cache.readout(gw, binding.READ_WINDOW), lambda: None, 3)
+        win_bytes = 8 * Bd * Hd * Fd * dd + 4 * Bd * Hd * N * dd
+        res["decode"]["prefill"] = {"ms": ms_pre, "tokens": Bd * N, "tokens_per_s": Bd * N / (ms_pre * 1e-3),
+                                    "algorithmic_bytes": pre_bytes,
+                                    "hbm_frac": pre_bytes / (ms_pre * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        res["decode"]["readout_window"] = {"ms": ms_win, "rows": N, "algorithmic_bytes": win_bytes,
+                                           "hbm_frac": win_bytes / (ms_win * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                           "what": "full inverse of the gated cache, all 32768 live rows, fp32 (output allocated by the call)"}
+        del cache, Vp, Qp, gw
         torch.cuda.empty_cache()
         # the same steps with deferred updates: the cache is only read, every `cap` steps one sweep applies the
         # pending rank-one updates (same outputs up to fp32 rounding; prefix_fft lags until the flush)

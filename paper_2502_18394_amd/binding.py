@@ -290,6 +290,11 @@ class PrefixCache:
         self._ws = None
         _check(L.spectre_prefix_init(ctypes.byref(self.c), _stream(None)))
 
+    def reset(self, stream=None):
+        """Back to the empty cache (t = 0, zero state); memory rows, if any, must be set again."""
+        self.c.n_pending = 0
+        _check(lib().spectre_prefix_init(ctypes.byref(self.c), _stream(stream)))
+
     def set_memory(self, mem, stream=None):
         """mem float32 [1 or B, H, N_mem, d]: the persistent memory rows; call once, before any token."""
         if mem.dtype != torch.float32 or mem.ndim != 4 or tuple(mem.shape[1:]) != (self.H, self.N_mem, self.d):
