@@ -297,8 +297,21 @@ static int mix_chirp(const void *v, const float2 *g, void *out, int B, int L, in
         if (e != hipSuccess) return fail_hip(e, "small_fwd(kernel)");
         e = launch_big(pl, scr, nullptr, 0, n, 1, st);
         if (e != hipSuccess) return fail_hip(e, "big(kernel)");
-        e = launch_chirp_gate(scr, gp, BH, c.M, pl.N1, pl.N2, ph0, n, st);
+        // short padded lengths run the data pass as one in-LDS launch, which wants the gate in plain bin order
+        e = slab_supported(c.M) ? launch_chirp_gate_plain(scr, gp, BH, c.M, pl.N1, pl.N2, pl.P, ph0, n, st)
+                                : launch_chirp_gate(scr, gp, BH, c.M, pl.N1, pl.N2, ph0, n, st);
         if (e != hipSuccess) return fail_hip(e, "chirp_gate");
+    }
+    if (slab_supported(c.M)) {
+        const float2 *roots = nullptr;
+        rc = get_roots(c.M, &roots);
+        if (rc) return rc;
+        const int *order = nullptr;
+        rc = get_slab_order(c.M, &order);
+        if (rc) return rc;
+        e = launch_mix_slab((int)io, v, gp, out, roots, order, B, c.M, H, st, L);
+        if (e != hipSuccess) return fail_hip(e, "mix_slab(padded)");
+        return SPECTRE_OK;
     }
     // the data: zero-padded to M, first L rows of the result kept
     const int chunk = mix_chunk_heads(BH, c.M, d);

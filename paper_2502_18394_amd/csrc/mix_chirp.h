@@ -31,6 +31,11 @@ hipError_t launch_chirp_post(const float2 *U, const float2 *w, float2 *KK, int L
 hipError_t launch_chirp_gate(const float2 *scr, float2 *gp, int BH, int M, int N1, int N2, int ph0, int nphl,
                              hipStream_t st);
 
+// The same spectra as per-head gates g [BH][M/2+1] in plain bin order, unscaled: the gate argument of the in-LDS
+// kernel when it runs the padded convolution (M <= 2048).
+hipError_t launch_chirp_gate_plain(const float2 *scr, float2 *g, int BH, int M, int N1, int N2, int P, int ph0,
+                                   int nphl, hipStream_t st);
+
 // Host: chirp w [L] and the chirp filter's M-point spectrum in the big kernel's register order
 // ([N2][N1], scaled by 1/M), both evaluated in fp64.
 void chirp_tables_host(int L, int M, int N1, int N2, int P, float2 *w, float2 *filt);

@@ -77,6 +77,31 @@ __global__ __launch_bounds__(256) void k_chirp_gate(const float2 *__restrict__ s
     gp[(bh * N2 + k2) * N1 + r] = make_float2(z.x * scale, z.y * scale);
 }
 
+// The same spectra in plain bin order for the in-LDS kernel: g[bh][k] = spectrum bin k = k2 + N2 k1 of pseudo-head
+// column (bh / 32, bh % 32), which the forward-only big kernel left at position digit_reverse16(k1) of column k2;
+// unscaled (that kernel divides by its length itself).
+__global__ __launch_bounds__(256) void k_chirp_gate_plain(const float2 *__restrict__ scr, float2 *__restrict__ g, int BH,
+                                                          int F, int N1, int N2, int P, int ph0, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int k = (int)(idx % F);
+    const size_t lh = idx / F;                        // head index within this group of pseudo-heads
+    const int phl = (int)(lh / 32), p = (int)(lh % 32);
+    const size_t bh = (size_t)ph0 * 32 + lh;
+    if (bh >= (size_t)BH) return;
+    const int k2 = k % N2, k1 = k / N2;
+    const int pos = (P == 2) ? (((k1 & 15) << 4) | (k1 >> 4)) : (((k1 & 15) << 8) | (k1 & 0xF0) | (k1 >> 8));
+    g[bh * F + k] = scr[(((size_t)phl * N2 + k2) * 32 + p) * N1 + pos];
+}
+
+hipError_t launch_chirp_gate_plain(const float2 *scr, float2 *g, int BH, int M, int N1, int N2, int P, int ph0,
+                                   int nphl, hipStream_t st) {
+    const int F = M / 2 + 1;
+    const size_t total = (size_t)nphl * 32 * F;
+    k_chirp_gate_plain<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(scr, g, BH, F, N1, N2, P, ph0, total);
+    return hipGetLastError();
+}
+
 hipError_t launch_chirp_pre(const float2 *g, const float2 *w, float2 *A, int BH, int L, int nph, hipStream_t st) {
     const size_t total = (size_t)L * nph * 32;
     k_chirp_pre<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(g, w, A, BH, L, nph, total);

@@ -13,8 +13,9 @@ bool slab_supported(int L);
 void slab_bin_order(int L, int *bin_of_pos);
 
 // out = irfft_L(g * rfft_L(v)) for d = 64; roots = device table [L] of exp(-j 2 pi m / L), bin_of_pos = device
-// copy of slab_bin_order(L).
+// copy of slab_bin_order(L).  With 0 < rows < L the tensors hold `rows` rows per sequence: v is taken as followed
+// by L - rows zero rows and only the first `rows` rows of the result are written.
 hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, const float2 *roots,
-                           const int *bin_of_pos, int B, int L, int H, hipStream_t st);
+                           const int *bin_of_pos, int B, int L, int H, hipStream_t st, int rows = 0);
 
 }  // namespace spectre

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
                                                   typename IO::pair_t *__restrict__ out,
                                                   const float2 *__restrict__ roots_g,
                                                   const int *__restrict__ bin_of_pos, int L, int H,
-                                                  SlabRadices rad) {
+                                                  SlabRadices rad, int rows) {
     extern __shared__ float2 lds_slab[];
     float2 *slab = lds_slab;
     float2 *roots = slab + (size_t)L * PP;
@@ -110,14 +110,16 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
     // rows l = tid/PP + kRows i.  Sixteen loads are put in flight before any is consumed (all 196 rows of
     // the ViT grid at once for fp32 half heads); the first batch flies while the gate table below is built.
     const int lp_in = tid & (PP - 1), row_in = tid / PP;
-    const typename IO::pair_t *src = v + (((size_t)b * L) * H + h) * 32 + part * PP + lp_in;
+    // the tensors hold `rows` <= L rows per sequence; the transform sees them followed by zeros and only the first
+    // `rows` rows of the result are kept (zero-padded linear convolution)
+    const typename IO::pair_t *src = v + (((size_t)b * rows) * H + h) * 32 + part * PP + lp_in;
     const size_t rs = (size_t)H * 32;
     constexpr int kBatch = 16;
     typename IO::pair_t val[kBatch];
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
         const int l = row_in + kRows * i;
-        val[i] = (l < L) ? src[(size_t)l * rs] : IO::zero();
+        val[i] = (l < rows) ? src[(size_t)l * rs] : IO::zero();
     }
 
     // roots of unity and the gate in position order (bin_of_pos[p] = the bin that position p holds after
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
             const int l = l0 + kRows * i;
-            val[i] = (l < L) ? src[(size_t)l * rs] : IO::zero();
+            val[i] = (l < rows) ? src[(size_t)l * rs] : IO::zero();
         }
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
@@ -183,8 +185,8 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
         __syncthreads();
     }
     {
-        typename IO::pair_t *dst = out + (((size_t)b * L) * H + h) * 32 + part * PP + lp_in;
-        for (int l = row_in; l < L; l += kRows) dst[(size_t)l * rs] = IO::pack(slab[l * PP + lp_in]);
+        typename IO::pair_t *dst = out + (((size_t)b * rows) * H + h) * 32 + part * PP + lp_in;
+        for (int l = row_in; l < rows; l += kRows) dst[(size_t)l * rs] = IO::pack(slab[l * PP + lp_in]);
     }
 }
 
@@ -249,7 +251,7 @@ void slab_bin_order(int L, int *bin_of_pos) {
 
 template <typename IO, int PP>
 static hipError_t mix_slab_t(const void *v, const float2 *g, void *out, const float2 *roots, const int *bin_of_pos,
-                             int B, int L, int H, hipStream_t st) {
+                             int B, int L, int H, int rows, hipStream_t st) {
     const size_t lds = ((size_t)L * PP + 2 * (size_t)L) * sizeof(float2);
     const SlabRadices rad = slab_radices(L);
     auto kern = k_mix_slab<IO, PP>;
@@ -260,7 +262,7 @@ static hipError_t mix_slab_t(const void *v, const float2 *g, void *out, const fl
     }
     kern<<<dim3(B * H * (32 / PP)), dim3(256), lds, st>>>(static_cast<const typename IO::pair_t *>(v), g,
                                                          static_cast<typename IO::pair_t *>(out), roots, bin_of_pos, L, H,
-                                                         rad);
+                                                         rad, rows);
     return hipGetLastError();
 }
 
@@ -274,13 +276,15 @@ int slab_pairs_per_workgroup(int io, int BH, int L) {
 }
 
 hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, const float2 *roots,
-                           const int *bin_of_pos, int B, int L, int H, hipStream_t st) {
+                           const int *bin_of_pos, int B, int L, int H, hipStream_t st, int rows) {
+    if (rows <= 0) rows = L;
+    if (rows > L) return hipErrorInvalidValue;
     const int pp = slab_pairs_per_workgroup(io, B * H, L);
     if ((size_t)L * (pp + 2) * sizeof(float2) > (size_t)160 * 1024) return hipErrorInvalidValue;
 #define SPECTRE_SLAB_CASE(PPV)                                                                       \
     case PPV:                                                                                       \
-        return io ? mix_slab_t<IoBf16, PPV>(v, g, out, roots, bin_of_pos, B, L, H, st)              \
-                  : mix_slab_t<IoF32, PPV>(v, g, out, roots, bin_of_pos, B, L, H, st);
+        return io ? mix_slab_t<IoBf16, PPV>(v, g, out, roots, bin_of_pos, B, L, H, rows, st)        \
+                  : mix_slab_t<IoF32, PPV>(v, g, out, roots, bin_of_pos, B, L, H, rows, st);
     switch (pp) {
         SPECTRE_SLAB_CASE(4) SPECTRE_SLAB_CASE(8) SPECTRE_SLAB_CASE(16) SPECTRE_SLAB_CASE(32)
         default: return hipErrorInvalidValue;

@@ -129,10 +129,12 @@ def test_vit_config_full_size(oracle):
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
 @pytest.mark.parametrize("B,L,H", [(1, 11, 1), (2, 197, 3), (1, 1, 2), (1, 1000, 2), (1, 1031, 1), (2, 3000, 2),
-                                   (1, 12289, 1), (3, 640, 40), (1, 3 * 4096, 2)])
+                                   (1, 12289, 1), (3, 640, 40), (1, 3 * 4096, 2), (2, 1021, 2), (1, 509, 3),
+                                   (3, 257, 5), (16, 197, 12)])
 def test_any_other_length(oracle, B, L, H, io):
-    """Lengths with neither a power-of-two nor an in-LDS plan (primes, 197 = 14*14 patches + a class
-    token, 1000, 3*2^k): padded power-of-two convolution with a chirp-z evaluated kernel."""
+    """Lengths with neither a four-step nor an in-LDS plan (primes, 197 = 14*14 patches + a class token):
+    zero-padded convolution with a chirp-z evaluated kernel; padded lengths up to 2048 (L <= 1024: 11, 197, 257,
+    509, 1021) run the data pass in the in-LDS kernel, longer ones (1031, 3000, 12289) in the four-step kernels."""
     print(f"case B={B} L={L} H={H} io={io}", flush=True)
     got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 11 * L + H)
     err = rel_l2(got, want)
