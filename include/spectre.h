@@ -24,10 +24,13 @@
  *     from run to run.  A long spectre_mix_forward call runs every other head group
  *     on a helper stream of the library's own (default priority), forked from and
  *     joined back into `stream` with events: to the caller the call still behaves
- *     as work enqueued on `stream`, also under HIP graph capture.  Two environment
+ *     as work enqueued on `stream`, also under HIP graph capture.  Three environment
  *     variables exist for measurements: SPECTRE_ONE_LANE (any value) keeps every
  *     group on `stream`; SPECTRE_CHUNK_MB=<n> sets the total size of the transform
- *     scratch in flight (default 204, sized for the 256 MB memory-side cache).
+ *     scratch in flight (default 204, sized for the 256 MB memory-side cache);
+ *     SPECTRE_NO_FUSED (any value) sends n = 4096 through the three four-step kernels
+ *     instead of the single kernel it has of its own.  They are read at every call and
+ *     must not change between a *_workspace_bytes query and the call it sizes.
  *   - The caller owns every buffer, including the scratch workspace `ws`, whose
  *     minimum size the matching *_workspace_bytes function returns.  The library
  *     itself only keeps small per-device read-only tables (roots of unity) and a
