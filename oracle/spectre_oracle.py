@@ -17,8 +17,9 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "spectre_oracle.c")
-_LIB = os.path.join(_HERE, "libspectre_oracle.so")
+# The two variables let the planted-mistake test point a child test run at a deliberately wrong copy of the source.
+_SRC = os.environ.get("SPECTRE_ORACLE_SOURCE", os.path.join(_HERE, "spectre_oracle.c"))
+_LIB = os.environ.get("SPECTRE_ORACLE_LIBRARY", os.path.join(_HERE, "libspectre_oracle.so"))
 
 NAIVE = 0   # the O(n^2) sums exactly as printed
 FAST = 1    # radix-2 FFT (Bluestein for other lengths)
