@@ -1,4 +1,4 @@
-"""The pins must catch mistakes: thirty-one deliberately wrong copies of the oracle (a flipped sign, a dropped term,
+"""The pins must catch mistakes: thirty-five deliberately wrong copies of the oracle (a flipped sign, a dropped term,
 a wrong index, a transposed operand, ...) are compiled one by one and the pin files that cover the changed function are
 run against each copy in a child process; every copy has to fail at least one pin.  CPU only; the mistakes are planted
 in the oracle's source, nothing here touches the GPU path."""
@@ -137,6 +137,22 @@ MISTAKES = [
      'w[i] = (cur[2 * i] + cur[2 * i + 1]) / sqrt(2.0);',
      'w[i] = (cur[2 * i] + cur[2 * i + 1]) / 2.0;',
      ('tests/test_oracle_wrm.py',)),
+    ('Toeplitz taps applied mirrored',
+     'int src = k - m;',
+     'int src = k + m;',
+     ('tests/test_oracle_mixer_gate.py',)),
+    ('Toeplitz update without the identity term',
+     'cplx acc = raw[k];',
+     'cplx acc = { 0.0, 0.0 };',
+     ('tests/test_oracle_mixer_gate.py',)),
+    ('projection weights transposed',
+     'av += x[i] * wv[(size_t)i * d + j];',
+     'av += x[i] * wv[(size_t)j * d + i];',
+     ('tests/test_oracle_mixer_gate.py',)),
+    ('query pooled over the wrong axis stride',
+     'for (int l = 0; l < L; ++l) s += Q[(((size_t)b * L + l) * H + h) * d + c];',
+     'for (int l = 0; l < L; ++l) s += Q[(((size_t)b * L + l) * H + c % H) * d + c];',
+     ('tests/test_oracle_mixer_gate.py',)),
 ]
 
 
