@@ -383,7 +383,23 @@ __global__ __launch_bounds__(256) void k_readout_final_lazy(const float *__restr
     const float *ksrc = kpart + (size_t)bh * nchunks * 32 + p;
     float2 s = make_float2(0.f, 0.f);
     float ks = 0.f;
-    for (int c = grp; c < nchunks; c += 8) {
+    int c = grp;
+    for (; c + 56 < nchunks; c += 64) {          // eight loads of each kind in flight, added in the same order
+        float2 v[8];
+        float kv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            v[i] = src[(size_t)(c + 8 * i) * 32];
+            kv[i] = ksrc[(size_t)(c + 8 * i) * 32];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            s.x += v[i].x;
+            s.y += v[i].y;
+            ks += kv[i];
+        }
+    }
+    for (; c < nchunks; c += 8) {
         const float2 v = src[(size_t)c * 32];
         s.x += v.x;
         s.y += v.y;
@@ -406,10 +422,20 @@ __global__ __launch_bounds__(256) void k_readout_final_lazy(const float *__restr
             t.x += red[r][p].x;
             t.y += red[r][p].y;
         }
-        for (int i = 0; i < npend; ++i) {
-            const float2 dlt = *reinterpret_cast<const float2 *>(pending + ((size_t)i * BH + bh) * 64 + 2 * p);
-            t.x = fmaf(kred[0][i], dlt.x, t.x);
-            t.y = fmaf(kred[0][i], dlt.y, t.y);
+        for (int i0 = 0; i0 < npend; i0 += 8) {     // eight delta rows in flight
+            float2 dlt[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                dlt[i] = (i0 + i < npend)
+                             ? *reinterpret_cast<const float2 *>(pending + ((size_t)(i0 + i) * BH + bh) * 64 + 2 * p)
+                             : make_float2(0.f, 0.f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i0 + i < npend) {
+                    t.x = fmaf(kred[0][i0 + i], dlt[i].x, t.x);
+                    t.y = fmaf(kred[0][i0 + i], dlt[i].y, t.y);
+                }
+            }
         }
         out[(size_t)bh * 32 + p] = IO::pack(t);
     }
@@ -424,7 +450,18 @@ __global__ __launch_bounds__(256) void k_readout_final(const float *__restrict__
     const int p = threadIdx.x & 31, grp = threadIdx.x >> 5, bh = blockIdx.x;
     const float2 *src = reinterpret_cast<const float2 *>(partial + (size_t)bh * nchunks * 64) + p;
     float2 s = make_float2(0.f, 0.f);
-    for (int c = grp; c < nchunks; c += 8) {
+    int c = grp;
+    for (; c + 56 < nchunks; c += 64) {          // eight loads in flight, added in the same order
+        float2 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = src[(size_t)(c + 8 * i) * 32];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            s.x += v[i].x;
+            s.y += v[i].y;
+        }
+    }
+    for (; c < nchunks; c += 8) {
         const float2 v = src[(size_t)c * 32];
         s.x += v.x;
         s.y += v.y;
