@@ -442,7 +442,7 @@ hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev 
     const int M = (P.Hg == 1) ? B * H : B;
     const int ntiles = (2 * F + 63) / 64;
     const int gy = P.Hg == 1 ? 1 : H;
-    int gx = (1024 + gy - 1) / gy;                 // about 4 workgroups per compute unit in total
+    int gx = (4096 + gy - 1) / gy;                 // about 16 workgroups per compute unit in total (1024: 5 % slower)
     if (gx > (ntiles + 3) / 4) gx = (ntiles + 3) / 4;
     {   // shrink the grid to the smallest one with the same number of tiles per wave (no ragged last round)
         const int iters = (ntiles + 4 * gx - 1) / (4 * gx);
