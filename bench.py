@@ -371,6 +371,9 @@ def main():
                 "hbm_frac_vs_update_every_step": sweep_bytes / (ms_def * 1e-3) / 1e9 / HBM_PEAK_GBS}
             del cache
             torch.cuda.empty_cache()
+        # headline of the decode path as shipped: Alg. 1 with an update at every token (`tokens_per_s` above) and the
+        # same outputs with deferred updates
+        res["decode"]["tokens_per_s_deferred_cap16"] = res["decode_deferred"]["cap16"]["tokens_per_s"]
         del Pd
         torch.cuda.empty_cache()
         if not args.no_secondary:
