@@ -352,7 +352,14 @@ def main():
         res["decode"]["readout_window"] = {"ms": ms_win, "rows": N, "algorithmic_bytes": win_bytes,
                                            "hbm_frac": win_bytes / (ms_win * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                            "what": "full inverse of the gated cache, all 32768 live rows, fp32 (output allocated by the call)"}
-        del cache, Vp, Qp, gw
+        # Eq. 5 for 32 tokens appended at once (chunked prefill, speculative verification): one sweep over the cache
+        v32 = device_tokens((Bd, 32, Hd, dd), synth.BASE_SEED + 10, torch.float32)
+        q32 = device_tokens((Bd, 32, Hd, dd), synth.BASE_SEED + 11, torch.float32)
+        ms_app = time_loop(lambda: cache.update(v32, q32), 5, 1)
+        res["decode"]["append_32_tokens"] = {"ms": ms_app, "tokens_per_s": Bd * 32 / (ms_app * 1e-3),
+                                             "algorithmic_bytes": sweep_bytes,
+                                             "hbm_frac": sweep_bytes / (ms_app * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del cache, Vp, Qp, gw, v32, q32
         torch.cuda.empty_cache()
         # the same steps with deferred updates: the cache is only read, every `cap` steps one sweep applies the
         # pending rank-one updates (same outputs up to fp32 rounding; prefix_fft lags until the flush)

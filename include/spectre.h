@@ -273,6 +273,8 @@ int spectre_prefix_set_memory(spectre_prefix_cache *cache /*host*/, const float 
  *        s = N_mem + t mod N_max;  delta = v_t - [t >= N_max] v_buf[s];
  *        prefix_fft[k, :] += delta * exp(-j 2 pi ((k s) mod n)/n)   for every bin k;
  *        sum_q += q_t - [t >= N_max] q_buf[s];  v_buf[s] = v_t;  q_buf[s] = q_t;  t += 1.
+ *        The ring buffers and sum_q are updated token by token, in order; the cache itself takes the
+ *        rank-one terms of up to SPECTRE_MAX_PENDING tokens in one sweep (their sum, by linearity).
  * On success cache->t has advanced by T.
  */
 size_t spectre_prefix_update_workspace_bytes(const spectre_prefix_cache *cache /*host*/, int T,

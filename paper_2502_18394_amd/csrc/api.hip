@@ -752,7 +752,8 @@ size_t spectre_prefix_update_workspace_bytes(const spectre_prefix_cache *c, int 
     (void)io;
     if (!c || T < 1 || c->B < 1 || c->H < 1 || c->d < 2 || c->N_max < 1 || c->N_mem < 0) return 0;
     const int BH = c->B * c->H;
-    return align256((size_t)BH * c->d * sizeof(float)) + align256(gate_partial_bytes(c->B, T, c->H, c->d)) +
+    const int rows = T < kMaxPending ? T : kMaxPending;      // delta rows of one batch of appended tokens
+    return align256((size_t)rows * BH * c->d * sizeof(float)) + align256(gate_partial_bytes(c->B, T, c->H, c->d)) +
            scratch_bytes(BH, window_len(c), c->d);
 }
 
@@ -772,7 +773,7 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
     const int B = c->B, H = c->H, d = c->d, N = window_len(c), W = c->N_max, M0 = c->N_mem, BH = B * H, F = N / 2 + 1;
     char *w = static_cast<char *>(ws);
     float *delta = reinterpret_cast<float *>(w);
-    w += align256((size_t)BH * d * sizeof(float));
+    w += align256((size_t)(T < kMaxPending ? T : kMaxPending) * BH * d * sizeof(float));
     double *partial = reinterpret_cast<double *>(w);
     w += align256(gate_partial_bytes(B, T, H, d));
     float2 *scr = reinterpret_cast<float2 *>(w);
@@ -807,14 +808,33 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
         c->t = T;
         return SPECTRE_OK;
     }
-    for (int ti = 0; ti < T; ++ti) {
+    if (T == 1) {
         const int slot = M0 + (int)(c->t % W), evict = c->t >= W ? 1 : 0;
-        e = launch_ring_update((int)io, v_new, q_new, T, ti, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf),
+        e = launch_ring_update((int)io, v_new, q_new, T, 0, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf),
                                static_cast<double *>(c->sum_q), delta, B, H, d, N, slot, evict, st);
         if (e != hipSuccess) return fail_hip(e, "ring_update");
         e = launch_sweep(true, false, X, delta, static_cast<const float2 *>(c->twiddle), nullptr, nullptr, BH, F, N, slot, st);
         if (e != hipSuccess) return fail_hip(e, "sweep(update)");
         c->t += 1;
+        return SPECTRE_OK;
+    }
+    // several tokens: Eq. 5 is a sum of rank-one terms, so up to kMaxPending of them go into the cache in ONE sweep
+    // (the ring buffers are still updated token by token, in order: a ring shorter than the batch reuses its slots)
+    for (int t0 = 0; t0 < T; t0 += kMaxPending) {
+        const int nb = (T - t0 < kMaxPending) ? T - t0 : kMaxPending;
+        int slots[kMaxPending];
+        for (int i = 0; i < nb; ++i) {
+            const int slot = M0 + (int)(c->t % W), evict = c->t >= W ? 1 : 0;
+            slots[i] = slot;
+            e = launch_ring_update((int)io, v_new, q_new, T, t0 + i, static_cast<float *>(c->v_buf),
+                                   static_cast<float *>(c->q_buf), static_cast<double *>(c->sum_q),
+                                   delta + (size_t)i * BH * d, B, H, d, N, slot, evict, st);
+            if (e != hipSuccess) return fail_hip(e, "ring_update");
+            c->t += 1;
+        }
+        e = launch_sweep_lazy(true, false, X, delta, static_cast<const float2 *>(c->twiddle), nullptr, nullptr, nullptr, BH,
+                              F, N, 0, nb, slots, st);
+        if (e != hipSuccess) return fail_hip(e, "sweep(batch update)");
     }
     return SPECTRE_OK;
 }

@@ -63,6 +63,33 @@ def test_multi_token_append_equals_single_steps(oracle):
     _assert_state(c, oc, "after 1 + 299 tokens")
 
 
+@pytest.mark.parametrize("N,T0,appends,io", [
+    (512, 500, (2, 31, 32, 33, 64, 5), "f32"),      # batches of every size around the 32 tokens one sweep takes
+    (768, 700, (100, 7), "bf16"),                   # window length with an odd factor, wraps and evicts
+    (4096, 0, (1, 40, 3), "f32"),                   # from an empty cache: a single token first, then batches
+])
+def test_appends_of_several_tokens_go_in_with_one_sweep_per_32(oracle, N, T0, appends, io):
+    """Eq. 5 for T tokens at once (after the pre-fill): the library applies up to 32 rank-one terms per sweep over
+    the cache; the oracle applies them one by one."""
+    from paper_2502_18394_amd import binding
+    B, H, d = 2, 2, 64
+    print(f"case N={N} T0={T0} appends={appends} io={io}", flush=True)
+    c = binding.PrefixCache(B, H, d, N)
+    oc = oracle.PrefixCache(B, H, d, N)
+    if T0:
+        v, vs = synth.tokens(40, (B, T0, H, d), io)
+        q, qs = synth.tokens(41, (B, T0, H, d), io)
+        c.update(to_device(vs, io), to_device(qs, io))
+        oc.prefill(v.astype(np.float64), q.astype(np.float64))
+    for j, T in enumerate(appends):
+        v, vs = synth.tokens(42 + 2 * j, (B, T, H, d), io)
+        q, qs = synth.tokens(43 + 2 * j, (B, T, H, d), io)
+        c.update(to_device(vs, io), to_device(qs, io))
+        for i in range(T):
+            oc.update(v[:, i:i + 1].astype(np.float64), q[:, i:i + 1].astype(np.float64))
+        _assert_state(c, oc, f"after an append of {T}")
+
+
 @pytest.mark.parametrize("N,T,io", [(256, 90, "f32"), (256, 700, "f32"), (1024, 1024, "bf16"), (16384, 300, "f32"),
                                     (1280, 1500, "f32"), (7168, 7000, "bf16")])
 def test_readouts_match_oracle(oracle, N, T, io):
