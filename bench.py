@@ -359,7 +359,12 @@ def main():
         res["decode"]["append_32_tokens"] = {"ms": ms_app, "tokens_per_s": Bd * 32 / (ms_app * 1e-3),
                                              "algorithmic_bytes": sweep_bytes,
                                              "hbm_frac": sweep_bytes / (ms_app * 1e-3) / 1e9 / HBM_PEAK_GBS}
-        del cache, Vp, Qp, gw, v32, q32
+        # and for 4096 tokens at once: ring buffers brought up to date in one pass, window transformed afresh
+        v4k = device_tokens((Bd, 4096, Hd, dd), synth.BASE_SEED + 12, torch.float32)
+        q4k = device_tokens((Bd, 4096, Hd, dd), synth.BASE_SEED + 13, torch.float32)
+        ms_app4k = time_loop(lambda: cache.update(v4k, q4k), 3, 1)
+        res["decode"]["append_4096_tokens"] = {"ms": ms_app4k, "tokens_per_s": Bd * 4096 / (ms_app4k * 1e-3)}
+        del cache, Vp, Qp, gw, v32, q32, v4k, q4k
         torch.cuda.empty_cache()
         # the same steps with deferred updates: the cache is only read, every `cap` steps one sweep applies the
         # pending rank-one updates (same outputs up to fp32 rounding; prefix_fft lags until the flush)

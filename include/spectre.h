@@ -275,6 +275,8 @@ int spectre_prefix_set_memory(spectre_prefix_cache *cache /*host*/, const float 
  *        sum_q += q_t - [t >= N_max] q_buf[s];  v_buf[s] = v_t;  q_buf[s] = q_t;  t += 1.
  *        The ring buffers and sum_q are updated token by token, in order; the cache itself takes the
  *        rank-one terms of up to SPECTRE_MAX_PENDING tokens in one sweep (their sum, by linearity).
+ *        From 160 tokens on (and T <= N_max) the ring buffers are instead brought up to date in one
+ *        pass and the window is transformed afresh, as in the pre-fill: the same state, cheaper.
  * On success cache->t has advanced by T.
  */
 size_t spectre_prefix_update_workspace_bytes(const spectre_prefix_cache *cache /*host*/, int T,

@@ -187,6 +187,10 @@ int get_pow2_plan(int L, Pow2Plan *pl) {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Appends of at least this many tokens re-transform the window instead of sweeping the cache once per 32 tokens
+// (a sweep costs about a quarter of a window transform at the decode benchmark's shape).
+constexpr int kAppendRetransform = 160;
+
 // Scratch columns are processed in groups of heads small enough to stay in the memory-side
 // cache between the three kernels of a group.
 int mix_chunk_heads(int BH, int L, int d) {
@@ -816,6 +820,20 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
         e = launch_sweep(true, false, X, delta, static_cast<const float2 *>(c->twiddle), nullptr, nullptr, BH, F, N, slot, st);
         if (e != hipSuccess) return fail_hip(e, "sweep(update)");
         c->t += 1;
+        return SPECTRE_OK;
+    }
+    // many tokens (T up to the ring capacity): cheaper than T / 32 sweeps is to bring the ring buffers up to date in
+    // one pass and transform the window afresh, as the pre-fill does (the cache IS the transform of the window)
+    if (T >= kAppendRetransform && T <= W) {
+        const int s0 = (int)(c->t % W);
+        e = launch_ring_append((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), partial,
+                               B, T, H, N, M0, W, s0, c->t, st);
+        if (e != hipSuccess) return fail_hip(e, "ring_append");
+        e = launch_pool_final(partial, static_cast<double *>(c->sum_q), B, H * d, (T + kPoolRows - 1) / kPoolRows, st, true);
+        if (e != hipSuccess) return fail_hip(e, "pool_final(append)");
+        rc = transform_window(c, scr, st);
+        if (rc) return rc;
+        c->t += T;
         return SPECTRE_OK;
     }
     // several tokens: Eq. 5 is a sum of rank-one terms, so up to kMaxPending of them go into the cache in ONE sweep

@@ -24,7 +24,9 @@ hipError_t launch_pool(int io, const void *q, double *partial, double *sum_q, in
                        hipStream_t st);
 
 // sum [B][row] = sum over chunks of partial [B][nchunks][row], added in a fixed order in fp64.
-hipError_t launch_pool_final(const double *partial, double *sum, int B, int row, int nchunks, hipStream_t st);
+// sum[b][ch] = (accumulate ? sum[b][ch] : 0) + sum over chunks of partial[b][chunk][ch]
+hipError_t launch_pool_final(const double *partial, double *sum, int B, int row, int nchunks, hipStream_t st,
+                             bool accumulate = false);
 
 // g [B,H,F] from sum_q; hid is scratch [B,H,d_g]; raw is scratch [B,H,F] complex, only used when
 // P.toeplitz is set; phase already reduced modulo n_fft.

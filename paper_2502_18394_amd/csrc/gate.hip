@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void k_pool_partial_x16(const uint4 *__restric
 // pool, stage 2: sum_q[b][ch] = sum over chunks.  grid (row/32, B); 256 lanes = 32 channels x 8
 // chunk groups; group r adds chunks r, r+8, ... in order, the 8 group sums are then added in order.
 __global__ __launch_bounds__(256) void k_pool_final(const double *__restrict__ partial,
-                                                    double *__restrict__ sum_q, int row, int nchunks) {
+                                                    double *__restrict__ sum_q, int row, int nchunks, int accumulate) {
     __shared__ double red[8][32];
     const int lane = threadIdx.x & 31, grp = threadIdx.x >> 5;
     const int ch = blockIdx.x * 32 + lane, b = blockIdx.y;
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void k_pool_final(const double *__restrict__ p
         double t = red[0][lane];
 #pragma unroll
         for (int r = 1; r < 8; ++r) t += red[r][lane];
-        sum_q[(size_t)b * row + ch] = t;
+        sum_q[(size_t)b * row + ch] = accumulate ? sum_q[(size_t)b * row + ch] + t : t;
     }
 }
 
@@ -423,12 +423,13 @@ hipError_t launch_pool(int io, const void *q, double *partial, double *sum_q, in
                                                     reinterpret_cast<double2 *>(partial), L, ppr, kPoolRows, nchunks);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_pool_final<<<dim3((H * d + 31) / 32, B), 256, 0, st>>>(partial, sum_q, H * d, nchunks);
+    k_pool_final<<<dim3((H * d + 31) / 32, B), 256, 0, st>>>(partial, sum_q, H * d, nchunks, 0);
     return hipGetLastError();
 }
 
-hipError_t launch_pool_final(const double *partial, double *sum, int B, int row, int nchunks, hipStream_t st) {
-    k_pool_final<<<dim3((row + 31) / 32, B), 256, 0, st>>>(partial, sum, row, nchunks);
+hipError_t launch_pool_final(const double *partial, double *sum, int B, int row, int nchunks, hipStream_t st,
+                             bool accumulate) {
+    k_pool_final<<<dim3((row + 31) / 32, B), 256, 0, st>>>(partial, sum, row, nchunks, accumulate ? 1 : 0);
     return hipGetLastError();
 }
 

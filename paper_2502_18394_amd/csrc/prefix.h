@@ -24,6 +24,10 @@ hipError_t launch_sweep(bool update, bool read, float2 *X, const float *delta, c
 //   flush: apply all npend pending updates to X;  read: readout partials for the row `slot_new` with gate g;
 //   without flush the kappa partials kpart [BH][chunks][32] of the pending tokens are produced as well.
 constexpr int kMaxPending = 32;
+// Ring-buffer bookkeeping for T <= W tokens appended at once (token i -> slot (s0 + i) mod W behind M0 memory rows,
+// evicting when t0 + i >= W); partial [B][ceil(T/256)][H*64] doubles = per-chunk sums of q_new - q_evicted.
+hipError_t launch_ring_append(int io, const void *V, const void *Q, float *v_buf, float *q_buf, double *partial, int B,
+                              int T, int H, int N, int M0, int W, int s0, long long t0, hipStream_t st);
 hipError_t launch_sweep_lazy(bool flush, bool read, float2 *X, const float *pending, const float2 *tw, const float2 *g,
                              float *partial, float *kpart, int BH, int F, int N, int slot_new, int npend,
                              const int *slots, hipStream_t st);

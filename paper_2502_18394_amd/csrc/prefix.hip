@@ -507,6 +507,43 @@ __global__ __launch_bounds__(256) void k_fill_ring(const typename IO::pair_t *__
     q_buf[idx] = q;
 }
 
+// Many tokens appended to a cache that already holds some (T <= ring capacity W, so every slot is written at most
+// once): token i of the call goes to ring slot (s0 + i) mod W, evicting what was there when t0 + i >= W (Eq. 5's
+// ring-buffer bookkeeping for T tokens at once).  grid (ceil(T / 256), B*H); 256 lanes = 32 channel pairs x 8 row
+// lanes; partial[b][chunk][h*64 + c] = the chunk's sum of q_new - q_evicted in fp64 (added to sum_q afterwards).
+template <typename IO>
+__global__ __launch_bounds__(256) void k_ring_append(const typename IO::pair_t *__restrict__ V,
+                                                     const typename IO::pair_t *__restrict__ Q,
+                                                     float2 *__restrict__ v_buf, float2 *__restrict__ q_buf,
+                                                     double *__restrict__ partial, int T, int H, int N, int M0, int W,
+                                                     int s0, long long t0, int nchunks) {
+    __shared__ double red[8][64];
+    const int p = threadIdx.x & 31, rl = threadIdx.x >> 5;
+    const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % H, b = bh / H;
+    double sx = 0.0, sy = 0.0;
+    for (int i = chunk * 256 + rl; i < min(T, chunk * 256 + 256); i += 8) {
+        const int slot = (int)(((long long)s0 + i) % W);
+        const size_t ring = ((size_t)bh * N + M0 + slot) * 32 + p;
+        const size_t src = (((size_t)b * T + i) * H + h) * 32 + p;
+        const float2 vn = IO::unpack(V[src]), qn = IO::unpack(Q[src]);
+        float2 qo = make_float2(0.f, 0.f);
+        if (t0 + i >= W) qo = q_buf[ring];
+        sx += (double)qn.x - (double)qo.x;
+        sy += (double)qn.y - (double)qo.y;
+        v_buf[ring] = vn;
+        q_buf[ring] = qn;
+    }
+    red[rl][2 * p] = sx;
+    red[rl][2 * p + 1] = sy;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        double t = red[0][threadIdx.x];
+#pragma unroll
+        for (int r = 1; r < 8; ++r) t += red[r][threadIdx.x];
+        partial[((size_t)b * nchunks + chunk) * (H * 64) + h * 64 + threadIdx.x] = t;
+    }
+}
+
 // Memory rows (Sec. 3.4): v_buf[bh][m][c] = mem[b or 0][h][m][c], m < Nmem.  One lane per element.
 __global__ __launch_bounds__(256) void k_set_memory(const float *__restrict__ mem, float *__restrict__ v_buf, int H,
                                                     int N, int Nmem, int d, int per_batch, size_t total) {
@@ -687,6 +724,21 @@ hipError_t launch_fill_ring(int io, const void *V, const void *Q, float *v_buf, 
         k_fill_ring<IoF32><<<grid, 256, 0, st>>>(static_cast<const float2 *>(V), static_cast<const float2 *>(Q),
                                                  reinterpret_cast<float2 *>(v_buf), reinterpret_cast<float2 *>(q_buf),
                                                  T, H, N, row0, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_ring_append(int io, const void *V, const void *Q, float *v_buf, float *q_buf, double *partial, int B,
+                              int T, int H, int N, int M0, int W, int s0, long long t0, hipStream_t st) {
+    const int nchunks = (T + 255) / 256;
+    const dim3 grid(nchunks, B * H);
+    if (io)
+        k_ring_append<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(V), static_cast<const uint32_t *>(Q),
+                                                    reinterpret_cast<float2 *>(v_buf), reinterpret_cast<float2 *>(q_buf),
+                                                    partial, T, H, N, M0, W, s0, t0, nchunks);
+    else
+        k_ring_append<IoF32><<<grid, 256, 0, st>>>(static_cast<const float2 *>(V), static_cast<const float2 *>(Q),
+                                                   reinterpret_cast<float2 *>(v_buf), reinterpret_cast<float2 *>(q_buf),
+                                                   partial, T, H, N, M0, W, s0, t0, nchunks);
     return hipGetLastError();
 }
 

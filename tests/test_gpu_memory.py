@@ -57,7 +57,8 @@ def test_memory_cache_tracks_the_oracle(oracle, N_mem, N_max, T0, steps, io, sha
 
 @pytest.mark.parametrize("N_mem,N_max,T,io", [(16, 240, 90, "f32"), (16, 240, 700, "f32"), (64, 960, 960, "bf16"),
                                               (32, 16352, 300, "f32"),
-                                              (255, 1, 40, "f32")])    # 39 appended tokens that all hit the one ring slot
+                                              (255, 1, 40, "f32"),     # 39 appended tokens that all hit the one ring slot
+                                              (16, 240, 440, "f32")])   # 200 appended at once: window re-transformed
 def test_memory_readouts_match_oracle(oracle, N_mem, N_max, T, io):
     from paper_2502_18394_amd import binding
     B, H, d = 2, 3, 64

@@ -67,10 +67,14 @@ def test_multi_token_append_equals_single_steps(oracle):
     (512, 500, (2, 31, 32, 33, 64, 5), "f32"),      # batches of every size around the 32 tokens one sweep takes
     (768, 700, (100, 7), "bf16"),                   # window length with an odd factor, wraps and evicts
     (4096, 0, (1, 40, 3), "f32"),                   # from an empty cache: a single token first, then batches
+    (512, 500, (200, 512, 160, 3, 159), "f32"),     # 160 tokens or more: ring buffers in one pass, window re-transformed
+    (768, 100, (300, 768, 33), "bf16"),             # the same on a window with an odd factor, up to the ring capacity
+    (256, 200, (300,), "f32"),                      # more tokens than the ring holds: 32 per sweep again
 ])
 def test_appends_of_several_tokens_go_in_with_one_sweep_per_32(oracle, N, T0, appends, io):
     """Eq. 5 for T tokens at once (after the pre-fill): the library applies up to 32 rank-one terms per sweep over
-    the cache; the oracle applies them one by one."""
+    the cache, or, from 160 tokens on, updates the ring buffers in one pass and transforms the window afresh; the
+    oracle applies the tokens one by one."""
     from paper_2502_18394_amd import binding
     B, H, d = 2, 2, 64
     print(f"case N={N} T0={T0} appends={appends} io={io}", flush=True)
