@@ -575,10 +575,27 @@ __global__ __launch_bounds__(256) void k_untangle(const float2 *__restrict__ scr
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int F = N / 2 + 1;
-    const int p = (int)(idx % 32);
-    const size_t r = idx / 32;
-    const int k = (int)(r % F);
-    const int bhl = (int)(r / F);
+    // Lane order: a wave takes 8 pairs x 8 bins whose first-pass digit a differs (k1 = a N1/16 + m, a < 8 covers
+    // every bin below N/2): in the digit-reversed columns of the scratch those are 8 adjacent positions, so a wave
+    // reads 64-byte runs of 8 columns instead of 8 bytes of 64 columns; the Nyquist bins come last.
+    const int M = N1 / 16;
+    const size_t nbh = total / ((size_t)F * 32), main_total = nbh * (size_t)(N / 2) * 32;
+    int p, k, bhl;
+    if (idx < main_total) {
+        const int p_lo = (int)(idx & 7), a = (int)((idx >> 3) & 7), p_hi = (int)((idx >> 6) & 3);
+        size_t rest = idx >> 8;
+        const int m = (int)(rest % M);
+        rest /= M;
+        const int k2 = (int)(rest % N2);
+        bhl = (int)(rest / N2);
+        p = p_hi * 8 + p_lo;
+        k = k2 + N2 * (a * M + m);
+    } else {
+        const size_t j = idx - main_total;
+        p = (int)(j % 32);
+        bhl = (int)(j / 32);
+        k = N / 2;
+    }
     const float2 zk = scr[scratch_index(bhl, k, p, N1, N2, P)];
     const float2 zn = scr[scratch_index(bhl, (N - k) % N, p, N1, N2, P)];
     float4 o;
