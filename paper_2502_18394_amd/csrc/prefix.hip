@@ -615,10 +615,17 @@ __global__ __launch_bounds__(256) void k_tangle(const float4 *__restrict__ X, co
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int F = N / 2 + 1;
-    const int p = (int)(idx % 32);
-    const size_t r = idx / 32;
-    const int k = (int)(r % N);
-    const int bhl = (int)(r / N);
+    // Lane order as in k_untangle: a wave takes 4 pairs x the 16 bins k1 = a N1/16 + m, a = 0..15, which are 16
+    // adjacent positions (128 bytes) of each of the 4 scratch columns it writes.
+    const int M = N1 / 16;
+    const int p_lo = (int)(idx & 3), a = (int)((idx >> 2) & 15), p_hi = (int)((idx >> 6) & 7);
+    size_t rest = idx >> 9;
+    const int m = (int)(rest % M);
+    rest /= M;
+    const int k2 = (int)(rest % N2);
+    const int bhl = (int)(rest / N2);
+    const int p = p_hi * 4 + p_lo;
+    const int k = k2 + N2 * (a * M + m);
     const size_t bh = (size_t)(bh0 + bhl);
     const bool upper = 2 * k > N;
     const int ks = upper ? N - k : k;
