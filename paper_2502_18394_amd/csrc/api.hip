@@ -785,11 +785,13 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
     hipError_t e;
     if (c->t == 0 && T > 1) {
         if (T > W) return fail(SPECTRE_EINVAL, "prefix_update: prompt of %d tokens exceeds N_max=%d", T, W);
-        e = launch_fill_ring((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), B, T, H, N,
-                             M0, st);
-        if (e != hipSuccess) return fail_hip(e, "fill_ring");
-        e = launch_pool((int)io, q_new, partial, static_cast<double *>(c->sum_q), B, T, H, d, st);
-        if (e != hipSuccess) return fail_hip(e, "pool");
+        // the ring buffers are all zero on an empty cache (spectre_prefix_init): only the prompt's rows are written,
+        // and the same pass sums the queries
+        e = launch_ring_append((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), partial,
+                               B, T, H, N, M0, W, 0, 0, st);
+        if (e != hipSuccess) return fail_hip(e, "ring_append(prompt)");
+        e = launch_pool_final(partial, static_cast<double *>(c->sum_q), B, H * d, (T + kPoolRows - 1) / kPoolRows, st, false);
+        if (e != hipSuccess) return fail_hip(e, "pool_final(prompt)");
         if (M0 > 0) {                       // the window starts with the memory rows: transform the ring buffer itself
             rc = transform_window(c, scr, st);
             if (rc) return rc;

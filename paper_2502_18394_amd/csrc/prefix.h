@@ -35,10 +35,6 @@ hipError_t launch_readout_final_lazy(int io, const float *partial, const float *
                                      int BH, int F, int npend, hipStream_t st);
 // out [B,1,H,d] (io dtype) from the sweep's partial sums.
 hipError_t launch_readout_final(int io, const float *partial, void *out, int BH, int F, hipStream_t st);
-
-// Prompt rows into the ring buffers from row `row0` on (rows below it are kept), zero beyond the prompt.
-hipError_t launch_fill_ring(int io, const void *V, const void *Q, float *v_buf, float *q_buf, int B, int T, int H,
-                            int N, int row0, hipStream_t st);
 // Memory rows mem [mem_batch (1 or B), H, Nmem, 64] into rows 0..Nmem-1 of v_buf [B, H, N, 64].
 hipError_t launch_set_memory(const float *mem, int mem_batch, float *v_buf, int B, int H, int N, int Nmem,
                              hipStream_t st);

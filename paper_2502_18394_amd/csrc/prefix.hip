@@ -481,34 +481,8 @@ __global__ __launch_bounds__(256) void k_readout_final(const float *__restrict__
 
 // ------------------------------------------------------------------------------------------
 // pre-fill helpers.
-// Ring buffers from the prompt: v_buf[bh][row0 + l][c] = V[b][l][h][c] for l < T, 0 beyond; rows below
-// row0 (the persistent memory of Sec. 3.4) are left as they are.
-template <typename IO>
-__global__ __launch_bounds__(256) void k_fill_ring(const typename IO::pair_t *__restrict__ V,
-                                                   const typename IO::pair_t *__restrict__ Q,
-                                                   float2 *__restrict__ v_buf, float2 *__restrict__ q_buf, int T,
-                                                   int H, int N, int row0, size_t total) {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int p = (int)(idx % 32);
-    const size_t r = idx / 32;
-    const int l = (int)(r % N) - row0;
-    if (l < 0) return;
-    const size_t bh = r / N;
-    const int h = (int)(bh % H);
-    const size_t b = bh / H;
-    float2 v = make_float2(0.f, 0.f), q = v;
-    if (l < T) {
-        const size_t src = ((b * T + l) * H + h) * 32 + p;
-        v = IO::unpack(V[src]);
-        q = IO::unpack(Q[src]);
-    }
-    v_buf[idx] = v;
-    q_buf[idx] = q;
-}
-
-// Many tokens appended to a cache that already holds some (T <= ring capacity W, so every slot is written at most
-// once): token i of the call goes to ring slot (s0 + i) mod W, evicting what was there when t0 + i >= W (Eq. 5's
+// Many tokens appended at once - the prompt on an empty cache (whose ring buffers are all zero), or a long append to
+// a cache that already holds some (T <= ring capacity W, so every slot is written at most once): token i of the call goes to ring slot (s0 + i) mod W, evicting what was there when t0 + i >= W (Eq. 5's
 // ring-buffer bookkeeping for T tokens at once).  grid (ceil(T / 256), B*H); 256 lanes = 32 channel pairs x 8 row
 // lanes; partial[b][chunk][h*64 + c] = the chunk's sum of q_new - q_evicted in fp64 (added to sum_q afterwards).
 template <typename IO>
@@ -521,17 +495,31 @@ __global__ __launch_bounds__(256) void k_ring_append(const typename IO::pair_t *
     const int p = threadIdx.x & 31, rl = threadIdx.x >> 5;
     const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % H, b = bh / H;
     double sx = 0.0, sy = 0.0;
-    for (int i = chunk * 256 + rl; i < min(T, chunk * 256 + 256); i += 8) {
-        const int slot = (int)(((long long)s0 + i) % W);
-        const size_t ring = ((size_t)bh * N + M0 + slot) * 32 + p;
-        const size_t src = (((size_t)b * T + i) * H + h) * 32 + p;
-        const float2 vn = IO::unpack(V[src]), qn = IO::unpack(Q[src]);
-        float2 qo = make_float2(0.f, 0.f);
-        if (t0 + i >= W) qo = q_buf[ring];
-        sx += (double)qn.x - (double)qo.x;
-        sy += (double)qn.y - (double)qo.y;
-        v_buf[ring] = vn;
-        q_buf[ring] = qn;
+    const int i_end = min(T, chunk * 256 + 256);
+    for (int i0 = chunk * 256 + rl; i0 < i_end; i0 += 64) {          // eight rows per trip, their loads up front
+        typename IO::pair_t rv[8], rq[8];
+        float2 qo[8];
+        size_t ring[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = min(i0 + 8 * u, i_end - 1);               // clamped: rows past the end are not stored
+            const int slot = (int)(((long long)s0 + i) % W);
+            ring[u] = ((size_t)bh * N + M0 + slot) * 32 + p;
+            const size_t src = (((size_t)b * T + i) * H + h) * 32 + p;
+            rv[u] = V[src];
+            rq[u] = Q[src];
+            qo[u] = (t0 + i >= W) ? q_buf[ring[u]] : make_float2(0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (i0 + 8 * u < i_end) {
+                const float2 vn = IO::unpack(rv[u]), qn = IO::unpack(rq[u]);
+                sx += (double)qn.x - (double)qo[u].x;
+                sy += (double)qn.y - (double)qo[u].y;
+                v_buf[ring[u]] = vn;
+                q_buf[ring[u]] = qn;
+            }
+        }
     }
     red[rl][2 * p] = sx;
     red[rl][2 * p + 1] = sy;
@@ -733,21 +721,6 @@ hipError_t launch_set_memory(const float *mem, int mem_batch, float *v_buf, int 
     const size_t total = (size_t)B * H * Nmem * 64;
     k_set_memory<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(mem, v_buf, H, N, Nmem, 64, mem_batch == B ? 1 : 0,
                                                                   total);
-    return hipGetLastError();
-}
-
-hipError_t launch_fill_ring(int io, const void *V, const void *Q, float *v_buf, float *q_buf, int B, int T, int H,
-                            int N, int row0, hipStream_t st) {
-    const size_t total = (size_t)B * H * N * 32;
-    const unsigned grid = (unsigned)((total + 255) / 256);
-    if (io)
-        k_fill_ring<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(V), static_cast<const uint32_t *>(Q),
-                                                  reinterpret_cast<float2 *>(v_buf),
-                                                  reinterpret_cast<float2 *>(q_buf), T, H, N, row0, total);
-    else
-        k_fill_ring<IoF32><<<grid, 256, 0, st>>>(static_cast<const float2 *>(V), static_cast<const float2 *>(Q),
-                                                 reinterpret_cast<float2 *>(v_buf), reinterpret_cast<float2 *>(q_buf),
-                                                 T, H, N, row0, total);
     return hipGetLastError();
 }
 
