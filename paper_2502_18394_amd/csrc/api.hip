@@ -792,7 +792,9 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
         if (e != hipSuccess) return fail_hip(e, "ring_append(prompt)");
         e = launch_pool_final(partial, static_cast<double *>(c->sum_q), B, H * d, (T + kPoolRows - 1) / kPoolRows, st, false);
         if (e != hipSuccess) return fail_hip(e, "pool_final(prompt)");
-        if (M0 > 0) {                       // the window starts with the memory rows: transform the ring buffer itself
+        // with memory rows the window starts with them, and a prompt that fills most of the ring is read faster from
+        // the ring buffers just written (whole contiguous rows per head) than from the token tensor: transform the window
+        if (M0 > 0 || 2 * T >= W) {
             rc = transform_window(c, scr, st);
             if (rc) return rc;
             c->t = T;
