@@ -229,8 +229,9 @@ template <bool VEC, int RG>   // VEC: d_g % 4 == 0 and 16-byte aligned rows; RG:
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RG <= 2 ? 4 : 2))) void k_gate_out(const float *__restrict__ hid, const float *__restrict__ W2,
                                                   const float *__restrict__ b2,
                                                   const float *__restrict__ mbias, float2 *__restrict__ g,
-                                                  int B, int H, int Hg, int dg, int F, int r_base) {
-    extern __shared__ float hs[];                    // [4*RG][dgs] hidden rows of this pass, zero padded
+                                                  int B, int H, int Hg, int dg, int F, int r_base0) {
+    extern __shared__ float hs[];
+    const int r_base = r_base0 + 32 * (int)blockIdx.z;   // blockIdx.z: 32-row tile of the rows (sequences)                    // [4*RG][dgs] hidden rows of this pass, zero padded
     const int dgp = (dg + 3) & ~3, dgs = dgp + 4;    // row stride padded against bank conflicts
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int twoF = 2 * F;
@@ -455,22 +456,29 @@ hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev 
     // with the Toeplitz update the MLP output goes to `raw` un-activated and a second pass finishes it
     const float *out_bias = P.toeplitz ? nullptr : P.modrelu_bias;
     float2 *out_g = P.toeplitz ? raw : g;
-    for (int r_base = 0; r_base < M; r_base += 32) {
-        const int rows = (M - r_base < 32) ? M - r_base : 32;
-        const int rg = (rows + 3) / 4;            // 1..8 row groups in this pass
+    {
+        // every 32-row tile of the rows in one launch (grid.z); a single tile takes the narrowest kernel that fits
+        const int ntile = (M + 31) / 32;
+        const int rows = (ntile > 1) ? 32 : M;
+        const int rg = (rows + 3) / 4;            // 1..8 row groups per tile
         const size_t lds = ((size_t)4 * (rg <= 1 ? 1 : rg <= 2 ? 2 : rg <= 4 ? 4 : 8) * (dgp + 4) +
                             4 * 64 * ((vec && P.d_g == 64) ? kHalfStride : kTileStride)) * sizeof(float);
-#define SPECTRE_GATE_OUT(V, R) k_gate_out<V, R><<<grid, 256, lds, st>>>(hid, P.W2, P.b2, out_bias, out_g, B, H, P.Hg, P.d_g, F, r_base)
-        if (vec) {
-            if (rg <= 1) SPECTRE_GATE_OUT(true, 1); else if (rg <= 2) SPECTRE_GATE_OUT(true, 2);
-            else if (rg <= 4) SPECTRE_GATE_OUT(true, 4); else SPECTRE_GATE_OUT(true, 8);
-        } else {
-            if (rg <= 1) SPECTRE_GATE_OUT(false, 1); else if (rg <= 2) SPECTRE_GATE_OUT(false, 2);
-            else if (rg <= 4) SPECTRE_GATE_OUT(false, 4); else SPECTRE_GATE_OUT(false, 8);
-        }
+        for (int z0 = 0; z0 < ntile; z0 += 65535) {
+            const int nz = (ntile - z0 < 65535) ? ntile - z0 : 65535;
+            const dim3 grid3(grid.x, grid.y, nz);
+            const int r_base = 32 * z0;
+#define SPECTRE_GATE_OUT(V, R) k_gate_out<V, R><<<grid3, 256, lds, st>>>(hid, P.W2, P.b2, out_bias, out_g, B, H, P.Hg, P.d_g, F, r_base)
+            if (vec) {
+                if (rg <= 1) SPECTRE_GATE_OUT(true, 1); else if (rg <= 2) SPECTRE_GATE_OUT(true, 2);
+                else if (rg <= 4) SPECTRE_GATE_OUT(true, 4); else SPECTRE_GATE_OUT(true, 8);
+            } else {
+                if (rg <= 1) SPECTRE_GATE_OUT(false, 1); else if (rg <= 2) SPECTRE_GATE_OUT(false, 2);
+                else if (rg <= 4) SPECTRE_GATE_OUT(false, 4); else SPECTRE_GATE_OUT(false, 8);
+            }
 #undef SPECTRE_GATE_OUT
-        hipError_t e2 = hipGetLastError();
-        if (e2 != hipSuccess) return e2;
+            hipError_t e2 = hipGetLastError();
+            if (e2 != hipSuccess) return e2;
+        }
     }
     const size_t total = (size_t)B * H * F;
     if (P.toeplitz) {
