@@ -790,7 +790,7 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
         e = launch_ring_append((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), partial,
                                B, T, H, N, M0, W, 0, 0, st);
         if (e != hipSuccess) return fail_hip(e, "ring_append(prompt)");
-        e = launch_pool_final(partial, static_cast<double *>(c->sum_q), B, H * d, (T + kPoolRows - 1) / kPoolRows, st, false);
+        e = launch_pool_final(partial, static_cast<double *>(c->sum_q), B, H * d, (T + 255) / 256, st, false);
         if (e != hipSuccess) return fail_hip(e, "pool_final(prompt)");
         // with memory rows the window starts with them, and a prompt that fills most of the ring is read faster from
         // the ring buffers just written (whole contiguous rows per head) than from the token tensor: transform the window
@@ -833,7 +833,7 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
         e = launch_ring_append((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), partial,
                                B, T, H, N, M0, W, s0, c->t, st);
         if (e != hipSuccess) return fail_hip(e, "ring_append");
-        e = launch_pool_final(partial, static_cast<double *>(c->sum_q), B, H * d, (T + kPoolRows - 1) / kPoolRows, st, true);
+        e = launch_pool_final(partial, static_cast<double *>(c->sum_q), B, H * d, (T + 255) / 256, st, true);
         if (e != hipSuccess) return fail_hip(e, "pool_final(append)");
         rc = transform_window(c, scr, st);
         if (rc) return rc;

@@ -399,29 +399,40 @@ __global__ __launch_bounds__(256) void k_gate_phase(float2 *__restrict__ g, int 
 }
 
 // ------------------------------------------------------------------------------------------
+// Rows summed by one workgroup of the pooling pass: kPoolRows, halved (down to 16) while the pass would launch
+// fewer than about two workgroups per compute unit (short sequences: 8192 rows of 32 heads are only 32 chunks of 256).
+static int pool_rows(int B, int L, int H, int d) {
+    const long long wide = ((long long)H * d / 8 + 255) / 256;       // workgroups across a row with 16-byte lanes
+    int rows = kPoolRows;
+    while (rows > 16 && (long long)B * ((L + rows - 1) / rows) * wide < 512) rows /= 2;
+    return rows;
+}
+
 size_t gate_partial_bytes(int B, int L, int H, int d) {
-    const int nchunks = (L + kPoolRows - 1) / kPoolRows;
+    const int rows = pool_rows(B, L, H, d);
+    const int nchunks = (L + rows - 1) / rows;
     return (size_t)B * nchunks * H * d * sizeof(double);
 }
 
 hipError_t launch_pool(int io, const void *q, double *partial, double *sum_q, int B, int L, int H, int d,
                        hipStream_t st) {
     const int ppr = H * d / 2;
-    const int nchunks = (L + kPoolRows - 1) / kPoolRows;
+    const int rows = pool_rows(B, L, H, d);
+    const int nchunks = (L + rows - 1) / rows;
     dim3 grid((ppr + 255) / 256, nchunks, B);
     const bool aligned = (reinterpret_cast<uintptr_t>(q) & 15) == 0;
     if (io && ppr % 4 == 0 && aligned)
         k_pool_partial_x16<true><<<dim3((ppr / 4 + 255) / 256, nchunks, B), 256, 0, st>>>(
-            static_cast<const uint4 *>(q), partial, L, ppr / 4, kPoolRows, nchunks);
+            static_cast<const uint4 *>(q), partial, L, ppr / 4, rows, nchunks);
     else if (!io && ppr % 2 == 0 && aligned)
         k_pool_partial_x16<false><<<dim3((ppr / 2 + 255) / 256, nchunks, B), 256, 0, st>>>(
-            static_cast<const uint4 *>(q), partial, L, ppr / 2, kPoolRows, nchunks);
+            static_cast<const uint4 *>(q), partial, L, ppr / 2, rows, nchunks);
     else if (io)
         k_pool_partial<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(q),
-                                                     reinterpret_cast<double2 *>(partial), L, ppr, kPoolRows, nchunks);
+                                                     reinterpret_cast<double2 *>(partial), L, ppr, rows, nchunks);
     else
         k_pool_partial<IoF32><<<grid, 256, 0, st>>>(static_cast<const float2 *>(q),
-                                                    reinterpret_cast<double2 *>(partial), L, ppr, kPoolRows, nchunks);
+                                                    reinterpret_cast<double2 *>(partial), L, ppr, rows, nchunks);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     k_pool_final<<<dim3((H * d + 31) / 32, B), 256, 0, st>>>(partial, sum_q, H * d, nchunks, 0);
