@@ -230,7 +230,7 @@ extern "C" {
 
 const char *spectre_last_error(void) { return g_err.c_str(); }
 
-int spectre_version(void) { return 110; }
+int spectre_version(void) { return 120; }
 
 // 0 = no kernel, 1 = whole slab in LDS, 2 = four-step power-of-two path, 3 = any other length
 // through a padded power-of-two convolution, 4 = four-step path fused into one kernel (L = 4096).
