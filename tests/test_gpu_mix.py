@@ -175,3 +175,27 @@ def test_unsupported_lengths_are_refused():
         binding.mix_forward(v, g)
     assert e.value.code == binding.EUNSUPPORTED
     assert not binding.length_supported(3 * 131072, 64) and binding.length_supported(196, 64)
+
+
+def _route_boundary_cases():
+    """Seeded draw of shapes around the points where the mixer changes kernels: the in-LDS limit (2048), the
+    one-kernel length (4096), four-step lengths and their neighbours, head counts around multiples of eight."""
+    rng = np.random.default_rng(synth.BASE_SEED + 900)
+    anchors = [2048, 4096, 8192, 1024, 512, 256, 3 * 256, 5 * 256, 7 * 256, 3 * 4096 // 4, 196, 1000]
+    cases = []
+    for i in range(24):
+        a = int(anchors[i % len(anchors)])
+        L = max(1, a + int(rng.integers(-2, 3)))
+        B = int(rng.integers(1, 4))
+        H = int(rng.choice([1, 2, 3, 5, 7, 8, 9, 16, 17]))
+        cases.append((B, L, H, "bf16" if rng.integers(0, 2) else "f32"))
+    return cases
+
+
+@pytest.mark.parametrize("B,L,H,io", _route_boundary_cases())
+def test_shapes_around_the_route_boundaries(oracle, B, L, H, io):
+    print(f"case B={B} L={L} H={H} io={io}", flush=True)
+    got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 17 * L + H + B)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL[io]
