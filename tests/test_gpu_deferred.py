@@ -103,3 +103,75 @@ def test_deferred_argument_checks():
     with pytest.raises(binding.SpectreError) as e:
         c.flush()
     assert e.value.code == binding.EINVAL
+
+
+@pytest.mark.parametrize("seed,N_mem,N_max,defer", [(0, 0, 256, 0), (1, 0, 256, 16), (2, 16, 240, 5), (3, 0, 768, 32),
+                                                     (4, 32, 480, 16), (5, 0, 512, 7)])
+def test_random_sequences_of_operations_track_the_oracle(oracle, seed, N_mem, N_max, defer):
+    """A seeded mix of everything the cache can be asked to do - fused steps (eager or deferred), appends of 1 to
+    N_max tokens (one sweep per token, 32 per sweep, window re-transformed), explicit flushes, both readouts - with
+    the oracle applying Eq. 5 token by token beside it; state and outputs are compared after every operation."""
+    from paper_2502_18394_amd import binding
+    B, H, d = 2, 2, 64
+    n = N_mem + N_max
+    rng = np.random.default_rng(700 + seed)
+    c = binding.PrefixCache(B, H, d, N_max, N_mem=N_mem, defer=defer)
+    oc = oracle.MemoryPrefixCache(B, H, d, N_mem, N_max)
+    M = rng.standard_normal((B, H, N_mem, d)).astype(np.float32)
+    if N_mem:
+        c.set_memory(torch.from_numpy(M).cuda())
+    oc.prefill(M.astype(np.float64))
+    p = synth.gate_params(710 + seed, H, d, n)
+    P = binding.GateParams(p)
+
+    def tokens(T):
+        v = rng.standard_normal((B, T, H, d)).astype(np.float32)
+        q = rng.standard_normal((B, T, H, d)).astype(np.float32)
+        return v, q
+
+    def check_state(tag):
+        c.flush()
+        torch.cuda.synchronize()
+        spec = rel_l2(c.prefix_fft.cpu().numpy(), oc.spec)
+        sq = rel_l2(c.sum_q.cpu().numpy(), oc.sum_q)
+        assert c.t == oc.t and spec <= 1e-5 and sq <= 1e-12, (tag, c.t, oc.t, spec, sq)
+        assert np.array_equal(c.v_buf.cpu().numpy(), oc.v_buf.astype(np.float32)), tag
+
+    sizes = [1, 2, 7, 31, 32, 33, 70, 160, 200, N_max]
+    log = []
+    for i in range(40):
+        op = rng.choice(["step", "step", "step", "append", "flush", "newest", "window"])
+        if oc.t == 0 and op in ("newest", "window"):
+            op = "step"
+        log.append(op)
+        if op == "step":
+            v, q = tokens(1)
+            out = c.step(torch.from_numpy(v).cuda(), torch.from_numpy(q).cuda(), P)
+            oc.update(v.astype(np.float64), q.astype(np.float64))
+            want = oc.readout_newest(oracle.gate(oc.sum_q, 1.0 / N_max, f64(p), n, 0))
+            assert rel_l2(from_device(out), want) <= 1e-5, (i, log)
+        elif op == "append":
+            T = int(rng.choice(sizes))
+            v, q = tokens(T)
+            c.update(torch.from_numpy(v).cuda(), torch.from_numpy(q).cuda())
+            for j in range(T):                  # also where the library pre-fills: the two are the same state
+                oc.update(v[:, j:j + 1].astype(np.float64), q[:, j:j + 1].astype(np.float64))
+            log[-1] = f"append{T}"
+            check_state((i, log))
+        elif op == "flush":
+            check_state((i, log))
+        else:
+            c.flush()
+            g = synth.random_gate(720 + i, B, H, n)
+            mode = binding.READ_NEWEST if op == "newest" else binding.READ_WINDOW
+            got = from_device(c.readout(torch.from_numpy(g).cuda(), mode))
+            if op == "newest":
+                want = oc.readout_newest(g.astype(np.complex128))
+            elif N_mem:
+                want = oc.readout_window(g.astype(np.complex128))          # live ring slots, oldest first
+            else:                                                          # plain cache: the last L' rows of the inverse
+                Lw = min(oc.t, N_max)
+                want = np.stack([oc.readout_row(g.astype(np.complex128), m) for m in range(n - Lw, n)], axis=1)
+            assert got.shape == want.shape and rel_l2(got, want) <= 1e-5, (i, log)
+    check_state(("end", log))
+    print(f"  operations: {' '.join(log)}", flush=True)
