@@ -113,3 +113,29 @@ def test_gate_with_toeplitz_update(oracle, B, L, H, r, shared, modrelu):
     p_plain = {k: v for k, v in p64.items() if k != "toeplitz"}
     plain = oracle.gate(oracle.pool_q(vals.astype(np.float64)), 1.0 / L, p_plain, L, 5 if r == 2 else 0)
     assert rel_l2(want, plain) > 1e-3
+
+
+def _seeded_gate_cases():
+    rng = np.random.default_rng(synth.BASE_SEED + 950)
+    cases = []
+    for _ in range(14):
+        B = int(rng.integers(1, 70))
+        H = int(rng.integers(1, 6))
+        L = int(rng.integers(1, 700))
+        d = 2 * int(rng.integers(1, 129))                     # 2 .. 256, even
+        dg = int(rng.integers(1, 257))
+        n = int(rng.integers(2, 3000))                        # transform length of the gate (even or odd)
+        cases.append((B, L, H, d, dg, n, "bf16" if rng.integers(0, 2) else "f32", bool(rng.integers(0, 2)),
+                      bool(rng.integers(0, 2)), int(rng.integers(0, 5000)) if rng.integers(0, 2) else 0))
+    return cases
+
+
+@pytest.mark.parametrize("B,L,H,d,dg,n,io,shared,modrelu,phase", _seeded_gate_cases())
+def test_gate_seeded_shapes(oracle, B, L, H, d, dg, n, io, shared, modrelu, phase):
+    """Channel counts, hidden widths, row counts and transform lengths drawn at random (seeded): every tiling tail of
+    the pooling, hidden and output kernels."""
+    print(f"case B={B} L={L} H={H} d={d} dg={dg} n={n} io={io} shared={shared} modrelu={modrelu} phase={phase}", flush=True)
+    got, want = run_gate(oracle, B, L, H, d, dg, n, io, shared=shared, modrelu=modrelu, phase=phase, seed=960 + B + L)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= 1e-5
