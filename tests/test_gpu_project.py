@@ -37,6 +37,18 @@ def test_project_matches_oracle(oracle, B, L, H, io, shared, want_q):
         assert q is None
 
 
+def _seeded_project_cases():
+    rng = np.random.default_rng(synth.BASE_SEED + 980)
+    return [(int(rng.integers(1, 4)), int(rng.integers(1, 3000)), int(rng.integers(1, 9)),
+             "bf16" if rng.integers(0, 2) else "f32", bool(rng.integers(0, 2)), bool(rng.integers(0, 2)))
+            for _ in range(10)]
+
+
+@pytest.mark.parametrize("B,L,H,io,shared,want_q", _seeded_project_cases())
+def test_project_seeded_shapes(oracle, B, L, H, io, shared, want_q):
+    test_project_matches_oracle(oracle, B, L, H, io, shared, want_q)
+
+
 def test_projection_feeds_gate_and_mixer(oracle):
     """x -> (V, sum_q) -> gate -> mixer equals the oracle's project -> pool -> gate -> mix."""
     from gpu_util import f64

@@ -53,6 +53,23 @@ def test_wrm_tile_sums_agree_whatever_the_alignment(io):
     assert torch.equal(a.view(torch.int16 if io == "bf16" else torch.int32), b.view(torch.int16 if io == "bf16" else torch.int32))
 
 
+def _seeded_wrm_cases():
+    rng = np.random.default_rng(synth.BASE_SEED + 970)
+    cases = []
+    for _ in range(12):
+        J = int(rng.integers(0, 13))
+        L = (1 << J) * int(rng.integers(1, 9)) * int(rng.choice([1, 1, 3, 5]))     # 2^J divides L
+        if L > 40000:
+            L = 1 << J
+        cases.append((int(rng.integers(1, 4)), L, int(rng.integers(1, 5)), J, "bf16" if rng.integers(0, 2) else "f32"))
+    return cases
+
+
+@pytest.mark.parametrize("B,L,H,J,io", _seeded_wrm_cases())
+def test_wrm_apply_seeded_shapes(oracle, B, L, H, J, io):
+    test_wrm_apply_matches_oracle(oracle, B, L, H, J, io)
+
+
 def test_wrm_special_gates_and_in_place(oracle):
     from paper_2502_18394_amd import binding
     B, L, H, J = 1, 2048, 2, 11
