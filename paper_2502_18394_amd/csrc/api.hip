@@ -416,6 +416,9 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
     int chunk = 0;
     const int lanes = mix_lanes(BH, L, d, &chunk);
     const size_t lane_bytes = align256((size_t)chunk * L * (d / 2) * sizeof(float2));
+    // opt-in, bf16 rows only: complex numbers cross between the three kernels as two bfloat16 instead of two fp32
+    const bool scr16 = (io == SPECTRE_BF16) && getenv("SPECTRE_SCRATCH_BF16") != nullptr;
+    if (scr16 && chunk < BH) chunk *= 2;               // twice the heads fit in a lane's scratch
     SideLane *side = nullptr;
     int dev = 0;
     if (lanes == 2) {
@@ -436,11 +439,11 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         const int lane = (lanes == 2) ? (group & 1) : 0;
         hipStream_t ls = lane ? side->stream : st;
         float2 *scr = reinterpret_cast<float2 *>(scr_base + (size_t)lane * lane_bytes);
-        e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, ls);
+        e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, ls, scr16);
         if (e != hipSuccess) { what = "small_fwd"; break; }
-        e = launch_big(pl, scr, gp, bh0, nbh, 0, ls);
+        e = launch_big(pl, scr, gp, bh0, nbh, 0, ls, false, scr16);
         if (e != hipSuccess) { what = "big"; break; }
-        e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls);
+        e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls, 0, 0, 0, scr16);
         if (e != hipSuccess) { what = "small_inv"; break; }
     }
     if (lanes == 2) {

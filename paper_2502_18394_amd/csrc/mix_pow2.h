@@ -32,13 +32,15 @@ bool pow2_split(int L, int *N1, int *N2, int *P);
 //               out (tensor [B, out_rows, H, d]); with ring_w > 0 instead the out_rows newest
 //               entries, oldest first, of a ring buffer in rows ring0 .. ring0+ring_w-1 whose
 //               newest entry is row ring0+newest
+// scr16 (bf16 rows, big: mode 0 only): the scratch holds each complex number as two bfloat16 in one 32-bit word at
+// the same element index (the buffer is used to half its size); all three kernels of a pass must agree on it.
 hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
-                            int bh0, int nbh, hipStream_t st);
+                            int bh0, int nbh, hipStream_t st, bool scr16 = false);
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
-                      hipStream_t st, bool shared_gate = false);
+                      hipStream_t st, bool shared_gate = false, bool scr16 = false);
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
                             int out_rows, int H, int bh0, int nbh, hipStream_t st, int ring0 = 0, int ring_w = 0,
-                            int newest = 0);
+                            int newest = 0, bool scr16 = false);
 // g [BH, L/2+1] -> gp [BH][N2][N1] in the big kernel's register order, scaled by 1/L and
 // extended to all L bins by Hermitian symmetry (real parts only at DC and Nyquist).
 hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st);

@@ -27,12 +27,26 @@ template <> struct TileStride<IoBf16> { static constexpr int value = 36; };
 template <> struct TileStride<IoF32> { static constexpr int value = 34; };
 
 // ------------------------------------------------------------------------------------------
+// Element of the transform scratch: one complex number per channel pair, as two fp32 (the default) or, on request
+// for bf16 rows, as two bfloat16 in a 32-bit word (half the bytes of every exchange between the three kernels;
+// the arithmetic stays fp32).
+struct ScrF32 {
+    typedef float2 elem_t;
+    __device__ static __forceinline__ float2 get(elem_t e) { return e; }
+    __device__ static __forceinline__ elem_t put(float2 v) { return v; }
+};
+struct ScrBf16 {
+    typedef uint32_t elem_t;
+    __device__ static __forceinline__ float2 get(elem_t e) { return IoBf16::unpack(e); }
+    __device__ static __forceinline__ elem_t put(float2 v) { return IoBf16::pack(v); }
+};
+
 // small_fwd: grid (N1/TT, nbh); block 32*TT threads.  Reads the N2*TT rows
 // {t1_0 + r + N1*t2} of one head (32 pairs each, one 128 B / 256 B segment per row),
 // stages them in LDS, then lane (pair p, t1_local) runs the N2-point DFT over t2.
-template <int N2, int TT, typename IO>
+template <int N2, int TT, typename IO, typename SC>
 __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t *__restrict__ v,
-                                                       float2 *__restrict__ scr,
+                                                       typename SC::elem_t *__restrict__ scr,
                                                        const float2 *__restrict__ twL, int rows, int H,
                                                        int N1, int bh0) {
     typedef typename IO::pair_t pair_t;
@@ -59,11 +73,11 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
 #pragma unroll
     for (int t2 = 0; t2 < N2; ++t2) x[t2] = IO::unpack(lds[(t2 * TT + tl) * S + p]);
     small_dft<N2, false>(x);
-    float2 *dst = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
+    typename SC::elem_t *dst = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
 #pragma unroll
     for (int k2 = 0; k2 < N2; ++k2) {
         const float2 y = (k2 == 0) ? x[0] : cmul(x[k2], twL[t1 * k2]);
-        dst[(size_t)k2 * 32 * N1] = y;
+        dst[(size_t)k2 * 32 * N1] = SC::put(y);
     }
 }
 
@@ -71,8 +85,8 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
 // are written to row l-row0 of out [B, out_rows, H, d].  With ring_w > 0 the rows are instead
 // gathered from a ring buffer that occupies rows ring0 .. ring0+ring_w-1 and whose newest entry
 // sits at ring0+newest: the out_rows newest entries are written oldest first.
-template <int N2, int TT, typename IO>
-__global__ __launch_bounds__(32 * TT) void k_small_inv(const float2 *__restrict__ scr,
+template <int N2, int TT, typename IO, typename SC>
+__global__ __launch_bounds__(32 * TT) void k_small_inv(const typename SC::elem_t *__restrict__ scr,
                                                        typename IO::pair_t *__restrict__ out,
                                                        const float2 *__restrict__ twL, int row0,
                                                        int out_rows, int H, int N1, int bh0, int ring0,
@@ -86,10 +100,13 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const float2 *__restrict_
     const int bhl = blockIdx.y, bh = bh0 + bhl, b = bh / H, h = bh % H;
     {
         const int tl = tid % TT, p = tid / TT, t1 = t1_0 + tl;
-        const float2 *src = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
+        const typename SC::elem_t *src = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
+        typename SC::elem_t raw[N2];
+#pragma unroll
+        for (int k2 = 0; k2 < N2; ++k2) raw[k2] = src[(size_t)k2 * 32 * N1];
         float2 y[N2];
 #pragma unroll
-        for (int k2 = 0; k2 < N2; ++k2) y[k2] = src[(size_t)k2 * 32 * N1];
+        for (int k2 = 0; k2 < N2; ++k2) y[k2] = SC::get(raw[k2]);
 #pragma unroll
         for (int k2 = 1; k2 < N2; ++k2) y[k2] = cmulc(y[k2], twL[t1 * k2]);
         small_dft<N2, true>(y);
@@ -156,8 +173,8 @@ __device__ __forceinline__ void exchange(float2 (&x)[16], float2 *buf, int tau) 
     if (!CROSS) __builtin_amdgcn_wave_barrier();
 }
 
-template <int P, int MODE>
-__global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const float2 *__restrict__ gp,
+template <int P, int MODE, typename SC>
+__global__ __launch_bounds__(256) void k_big(typename SC::elem_t *__restrict__ scr, const float2 *__restrict__ gp,
                                              const float2 *__restrict__ twN1, int N2, int ppw, int bh0,
                                              int nplanes_xcd, int g_step) {
     static_assert(P == 2 || P == 3, "N1 is 256 or 4096");
@@ -195,17 +212,18 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
         for (int j = 0; j < 16; ++j) G[j] = gsrc[j * TPC + tau];
     }
 
-    float2 *col = scr + (((size_t)bhl * N2 + k2) * 32 + pg * ppw + ci) * N1;
+    typedef typename SC::elem_t elem_t;
+    elem_t *col = scr + (((size_t)bhl * N2 + k2) * 32 + pg * ppw + ci) * N1;
     const int in_off = (MODE != 2) ? tau : 16 * tau, in_step = (MODE != 2) ? TPC : 1;
-    float2 nx[16];
+    elem_t nx[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) nx[j] = col[in_off + in_step * j];
     for (int c = ci; c < ppw; c += CPI) {
         float2 x[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) x[j] = nx[j];
+        for (int j = 0; j < 16; ++j) x[j] = SC::get(nx[j]);
         if (c + CPI < ppw) {                          // next column's loads fly during this one's passes
-            const float2 *ncol = col + (size_t)CPI * N1;
+            const elem_t *ncol = col + (size_t)CPI * N1;
 #pragma unroll
             for (int j = 0; j < 16; ++j) nx[j] = ncol[in_off + in_step * j];
         }
@@ -228,7 +246,7 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
         }
         if (MODE == 1) {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) col[16 * tau + j] = x[j];
+            for (int j = 0; j < 16; ++j) col[16 * tau + j] = SC::put(x[j]);
             if (kCross) __syncthreads();              // buf_f is rewritten by the next column
         } else {
             dft<16, true>(x);
@@ -243,7 +261,7 @@ __global__ __launch_bounds__(256) void k_big(float2 *__restrict__ scr, const flo
             for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[0][u - 1]);
             dft<16, true>(x);
 #pragma unroll
-            for (int j = 0; j < 16; ++j) col[tau + TPC * j] = x[j];
+            for (int j = 0; j < 16; ++j) col[tau + TPC * j] = SC::put(x[j]);
             if (kCross) __syncthreads();              // the next column's forward write reuses the buffer
         }
         col += (size_t)CPI * N1;
@@ -421,11 +439,12 @@ static hipError_t allow_lds(K kernel, size_t bytes) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-template <int N2, int TT, typename IO>
-static hipError_t small_fwd_t(const Pow2Plan &pl, const void *v, float2 *scr, int rows, int H, int bh0,
+template <int N2, int TT, typename IO, typename SC>
+static hipError_t small_fwd_t(const Pow2Plan &pl, const void *v, void *scr_v, int rows, int H, int bh0,
                               int nbh, hipStream_t st) {
     const size_t lds = (size_t)N2 * TT * TileStride<IO>::value * sizeof(typename IO::pair_t);
-    auto kern = k_small_fwd<N2, TT, IO>;
+    auto kern = k_small_fwd<N2, TT, IO, SC>;
+    typename SC::elem_t *scr = static_cast<typename SC::elem_t *>(scr_v);
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
     kern<<<dim3(pl.N1 / TT, nbh), dim3(32 * TT), lds, st>>>(
@@ -433,11 +452,12 @@ static hipError_t small_fwd_t(const Pow2Plan &pl, const void *v, float2 *scr, in
     return hipGetLastError();
 }
 
-template <int N2, int TT, typename IO>
-static hipError_t small_inv_t(const Pow2Plan &pl, const float2 *scr, void *out, int row0, int out_rows,
+template <int N2, int TT, typename IO, typename SC>
+static hipError_t small_inv_t(const Pow2Plan &pl, const void *scr_v, void *out, int row0, int out_rows,
                               int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w, int newest) {
     const size_t lds = (size_t)N2 * TT * TileStride<IO>::value * sizeof(typename IO::pair_t);
-    auto kern = k_small_inv<N2, TT, IO>;
+    auto kern = k_small_inv<N2, TT, IO, SC>;
+    const typename SC::elem_t *scr = static_cast<const typename SC::elem_t *>(scr_v);
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
     kern<<<dim3(pl.N1 / TT, nbh), dim3(32 * TT), lds, st>>>(
@@ -446,7 +466,8 @@ static hipError_t small_inv_t(const Pow2Plan &pl, const float2 *scr, void *out, 
 }
 
 #define SPECTRE_N2_CASE(FN, N, ...) \
-    case N: return io ? FN<N, 16, IoBf16>(__VA_ARGS__) : FN<N, 8, IoF32>(__VA_ARGS__);
+    case N: return io ? (scr16 ? FN<N, 16, IoBf16, ScrBf16>(__VA_ARGS__) : FN<N, 16, IoBf16, ScrF32>(__VA_ARGS__)) \
+                      : FN<N, 8, IoF32, ScrF32>(__VA_ARGS__);
 #define SPECTRE_DISPATCH_N2(FN, ...)                                         \
     switch (pl.N2) {                                                         \
         SPECTRE_N2_CASE(FN, 1, __VA_ARGS__) SPECTRE_N2_CASE(FN, 2, __VA_ARGS__) SPECTRE_N2_CASE(FN, 3, __VA_ARGS__)    \
@@ -459,23 +480,26 @@ static hipError_t small_inv_t(const Pow2Plan &pl, const float2 *scr, void *out, 
     }
 
 hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
-                            int bh0, int nbh, hipStream_t st) {
+                            int bh0, int nbh, hipStream_t st, bool scr16) {
+    if (scr16 && !io) return hipErrorInvalidValue;
     SPECTRE_DISPATCH_N2(small_fwd_t, pl, v, scratch, rows, H, bh0, nbh, st)
 }
 
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
                             int out_rows, int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w,
-                            int newest) {
+                            int newest, bool scr16) {
+    if (scr16 && !io) return hipErrorInvalidValue;
     SPECTRE_DISPATCH_N2(small_inv_t, pl, scratch, out, row0, out_rows, H, bh0, nbh, st, ring0, ring_w, newest)
 }
 
-template <int P, int MODE>
-static hipError_t big_t(const Pow2Plan &pl, float2 *scr, const float2 *gp, int bh0, int nbh, bool shared_gate,
+template <int P, int MODE, typename SC = ScrF32>
+static hipError_t big_t(const Pow2Plan &pl, float2 *scr_v, const float2 *gp, int bh0, int nbh, bool shared_gate,
                         hipStream_t st) {
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
     const size_t lds = (size_t)CPI * COLW * sizeof(float2);
     const int ppw = (P == 2) ? 16 : 4;   // pairs per workgroup; a multiple of CPI dividing 32
-    auto kern = k_big<P, MODE>;
+    auto kern = k_big<P, MODE, SC>;
+    typename SC::elem_t *scr = reinterpret_cast<typename SC::elem_t *>(scr_v);
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)nbh * pl.N2 * (32 / ppw);
@@ -486,7 +510,13 @@ static hipError_t big_t(const Pow2Plan &pl, float2 *scr, const float2 *gp, int b
 }
 
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
-                      hipStream_t st, bool shared_gate) {
+                      hipStream_t st, bool shared_gate, bool scr16) {
+    if (scr16) {                                       // the mixer's forward-gate-inverse pass only
+        if (mode != 0) return hipErrorInvalidValue;
+        if (pl.P == 2) return big_t<2, 0, ScrBf16>(pl, scratch, gp, bh0, nbh, shared_gate, st);
+        if (pl.P == 3) return big_t<3, 0, ScrBf16>(pl, scratch, gp, bh0, nbh, shared_gate, st);
+        return hipErrorInvalidValue;
+    }
     if (pl.P == 2) {
         if (mode == 0) return big_t<2, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st);
         if (mode == 1) return big_t<2, 1>(pl, scratch, gp, bh0, nbh, shared_gate, st);

@@ -76,6 +76,25 @@ def test_one_kernel_path_at_4096_and_the_three_kernel_path_behind_it(oracle, mon
     assert e1 <= TOL[io] and e3 <= TOL[io]
 
 
+@pytest.mark.parametrize("B,L,H", [(1, 8192, 3), (2, 12288, 2), (1, 32768, 5), (1, 131072, 1)])
+def test_bf16_scratch_option_stays_within_the_bf16_bar(oracle, monkeypatch, B, L, H):
+    """SPECTRE_SCRATCH_BF16: the three four-step kernels exchange bfloat16 pairs instead of fp32 pairs (opt-in, bf16
+    rows only).  Two more roundings to 8 mantissa bits: the error against the oracle must stay well inside the bar
+    for bf16 rows; fp32 rows ignore the switch and keep the fp32 bar."""
+    monkeypatch.delenv("SPECTRE_SCRATCH_BF16", raising=False)
+    seed = synth.BASE_SEED + 13 * H
+    plain, want, _ = run_case(oracle, B, L, H, 64, "bf16", seed=seed)
+    monkeypatch.setenv("SPECTRE_SCRATCH_BF16", "1")
+    got, _, _ = run_case(oracle, B, L, H, 64, "bf16", seed=seed)
+    e0, e1 = rel_l2(plain, want), rel_l2(got, want)
+    print(f"case B={B} L={L} H={H}: fp32 scratch {e0:.3e}  bf16 scratch {e1:.3e}", flush=True)
+    assert e0 <= TOL["bf16"] and e1 <= 5e-3
+    assert not np.array_equal(plain, got)                     # the switch did take the other kernels
+    if L <= 12288:
+        got32, want32, _ = run_case(oracle, B, L, H, 64, "f32", seed=seed)
+        assert rel_l2(got32, want32) <= TOL["f32"]
+
+
 def test_identity_gate_returns_input_on_gpu(oracle):
     B, L, H, d = 1, 4096, 2, 64
     g = np.ones((B, H, L // 2 + 1), np.complex64)
