@@ -207,18 +207,32 @@ int mix_chunk_heads(int BH, int L, int d) {
 }
 
 // Long calls run their head groups on two lanes (the caller's stream and a helper stream), each with half the
-// scratch budget, when that still leaves at least two groups; *chunk = heads per group.
-static int mix_lanes(int BH, int L, int d, int *chunk) {
+// scratch budget, when that still leaves at least two groups.  Two lanes get an even number of groups whose sizes
+// differ by at most one head (larger ones first), so that both lanes carry the same load and end together.
+// `scale` = heads that fit in the scratch bytes of one fp32-scratch head (2 with 16-bit scratch elements).
+struct MixGroups {
+    int lanes = 1, ngroups = 1, chunk = 1;            // chunk = heads in the largest group
+    int BH = 1;
+    int size(int group) const {                       // heads in group `group`
+        if (lanes == 1) { const int left = BH - group * chunk; return left < chunk ? left : chunk; }
+        return BH / ngroups + (group < BH % ngroups ? 1 : 0);
+    }
+};
+static MixGroups mix_groups(int BH, int L, int d, int scale) {
+    MixGroups m;
+    m.BH = BH;
     const int full = mix_chunk_heads(BH, L, d);
     const int half = full / 2;
     if (getenv("SPECTRE_ONE_LANE") || full >= BH || half < 1) {
-        *chunk = full;
-        return 1;
+        m.chunk = ((long long)full * scale < BH) ? full * scale : BH;
+        m.ngroups = (BH + m.chunk - 1) / m.chunk;
+        return m;
     }
-    // an even number of equally sized groups, so that both lanes carry the same load
-    const int ngroups = 2 * ((BH + 2 * half - 1) / (2 * half));
-    *chunk = (BH + ngroups - 1) / ngroups;
-    return 2;
+    const int cap = half * scale;
+    m.lanes = 2;
+    m.ngroups = 2 * ((BH + 2 * cap - 1) / (2 * cap));
+    m.chunk = (BH + m.ngroups - 1) / m.ngroups;
+    return m;
 }
 
 }  // namespace spectre
@@ -363,9 +377,8 @@ size_t spectre_mix_workspace_bytes(int B, int L, int H, int d, spectre_dtype io)
     if (route == 1) return 256;
     if (route == 3) return chirp_layout(BH, L, d).total();
     if (route == 4) return 256;
-    int chunk = 0;
-    const int lanes = mix_lanes(BH, L, d, &chunk);
-    return align256((size_t)BH * L * sizeof(float2)) + lanes * align256((size_t)chunk * L * (d / 2) * sizeof(float2));
+    const MixGroups m = mix_groups(BH, L, d, 1);
+    return align256((size_t)BH * L * sizeof(float2)) + m.lanes * align256((size_t)m.chunk * L * (d / 2) * sizeof(float2));
 }
 
 int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, int H, int d,
@@ -413,12 +426,14 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
     char *scr_base = static_cast<char *>(ws) + align256((size_t)BH * L * sizeof(float2));
     hipError_t e = launch_gate_expand(pl, static_cast<const float2 *>(g), gp, BH, st);
     if (e != hipSuccess) return fail_hip(e, "gate_expand");
-    int chunk = 0;
-    const int lanes = mix_lanes(BH, L, d, &chunk);
-    const size_t lane_bytes = align256((size_t)chunk * L * (d / 2) * sizeof(float2));
-    // opt-in, bf16 rows only: complex numbers cross between the three kernels as two bfloat16 instead of two fp32
-    const bool scr16 = (io == SPECTRE_BF16) && getenv("SPECTRE_SCRATCH_BF16") != nullptr;
-    if (scr16 && chunk < BH) chunk *= 2;               // twice the heads fit in a lane's scratch
+    // opt-in, bf16 rows only: complex numbers cross between the three kernels as two bfloat16 instead of two fp32,
+    // and twice the heads fit in a lane's scratch
+    bool scr16 = (io == SPECTRE_BF16) && getenv("SPECTRE_SCRATCH_BF16") != nullptr;
+    const MixGroups m1 = mix_groups(BH, L, d, 1);
+    const size_t lane_bytes = align256((size_t)m1.chunk * L * (d / 2) * sizeof(float2));   // as the workspace was sized
+    MixGroups mg = scr16 ? mix_groups(BH, L, d, 2) : m1;
+    if (scr16 && (mg.lanes != m1.lanes || (size_t)mg.chunk * L * (d / 2) * sizeof(uint32_t) > lane_bytes)) mg = m1;
+    const int lanes = mg.lanes;
     SideLane *side = nullptr;
     int dev = 0;
     if (lanes == 2) {
@@ -432,10 +447,10 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
             return fail_hip(e, "fork to helper stream");
         }
     }
-    int group = 0;
     const char *what = nullptr;
-    for (int bh0 = 0; bh0 < BH && !what; bh0 += chunk, ++group) {
-        const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
+    for (int group = 0, bh0 = 0; group < mg.ngroups && !what; ++group) {
+        const int nbh = mg.size(group);
+        if (nbh < 1) continue;
         const int lane = (lanes == 2) ? (group & 1) : 0;
         hipStream_t ls = lane ? side->stream : st;
         float2 *scr = reinterpret_cast<float2 *>(scr_base + (size_t)lane * lane_bytes);
@@ -445,6 +460,7 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         if (e != hipSuccess) { what = "big"; break; }
         e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls, 0, 0, 0, scr16);
         if (e != hipSuccess) { what = "small_inv"; break; }
+        bh0 += nbh;
     }
     if (lanes == 2) {
         // join: the caller's stream continues after the helper stream's last kernel (also on a launch error,
