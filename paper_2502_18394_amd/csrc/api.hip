@@ -45,7 +45,7 @@ int fail_hip(hipError_t e, const char *what) {
 // row kernels of one group overlap the arithmetic-heavy column kernel of the next; default priority.
 struct SideLane {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, gate = nullptr;
 };
 
 struct DeviceTables {
@@ -134,7 +134,9 @@ static int acquire_lane(int *dev_out, SideLane **out) {
     e = hipStreamCreateWithFlags(&l->stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&l->fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&l->join, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&l->gate, hipEventDisableTiming);
     if (e != hipSuccess) {
+        if (l->gate) (void)hipEventDestroy(l->gate);
         if (l->join) (void)hipEventDestroy(l->join);
         if (l->fork) (void)hipEventDestroy(l->fork);
         if (l->stream) (void)hipStreamDestroy(l->stream);
@@ -360,6 +362,7 @@ void spectre_shutdown(void) {
             (void)hipStreamSynchronize(l->stream);
             (void)hipEventDestroy(l->fork);
             (void)hipEventDestroy(l->join);
+            (void)hipEventDestroy(l->gate);
             (void)hipStreamDestroy(l->stream);
             delete l;
         }
@@ -424,8 +427,6 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
     if (rc) return rc;
     float2 *gp = static_cast<float2 *>(ws);
     char *scr_base = static_cast<char *>(ws) + align256((size_t)BH * L * sizeof(float2));
-    hipError_t e = launch_gate_expand(pl, static_cast<const float2 *>(g), gp, BH, st);
-    if (e != hipSuccess) return fail_hip(e, "gate_expand");
     // opt-in, bf16 rows only: complex numbers cross between the three kernels as two bfloat16 instead of two fp32,
     // and twice the heads fit in a lane's scratch
     bool scr16 = (io == SPECTRE_BF16) && getenv("SPECTRE_SCRATCH_BF16") != nullptr;
@@ -436,10 +437,13 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
     const int lanes = mg.lanes;
     SideLane *side = nullptr;
     int dev = 0;
+    hipError_t e = hipSuccess;
     if (lanes == 2) {
         rc = acquire_lane(&dev, &side);
         if (rc) return rc;
-        // fork: the helper stream starts after the expanded gate (and everything before it on the caller's stream)
+        // fork: the helper stream starts after everything before this call on the caller's stream.  Its first
+        // kernel (row transforms) does not read the gate, so it runs beside the gate expansion; the column kernel
+        // that follows waits for the event recorded behind the expansion.
         e = hipEventRecord(side->fork, st);
         if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
         if (e != hipSuccess) {
@@ -448,6 +452,13 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         }
     }
     const char *what = nullptr;
+    e = launch_gate_expand(pl, static_cast<const float2 *>(g), gp, BH, st);
+    if (e != hipSuccess) what = "gate_expand";
+    if (!what && lanes == 2) {
+        e = hipEventRecord(side->gate, st);
+        if (e != hipSuccess) what = "event behind the gate expansion";
+    }
+    bool side_has_gate = false;
     for (int group = 0, bh0 = 0; group < mg.ngroups && !what; ++group) {
         const int nbh = mg.size(group);
         if (nbh < 1) continue;
@@ -456,6 +467,11 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         float2 *scr = reinterpret_cast<float2 *>(scr_base + (size_t)lane * lane_bytes);
         e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, ls, scr16);
         if (e != hipSuccess) { what = "small_fwd"; break; }
+        if (lane && !side_has_gate) {
+            e = hipStreamWaitEvent(side->stream, side->gate, 0);
+            if (e != hipSuccess) { what = "wait for the gate expansion"; break; }
+            side_has_gate = true;
+        }
         e = launch_big(pl, scr, gp, bh0, nbh, 0, ls, false, scr16);
         if (e != hipSuccess) { what = "big"; break; }
         e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls, 0, 0, 0, scr16);
