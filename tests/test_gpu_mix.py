@@ -95,6 +95,33 @@ def test_bf16_scratch_option_stays_within_the_bf16_bar(oracle, monkeypatch, B, L
         assert rel_l2(got32, want32) <= TOL["f32"]
 
 
+@pytest.mark.parametrize("B,H,mb,one_lane", [(1, 11, 12, False), (1, 7, 12, False), (3, 1, 4, False), (1, 3, 4, True),
+                                              (2, 5, 2, False), (1, 13, 12, True)])
+def test_head_groups_of_any_size_give_the_same_rows(oracle, monkeypatch, B, H, mb, one_lane):
+    """Long calls take their heads in groups (one stream, or two streams with an even number of groups whose sizes
+    differ by at most one head, some of them empty when there are fewer heads than groups).  Every head is
+    transformed on its own, so the grouping must not change a bit; SPECTRE_CHUNK_MB shrinks the groups far enough
+    to get several of them at a small length.  The same groupings with the bfloat16 scratch stay within its bar."""
+    L, io = 8192, "bf16"
+    seed = synth.BASE_SEED + 17 * H + B
+    for k in ("SPECTRE_CHUNK_MB", "SPECTRE_ONE_LANE", "SPECTRE_SCRATCH_BF16"):
+        monkeypatch.delenv(k, raising=False)
+    plain, want, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    assert rel_l2(plain, want) <= TOL[io]
+    monkeypatch.setenv("SPECTRE_CHUNK_MB", str(mb))
+    if one_lane:
+        monkeypatch.setenv("SPECTRE_ONE_LANE", "1")
+    got, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    print(f"case B={B} H={H} chunk_mb={mb} one_lane={one_lane}: identical {np.array_equal(got, plain)}", flush=True)
+    assert np.array_equal(got, plain)
+    monkeypatch.setenv("SPECTRE_SCRATCH_BF16", "1")
+    got16, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    monkeypatch.delenv("SPECTRE_CHUNK_MB")
+    monkeypatch.delenv("SPECTRE_ONE_LANE", raising=False)
+    plain16, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    assert np.array_equal(got16, plain16) and rel_l2(got16, want) <= 5e-3
+
+
 def test_identity_gate_returns_input_on_gpu(oracle):
     B, L, H, d = 1, 4096, 2, 64
     g = np.ones((B, H, L // 2 + 1), np.complex64)
