@@ -10,6 +10,8 @@
 // forward ones in reverse, so nothing is ever reordered.
 #include "mix_slab.h"
 
+#include <stdlib.h>
+
 #include <vector>
 
 #include "fft_regs.h"
@@ -86,23 +88,39 @@ struct SlabRadices {
     int r[10];
 };
 
+// Lengths whose radix list is also known at compile time (it must equal what slab_radices() returns on the host,
+// which the launcher checks): the kernel variant for such a length has every LDS offset, stride and twiddle index
+// folded into its instructions (55-80 registers instead of 120, no address arithmetic left in the passes).
+template <int LC> struct CtRadices;
+template <> struct CtRadices<196> { static constexpr int count = 2, r0 = 14, r1 = 14, r2 = 1; };
+template <> struct CtRadices<256> { static constexpr int count = 2, r0 = 16, r1 = 16, r2 = 1; };
+template <> struct CtRadices<512> { static constexpr int count = 3, r0 = 16, r1 = 16, r2 = 2; };
+template <> struct CtRadices<1024> { static constexpr int count = 3, r0 = 16, r1 = 16, r2 = 4; };
+template <> struct CtRadices<2048> { static constexpr int count = 3, r0 = 16, r1 = 16, r2 = 8; };
+
 // grid = B*H*(32/PP) workgroups of 256 lanes, PP channel pairs each: a whole head, half a head when rows
 // are fp32 (still full 128-byte row segments, half the LDS, twice the workgroups per CU), or as little as
 // 4 pairs when there are few heads (then the call is one launch over every compute unit instead of four
 // dependent ones) or the sequence is long (the slab must fit in LDS).
 // LDS: slab [L][PP] float2, roots [L], gpos [L].
-template <typename IO, int PP>
-__global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__restrict__ v,
-                                                  const float2 *__restrict__ g,
-                                                  typename IO::pair_t *__restrict__ out,
-                                                  const float2 *__restrict__ roots_g,
-                                                  const int *__restrict__ bin_of_pos, int L, int H,
-                                                  SlabRadices rad, int rows) {
+// NT = lanes per workgroup.  LC = 0: the length and its radices are run-time arguments; LC > 0: compile-time
+// constants (CtRadices).  For LC = 196 (the 14 x 14 patch grid, radices 14, 14) with NT = 448, PP = 32 the 14 * 32
+// butterflies of a pass fill seven waves exactly (224 of 256 lanes with NT = 256, PP = 16) and a lane loads and
+// stores exactly 14 rows.
+template <typename IO, int PP, int NT = 256, int LC = 0>
+__global__ __launch_bounds__(NT) void k_mix_slab(const typename IO::pair_t *__restrict__ v,
+                                                 const float2 *__restrict__ g,
+                                                 typename IO::pair_t *__restrict__ out,
+                                                 const float2 *__restrict__ roots_g,
+                                                 const int *__restrict__ bin_of_pos, int L_arg, int H,
+                                                 SlabRadices rad, int rows) {
+    const int L = LC ? LC : L_arg;
     extern __shared__ float2 lds_slab[];
     float2 *slab = lds_slab;
     float2 *roots = slab + (size_t)L * PP;
     float2 *gpos = roots + L;
-    constexpr int kParts = 32 / PP, kRows = 256 / PP;      // workgroups per head; rows covered per sweep
+    constexpr int kParts = 32 / PP, kRows = NT / PP;       // workgroups per head; rows covered per sweep
+    static_assert(NT % PP == 0 && NT % 64 == 0, "whole rows per sweep, whole waves");
     const int tid = threadIdx.x;
     const int bh = blockIdx.x / kParts, part = blockIdx.x % kParts, b = bh / H, h = bh % H;
     const int F = L / 2 + 1;
@@ -126,24 +144,24 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
     // the last forward pass); full-length Hermitian extension, 1/L folded in.  The two dependent loads
     // (bin, then gate) are issued for all of a lane's positions at once: L <= 2048 = 8 * 256.
     {
-        constexpr int kPos = kSlabMaxL / 256;
+        constexpr int kPos = ((LC ? LC : kSlabMaxL) + NT - 1) / NT;
         int kbin[kPos];
         float2 gv[kPos], rv[kPos];
 #pragma unroll
         for (int i = 0; i < kPos; ++i) {
-            const int p = tid + 256 * i;
+            const int p = tid + NT * i;
             kbin[i] = (p < L) ? bin_of_pos[p] : 0;
             rv[i] = (p < L) ? roots_g[p] : make_float2(0.f, 0.f);
         }
 #pragma unroll
         for (int i = 0; i < kPos; ++i) {
             const int k = kbin[i];
-            gv[i] = (tid + 256 * i < L) ? g[(size_t)bh * F + (2 * k <= L ? k : L - k)] : make_float2(0.f, 0.f);
+            gv[i] = (tid + NT * i < L) ? g[(size_t)bh * F + (2 * k <= L ? k : L - k)] : make_float2(0.f, 0.f);
         }
         const float sc = 1.0f / (float)L;
 #pragma unroll
         for (int i = 0; i < kPos; ++i) {
-            const int p = tid + 256 * i, k = kbin[i];
+            const int p = tid + NT * i, k = kbin[i];
             if (p < L) {
                 float2 val = gv[i];
                 if (2 * k > L) val.y = -val.y;
@@ -171,18 +189,43 @@ __global__ __launch_bounds__(256) void k_mix_slab(const typename IO::pair_t *__r
         }
     }
     __syncthreads();
-    int n = L;
-    for (int q = 0; q < rad.count; ++q) {
-        if (q == rad.count - 1) slab_pass_dispatch<false, true, true, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
-        else slab_pass_dispatch<false, false, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
-        n /= rad.r[q];
+    if constexpr (LC != 0) {
+        typedef CtRadices<LC> R;
+        constexpr int n0 = LC, n1 = n0 / R::r0, n2 = n1 / R::r1;
+        static_assert((R::count == 2 && n1 == R::r1) || (R::count == 3 && n2 == R::r2), "radices multiply to LC");
+        slab_pass<R::r0, false, false, false, PP>(slab, roots, gpos, LC, n0, tid, NT);
         __syncthreads();
-    }
-    for (int q = rad.count - 1; q >= 0; --q) {
-        n *= rad.r[q];
-        if (q == rad.count - 1) slab_pass_dispatch<true, false, true, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
-        else slab_pass_dispatch<true, false, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, 256);
+        if constexpr (R::count == 3) {
+            slab_pass<R::r1, false, false, false, PP>(slab, roots, gpos, LC, n1, tid, NT);
+            __syncthreads();
+            slab_pass<R::r2, false, true, true, PP>(slab, roots, gpos, LC, n2, tid, NT);
+            __syncthreads();
+            slab_pass<R::r2, true, false, true, PP>(slab, roots, gpos, LC, n2, tid, NT);
+            __syncthreads();
+            slab_pass<R::r1, true, false, false, PP>(slab, roots, gpos, LC, n1, tid, NT);
+            __syncthreads();
+        } else {
+            slab_pass<R::r1, false, true, true, PP>(slab, roots, gpos, LC, n1, tid, NT);
+            __syncthreads();
+            slab_pass<R::r1, true, false, true, PP>(slab, roots, gpos, LC, n1, tid, NT);
+            __syncthreads();
+        }
+        slab_pass<R::r0, true, false, false, PP>(slab, roots, gpos, LC, n0, tid, NT);
         __syncthreads();
+    } else {
+        int n = L;
+        for (int q = 0; q < rad.count; ++q) {
+            if (q == rad.count - 1) slab_pass_dispatch<false, true, true, PP>(rad.r[q], slab, roots, gpos, L, n, tid, NT);
+            else slab_pass_dispatch<false, false, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, NT);
+            n /= rad.r[q];
+            __syncthreads();
+        }
+        for (int q = rad.count - 1; q >= 0; --q) {
+            n *= rad.r[q];
+            if (q == rad.count - 1) slab_pass_dispatch<true, false, true, PP>(rad.r[q], slab, roots, gpos, L, n, tid, NT);
+            else slab_pass_dispatch<true, false, false, PP>(rad.r[q], slab, roots, gpos, L, n, tid, NT);
+            __syncthreads();
+        }
     }
     {
         typename IO::pair_t *dst = out + (((size_t)b * rows) * H + h) * 32 + part * PP + lp_in;
@@ -249,18 +292,24 @@ void slab_bin_order(int L, int *bin_of_pos) {
     }
 }
 
-template <typename IO, int PP>
+template <typename IO, int PP, int NT = 256, int LC = 0>
 static hipError_t mix_slab_t(const void *v, const float2 *g, void *out, const float2 *roots, const int *bin_of_pos,
                              int B, int L, int H, int rows, hipStream_t st) {
     const size_t lds = ((size_t)L * PP + 2 * (size_t)L) * sizeof(float2);
     const SlabRadices rad = slab_radices(L);
-    auto kern = k_mix_slab<IO, PP>;
+    auto kern = k_mix_slab<IO, PP, NT, LC>;
+    if constexpr (LC != 0) {
+        typedef CtRadices<LC> R;
+        if (L != LC || rad.count != R::count || rad.r[0] != R::r0 || rad.r[1] != R::r1 ||
+            (R::count == 3 && rad.r[2] != R::r2))
+            return hipErrorInvalidValue;
+    }
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    kern<<<dim3(B * H * (32 / PP)), dim3(256), lds, st>>>(static_cast<const typename IO::pair_t *>(v), g,
+    kern<<<dim3(B * H * (32 / PP)), dim3(NT), lds, st>>>(static_cast<const typename IO::pair_t *>(v), g,
                                                          static_cast<typename IO::pair_t *>(out), roots, bin_of_pos, L, H,
                                                          rad, rows);
     return hipGetLastError();
@@ -281,14 +330,27 @@ hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, co
     if (rows > L) return hipErrorInvalidValue;
     const int pp = slab_pairs_per_workgroup(io, B * H, L);
     if ((size_t)L * (pp + 2) * sizeof(float2) > (size_t)160 * 1024) return hipErrorInvalidValue;
-#define SPECTRE_SLAB_CASE(PPV)                                                                       \
+    if (L == 196 && pp >= 16 && (long long)B * H >= 512 && !getenv("SPECTRE_NO_SLAB_CT"))   // whole heads still fill the chip
+        return io ? mix_slab_t<IoBf16, 32, 448, 196>(v, g, out, roots, bin_of_pos, B, L, H, rows, st)
+                  : mix_slab_t<IoF32, 32, 448, 196>(v, g, out, roots, bin_of_pos, B, L, H, rows, st);
+    const bool ct = !getenv("SPECTRE_NO_SLAB_CT");
+#define SPECTRE_SLAB_LEN(PPV, LCV)                                                                          \
+    if (ct && L == LCV)                                                                                     \
+        return io ? mix_slab_t<IoBf16, PPV, 256, LCV>(v, g, out, roots, bin_of_pos, B, L, H, rows, st)      \
+                  : mix_slab_t<IoF32, PPV, 256, LCV>(v, g, out, roots, bin_of_pos, B, L, H, rows, st);
+#define SPECTRE_SLAB_CASE(PPV, LENS)                                                                 \
     case PPV:                                                                                       \
+        LENS                                                                                        \
         return io ? mix_slab_t<IoBf16, PPV>(v, g, out, roots, bin_of_pos, B, L, H, rows, st)        \
                   : mix_slab_t<IoF32, PPV>(v, g, out, roots, bin_of_pos, B, L, H, rows, st);
-    switch (pp) {
-        SPECTRE_SLAB_CASE(4) SPECTRE_SLAB_CASE(8) SPECTRE_SLAB_CASE(16) SPECTRE_SLAB_CASE(32)
+    switch (pp) {                       // only the (pairs, length) combinations the rule above can produce
+        SPECTRE_SLAB_CASE(4, SPECTRE_SLAB_LEN(4, 256) SPECTRE_SLAB_LEN(4, 512) SPECTRE_SLAB_LEN(4, 1024) SPECTRE_SLAB_LEN(4, 2048))
+        SPECTRE_SLAB_CASE(8, SPECTRE_SLAB_LEN(8, 256) SPECTRE_SLAB_LEN(8, 512))
+        SPECTRE_SLAB_CASE(16, SPECTRE_SLAB_LEN(16, 256) SPECTRE_SLAB_LEN(16, 512))
+        SPECTRE_SLAB_CASE(32, SPECTRE_SLAB_LEN(32, 256))
         default: return hipErrorInvalidValue;
     }
+#undef SPECTRE_SLAB_LEN
 #undef SPECTRE_SLAB_CASE
 }
 

@@ -122,6 +122,23 @@ def test_head_groups_of_any_size_give_the_same_rows(oracle, monkeypatch, B, H, m
     assert np.array_equal(got16, plain16) and rel_l2(got16, want) <= 5e-3
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H", [(64, 8), (43, 12), (171, 3)])
+def test_patch_grid_length_with_many_heads_takes_its_own_kernel(oracle, monkeypatch, B, H, io):
+    """L = 196 (14 x 14 patches) with at least 512 heads runs a variant of the in-LDS kernel whose length and radices
+    (14, 14) are compile-time constants and whose workgroups are seven waves on a whole head.  Same passes, same
+    arithmetic as the general kernel (SPECTRE_NO_SLAB_CT forces that one): both must match the oracle and each other."""
+    L = 196
+    seed = synth.BASE_SEED + 19 * H + B
+    monkeypatch.delenv("SPECTRE_NO_SLAB_CT", raising=False)
+    got, want, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    monkeypatch.setenv("SPECTRE_NO_SLAB_CT", "1")
+    general, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    e1, e2, e12 = rel_l2(got, want), rel_l2(general, want), rel_l2(got, general)
+    print(f"case B={B} H={H} io={io}: own kernel {e1:.3e}  general {e2:.3e}  between {e12:.3e}", flush=True)
+    assert e1 <= TOL[io] and e2 <= TOL[io] and e12 <= (1e-6 if io == "f32" else 2e-3)
+
+
 def test_identity_gate_returns_input_on_gpu(oracle):
     B, L, H, d = 1, 4096, 2, 64
     g = np.ones((B, H, L // 2 + 1), np.complex64)
