@@ -123,39 +123,50 @@ __global__ __launch_bounds__(256) void k_pool_final(const double *__restrict__ p
 }
 
 // ------------------------------------------------------------------------------------------
-// hidden: one workgroup per (b, h).  LayerNorm statistics in fp64 (d values), the small
-// d x d_g product on the vector units.
+// hidden: one workgroup per (b, h).  LayerNorm statistics in fp64 (d <= 256 values, one per lane: two tree
+// reductions in a fixed order), then the small d x d_g product on the vector units with the d terms of an output
+// split over 256 / d_g lane groups (fixed split, partial sums added in group order).
+__device__ __forceinline__ double block_sum_256(double x, double *red, int lane, int wave) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    if (lane == 0) red[wave] = x;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 __global__ __launch_bounds__(256) void k_gate_hidden(const double *__restrict__ sum_q, double inv_count,
                                                      const float *__restrict__ gamma,
                                                      const float *__restrict__ beta, float eps,
                                                      const float *__restrict__ W1,
                                                      const float *__restrict__ b1, float *__restrict__ hid,
                                                      int H, int Hg, int d, int dg) {
-    __shared__ double xs[256];
     __shared__ float qbar[256];
-    __shared__ double stat[2];
+    __shared__ float part[256];
+    __shared__ double red[8];
     const int bh = blockIdx.x, h = bh % H, hp = (Hg == 1) ? 0 : h;
-    const int tid = threadIdx.x;
-    if (tid < d) xs[tid] = inv_count * sum_q[(size_t)bh * d + tid];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const double x = (tid < d) ? inv_count * sum_q[(size_t)bh * d + tid] : 0.0;
+    const double mean = block_sum_256(x, red, lane, wave) / d;
+    const double dev = (tid < d) ? x - mean : 0.0;
+    const double var = block_sum_256(dev * dev, red + 4, lane, wave) / d;
+    const double rstd = 1.0 / sqrt(var + (double)eps);
+    if (tid < d) qbar[tid] = (float)((double)gamma[hp * d + tid] * dev * rstd + (double)beta[hp * d + tid]);
     __syncthreads();
-    if (tid == 0) {
-        double mean = 0.0, var = 0.0;
-        for (int i = 0; i < d; ++i) mean += xs[i];
-        mean /= d;
-        for (int i = 0; i < d; ++i) var += (xs[i] - mean) * (xs[i] - mean);
-        var /= d;
-        stat[0] = mean;
-        stat[1] = 1.0 / sqrt(var + (double)eps);
+    const int nseg = (dg <= 64) ? 4 : (dg <= 128) ? 2 : 1, cols = 256 / nseg;
+    const int jcol = tid % cols, seg = tid / cols;
+    const int dseg = (d + nseg - 1) / nseg, i0 = seg * dseg, i1 = (i0 + dseg < d) ? i0 + dseg : d;
+    float a = 0.f;
+    if (jcol < dg) {
+        const float *w = W1 + (size_t)hp * d * dg + jcol;
+#pragma unroll 8
+        for (int i = i0; i < i1; ++i) a = fmaf(qbar[i], w[(size_t)i * dg], a);
     }
-    __syncthreads();
-    if (tid < d)
-        qbar[tid] = (float)((double)gamma[hp * d + tid] * (xs[tid] - stat[0]) * stat[1] + (double)beta[hp * d + tid]);
+    part[tid] = a;
     __syncthreads();
     if (tid < dg) {
-        float a = b1[hp * dg + tid];
-        const float *w = W1 + (size_t)hp * d * dg + tid;
-        for (int i = 0; i < d; ++i) a = fmaf(qbar[i], w[(size_t)i * dg], a);
-        hid[(size_t)bh * dg + tid] = 0.5f * a * (1.0f + erff(a * 0.70710678118654752440f));
+        float t = b1[hp * dg + tid];
+        for (int q = 0; q < nseg; ++q) t += part[q * cols + tid];
+        hid[(size_t)bh * dg + tid] = 0.5f * t * (1.0f + erff(t * 0.70710678118654752440f));
     }
 }
 
