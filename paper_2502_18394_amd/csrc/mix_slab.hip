@@ -315,11 +315,13 @@ static hipError_t mix_slab_t(const void *v, const float2 *g, void *out, const fl
     return hipGetLastError();
 }
 
-// Pairs per workgroup: as many as fit in LDS (slab L*PP + two tables of L complex numbers), no more than keeps
-// every compute unit busy (B*H*32/PP >= 256 workgroups), at most a whole head (half a head for fp32 rows).
+// Pairs per workgroup: as many as leave room for three workgroups per compute unit (slab L*PP + two tables of L
+// complex numbers <= 52 KB; measured at B*H = 3072: L = 512 and the padded 197 are 5-24 % faster with 8 pairs than
+// with 16, L = 256 bf16 30 % faster with 16 than with 32), no more than keeps every compute unit busy
+// (B*H*32/PP >= 256 workgroups), at most a whole head (half a head for fp32 rows).
 int slab_pairs_per_workgroup(int io, int BH, int L) {
     int pp = io ? 32 : 16;
-    while (pp > 4 && (size_t)L * (pp + 2) * sizeof(float2) > (size_t)72 * 1024) pp /= 2;   // two workgroups per CU
+    while (pp > 4 && (size_t)L * (pp + 2) * sizeof(float2) > (size_t)52 * 1024) pp /= 2;   // three workgroups per CU
     while (pp > 4 && (long long)BH * (32 / pp) < 256) pp /= 2;
     return pp;
 }
