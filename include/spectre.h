@@ -24,7 +24,7 @@
  *     from run to run.  A long spectre_mix_forward call runs every other head group
  *     on a helper stream of the library's own (default priority), forked from and
  *     joined back into `stream` with events: to the caller the call still behaves
- *     as work enqueued on `stream`, also under HIP graph capture.  Five environment
+ *     as work enqueued on `stream`, also under HIP graph capture.  Six environment
  *     variables exist for measurements: SPECTRE_ONE_LANE (any value) keeps every
  *     group on `stream`; SPECTRE_CHUNK_MB=<n> sets the total size of the transform
  *     scratch in flight (default 204, sized for the 256 MB memory-side cache);
@@ -36,7 +36,9 @@
  *     about 2.9e-3, and a call at n = 131072 takes about 14 % less time.  Off by default: the
  *     spectrum then no longer exists in fp32 between the kernels.  SPECTRE_NO_SLAB_CT (any value)
  *     makes the in-LDS kernel take its run-time-length form also for the lengths that have a
- *     compile-time form (196, 256, 512, 1024, 2048).  They are read at every call and
+ *     compile-time form (196, 256, 512, 1024, 2048); SPECTRE_NO_AFFINE (any value) switches off
+ *     the placement of all workgroups of a head on one XCD that four-step lengths up to 12288
+ *     use when a call has a multiple of 8 heads.  They are read at every call and
  *     must not change between a *_workspace_bytes query and the call it sizes.
  *   - The caller owns every buffer, including the scratch workspace `ws`, whose
  *     minimum size the matching *_workspace_bytes function returns.  The library

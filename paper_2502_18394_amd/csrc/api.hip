@@ -465,16 +465,20 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         const int lane = (lanes == 2) ? (group & 1) : 0;
         hipStream_t ls = lane ? side->stream : st;
         float2 *scr = reinterpret_cast<float2 *>(scr_base + (size_t)lane * lane_bytes);
-        e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, ls, scr16);
+        // short columns (L <= 12288): a head's scratch fits the 4 MB L2 of one XCD, see head_affine() in mix_pow2.hip;
+        // measured -7 % at L = 8192, -10 % at 4096 (three kernels), nothing or a loss from 16384 on
+        const bool affine = !scr16 && nbh % 8 == 0 && (size_t)L * (d / 2) * sizeof(float2) <= ((size_t)3 << 20) &&
+                            !getenv("SPECTRE_NO_AFFINE");
+        e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, ls, scr16, affine);
         if (e != hipSuccess) { what = "small_fwd"; break; }
         if (lane && !side_has_gate) {
             e = hipStreamWaitEvent(side->stream, side->gate, 0);
             if (e != hipSuccess) { what = "wait for the gate expansion"; break; }
             side_has_gate = true;
         }
-        e = launch_big(pl, scr, gp, bh0, nbh, 0, ls, false, scr16);
+        e = launch_big(pl, scr, gp, bh0, nbh, 0, ls, false, scr16, affine);
         if (e != hipSuccess) { what = "big"; break; }
-        e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls, 0, 0, 0, scr16);
+        e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls, 0, 0, 0, scr16, affine);
         if (e != hipSuccess) { what = "small_inv"; break; }
         bh0 += nbh;
     }

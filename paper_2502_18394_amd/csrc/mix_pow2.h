@@ -34,13 +34,15 @@ bool pow2_split(int L, int *N1, int *N2, int *P);
 //               newest entry is row ring0+newest
 // scr16 (bf16 rows, big: mode 0 only): the scratch holds each complex number as two bfloat16 in one 32-bit word at
 // the same element index (the buffer is used to half its size); all three kernels of a pass must agree on it.
+// affine (nbh a multiple of 8; big: mode 0, fp32 scratch): every workgroup of head bh0 + 8 s + x runs on XCD x, and the
+// three kernels walk s up, down, up, so that part of the scratch is read from the L2 it was written through.
 hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
-                            int bh0, int nbh, hipStream_t st, bool scr16 = false);
+                            int bh0, int nbh, hipStream_t st, bool scr16 = false, bool affine = false);
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
-                      hipStream_t st, bool shared_gate = false, bool scr16 = false);
+                      hipStream_t st, bool shared_gate = false, bool scr16 = false, bool affine = false);
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
                             int out_rows, int H, int bh0, int nbh, hipStream_t st, int ring0 = 0, int ring_w = 0,
-                            int newest = 0, bool scr16 = false);
+                            int newest = 0, bool scr16 = false, bool affine = false);
 // g [BH, L/2+1] -> gp [BH][N2][N1] in the big kernel's register order, scaled by 1/L and
 // extended to all L bins by Hermitian symmetry (real parts only at DC and Nyquist).
 hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st);

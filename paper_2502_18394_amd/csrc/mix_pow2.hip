@@ -41,6 +41,19 @@ struct ScrBf16 {
     __device__ static __forceinline__ elem_t put(float2 v) { return IoBf16::pack(v); }
 };
 
+// Head-affine placement (aff = heads in the launch, a multiple of 8; 0 = off).  Workgroup ids are dealt round-robin
+// to the 8 XCDs, each with its own L2.  Here the per_head workgroups of head 8 * slot + xcd all get ids congruent to
+// xcd mod 8, so a head's scratch is written and read through one L2, and the three kernels walk the slots in
+// alternating order (row transforms up, column kernel down, inverse row transforms up), so that each starts with
+// what its predecessor wrote last.  Pays when a few heads' scratch fits one 4 MB L2 (L <= 8192).
+__device__ __forceinline__ void head_affine(int id, int per_head, int aff, bool reverse, int *bhl, int *within) {
+    const int xcd = id & 7, idx = id >> 3;
+    int slot = idx / per_head;
+    *within = idx - slot * per_head;
+    if (reverse) slot = aff / 8 - 1 - slot;
+    *bhl = 8 * slot + xcd;
+}
+
 // small_fwd: grid (N1/TT, nbh); block 32*TT threads.  Reads the N2*TT rows
 // {t1_0 + r + N1*t2} of one head (32 pairs each, one 128 B / 256 B segment per row),
 // stages them in LDS, then lane (pair p, t1_local) runs the N2-point DFT over t2.
@@ -48,14 +61,16 @@ template <int N2, int TT, typename IO, typename SC>
 __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t *__restrict__ v,
                                                        typename SC::elem_t *__restrict__ scr,
                                                        const float2 *__restrict__ twL, int rows, int H,
-                                                       int N1, int bh0) {
+                                                       int N1, int bh0, int aff) {
     typedef typename IO::pair_t pair_t;
     constexpr int S = TileStride<IO>::value;
     extern __shared__ unsigned char smem_raw[];
     pair_t *lds = reinterpret_cast<pair_t *>(smem_raw);
     const int tid = threadIdx.x;
-    const int t1_0 = blockIdx.x * TT;
-    const int bhl = blockIdx.y, bh = bh0 + bhl, b = bh / H, h = bh % H;
+    int tile = blockIdx.x, bhl = blockIdx.y;
+    if (aff) head_affine(blockIdx.x, N1 / TT, aff, false, &bhl, &tile);
+    const int t1_0 = tile * TT;
+    const int bh = bh0 + bhl, b = bh / H, h = bh % H;
     {
         const int lp = tid & 31, r = tid >> 5;
         pair_t val[N2];
@@ -90,14 +105,16 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const typename SC::elem_t
                                                        typename IO::pair_t *__restrict__ out,
                                                        const float2 *__restrict__ twL, int row0,
                                                        int out_rows, int H, int N1, int bh0, int ring0,
-                                                       int ring_w, int newest) {
+                                                       int ring_w, int newest, int aff) {
     typedef typename IO::pair_t pair_t;
     constexpr int S = TileStride<IO>::value;
     extern __shared__ unsigned char smem_raw[];
     pair_t *lds = reinterpret_cast<pair_t *>(smem_raw);
     const int tid = threadIdx.x;
-    const int t1_0 = blockIdx.x * TT;
-    const int bhl = blockIdx.y, bh = bh0 + bhl, b = bh / H, h = bh % H;
+    int tile = blockIdx.x, bhl = blockIdx.y;
+    if (aff) head_affine(blockIdx.x, N1 / TT, aff, false, &bhl, &tile);
+    const int t1_0 = tile * TT;
+    const int bh = bh0 + bhl, b = bh / H, h = bh % H;
     {
         const int tl = tid % TT, p = tid / TT, t1 = t1_0 + tl;
         const typename SC::elem_t *src = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
@@ -176,7 +193,7 @@ __device__ __forceinline__ void exchange(float2 (&x)[16], float2 *buf, int tau) 
 template <int P, int MODE, typename SC>
 __global__ __launch_bounds__(256) void k_big(typename SC::elem_t *__restrict__ scr, const float2 *__restrict__ gp,
                                              const float2 *__restrict__ twN1, int N2, int ppw, int bh0,
-                                             int nplanes_xcd, int g_step) {
+                                             int nplanes_xcd, int g_step, int aff) {
     static_assert(P == 2 || P == 3, "N1 is 256 or 4096");
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
     constexpr bool kCross = (P == 3);                // does the pass 0 <-> 1 exchange span waves?
@@ -191,9 +208,15 @@ __global__ __launch_bounds__(256) void k_big(typename SC::elem_t *__restrict__ s
         const int xcd = blk & 7, idx = blk >> 3;
         blk = ((idx / groups) * 8 + xcd) * groups + idx % groups;
     }
-    const int pg = blk % groups;
+    int pg = blk % groups;
     blk /= groups;
-    const int k2 = blk % N2, bhl = blk / N2;
+    int k2 = blk % N2, bhl = blk / N2;
+    if (aff) {                                       // all planes of a head on one XCD, heads walked downwards
+        int within;
+        head_affine(blockIdx.x, N2 * groups, aff, true, &bhl, &within);
+        pg = within % groups;
+        k2 = within / groups;
+    }
     float2 *buf_f = lds_big + ci * COLW;             // forward exchanges
     float2 *buf_i = buf_f;                           // inverse cross-wave exchange: same buffer
 
@@ -441,27 +464,29 @@ static hipError_t allow_lds(K kernel, size_t bytes) {
 
 template <int N2, int TT, typename IO, typename SC>
 static hipError_t small_fwd_t(const Pow2Plan &pl, const void *v, void *scr_v, int rows, int H, int bh0,
-                              int nbh, hipStream_t st) {
+                              int nbh, hipStream_t st, int aff) {
     const size_t lds = (size_t)N2 * TT * TileStride<IO>::value * sizeof(typename IO::pair_t);
     auto kern = k_small_fwd<N2, TT, IO, SC>;
     typename SC::elem_t *scr = static_cast<typename SC::elem_t *>(scr_v);
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
-    kern<<<dim3(pl.N1 / TT, nbh), dim3(32 * TT), lds, st>>>(
-        static_cast<const typename IO::pair_t *>(v), scr, pl.twL, rows, H, pl.N1, bh0);
+    const dim3 grid = aff ? dim3(pl.N1 / TT * nbh) : dim3(pl.N1 / TT, nbh);
+    kern<<<grid, dim3(32 * TT), lds, st>>>(
+        static_cast<const typename IO::pair_t *>(v), scr, pl.twL, rows, H, pl.N1, bh0, aff);
     return hipGetLastError();
 }
 
 template <int N2, int TT, typename IO, typename SC>
 static hipError_t small_inv_t(const Pow2Plan &pl, const void *scr_v, void *out, int row0, int out_rows,
-                              int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w, int newest) {
+                              int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w, int newest, int aff) {
     const size_t lds = (size_t)N2 * TT * TileStride<IO>::value * sizeof(typename IO::pair_t);
     auto kern = k_small_inv<N2, TT, IO, SC>;
     const typename SC::elem_t *scr = static_cast<const typename SC::elem_t *>(scr_v);
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
-    kern<<<dim3(pl.N1 / TT, nbh), dim3(32 * TT), lds, st>>>(
-        scr, static_cast<typename IO::pair_t *>(out), pl.twL, row0, out_rows, H, pl.N1, bh0, ring0, ring_w, newest);
+    const dim3 grid = aff ? dim3(pl.N1 / TT * nbh) : dim3(pl.N1 / TT, nbh);
+    kern<<<grid, dim3(32 * TT), lds, st>>>(
+        scr, static_cast<typename IO::pair_t *>(out), pl.twL, row0, out_rows, H, pl.N1, bh0, ring0, ring_w, newest, aff);
     return hipGetLastError();
 }
 
@@ -480,21 +505,25 @@ static hipError_t small_inv_t(const Pow2Plan &pl, const void *scr_v, void *out, 
     }
 
 hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
-                            int bh0, int nbh, hipStream_t st, bool scr16) {
+                            int bh0, int nbh, hipStream_t st, bool scr16, bool affine) {
     if (scr16 && !io) return hipErrorInvalidValue;
-    SPECTRE_DISPATCH_N2(small_fwd_t, pl, v, scratch, rows, H, bh0, nbh, st)
+    if (affine && nbh % 8 != 0) return hipErrorInvalidValue;
+    const int aff = affine ? nbh : 0;
+    SPECTRE_DISPATCH_N2(small_fwd_t, pl, v, scratch, rows, H, bh0, nbh, st, aff)
 }
 
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
                             int out_rows, int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w,
-                            int newest, bool scr16) {
+                            int newest, bool scr16, bool affine) {
     if (scr16 && !io) return hipErrorInvalidValue;
-    SPECTRE_DISPATCH_N2(small_inv_t, pl, scratch, out, row0, out_rows, H, bh0, nbh, st, ring0, ring_w, newest)
+    if (affine && nbh % 8 != 0) return hipErrorInvalidValue;
+    const int aff = affine ? nbh : 0;
+    SPECTRE_DISPATCH_N2(small_inv_t, pl, scratch, out, row0, out_rows, H, bh0, nbh, st, ring0, ring_w, newest, aff)
 }
 
 template <int P, int MODE, typename SC = ScrF32>
 static hipError_t big_t(const Pow2Plan &pl, float2 *scr_v, const float2 *gp, int bh0, int nbh, bool shared_gate,
-                        hipStream_t st) {
+                        hipStream_t st, int aff = 0) {
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
     const size_t lds = (size_t)CPI * COLW * sizeof(float2);
     const int ppw = (P == 2) ? 16 : 4;   // pairs per workgroup; a multiple of CPI dividing 32
@@ -505,12 +534,18 @@ static hipError_t big_t(const Pow2Plan &pl, float2 *scr_v, const float2 *gp, int
     const unsigned grid = (unsigned)nbh * pl.N2 * (32 / ppw);
     const int planes = nbh * pl.N2;                    // remapping needs the plane count to split 8 ways
     kern<<<dim3(grid), dim3(256), lds, st>>>(scr, gp, pl.twN1, pl.N2, ppw, bh0, planes % 8 == 0 ? planes : 0,
-                                             shared_gate ? 0 : 1);
+                                             shared_gate ? 0 : 1, aff);
     return hipGetLastError();
 }
 
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
-                      hipStream_t st, bool shared_gate, bool scr16) {
+                      hipStream_t st, bool shared_gate, bool scr16, bool affine) {
+    if (affine) {                                      // the mixer's forward-gate-inverse pass, fp32 scratch
+        if (mode != 0 || scr16 || nbh % 8 != 0) return hipErrorInvalidValue;
+        if (pl.P == 2) return big_t<2, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st, nbh);
+        if (pl.P == 3) return big_t<3, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st, nbh);
+        return hipErrorInvalidValue;
+    }
     if (scr16) {                                       // the mixer's forward-gate-inverse pass only
         if (mode != 0) return hipErrorInvalidValue;
         if (pl.P == 2) return big_t<2, 0, ScrBf16>(pl, scratch, gp, bh0, nbh, shared_gate, st);

@@ -139,6 +139,22 @@ def test_patch_grid_length_with_many_heads_takes_its_own_kernel(oracle, monkeypa
     assert e1 <= TOL[io] and e2 <= TOL[io] and e12 <= (1e-6 if io == "f32" else 2e-3)
 
 
+@pytest.mark.parametrize("B,L,H,io", [(1, 8192, 8, "f32"), (2, 8192, 12, "bf16"), (1, 6144, 16, "bf16"), (1, 12288, 8, "f32"),
+                                       (3, 5120, 8, "bf16")])
+def test_head_affine_placement_changes_no_bit(oracle, monkeypatch, B, L, H, io):
+    """Four-step lengths up to 12288 with a multiple of 8 heads in a call place every workgroup of a head on one XCD
+    and walk the heads up, down, up through the three kernels (L2 reuse).  It is only a renumbering of workgroups:
+    the rows must equal those of the plain numbering (SPECTRE_NO_AFFINE) bit for bit, and match the oracle."""
+    seed = synth.BASE_SEED + 23 * H + L
+    monkeypatch.delenv("SPECTRE_NO_AFFINE", raising=False)
+    got, want, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    monkeypatch.setenv("SPECTRE_NO_AFFINE", "1")
+    plain, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    err = rel_l2(got, want)
+    print(f"case B={B} L={L} H={H} io={io}: rel_l2 {err:.3e} identical {np.array_equal(got, plain)}", flush=True)
+    assert err <= TOL[io] and np.array_equal(got, plain)
+
+
 def test_identity_gate_returns_input_on_gpu(oracle):
     B, L, H, d = 1, 4096, 2, 64
     g = np.ones((B, H, L // 2 + 1), np.complex64)
