@@ -283,7 +283,7 @@ def main():
                       "hbm_frac": proj_bytes / (ms_proj * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "tflops": proj_flops / (ms_proj * 1e-3) / 1e12,
                       "what": "spectre_project: V = X W_v per head + pooled query in one pass over X (bf16 rows: "
-                              "32x32x16 bf16 MFMA with two-term weights; fp32 rows: 32x32x2 fp32 MFMA); includes "
+                              "32x32x16 bf16 MFMA with two-term weights; fp32 rows: the same instruction on three-term splits); includes "
                               "allocating the outputs"}
     # wavelet refinement (next-row item) applied to the mixer's output, full depth
     J = synth.max_wavelet_levels(L)

@@ -7,8 +7,8 @@
 // fp64.  Q itself is written only on request (the Prefix-FFT pre-fill keeps the query rows).
 //
 // The products run on the matrix cores: a wave owns 32 rows of one head, the 64 input channels are
-// the reduction axis, two 32-column blocks the outputs.  fp32 rows use v_mfma_f32_32x32x2_f32, bf16
-// rows v_mfma_f32_32x32x16_bf16 with the weights split into two bf16 terms.
+// the reduction axis, two 32-column blocks the outputs.  Both row types use v_mfma_f32_32x32x16_bf16:
+// bf16 rows with the weights split into two bf16 terms, fp32 rows with rows and weights split into three.
 #include "project.h"
 
 #include "common.h"
@@ -18,40 +18,7 @@ namespace spectre {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kProjRows = 512;    // rows of one head per workgroup (4 tiles of 32 per wave; 1024: 3 % slower, 256: 5 %)
-constexpr int kWStride = 65;      // LDS row stride of the weight matrices (floats)
 constexpr int kOStride = 66;      // LDS row stride of a wave's output staging tile (floats)
-
-template <typename IO> struct ProjLoad;
-template <> struct ProjLoad<IoF32> {   // four consecutive channels of a row
-    __device__ static __forceinline__ float4 load(const void *base, size_t elem) {
-        return *reinterpret_cast<const float4 *>(static_cast<const float *>(base) + elem);
-    }
-};
-template <> struct ProjLoad<IoBf16> {
-    __device__ static __forceinline__ float4 load(const void *base, size_t elem) {
-        const uint2 w = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(base) + elem);
-        const float2 a = IoBf16::unpack(w.x), b = IoBf16::unpack(w.y);
-        return make_float4(a.x, a.y, b.x, b.y);
-    }
-};
-
-// One 32 x 64 product of the rows held in a[] (lane l: row l%32, channels 8q + 4*(l/32) + {0..3})
-// with a 64 x 64 matrix in LDS.  MFMA number m of group q pairs channel 8q + m (lanes 0-31) with
-// 8q + 4 + m (lanes 32-63) on both operands.
-__device__ __forceinline__ void proj_mfma(const float4 (&a)[8], const float *__restrict__ w_lds, int lane,
-                                          floatx16 &acc0, floatx16 &acc1) {
-    const int j = lane & 31, half = lane >> 5;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const float av[4] = {a[q].x, a[q].y, a[q].z, a[q].w};
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const float *wr = w_lds + (8 * q + 4 * half + m) * kWStride + j;
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], wr[0], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], wr[32], acc1, 0, 0, 0);
-        }
-    }
-}
 
 // Accumulator register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32 of a block.
 // The tile goes through LDS so that rows leave as whole 128-byte (bf16) / 256-byte (fp32) segments.
@@ -74,73 +41,6 @@ __device__ __forceinline__ void proj_store(const floatx16 &acc0, const floatx16 
         if (row < rows_left) dst[(size_t)row * row_stride_pairs + j] = IO::pack(val);
     }
     __builtin_amdgcn_wave_barrier();
-}
-
-// grid (H, ceil(L / kProjRows), B); 256 lanes.
-template <typename IO, bool WANT_Q>
-__global__ __launch_bounds__(256) void k_project(const void *__restrict__ x, const float *__restrict__ Wq,
-                                                 const float *__restrict__ Wv, int Hw,
-                                                 typename IO::pair_t *__restrict__ v_out,
-                                                 typename IO::pair_t *__restrict__ q_out,
-                                                 double *__restrict__ partial, int L, int H, int nchunks) {
-    extern __shared__ float lds_proj[];
-    float *wv = lds_proj;                                  // [64][kWStride]
-    float *wq = wv + 64 * kWStride;                        // [64][kWStride], only filled when WANT_Q
-    float *stage_all = wq + (WANT_Q ? 64 * kWStride : 0);  // 4 x [32][kOStride]; reused for the pooling
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;   // head fastest: whole token rows in flight
-    const int hw = (Hw == 1) ? 0 : h;
-    for (int idx = tid; idx < 64 * 64; idx += 256) {
-        wv[(idx >> 6) * kWStride + (idx & 63)] = Wv[(size_t)hw * 4096 + idx];
-        if (WANT_Q) wq[(idx >> 6) * kWStride + (idx & 63)] = Wq[(size_t)hw * 4096 + idx];
-    }
-    __syncthreads();
-    float *stage = stage_all + wave * (32 * kOStride);
-    const int i = lane & 31, half = lane >> 5;
-    const size_t rsp = (size_t)H * 32;                     // row stride in channel pairs
-    float pool[32];
-#pragma unroll
-    for (int r = 0; r < 32; ++r) pool[r] = 0.f;
-
-    const int row_end = min(L, (chunk + 1) * kProjRows);
-    for (int r0 = chunk * kProjRows + wave * 32; r0 < row_end; r0 += 128) {
-        const int row = r0 + i;
-        float4 a[8];
-        const size_t elem = (((size_t)b * L + (row < L ? row : 0)) * H + h) * 64 + 4 * half;
-#pragma unroll
-        for (int q = 0; q < 8; ++q)
-            a[q] = (row < L) ? ProjLoad<IO>::load(x, elem + 8 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            pool[4 * q + 0] += a[q].x;
-            pool[4 * q + 1] += a[q].y;
-            pool[4 * q + 2] += a[q].z;
-            pool[4 * q + 3] += a[q].w;
-        }
-        const size_t out_pair = (((size_t)b * L + r0) * H + h) * 32;
-        floatx16 acc0 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, acc1 = acc0;
-        proj_mfma(a, wv, lane, acc0, acc1);
-        proj_store<IO>(acc0, acc1, stage, v_out + out_pair, rsp, L - r0, lane);
-        if (WANT_Q) {
-            floatx16 q0 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, q1 = q0;
-            proj_mfma(a, wq, lane, q0, q1);
-            proj_store<IO>(q0, q1, stage, q_out + out_pair, rsp, L - r0, lane);
-        }
-    }
-    // column sums of X over this workgroup's rows: lane (i, half) holds channels 8q + 4 half + e in
-    // pool[4q + e]; the 32 lanes of a half and the 4 waves are added in a fixed order, in fp64
-    __syncthreads();
-    float *red = stage_all;                                // [4 waves][64 lanes][33]
-#pragma unroll
-    for (int r = 0; r < 32; ++r) red[(wave * 64 + lane) * 33 + r] = pool[r];
-    __syncthreads();
-    if (tid < 64) {
-        const int c = tid, q = c >> 3, hf = (c >> 2) & 1, e = c & 3;
-        double s = 0.0;
-        for (int w = 0; w < 4; ++w)
-            for (int l = 0; l < 32; ++l) s += (double)red[(w * 64 + hf * 32 + l) * 33 + 4 * q + e];
-        partial[((size_t)b * nchunks + chunk) * (H * 64) + h * 64 + c] = s;
-    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -254,6 +154,140 @@ __global__ __launch_bounds__(256) void k_project_bf16(const uint16_t *__restrict
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// fp32 rows on the bf16 matrix instruction: v_mfma_f32_32x32x2_f32 runs at 1/16 of the bf16 rate, which made the
+// fp32 projection matrix-core-bound.  Every fp32 value is the exact sum of three bf16 terms up to 2^-27 of itself
+// (x1 = bf16(x), x2 = bf16(x - x1), x3 = bf16(x - x1 - x2); the subtractions are exact), so x w is evaluated as the six
+// products x1 w1, x1 w2, x2 w1, x1 w3, x2 w2, x3 w1 (each exact in the fp32 accumulator's input precision), smallest
+// first; the three dropped products are below 2^-26 |x w|, i.e. below the rounding of the fp32 accumulation.  Six bf16
+// instructions of 32 cycles replace sixteen fp32 ones of 64.
+__device__ __forceinline__ void proj_fill_w_bf16x3(const float *__restrict__ W, uint4 *__restrict__ w1,
+                                                   uint4 *__restrict__ w2, uint4 *__restrict__ w3, int tid) {
+    for (int idx = tid; idx < 4 * 2 * 64; idx += 256) {
+        const int lane = idx & 63, cb = (idx >> 6) & 1, ks = idx >> 7;
+        const int j = cb * 32 + (lane & 31), k0 = 16 * ks + 8 * (lane >> 5);
+        bf16x8 t1, t2, t3;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float w = W[(k0 + e) * 64 + j];
+            const __bf16 b1 = (__bf16)w;
+            const float r1 = w - (float)b1;
+            const __bf16 b2 = (__bf16)r1;
+            const float r2 = r1 - (float)b2;
+            t1[e] = b1;
+            t2[e] = b2;
+            t3[e] = (__bf16)r2;
+        }
+        w1[idx] = __builtin_bit_cast(uint4, t1);
+        w2[idx] = __builtin_bit_cast(uint4, t2);
+        w3[idx] = __builtin_bit_cast(uint4, t3);
+    }
+}
+
+struct Split3 {
+    bf16x8 t1[4], t2[4], t3[4];      // per k-step: the lane's 8 channels as three bf16 terms
+};
+
+__device__ __forceinline__ void proj_mfma_split(const Split3 &a, const uint4 *__restrict__ w1,
+                                                const uint4 *__restrict__ w2, const uint4 *__restrict__ w3, int lane,
+                                                floatx16 &acc0, floatx16 &acc1) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        const int i0 = (ks * 2 + 0) * 64 + lane, i1 = (ks * 2 + 1) * 64 + lane;
+        const bf16x8 p0 = __builtin_bit_cast(bf16x8, w1[i0]), p1 = __builtin_bit_cast(bf16x8, w1[i1]);
+        const bf16x8 q0 = __builtin_bit_cast(bf16x8, w2[i0]), q1 = __builtin_bit_cast(bf16x8, w2[i1]);
+        const bf16x8 r0 = __builtin_bit_cast(bf16x8, w3[i0]), r1 = __builtin_bit_cast(bf16x8, w3[i1]);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t1[ks], r0, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t1[ks], r1, acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t3[ks], p0, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t3[ks], p1, acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t2[ks], q0, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t2[ks], q1, acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t1[ks], q0, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t1[ks], q1, acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t2[ks], p0, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t2[ks], p1, acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t1[ks], p0, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.t1[ks], p1, acc1, 0, 0, 0);
+    }
+}
+
+// grid (H, ceil(L / kProjRows), B); 256 lanes.  Lane l holds row l%32 and channels 16 ks + 8 (l/32) .. +7 of k-step ks.
+template <bool WANT_Q>
+__global__ __launch_bounds__(256) void k_project_f32(const float *__restrict__ x, const float *__restrict__ Wq,
+                                                     const float *__restrict__ Wv, int Hw,
+                                                     float2 *__restrict__ v_out, float2 *__restrict__ q_out,
+                                                     double *__restrict__ partial, int L, int H, int nchunks) {
+    extern __shared__ float lds_proj[];
+    uint4 *wv1 = reinterpret_cast<uint4 *>(lds_proj);      // 512 x 16 B each
+    uint4 *wv2 = wv1 + 512, *wv3 = wv2 + 512;
+    uint4 *wq1 = wv3 + 512, *wq2 = wq1 + 512, *wq3 = wq2 + 512;
+    float *stage_all = reinterpret_cast<float *>(WANT_Q ? wq3 + 512 : wv3 + 512);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;   // head fastest: whole token rows in flight
+    const int hw = (Hw == 1) ? 0 : h;
+    proj_fill_w_bf16x3(Wv + (size_t)hw * 4096, wv1, wv2, wv3, tid);
+    if (WANT_Q) proj_fill_w_bf16x3(Wq + (size_t)hw * 4096, wq1, wq2, wq3, tid);
+    __syncthreads();
+    float *stage = stage_all + wave * (32 * kOStride);
+    const int i = lane & 31, half = lane >> 5;
+    const size_t rsp = (size_t)H * 32;
+    float pool[32];
+#pragma unroll
+    for (int r = 0; r < 32; ++r) pool[r] = 0.f;
+
+    const int row_end = min(L, (chunk + 1) * kProjRows);
+    for (int r0 = chunk * kProjRows + wave * 32; r0 < row_end; r0 += 128) {
+        const int row = r0 + i;
+        const float *src = x + (((size_t)b * L + (row < L ? row : 0)) * H + h) * 64 + 8 * half;
+        float4 raw[8];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            raw[2 * ks] = (row < L) ? *reinterpret_cast<const float4 *>(src + 16 * ks) : make_float4(0.f, 0.f, 0.f, 0.f);
+            raw[2 * ks + 1] = (row < L) ? *reinterpret_cast<const float4 *>(src + 16 * ks + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        Split3 a;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const float xv[8] = {raw[2 * ks].x, raw[2 * ks].y, raw[2 * ks].z, raw[2 * ks].w,
+                                 raw[2 * ks + 1].x, raw[2 * ks + 1].y, raw[2 * ks + 1].z, raw[2 * ks + 1].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pool[8 * ks + e] += xv[e];
+                const __bf16 b1 = (__bf16)xv[e];
+                const float r1 = xv[e] - (float)b1;
+                const __bf16 b2 = (__bf16)r1;
+                const float r2 = r1 - (float)b2;
+                a.t1[ks][e] = b1;
+                a.t2[ks][e] = b2;
+                a.t3[ks][e] = (__bf16)r2;
+            }
+        }
+        const size_t out_pair = (((size_t)b * L + r0) * H + h) * 32;
+        floatx16 acc0 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, acc1 = acc0;
+        proj_mfma_split(a, wv1, wv2, wv3, lane, acc0, acc1);
+        proj_store<IoF32>(acc0, acc1, stage, v_out + out_pair, rsp, L - r0, lane);
+        if (WANT_Q) {
+            floatx16 q0 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, q1 = q0;
+            proj_mfma_split(a, wq1, wq2, wq3, lane, q0, q1);
+            proj_store<IoF32>(q0, q1, stage, q_out + out_pair, rsp, L - r0, lane);
+        }
+    }
+    // column sums: lane (i, half) holds channel 16 ks + 8 half + e in pool[8 ks + e]
+    __syncthreads();
+    float *red = stage_all;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) red[(wave * 64 + lane) * 33 + r] = pool[r];
+    __syncthreads();
+    if (tid < 64) {
+        const int c = tid, ks = c >> 4, hf = (c >> 3) & 1, e = c & 7;
+        double s = 0.0;
+        for (int w = 0; w < 4; ++w)
+            for (int l = 0; l < 32; ++l) s += (double)red[(w * 64 + hf * 32 + l) * 33 + 8 * ks + e];
+        partial[((size_t)b * nchunks + chunk) * (H * 64) + h * 64 + c] = s;
+    }
+}
+
 // sum_q[b,h,j] = sum_i sum_x[b,h,i] Wq[h,i,j] in fp64.  One workgroup of 64 lanes per (b,h).
 __global__ __launch_bounds__(64) void k_project_pooled(const double *__restrict__ sum_x, const float *__restrict__ Wq,
                                                        int Hw, int H, double *__restrict__ sum_q) {
@@ -267,27 +301,6 @@ __global__ __launch_bounds__(64) void k_project_pooled(const double *__restrict_
 }
 
 int project_chunks(int L) { return (L + kProjRows - 1) / kProjRows; }
-
-size_t project_lds_bytes(bool want_q) {
-    const size_t stage = (size_t)4 * 32 * kOStride, red = (size_t)4 * 64 * 33;
-    return ((size_t)64 * kWStride * (want_q ? 2 : 1) + (stage > red ? stage : red)) * sizeof(float);
-}
-
-template <typename IO, bool WANT_Q>
-static hipError_t project_t(const void *x, const float *Wq, const float *Wv, int Hw, void *v_out, void *q_out,
-                            double *partial, int B, int L, int H, hipStream_t st) {
-    const size_t lds = project_lds_bytes(WANT_Q);
-    auto kern = k_project<IO, WANT_Q>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    const int nch = project_chunks(L);
-    kern<<<dim3(H, nch, B), dim3(256), lds, st>>>(x, Wq, Wv, Hw, static_cast<typename IO::pair_t *>(v_out),
-                                                  static_cast<typename IO::pair_t *>(q_out), partial, L, H, nch);
-    return hipGetLastError();
-}
 
 hipError_t launch_project(int io, const void *x, const float *Wq, const float *Wv, int Hw, void *v_out, void *q_out,
                           double *partial, int B, int L, int H, hipStream_t st) {
@@ -312,8 +325,27 @@ hipError_t launch_project(int io, const void *x, const float *Wq, const float *W
         }
         return hipGetLastError();
     }
-    return q_out ? project_t<IoF32, true>(x, Wq, Wv, Hw, v_out, q_out, partial, B, L, H, st)
-                 : project_t<IoF32, false>(x, Wq, Wv, Hw, v_out, q_out, partial, B, L, H, st);
+    {
+        const size_t stage = (size_t)4 * 32 * kOStride, red = (size_t)4 * 64 * 33;
+        const size_t lds = (size_t)512 * 16 * (q_out ? 6 : 3) + (stage > red ? stage : red) * sizeof(float);
+        const int nch = project_chunks(L);
+        dim3 grid(H, nch, B);
+        if (q_out) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_project_f32<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            k_project_f32<true><<<grid, 256, lds, st>>>(static_cast<const float *>(x), Wq, Wv, Hw,
+                                                        static_cast<float2 *>(v_out), static_cast<float2 *>(q_out),
+                                                        partial, L, H, nch);
+        } else {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_project_f32<false>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            k_project_f32<false><<<grid, 256, lds, st>>>(static_cast<const float *>(x), Wq, Wv, Hw,
+                                                         static_cast<float2 *>(v_out), nullptr, partial, L, H, nch);
+        }
+        return hipGetLastError();
+    }
 }
 
 hipError_t launch_project_pooled(const double *sum_x, const float *Wq, int Hw, int B, int H, double *sum_q,
