@@ -54,6 +54,38 @@ __device__ __forceinline__ void head_affine(int id, int per_head, int aff, bool 
     *bhl = 8 * slot + xcd;
 }
 
+// exp(-j 2 pi t1 k2 / L) for k2 = 1 .. N2-1.  Only the powers of two are read from the table (five loads instead of
+// 31 scattered ones at N2 = 32: the gathers were most of the kernel's cache-line requests).  With k2 = 4a + b the
+// others are hi[a] * lo[b], products of at most five table values in all, i.e. within 4 rounding errors of the table
+// value; only hi and lo stay in registers, the product is formed where it is used.
+template <int N2>
+struct SmallTwiddles {
+    float2 lo[4], hi[8];
+    __device__ __forceinline__ SmallTwiddles(const float2 *__restrict__ twL, int t1) {
+        float2 p[5];
+#pragma unroll
+        for (int e = 0; e < 5; ++e) p[e] = ((1 << e) < N2) ? twL[t1 << e] : make_float2(1.f, 0.f);
+        lo[0] = make_float2(1.f, 0.f);
+        lo[1] = p[0];
+        lo[2] = p[1];
+        lo[3] = cmul(p[1], p[0]);
+        hi[0] = make_float2(1.f, 0.f);
+        hi[1] = p[2];
+        hi[2] = p[3];
+        hi[3] = cmul(p[3], p[2]);
+        hi[4] = p[4];
+        hi[5] = cmul(p[4], p[2]);
+        hi[6] = cmul(p[4], p[3]);
+        hi[7] = cmul(p[4], hi[3]);
+    }
+    __device__ __forceinline__ float2 operator()(int k2) const {     // k2 a compile-time constant after unrolling
+        const int a = k2 >> 2, b = k2 & 3;
+        if (a == 0) return lo[b];
+        if (b == 0) return hi[a];
+        return cmul(hi[a], lo[b]);
+    }
+};
+
 // small_fwd: grid (N1/TT, nbh); block 32*TT threads.  Reads the N2*TT rows
 // {t1_0 + r + N1*t2} of one head (32 pairs each, one 128 B / 256 B segment per row),
 // stages them in LDS, then lane (pair p, t1_local) runs the N2-point DFT over t2.
@@ -89,9 +121,10 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
     for (int t2 = 0; t2 < N2; ++t2) x[t2] = IO::unpack(lds[(t2 * TT + tl) * S + p]);
     small_dft<N2, false>(x);
     typename SC::elem_t *dst = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
+    const SmallTwiddles<N2> tw(twL, t1);
 #pragma unroll
     for (int k2 = 0; k2 < N2; ++k2) {
-        const float2 y = (k2 == 0) ? x[0] : cmul(x[k2], twL[t1 * k2]);
+        const float2 y = (k2 == 0) ? x[0] : cmul(x[k2], tw(k2));
         dst[(size_t)k2 * 32 * N1] = SC::put(y);
     }
 }
@@ -124,8 +157,9 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const typename SC::elem_t
         float2 y[N2];
 #pragma unroll
         for (int k2 = 0; k2 < N2; ++k2) y[k2] = SC::get(raw[k2]);
+        const SmallTwiddles<N2> tw(twL, t1);
 #pragma unroll
-        for (int k2 = 1; k2 < N2; ++k2) y[k2] = cmulc(y[k2], twL[t1 * k2]);
+        for (int k2 = 1; k2 < N2; ++k2) y[k2] = cmulc(y[k2], tw(k2));
         small_dft<N2, true>(y);
 #pragma unroll
         for (int t2 = 0; t2 < N2; ++t2) lds[(t2 * TT + tl) * S + p] = IO::pack(y[t2]);
