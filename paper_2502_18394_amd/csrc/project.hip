@@ -87,7 +87,7 @@ __device__ __forceinline__ void proj_mfma_bf16(const uint4 (&a)[4], const uint4 
 }
 
 // grid (H, ceil(L / kProjRows), B); 256 lanes.
-template <bool WANT_Q>
+template <bool WANT_Q, bool MULTI>
 __global__ __launch_bounds__(256) void k_project_bf16(const uint16_t *__restrict__ x, const float *__restrict__ Wq,
                                                       const float *__restrict__ Wv, int Hw,
                                                       uint32_t *__restrict__ v_out, uint32_t *__restrict__ q_out,
@@ -108,8 +108,9 @@ __global__ __launch_bounds__(256) void k_project_bf16(const uint16_t *__restrict
     const int i = lane & 31, half = lane >> 5;
     const size_t rsp = (size_t)H * 32;
     const int row_end = min(L, (chunk + 1) * kProjRows);
-    const int b_end = min(B, ((int)blockIdx.z + 1) * bpw);
-    for (int b = blockIdx.z * bpw; b < b_end; ++b) {   // short sequences: several per workgroup, one weight set-up
+    const int b_first = MULTI ? blockIdx.z * bpw : blockIdx.z;
+    const int b_end = MULTI ? min(B, b_first + bpw) : b_first + 1;
+    for (int b = b_first; b < b_end; ++b) {            // MULTI (short sequences): several per workgroup, one weight set-up
     float pool[32];
 #pragma unroll
     for (int r = 0; r < 32; ++r) pool[r] = 0.f;
@@ -217,7 +218,7 @@ __device__ __forceinline__ void proj_mfma_split(const Split3 &a, const uint4 *__
 }
 
 // grid (H, ceil(L / kProjRows), B); 256 lanes.  Lane l holds row l%32 and channels 16 ks + 8 (l/32) .. +7 of k-step ks.
-template <bool WANT_Q>
+template <bool WANT_Q, bool MULTI>
 __global__ __launch_bounds__(256) void k_project_f32(const float *__restrict__ x, const float *__restrict__ Wq,
                                                      const float *__restrict__ Wv, int Hw,
                                                      float2 *__restrict__ v_out, float2 *__restrict__ q_out,
@@ -237,8 +238,9 @@ __global__ __launch_bounds__(256) void k_project_f32(const float *__restrict__ x
     const int i = lane & 31, half = lane >> 5;
     const size_t rsp = (size_t)H * 32;
     const int row_end = min(L, (chunk + 1) * kProjRows);
-    const int b_end = min(B, ((int)blockIdx.z + 1) * bpw);
-    for (int b = blockIdx.z * bpw; b < b_end; ++b) {   // short sequences: several per workgroup, one weight set-up
+    const int b_first = MULTI ? blockIdx.z * bpw : blockIdx.z;
+    const int b_end = MULTI ? min(B, b_first + bpw) : b_first + 1;
+    for (int b = b_first; b < b_end; ++b) {            // MULTI (short sequences): several per workgroup, one weight set-up
     float pool[32];
 #pragma unroll
     for (int r = 0; r < 32; ++r) pool[r] = 0.f;
@@ -321,49 +323,32 @@ static int project_bpw(int B, int L, int H) {
 
 hipError_t launch_project(int io, const void *x, const float *Wq, const float *Wv, int Hw, void *v_out, void *q_out,
                           double *partial, int B, int L, int H, hipStream_t st) {
-    const int bpw = project_bpw(B, L, H), gz = (B + bpw - 1) / bpw;
+    const int bpw = q_out ? 1 : project_bpw(B, L, H), gz = (B + bpw - 1) / bpw;   // Q rows too: registers are short
+    const size_t stage = (size_t)4 * 32 * kOStride, red = (size_t)4 * 64 * 33;
+    const size_t terms = io ? 2 : 3;                     // bf16 terms per weight
+    const size_t lds = (size_t)512 * 16 * terms * (q_out ? 2 : 1) + (stage > red ? stage : red) * sizeof(float);
+    const int nch = project_chunks(L);
+    const dim3 grid(H, nch, gz);
+#define SPECTRE_PROJECT_LAUNCH(KERN, XT, OT)                                                                  \
+    do {                                                                                                      \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(KERN),                              \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);             \
+        if (e != hipSuccess) return e;                                                                        \
+        KERN<<<grid, 256, lds, st>>>(static_cast<const XT *>(x), Wq, Wv, Hw, static_cast<OT *>(v_out),        \
+                                     static_cast<OT *>(q_out), partial, L, H, nch, B, bpw);                   \
+        return hipGetLastError();                                                                             \
+    } while (0)
+    const bool multi = bpw > 1;
     if (io) {
-        const size_t stage = (size_t)4 * 32 * kOStride, red = (size_t)4 * 64 * 33;
-        const size_t lds = (size_t)512 * 16 * (q_out ? 4 : 2) + (stage > red ? stage : red) * sizeof(float);
-        const int nch = project_chunks(L);
-        dim3 grid(H, nch, gz);
-        if (q_out) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_project_bf16<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            k_project_bf16<true><<<grid, 256, lds, st>>>(static_cast<const uint16_t *>(x), Wq, Wv, Hw,
-                                                         static_cast<uint32_t *>(v_out), static_cast<uint32_t *>(q_out),
-                                                         partial, L, H, nch, B, bpw);
-        } else {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_project_bf16<false>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            k_project_bf16<false><<<grid, 256, lds, st>>>(static_cast<const uint16_t *>(x), Wq, Wv, Hw,
-                                                          static_cast<uint32_t *>(v_out), nullptr, partial, L, H, nch, B, bpw);
-        }
-        return hipGetLastError();
+        if (q_out) SPECTRE_PROJECT_LAUNCH((k_project_bf16<true, false>), uint16_t, uint32_t);
+        else { if (multi) SPECTRE_PROJECT_LAUNCH((k_project_bf16<false, true>), uint16_t, uint32_t);
+               else SPECTRE_PROJECT_LAUNCH((k_project_bf16<false, false>), uint16_t, uint32_t); }
+    } else {
+        if (q_out) SPECTRE_PROJECT_LAUNCH((k_project_f32<true, false>), float, float2);
+        else { if (multi) SPECTRE_PROJECT_LAUNCH((k_project_f32<false, true>), float, float2);
+               else SPECTRE_PROJECT_LAUNCH((k_project_f32<false, false>), float, float2); }
     }
-    {
-        const size_t stage = (size_t)4 * 32 * kOStride, red = (size_t)4 * 64 * 33;
-        const size_t lds = (size_t)512 * 16 * (q_out ? 6 : 3) + (stage > red ? stage : red) * sizeof(float);
-        const int nch = project_chunks(L);
-        dim3 grid(H, nch, gz);
-        if (q_out) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_project_f32<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            k_project_f32<true><<<grid, 256, lds, st>>>(static_cast<const float *>(x), Wq, Wv, Hw,
-                                                        static_cast<float2 *>(v_out), static_cast<float2 *>(q_out),
-                                                        partial, L, H, nch, B, bpw);
-        } else {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_project_f32<false>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            k_project_f32<false><<<grid, 256, lds, st>>>(static_cast<const float *>(x), Wq, Wv, Hw,
-                                                         static_cast<float2 *>(v_out), nullptr, partial, L, H, nch, B, bpw);
-        }
-        return hipGetLastError();
-    }
+#undef SPECTRE_PROJECT_LAUNCH
 }
 
 hipError_t launch_project_pooled(const double *sum_x, const float *Wq, int Hw, int B, int H, double *sum_q,
