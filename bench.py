@@ -39,7 +39,6 @@ def parse():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=32)
-    ap.add_argument("--no-membw", action="store_true", help="skip the streaming-bandwidth probe")
     ap.add_argument("--no-secondary", action="store_true",
                     help="skip the secondary decode row (window of 65536 slots), e.g. under a profiler so that every\n"
                          "cache kernel in the trace belongs to the decode_32k workload")
@@ -120,25 +119,6 @@ def cpu_baseline(cfg, L):
     full = dt * (cfg["B"] * H / Hs)
     return {"value": cfg["B"] * L / full, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"gate+mix_forward of {Hs} of {cfg['B'] * H} heads at L={L} took {dt:.2f} s, scaled to all heads"}
-
-
-def membw_probe():
-    """Measured streaming bandwidth of this GPU (child process: paper_2502_18394_amd/membw_probe)."""
-    import subprocess
-    exe = os.path.join(ROOT, "paper_2502_18394_amd", "membw_probe")
-    if not os.path.exists(exe):
-        return None
-    try:
-        out = subprocess.run([exe, "128", "4096"], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True,
-                             timeout=120).stdout
-    except Exception as e:   # the probe is informative only
-        return {"error": str(e)}
-    res = {"unit": "GB/s", "what": "grid-stride float4 kernels; read, write, in-place read+write, copy"}
-    for line in out.splitlines():
-        f = line.split()
-        if len(f) == 5 and f[0].isdigit():
-            res[f"{f[0]}MB"] = dict(zip(("read", "write", "rw", "copy"), (float(x) for x in f[1:])))
-    return res
 
 
 def sweep(args):
@@ -297,14 +277,11 @@ def main():
                   "what": "spectre_wrm_apply: V + iDWT(s * DWT(V)), Haar, one gate per band and channel"}
     if cfg["io"] == "bf16" and not args.no_secondary and binding.mix_workspace_bytes(B, L, H, d, binding.BF16) > 256:
         # opt-in variant, reported beside the default and never as `value`: bfloat16 pairs between the three kernels
-        os.environ["SPECTRE_SCRATCH_BF16"] = "1"
-        try:
-            ms16 = time_loop(mix_only, args.steps, 2)
-        finally:
-            del os.environ["SPECTRE_SCRATCH_BF16"]
+        ms16 = time_loop(lambda: binding.mix_forward(V, g, out=out, ws=ws_mix, flags=binding.MIX_BF16_SCRATCH),
+                         args.steps, 2)
         res["mix_only_bf16_scratch"] = {"ms": ms16, "tokens_per_s": tokens / (ms16 * 1e-3),
                                         "hbm_frac": mix_bytes / (ms16 * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                        "what": "SPECTRE_SCRATCH_BF16=1: same call, fp32 arithmetic, the two exchanges "
+                                        "what": "flag SPECTRE_MIX_BF16_SCRATCH: same call, fp32 arithmetic, the two exchanges "
                                                 "between the kernels in bfloat16 (rel-L2 2.9e-3 instead of 1.7e-3)"}
     del V, Q, out, g, ws_mix, ws_gate, P, Wq, Wv, ws_proj, s_lv, ws_wrm, wrm_out
     torch.cuda.empty_cache()
@@ -417,8 +394,6 @@ def main():
             del cache, Pw
             torch.cuda.empty_cache()
 
-    if not args.no_membw:
-        res["membw_probe"] = membw_probe()
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_baseline(cfg, L)
     print(json.dumps(res), flush=True)

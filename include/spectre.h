@@ -18,32 +18,23 @@
  *   - F = floor(n/2) + 1 is the number of stored bins of an n-point real
  *     transform (App. B, Cor. B.2).  The forward transform is unnormalised
  *     (Eq. 1), the inverse carries 1/n.
- *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL =
- *     the default stream) and return without synchronising.  Inputs are never
- *     modified; outputs are fully overwritten; results are bitwise reproducible
- *     from run to run.  A long spectre_mix_forward call runs every other head group
- *     on a helper stream of the library's own (default priority), forked from and
- *     joined back into `stream` with events: to the caller the call still behaves
- *     as work enqueued on `stream`, also under HIP graph capture.  Six environment
- *     variables exist for measurements: SPECTRE_ONE_LANE (any value) keeps every
- *     group on `stream`; SPECTRE_CHUNK_MB=<n> sets the total size of the transform
- *     scratch in flight (default 204, sized for the 256 MB memory-side cache);
- *     SPECTRE_NO_FUSED (any value) sends n = 4096 through the three four-step kernels
- *     instead of the single kernel it has of its own; SPECTRE_SCRATCH_BF16 (any value;
- *     bfloat16 rows on the four-step route only) lets the complex numbers cross between the
- *     three kernels as two bfloat16 instead of two fp32: the arithmetic stays fp32, the error
- *     against the exact result grows from about 1.7e-3 (the rounding of the output rows) to
- *     about 2.9e-3, and a call at n = 131072 takes about 14 % less time.  Off by default: the
- *     spectrum then no longer exists in fp32 between the kernels.  SPECTRE_NO_SLAB_CT (any value)
- *     makes the in-LDS kernel take its run-time-length form also for the lengths that have a
- *     compile-time form (196, 256, 512, 1024, 2048); SPECTRE_NO_AFFINE (any value) switches off
- *     the placement of all workgroups of a head on one XCD that four-step lengths up to 12288
- *     use when a call has a multiple of 8 heads.  They are read at every call and
- *     must not change between a *_workspace_bytes query and the call it sizes.
+ *   - Compute calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and return: they never allocate device or pinned memory, never
+ *     copy from the host, never create streams or events and never synchronise, so they may
+ *     be captured into a HIP graph.  Everything of that kind happens in spectre_prepare
+ *     (and in spectre_prefix_init, which calls it): a compute call for a transform length
+ *     that has not been prepared on the current device returns SPECTRE_ENOTREADY and
+ *     enqueues nothing.  Inputs are never modified; outputs are fully overwritten; results
+ *     are bitwise reproducible from run to run.  A long spectre_mix_forward call runs every
+ *     other head group on a helper stream of the library's own (default priority, made by
+ *     spectre_prepare), forked from and joined back into `stream` with events: to the
+ *     caller the call still behaves as work enqueued on `stream`, also under HIP graph
+ *     capture.  The library reads no environment variable; spectre_set_option holds the few
+ *     tuning switches that exist for measurements, none of which changes a result.
  *   - The caller owns every buffer, including the scratch workspace `ws`, whose
  *     minimum size the matching *_workspace_bytes function returns.  The library
- *     itself only keeps small per-device read-only tables (roots of unity) and a
- *     helper stream with two events, created on first use and kept until
+ *     itself only keeps small per-device read-only tables (roots of unity, bin orders)
+ *     and a helper stream with three events, created by spectre_prepare and kept until
  *     spectre_shutdown().
  *   - Every function returning int returns a spectre_status; on failure nothing
  *     has been enqueued (argument errors are detected on the host before any
@@ -74,7 +65,8 @@ typedef enum {
     SPECTRE_EINVAL = 1,       /* null pointer, non-positive size, overlapping in/out, bad enum */
     SPECTRE_EUNSUPPORTED = 2, /* valid request this build has no kernel for (length, d, ...)   */
     SPECTRE_EWORKSPACE = 3,   /* ws == NULL or ws_bytes below the *_workspace_bytes figure      */
-    SPECTRE_EHIP = 4          /* a HIP runtime call failed; text in spectre_last_error()        */
+    SPECTRE_EHIP = 4,         /* a HIP runtime call failed; text in spectre_last_error()        */
+    SPECTRE_ENOTREADY = 5     /* spectre_prepare has not been called for this length and device */
 } spectre_status;
 
 typedef enum { SPECTRE_F32 = 0, SPECTRE_BF16 = 1 } spectre_dtype;
@@ -88,8 +80,40 @@ int spectre_version(void);
 /* 1 if an n-point transform is available for channel count d, else 0. */
 int spectre_length_supported(int n, int d);
 
-/* Frees the per-device tables.  Optional; safe to call more than once. */
+/*
+ * spectre_prepare - set-up for transform length n (a mixer length L, or a cache window N_mem + N_max)
+ * with d channels per head, on the current device: builds the read-only tables every kernel route of
+ * that length uses (values computed in fp64 on the host, copied once) and, the first time, the helper
+ * stream and its events.  This is the one call that allocates, copies and synchronises; it is
+ * idempotent and cheap when there is nothing left to do.  Returns SPECTRE_EUNSUPPORTED when no
+ * kernel exists for (n, d).  Not to be called while a stream of the device is being captured.
+ */
+int spectre_prepare(int n, int d);
+
+/* Frees the per-device tables and helper streams (lengths must be prepared again afterwards).
+ * Optional; safe to call more than once. */
 void spectre_shutdown(void);
+
+/*
+ * Tuning switches for measurements and tests.  Process-wide, host-side, read at every call; they
+ * must not change between a *_workspace_bytes query and the call it sizes.  None changes a result
+ * (the same arithmetic in the same order; at most which of two kernels of identical arithmetic
+ * runs, where tests compare the two).  value < 0 restores the default.
+ *   SPECTRE_OPT_LANES              1 keeps every head group of a long spectre_mix_forward call on
+ *                                  `stream`; 2 (default) alternates them with the helper stream
+ *   SPECTRE_OPT_SCRATCH_MB         total transform scratch in flight, MiB (default 204: sized for
+ *                                  the 256 MB memory-side cache)
+ *   SPECTRE_OPT_FUSED_4096         0 sends n = 4096 through the three four-step kernels instead of
+ *                                  the single kernel it has of its own (default 1)
+ *   SPECTRE_OPT_SLAB_COMPILE_TIME  0 makes the in-LDS kernel take its run-time-length form also
+ *                                  for the lengths that have a compile-time form (default 1)
+ *   SPECTRE_OPT_HEAD_AFFINE        0 switches off the placement of all workgroups of a head on one
+ *                                  XCD that four-step lengths up to 12288 use (default 1)
+ */
+enum { SPECTRE_OPT_LANES = 0, SPECTRE_OPT_SCRATCH_MB = 1, SPECTRE_OPT_FUSED_4096 = 2,
+       SPECTRE_OPT_SLAB_COMPILE_TIME = 3, SPECTRE_OPT_HEAD_AFFINE = 4, SPECTRE_OPT_COUNT_ = 5 };
+int spectre_set_option(int which, long value);
+long spectre_get_option(int which);
 
 /* ------------------------------------------------------------------------------------------
  * Gate parameters (Sec. 3.2 step 3a and 3c; the same network serves Algorithm 1's decode gate).
@@ -211,6 +235,19 @@ size_t spectre_mix_workspace_bytes(int B, int L, int H, int d, spectre_dtype io)
 int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, int H, int d,
                         spectre_dtype io, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * spectre_mix_forward_ex - the same call with option flags (flags = 0 is spectre_mix_forward).
+ *   SPECTRE_MIX_BF16_SCRATCH   bfloat16 rows on the four-step route only (ignored elsewhere): the
+ *        complex numbers that cross between the three kernels of that route are stored as two
+ *        bfloat16 instead of two fp32.  The arithmetic stays fp32, the error against the exact
+ *        result grows from about 1.7e-3 (the rounding of the output rows) to about 2.9e-3, and a
+ *        call at n = 131072 takes about 14 % less time.  The spectrum then no longer exists in
+ *        fp32 between the kernels, which is why it has to be asked for.
+ */
+enum { SPECTRE_MIX_BF16_SCRATCH = 1 };
+int spectre_mix_forward_ex(const void *v, const void *g, void *out, int B, int L, int H, int d,
+                           spectre_dtype io, unsigned flags, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Prefix-FFT cache, Sec. 3.3 and Algorithm 1.  One cache serves B*H heads that advance in
  * lock-step (one token counter).  The caller allocates the five device arrays (sizes from
@@ -254,7 +291,8 @@ enum { SPECTRE_PREFIX_FFT = 0, SPECTRE_PREFIX_VBUF = 1, SPECTRE_PREFIX_QBUF = 2,
  * rows; 0 on bad arguments. */
 size_t spectre_prefix_bytes(int B, int H, int d, int n, int which);
 
-/* Zeroes the state, fills the twiddle table (computed in fp64, rounded once), sets t = 0. */
+/* Zeroes the state, fills the twiddle table (computed in fp64, rounded once), sets t = 0.  A set-up
+ * call: it runs spectre_prepare(N_mem + N_max, d) first, so it may allocate and synchronise. */
 int spectre_prefix_init(spectre_prefix_cache *cache /*host*/, void *stream);
 
 /* Applies the pending deferred updates (one sweep over the cache); a no-op when there are none.

@@ -15,7 +15,9 @@ LIB_PATH = os.path.join(_HERE, "libspectre_hip.so")
 
 F32, BF16 = 0, 1
 READ_NEWEST, READ_WINDOW = 0, 1
-OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ENOTREADY = 0, 1, 2, 3, 4, 5
+OPT_LANES, OPT_SCRATCH_MB, OPT_FUSED_4096, OPT_SLAB_COMPILE_TIME, OPT_HEAD_AFFINE = 0, 1, 2, 3, 4
+MIX_BF16_SCRATCH = 1
 
 _lib = None
 
@@ -62,6 +64,7 @@ def lib():
                      "spectre_prefix_update_workspace_bytes", "spectre_prefix_readout_workspace_bytes",
                      "spectre_prefix_step_workspace_bytes", "spectre_prefix_set_memory_workspace_bytes"):
             getattr(L, name).restype = ctypes.c_size_t
+        L.spectre_get_option.restype = ctypes.c_long
         _lib = L
     return _lib
 
@@ -106,22 +109,52 @@ def length_supported(n, d):
     return bool(lib().spectre_length_supported(ctypes.c_int(n), ctypes.c_int(d)))
 
 
+_prepared = set()
+
+
+def prepare(n, d=64):
+    """Set-up for transform length n on the current device (tables, helper stream): the library's one call that
+    allocates and synchronises.  The functions below call it the first time they see a length."""
+    key = (torch.cuda.current_device(), int(n), int(d))
+    if key not in _prepared:
+        _check(lib().spectre_prepare(ctypes.c_int(n), ctypes.c_int(d)))
+        _prepared.add(key)
+
+
+def shutdown():
+    """Free the library's tables and helper streams; lengths are prepared again on their next use."""
+    lib().spectre_shutdown()
+    _prepared.clear()
+
+
+def set_option(which, value):
+    """Tuning switch `which` (one of the OPT_* constants) := value; value < 0 restores the default."""
+    _check(lib().spectre_set_option(ctypes.c_int(which), ctypes.c_long(value)))
+
+
+def get_option(which):
+    return int(lib().spectre_get_option(ctypes.c_int(which)))
+
+
 def mix_workspace_bytes(B, L, H, d, io):
     return int(lib().spectre_mix_workspace_bytes(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H),
                                                  ctypes.c_int(d), ctypes.c_int(io)))
 
 
-def mix_forward(v, g, out=None, ws=None, stream=None):
-    """out[b,:,h,c] = irfft_L(g[b,h,:] * rfft_L(v[b,:,h,c])); v [B,L,H,d] f32/bf16, g complex64 [B,H,L//2+1]."""
+def mix_forward(v, g, out=None, ws=None, stream=None, flags=0):
+    """out[b,:,h,c] = irfft_L(g[b,h,:] * rfft_L(v[b,:,h,c])); v [B,L,H,d] f32/bf16, g complex64 [B,H,L//2+1].
+    flags: 0 or MIX_BF16_SCRATCH (see spectre_mix_forward_ex)."""
     B, L, H, d = v.shape
+    prepare(L, d)
     io = _dtype_code(v)
     if g.dtype != torch.complex64 or tuple(g.shape) != (B, H, L // 2 + 1):
         raise ValueError("g must be complex64 [B,H,L//2+1]")
     if out is None:
         out = torch.empty_like(v)
     ws, wsp, wsn = _workspace(mix_workspace_bytes(B, L, H, d, io), v.device, ws)
-    _check(lib().spectre_mix_forward(_dev(v, "v"), _dev(g, "g"), _dev(out, "out"), ctypes.c_int(B), ctypes.c_int(L),
-                                     ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(io), wsp, wsn, _stream(stream)))
+    _check(lib().spectre_mix_forward_ex(_dev(v, "v"), _dev(g, "g"), _dev(out, "out"), ctypes.c_int(B), ctypes.c_int(L),
+                                        ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(io), ctypes.c_uint(flags),
+                                        wsp, wsn, _stream(stream)))
     return out
 
 
@@ -299,6 +332,7 @@ class PrefixCache:
         """mem float32 [1 or B, H, N_mem, d]: the persistent memory rows; call once, before any token."""
         if mem.dtype != torch.float32 or mem.ndim != 4 or tuple(mem.shape[1:]) != (self.H, self.N_mem, self.d):
             raise ValueError("mem must be float32 [1 or B, H, N_mem, d]")
+        prepare(self.n, self.d)
         need = lib().spectre_prefix_set_memory_workspace_bytes(ctypes.byref(self.c))
         self._ws, wsp, wsn = _workspace(need, mem.device, self._ws)
         _check(lib().spectre_prefix_set_memory(ctypes.byref(self.c), _dev(mem, "mem"), ctypes.c_int(mem.shape[0]),
@@ -320,6 +354,7 @@ class PrefixCache:
         B, T, H, d = v_new.shape
         assert (B, H, d) == (self.B, self.H, self.d) and q_new.shape == v_new.shape and q_new.dtype == v_new.dtype
         io = _dtype_code(v_new)
+        prepare(self.n, self.d)
         need = lib().spectre_prefix_update_workspace_bytes(ctypes.byref(self.c), ctypes.c_int(T), ctypes.c_int(io))
         self._ws, wsp, wsn = _workspace(need, v_new.device, self._ws)
         _check(lib().spectre_prefix_update(ctypes.byref(self.c), _dev(v_new, "v_new"), _dev(q_new, "q_new"),
@@ -327,6 +362,7 @@ class PrefixCache:
 
     def readout(self, g, mode=READ_NEWEST, dtype=torch.float32, stream=None):
         io = F32 if dtype == torch.float32 else BF16
+        prepare(self.n, self.d)
         rows = 1 if mode == READ_NEWEST else min(self.t, self.N)
         out = torch.empty((self.B, rows, self.H, self.d), dtype=dtype, device=g.device)
         need = lib().spectre_prefix_readout_workspace_bytes(ctypes.byref(self.c), ctypes.c_int(mode), ctypes.c_int(io))

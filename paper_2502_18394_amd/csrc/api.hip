@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -25,6 +26,14 @@
 namespace spectre {
 
 static thread_local std::string g_err;
+
+// Process-wide tuning switches (spectre_set_option); none of them changes a result.
+static std::atomic<long> g_opt[SPECTRE_OPT_COUNT_];
+static const long kOptDefault[SPECTRE_OPT_COUNT_] = {2, 204, 1, 1, 1};
+long option(int which) {
+    const long v = g_opt[which].load(std::memory_order_relaxed);
+    return v > 0 ? v - 1 : kOptDefault[which];       // stored as value + 1 so that zero-initialised = default
+}
 
 int fail(int code, const char *fmt, ...) {
     char buf[512];
@@ -53,6 +62,7 @@ struct DeviceTables {
     std::map<int, float2 *> chirp;   // L -> device array: chirp [L], then its filter spectrum [M]
     std::map<int, int *> slab_order; // L -> device array [L]: bin held by each position of the in-LDS transform
     std::vector<struct SideLane *> lanes;   // idle helper streams (with their fork/join events)
+    int lanes_made = 0;
 };
 static std::mutex g_mu;
 static std::map<int, DeviceTables> g_tables;
@@ -66,7 +76,13 @@ static void fill_roots(std::vector<float2> &h, int n) {
     }
 }
 
-int get_roots(int n, const float2 **out) {
+// Compute calls look tables up (make = false) and never create them: creating allocates and copies, which only
+// spectre_prepare may do.
+static int not_ready(const char *what, int n) {
+    return fail(SPECTRE_ENOTREADY, "%s for length %d missing on this device: call spectre_prepare first", what, n);
+}
+
+int get_roots(int n, const float2 **out, bool make) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
@@ -74,6 +90,7 @@ int get_roots(int n, const float2 **out) {
     DeviceTables &t = g_tables[dev];
     auto it = t.roots.find(n);
     if (it == t.roots.end()) {
+        if (!make) return not_ready("roots of unity", n);
         std::vector<float2> h;
         fill_roots(h, n);
         float2 *d = nullptr;
@@ -90,7 +107,7 @@ int get_roots(int n, const float2 **out) {
     return SPECTRE_OK;
 }
 
-static int get_slab_order(int L, const int **out) {
+static int get_slab_order(int L, const int **out, bool make = false) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
@@ -98,6 +115,7 @@ static int get_slab_order(int L, const int **out) {
     DeviceTables &t = g_tables[dev];
     auto it = t.slab_order.find(L);
     if (it == t.slab_order.end()) {
+        if (!make) return not_ready("bin order table", L);
         std::vector<int> h((size_t)L);
         slab_bin_order(L, h.data());
         int *d = nullptr;
@@ -114,21 +132,41 @@ static int get_slab_order(int L, const int **out) {
     return SPECTRE_OK;
 }
 
+static void release_lane(int dev, SideLane *l) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_tables[dev].lanes.push_back(l);
+}
+
 // Helper lanes are pooled per device: a call takes one for the time it enqueues work and puts it back
 // (work already enqueued keeps its order; events may be re-recorded once the waits on them are enqueued).
+// *out = nullptr when the pool is empty (not prepared, or other host threads hold the lanes): the call then keeps
+// all its groups on the caller's stream.
 static int acquire_lane(int *dev_out, SideLane **out) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
     *dev_out = dev;
+    *out = nullptr;
+    std::lock_guard<std::mutex> lk(g_mu);
+    DeviceTables &t = g_tables[dev];
+    if (!t.lanes.empty()) {
+        *out = t.lanes.back();
+        t.lanes.pop_back();
+    }
+    return SPECTRE_OK;
+}
+
+// One more helper lane for the current device's pool (spectre_prepare: one per call while the pool is empty).
+static int make_lane() {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
     {
         std::lock_guard<std::mutex> lk(g_mu);
         DeviceTables &t = g_tables[dev];
-        if (!t.lanes.empty()) {
-            *out = t.lanes.back();
-            t.lanes.pop_back();
-            return SPECTRE_OK;
-        }
+        if (t.lanes_made > 0 && !t.lanes.empty()) return SPECTRE_OK;
+        if (t.lanes_made >= 8) return SPECTRE_OK;
+        t.lanes_made += 1;
     }
     SideLane *l = new SideLane;
     e = hipStreamCreateWithFlags(&l->stream, hipStreamNonBlocking);
@@ -143,17 +181,13 @@ static int acquire_lane(int *dev_out, SideLane **out) {
         delete l;
         return fail_hip(e, "helper stream");
     }
-    *out = l;
+    release_lane(dev, l);
     return SPECTRE_OK;
 }
 
-static void release_lane(int dev, SideLane *l) {
-    std::lock_guard<std::mutex> lk(g_mu);
-    g_tables[dev].lanes.push_back(l);
-}
 
 // Chirp tables of an arbitrary length L (padded length M): *w [L], *filt [M].
-static int get_chirp(int L, const Pow2Plan &pl, const float2 **w, const float2 **filt) {
+static int get_chirp(int L, const Pow2Plan &pl, const float2 **w, const float2 **filt, bool make = false) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
@@ -161,6 +195,7 @@ static int get_chirp(int L, const Pow2Plan &pl, const float2 **w, const float2 *
     DeviceTables &t = g_tables[dev];
     auto it = t.chirp.find(L);
     if (it == t.chirp.end()) {
+        if (!make) return not_ready("chirp table", L);
         std::vector<float2> h((size_t)L + pl.L);
         chirp_tables_host(L, pl.L, pl.N1, pl.N2, pl.P, h.data(), h.data() + L);
         float2 *d = nullptr;
@@ -178,13 +213,13 @@ static int get_chirp(int L, const Pow2Plan &pl, const float2 **w, const float2 *
     return SPECTRE_OK;
 }
 
-int get_pow2_plan(int L, Pow2Plan *pl) {
+int get_pow2_plan(int L, Pow2Plan *pl, bool make) {
     int N1, N2, P;
     if (!pow2_split(L, &N1, &N2, &P)) return fail(SPECTRE_EUNSUPPORTED, "no four-step plan for length %d", L);
     pl->L = L; pl->N1 = N1; pl->N2 = N2; pl->P = P;
-    int rc = get_roots(L, &pl->twL);
+    int rc = get_roots(L, &pl->twL, make);
     if (rc) return rc;
-    return get_roots(N1, &pl->twN1);
+    return get_roots(N1, &pl->twN1, make);
 }
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -197,11 +232,7 @@ constexpr int kAppendRetransform = 160;
 // cache between the three kernels of a group.
 int mix_chunk_heads(int BH, int L, int d) {
     size_t per_head = (size_t)L * (size_t)(d / 2) * sizeof(float2);
-    size_t budget = (size_t)204 << 20;
-    if (const char *e = getenv("SPECTRE_CHUNK_MB")) {
-        long mb = atol(e);
-        if (mb > 0) budget = (size_t)mb << 20;
-    }
+    const size_t budget = (size_t)option(SPECTRE_OPT_SCRATCH_MB) << 20;
     size_t n = budget / per_head;
     if (n < 1) n = 1;
     if (n > (size_t)BH) n = (size_t)BH;
@@ -225,7 +256,7 @@ static MixGroups mix_groups(int BH, int L, int d, int scale) {
     m.BH = BH;
     const int full = mix_chunk_heads(BH, L, d);
     const int half = full / 2;
-    if (getenv("SPECTRE_ONE_LANE") || full >= BH || half < 1) {
+    if (option(SPECTRE_OPT_LANES) < 2 || full >= BH || half < 1) {
         m.chunk = ((long long)full * scale < BH) ? full * scale : BH;
         m.ngroups = (BH + m.chunk - 1) / m.chunk;
         return m;
@@ -257,7 +288,7 @@ static int mix_route(int BH, int L, int d) {
     // the in-LDS kernel is one launch: it wins when the length has no four-step plan, when there are many short
     // slabs, and when the whole call is small enough to be bound by the four-step path's dependent launches
     if (sl && (!p2 || (L <= 512 && BH >= 256) || (long long)BH * L <= 65536)) return 1;
-    if (fused_supported(L) && !getenv("SPECTRE_NO_FUSED")) return 4;
+    if (fused_supported(L) && option(SPECTRE_OPT_FUSED_4096)) return 4;
     if (p2) return 2;
     return chirp_padded_length(L) ? 3 : 0;
 }
@@ -289,6 +320,14 @@ static int mix_chirp(const void *v, const float2 *g, void *out, int B, int L, in
     const float2 *w = nullptr, *filt = nullptr;
     rc = get_chirp(L, pl, &w, &filt);
     if (rc) return rc;
+    const float2 *slab_roots = nullptr;
+    const int *slab_order = nullptr;
+    if (slab_supported(c.M)) {                         // all table look-ups before the first launch
+        rc = get_roots(c.M, &slab_roots);
+        if (rc) return rc;
+        rc = get_slab_order(c.M, &slab_order);
+        if (rc) return rc;
+    }
     char *base = static_cast<char *>(ws);
     float2 *gp = reinterpret_cast<float2 *>(base);
     float2 *scr = reinterpret_cast<float2 *>(base + c.gp);
@@ -323,13 +362,7 @@ static int mix_chirp(const void *v, const float2 *g, void *out, int B, int L, in
         if (e != hipSuccess) return fail_hip(e, "chirp_gate");
     }
     if (slab_supported(c.M)) {
-        const float2 *roots = nullptr;
-        rc = get_roots(c.M, &roots);
-        if (rc) return rc;
-        const int *order = nullptr;
-        rc = get_slab_order(c.M, &order);
-        if (rc) return rc;
-        e = launch_mix_slab((int)io, v, gp, out, roots, order, B, c.M, H, st, L);
+        e = launch_mix_slab((int)io, v, gp, out, slab_roots, slab_order, B, c.M, H, st, L);
         if (e != hipSuccess) return fail_hip(e, "mix_slab(padded)");
         return SPECTRE_OK;
     }
@@ -371,6 +404,56 @@ void spectre_shutdown(void) {
     (void)hipSetDevice(cur);
 }
 
+int spectre_set_option(int which, long value) {
+    if (which < 0 || which >= SPECTRE_OPT_COUNT_) return fail(SPECTRE_EINVAL, "set_option: unknown option %d", which);
+    if (value >= 0) {
+        if (which == SPECTRE_OPT_LANES && (value < 1 || value > 2)) return fail(SPECTRE_EINVAL, "set_option: lanes must be 1 or 2");
+        if (which == SPECTRE_OPT_SCRATCH_MB && (value < 1 || value > (1L << 20)))
+            return fail(SPECTRE_EINVAL, "set_option: scratch size out of range");
+    }
+    g_opt[which].store(value < 0 ? 0 : value + 1, std::memory_order_relaxed);
+    return SPECTRE_OK;
+}
+
+long spectre_get_option(int which) {
+    if (which < 0 || which >= SPECTRE_OPT_COUNT_) return -1;
+    return option(which);
+}
+
+int spectre_prepare(int n, int d) {
+    if (n < 1 || d < 1) return fail(SPECTRE_EINVAL, "prepare: non-positive size");
+    if (d != 64) return fail(SPECTRE_EUNSUPPORTED, "prepare: d=%d (only 64 is built)", d);
+    int N1, N2, P, rc;
+    const bool p2 = pow2_split(n, &N1, &N2, &P), sl = slab_supported(n);
+    const float2 *r = nullptr;
+    const int *o = nullptr;
+    Pow2Plan pl;
+    if (sl) {
+        if ((rc = get_roots(n, &r, true))) return rc;
+        if ((rc = get_slab_order(n, &o, true))) return rc;
+    }
+    if (p2 && (rc = get_pow2_plan(n, &pl, true))) return rc;
+    if (fused_supported(n) && (rc = get_roots(4096, &r, true))) return rc;
+    if (!sl && !p2) {
+        const int M = chirp_padded_length(n);
+        if (!M) return fail(SPECTRE_EUNSUPPORTED, "prepare: no kernel for length %d", n);
+        if ((rc = get_pow2_plan(M, &pl, true))) return rc;
+        const float2 *w = nullptr, *filt = nullptr;
+        if ((rc = get_chirp(n, pl, &w, &filt, true))) return rc;
+        if (slab_supported(M)) {
+            if ((rc = get_roots(M, &r, true))) return rc;
+            if ((rc = get_slab_order(M, &o, true))) return rc;
+        }
+    }
+    hipError_t (*const loaders[])() = {load_kernels_mix_pow2, load_kernels_mix_slab, load_kernels_mix_chirp, load_kernels_gate,
+                                       load_kernels_prefix, load_kernels_project, load_kernels_wrm};
+    for (auto load : loaders) {
+        const hipError_t e = load();
+        if (e != hipSuccess) return fail_hip(e, "prepare: loading kernels");
+    }
+    return make_lane();
+}
+
 size_t spectre_mix_workspace_bytes(int B, int L, int H, int d, spectre_dtype io) {
     (void)io;
     if (B < 1 || L < 2 || H < 1 || d < 2) return 0;
@@ -384,77 +467,37 @@ size_t spectre_mix_workspace_bytes(int B, int L, int H, int d, spectre_dtype io)
     return align256((size_t)BH * L * sizeof(float2)) + m.lanes * align256((size_t)m.chunk * L * (d / 2) * sizeof(float2));
 }
 
-int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, int H, int d,
-                        spectre_dtype io, void *ws, size_t ws_bytes, void *stream) {
-    if (!v || !g || !out) return fail(SPECTRE_EINVAL, "mix_forward: null pointer");
-    if (B < 1 || L < 1 || H < 1 || d < 1) return fail(SPECTRE_EINVAL, "mix_forward: non-positive size");
-    if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "mix_forward: bad dtype");
-    if ((long long)B * H > 0x7fffffffLL / 64) return fail(SPECTRE_EUNSUPPORTED, "mix_forward: B*H too large");
+static int check_mix_args(const void *v, const void *g, const void *out, int B, int L, int H, int d, spectre_dtype io,
+                          const char *who) {
+    if (!v || !g || !out) return fail(SPECTRE_EINVAL, "%s: null pointer", who);
+    if (B < 1 || L < 1 || H < 1 || d < 1) return fail(SPECTRE_EINVAL, "%s: non-positive size", who);
+    if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "%s: bad dtype", who);
+    if ((long long)B * H > 0x7fffffffLL / 64) return fail(SPECTRE_EUNSUPPORTED, "%s: B*H too large", who);
     const size_t bytes = (size_t)B * L * H * d * (io == SPECTRE_BF16 ? 2 : 4);
     const char *vb = static_cast<const char *>(v), *ob = static_cast<const char *>(out);
-    if (vb < ob + bytes && ob < vb + bytes) return fail(SPECTRE_EINVAL, "mix_forward: out overlaps v");
-    if (!spectre_length_supported(L, d))
-        return fail(SPECTRE_EUNSUPPORTED, "mix_forward: no kernel for L=%d, d=%d", L, d);
-    const size_t need = spectre_mix_workspace_bytes(B, L, H, d, io);
-    if (!ws || ws_bytes < need)
-        return fail(SPECTRE_EWORKSPACE, "mix_forward: workspace %zu < %zu bytes", ws_bytes, need);
-    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "mix_forward: ws not 256-byte aligned");
+    if (vb < ob + bytes && ob < vb + bytes) return fail(SPECTRE_EINVAL, "%s: out overlaps v", who);
+    return SPECTRE_OK;
+}
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int BH = B * H;
-    if (mix_route(BH, L, d) == 1) {
-        const float2 *roots = nullptr;
-        int rc = get_roots(L, &roots);
-        if (rc) return rc;
-        const int *order = nullptr;
-        rc = get_slab_order(L, &order);
-        if (rc) return rc;
-        hipError_t e = launch_mix_slab((int)io, v, static_cast<const float2 *>(g), out, roots, order, B, L, H, st);
-        if (e != hipSuccess) return fail_hip(e, "mix_slab");
-        return SPECTRE_OK;
-    }
-    if (mix_route(BH, L, d) == 3) return mix_chirp(v, static_cast<const float2 *>(g), out, B, L, H, d, io, ws, st);
-    if (mix_route(BH, L, d) == 4) {
-        const float2 *tw = nullptr;
-        int rc = get_roots(4096, &tw);
-        if (rc) return rc;
-        hipError_t e = launch_fused((int)io, v, static_cast<const float2 *>(g), out, tw, L, H, BH, st);
-        if (e != hipSuccess) return fail_hip(e, "fused mixer");
-        return SPECTRE_OK;
-    }
-    Pow2Plan pl;
-    int rc = get_pow2_plan(L, &pl);
-    if (rc) return rc;
-    float2 *gp = static_cast<float2 *>(ws);
-    char *scr_base = static_cast<char *>(ws) + align256((size_t)BH * L * sizeof(float2));
-    // opt-in, bf16 rows only: complex numbers cross between the three kernels as two bfloat16 instead of two fp32,
-    // and twice the heads fit in a lane's scratch
-    bool scr16 = (io == SPECTRE_BF16) && getenv("SPECTRE_SCRATCH_BF16") != nullptr;
-    const MixGroups m1 = mix_groups(BH, L, d, 1);
-    const size_t lane_bytes = align256((size_t)m1.chunk * L * (d / 2) * sizeof(float2));   // as the workspace was sized
-    MixGroups mg = scr16 ? mix_groups(BH, L, d, 2) : m1;
-    if (scr16 && (mg.lanes != m1.lanes || (size_t)mg.chunk * L * (d / 2) * sizeof(uint32_t) > lane_bytes)) mg = m1;
-    const int lanes = mg.lanes;
-    SideLane *side = nullptr;
-    int dev = 0;
+// The four-step route: gate expansion, then per head group the row transforms, the column kernel and the inverse
+// row transforms.  gp = expanded gate [BH][L]; lane_scr[i] = transform scratch of lane i (lane_bytes each).
+// side == nullptr keeps every group on st.
+static int mix_four_step(const Pow2Plan &pl, const void *v, const float2 *g, void *out, int BH, int L, int H, int d,
+                         spectre_dtype io, float2 *gp, char *scr_base, size_t lane_bytes, const MixGroups &mg,
+                         bool scr16, SideLane *side, hipStream_t st) {
     hipError_t e = hipSuccess;
-    if (lanes == 2) {
-        rc = acquire_lane(&dev, &side);
-        if (rc) return rc;
+    if (side) {
         // fork: the helper stream starts after everything before this call on the caller's stream.  Its first
         // kernel (row transforms) does not read the gate, so it runs beside the gate expansion; the column kernel
         // that follows waits for the event recorded behind the expansion.
         e = hipEventRecord(side->fork, st);
         if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
-        if (e != hipSuccess) {
-            release_lane(dev, side);
-            return fail_hip(e, "fork to helper stream");
-        }
+        if (e != hipSuccess) return fail_hip(e, "fork to helper stream");
     }
     const char *what = nullptr;
-    e = launch_gate_expand(pl, static_cast<const float2 *>(g), gp, BH, st);
+    e = launch_gate_expand(pl, g, gp, BH, st);
     if (e != hipSuccess) what = "gate_expand";
-    if (!what && lanes == 2) {
+    if (!what && side) {
         e = hipEventRecord(side->gate, st);
         if (e != hipSuccess) what = "event behind the gate expansion";
     }
@@ -462,13 +505,13 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
     for (int group = 0, bh0 = 0; group < mg.ngroups && !what; ++group) {
         const int nbh = mg.size(group);
         if (nbh < 1) continue;
-        const int lane = (lanes == 2) ? (group & 1) : 0;
+        const int lane = side ? (group & 1) : 0;
         hipStream_t ls = lane ? side->stream : st;
         float2 *scr = reinterpret_cast<float2 *>(scr_base + (size_t)lane * lane_bytes);
         // short columns (L <= 12288): a head's scratch fits the 4 MB L2 of one XCD, see head_affine() in mix_pow2.hip;
         // measured -7 % at L = 8192, -10 % at 4096 (three kernels), nothing or a loss from 16384 on
         const bool affine = !scr16 && nbh % 8 == 0 && (size_t)L * (d / 2) * sizeof(float2) <= ((size_t)3 << 20) &&
-                            !getenv("SPECTRE_NO_AFFINE");
+                            option(SPECTRE_OPT_HEAD_AFFINE) != 0;
         e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, ls, scr16, affine);
         if (e != hipSuccess) { what = "small_fwd"; break; }
         if (lane && !side_has_gate) {
@@ -482,12 +525,11 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
         if (e != hipSuccess) { what = "small_inv"; break; }
         bh0 += nbh;
     }
-    if (lanes == 2) {
+    if (side) {
         // join: the caller's stream continues after the helper stream's last kernel (also on a launch error,
         // so that nothing of this call is left running unordered)
         hipError_t ej = hipEventRecord(side->join, side->stream);
         if (ej == hipSuccess) ej = hipStreamWaitEvent(st, side->join, 0);
-        release_lane(dev, side);
         if (!what && ej != hipSuccess) {
             e = ej;
             what = "join from helper stream";
@@ -495,6 +537,70 @@ int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, i
     }
     if (what) return fail_hip(e, what);
     return SPECTRE_OK;
+}
+
+int spectre_mix_forward_ex(const void *v, const void *g, void *out, int B, int L, int H, int d,
+                           spectre_dtype io, unsigned flags, void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_mix_args(v, g, out, B, L, H, d, io, "mix_forward");
+    if (rc) return rc;
+    if (flags & ~(unsigned)SPECTRE_MIX_BF16_SCRATCH) return fail(SPECTRE_EINVAL, "mix_forward: unknown flag bits");
+    if (!spectre_length_supported(L, d))
+        return fail(SPECTRE_EUNSUPPORTED, "mix_forward: no kernel for L=%d, d=%d", L, d);
+    const size_t need = spectre_mix_workspace_bytes(B, L, H, d, io);
+    if (!ws || ws_bytes < need)
+        return fail(SPECTRE_EWORKSPACE, "mix_forward: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "mix_forward: ws not 256-byte aligned");
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int BH = B * H;
+    const int route = mix_route(BH, L, d);
+    if (route == 1) {
+        const float2 *roots = nullptr;
+        rc = get_roots(L, &roots);
+        if (rc) return rc;
+        const int *order = nullptr;
+        rc = get_slab_order(L, &order);
+        if (rc) return rc;
+        hipError_t e = launch_mix_slab((int)io, v, static_cast<const float2 *>(g), out, roots, order, B, L, H, st);
+        if (e != hipSuccess) return fail_hip(e, "mix_slab");
+        return SPECTRE_OK;
+    }
+    if (route == 3) return mix_chirp(v, static_cast<const float2 *>(g), out, B, L, H, d, io, ws, st);
+    if (route == 4) {
+        const float2 *tw = nullptr;
+        rc = get_roots(4096, &tw);
+        if (rc) return rc;
+        hipError_t e = launch_fused((int)io, v, static_cast<const float2 *>(g), out, tw, L, H, BH, st);
+        if (e != hipSuccess) return fail_hip(e, "fused mixer");
+        return SPECTRE_OK;
+    }
+    Pow2Plan pl;
+    rc = get_pow2_plan(L, &pl);
+    if (rc) return rc;
+    float2 *gp = static_cast<float2 *>(ws);
+    char *scr_base = static_cast<char *>(ws) + align256((size_t)BH * L * sizeof(float2));
+    // on request, bf16 rows only: complex numbers cross between the three kernels as two bfloat16 instead of two
+    // fp32, and twice the heads fit in a lane's scratch
+    const bool scr16 = (io == SPECTRE_BF16) && (flags & SPECTRE_MIX_BF16_SCRATCH);
+    const MixGroups m1 = mix_groups(BH, L, d, 1);
+    const size_t lane_bytes = align256((size_t)m1.chunk * L * (d / 2) * sizeof(float2));   // as the workspace was sized
+    MixGroups mg = scr16 ? mix_groups(BH, L, d, 2) : m1;
+    if (scr16 && (mg.lanes != m1.lanes || (size_t)mg.chunk * L * (d / 2) * sizeof(uint32_t) > lane_bytes)) mg = m1;
+    SideLane *side = nullptr;
+    int dev = 0;
+    if (mg.lanes == 2) {
+        rc = acquire_lane(&dev, &side);
+        if (rc) return rc;
+    }
+    rc = mix_four_step(pl, v, static_cast<const float2 *>(g), out, BH, L, H, d, io, gp, scr_base, lane_bytes, mg, scr16,
+                       side, st);
+    if (side) release_lane(dev, side);
+    return rc;
+}
+
+int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, int H, int d,
+                        spectre_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    return spectre_mix_forward_ex(v, g, out, B, L, H, d, io, 0u, ws, ws_bytes, stream);
 }
 
 // ------------------------------------------------------------------------------------------ gate
@@ -739,6 +845,8 @@ size_t spectre_prefix_bytes(int B, int H, int d, int N_max, int which) {
 int spectre_prefix_init(spectre_prefix_cache *c, void *stream) {
     int rc = check_cache(c, "prefix_init");
     if (rc) return rc;
+    rc = spectre_prepare(window_len(c), c->d);
+    if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     void *arr[4] = {c->prefix_fft, c->v_buf, c->q_buf, c->sum_q};
     const int which[4] = {SPECTRE_PREFIX_FFT, SPECTRE_PREFIX_VBUF, SPECTRE_PREFIX_QBUF, SPECTRE_PREFIX_SUMQ};
@@ -807,13 +915,18 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
     if (!v_new || !q_new) return fail(SPECTRE_EINVAL, "prefix_update: null pointer");
     if (T < 1) return fail(SPECTRE_EINVAL, "prefix_update: T < 1");
     if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "prefix_update: bad dtype");
-    rc = spectre_prefix_flush(c, stream);
-    if (rc) return rc;
     const size_t need = spectre_prefix_update_workspace_bytes(c, T, io);
     if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_update: workspace %zu < %zu bytes", ws_bytes, need);
     if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_update: ws not 256-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int B = c->B, H = c->H, d = c->d, N = window_len(c), W = c->N_max, M0 = c->N_mem, BH = B * H, F = N / 2 + 1;
+    if (c->t == 0 && T > 1 && T > W) return fail(SPECTRE_EINVAL, "prefix_update: prompt of %d tokens exceeds N_max=%d", T, W);
+    Pow2Plan pl;
+    rc = get_pow2_plan(N, &pl);                      // every route below may transform the window
+    if (rc) return rc;
+    // every host-side check has passed: from here on work is enqueued
+    rc = spectre_prefix_flush(c, stream);
+    if (rc) return rc;
     char *w = static_cast<char *>(ws);
     float *delta = reinterpret_cast<float *>(w);
     w += align256((size_t)(T < kMaxPending ? T : kMaxPending) * BH * d * sizeof(float));
@@ -823,7 +936,6 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
     float2 *X = static_cast<float2 *>(c->prefix_fft);
     hipError_t e;
     if (c->t == 0 && T > 1) {
-        if (T > W) return fail(SPECTRE_EINVAL, "prefix_update: prompt of %d tokens exceeds N_max=%d", T, W);
         // the ring buffers are all zero on an empty cache (spectre_prefix_init): only the prompt's rows are written,
         // and the same pass sums the queries
         e = launch_ring_append((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), partial,
@@ -839,9 +951,6 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
             c->t = T;
             return SPECTRE_OK;
         }
-        Pow2Plan pl;
-        rc = get_pow2_plan(N, &pl);
-        if (rc) return rc;
         const int chunk = mix_chunk_heads(BH, N, d);
         for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
             const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
@@ -885,17 +994,18 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
         const int nb = (T - t0 < kMaxPending) ? T - t0 : kMaxPending;
         int slots[kMaxPending];
         for (int i = 0; i < nb; ++i) {
-            const int slot = M0 + (int)(c->t % W), evict = c->t >= W ? 1 : 0;
+            const long long ti = c->t + i;
+            const int slot = M0 + (int)(ti % W), evict = ti >= W ? 1 : 0;
             slots[i] = slot;
             e = launch_ring_update((int)io, v_new, q_new, T, t0 + i, static_cast<float *>(c->v_buf),
                                    static_cast<float *>(c->q_buf), static_cast<double *>(c->sum_q),
                                    delta + (size_t)i * BH * d, B, H, d, N, slot, evict, st);
             if (e != hipSuccess) return fail_hip(e, "ring_update");
-            c->t += 1;
         }
         e = launch_sweep_lazy(true, false, X, delta, static_cast<const float2 *>(c->twiddle), nullptr, nullptr, nullptr, BH,
                               F, N, 0, nb, slots, st);
         if (e != hipSuccess) return fail_hip(e, "sweep(batch update)");
+        c->t += nb;                                    // the counter follows the spectrum, batch by batch
     }
     return SPECTRE_OK;
 }
@@ -917,6 +1027,9 @@ int spectre_prefix_set_memory(spectre_prefix_cache *c, const float *mem, int mem
     if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "prefix_set_memory: workspace %zu < %zu bytes", ws_bytes, need);
     if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "prefix_set_memory: ws not 256-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
+    Pow2Plan pl;
+    rc = get_pow2_plan(window_len(c), &pl);            // the look-up transform_window repeats: fail before any launch
+    if (rc) return rc;
     hipError_t e = launch_set_memory(mem, mem_batch, static_cast<float *>(c->v_buf), c->B, c->H, window_len(c), c->N_mem, st);
     if (e != hipSuccess) return fail_hip(e, "set_memory");
     return transform_window(c, static_cast<float2 *>(ws), st);

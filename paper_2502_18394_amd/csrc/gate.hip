@@ -513,4 +513,11 @@ hipError_t launch_gate_mlp(const double *sum_q, double inv_count, const GateDev 
     return hipGetLastError();
 }
 
+// Loads this translation unit's code object (the runtime loads them on first use): called by spectre_prepare so
+// that no compute call is the first to touch it.
+hipError_t load_kernels_gate() {
+    hipFuncAttributes a;
+    return hipFuncGetAttributes(&a, reinterpret_cast<const void *>(k_pool_final));
+}
+
 }  // namespace spectre

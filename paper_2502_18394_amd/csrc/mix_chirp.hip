@@ -172,4 +172,11 @@ void chirp_tables_host(int L, int M, int N1, int N2, int P, float2 *w, float2 *f
         }
 }
 
+// Loads this translation unit's code object (the runtime loads them on first use): called by spectre_prepare so
+// that no compute call is the first to touch it.
+hipError_t load_kernels_mix_chirp() {
+    hipFuncAttributes a;
+    return hipFuncGetAttributes(&a, reinterpret_cast<const void *>(k_chirp_pre));
+}
+
 }  // namespace spectre

@@ -637,4 +637,11 @@ hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, i
     return hipSuccess;
 }
 
+// Loads this translation unit's code object (the runtime loads them on first use): called by spectre_prepare so
+// that no compute call is the first to touch it.
+hipError_t load_kernels_mix_pow2() {
+    hipFuncAttributes a;
+    return hipFuncGetAttributes(&a, reinterpret_cast<const void *>(k_gate_expand));
+}
+
 }  // namespace spectre

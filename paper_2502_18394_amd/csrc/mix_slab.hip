@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "fft_regs.h"
+#include "internal.h"
 
 namespace spectre {
 
@@ -332,10 +333,10 @@ hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, co
     if (rows > L) return hipErrorInvalidValue;
     const int pp = slab_pairs_per_workgroup(io, B * H, L);
     if ((size_t)L * (pp + 2) * sizeof(float2) > (size_t)160 * 1024) return hipErrorInvalidValue;
-    if (L == 196 && pp >= 16 && (long long)B * H >= 512 && !getenv("SPECTRE_NO_SLAB_CT"))   // whole heads still fill the chip
+    if (L == 196 && pp >= 16 && (long long)B * H >= 512 && option(SPECTRE_OPT_SLAB_COMPILE_TIME) != 0)   // whole heads still fill the chip
         return io ? mix_slab_t<IoBf16, 32, 448, 196>(v, g, out, roots, bin_of_pos, B, L, H, rows, st)
                   : mix_slab_t<IoF32, 32, 448, 196>(v, g, out, roots, bin_of_pos, B, L, H, rows, st);
-    const bool ct = !getenv("SPECTRE_NO_SLAB_CT");
+    const bool ct = option(SPECTRE_OPT_SLAB_COMPILE_TIME) != 0;
 #define SPECTRE_SLAB_LEN(PPV, LCV)                                                                          \
     if (ct && L == LCV)                                                                                     \
         return io ? mix_slab_t<IoBf16, PPV, 256, LCV>(v, g, out, roots, bin_of_pos, B, L, H, rows, st)      \
@@ -354,6 +355,13 @@ hipError_t launch_mix_slab(int io, const void *v, const float2 *g, void *out, co
     }
 #undef SPECTRE_SLAB_LEN
 #undef SPECTRE_SLAB_CASE
+}
+
+// Loads this translation unit's code object (the runtime loads them on first use): called by spectre_prepare so
+// that no compute call is the first to touch it.
+hipError_t load_kernels_mix_slab() {
+    hipFuncAttributes a;
+    return hipFuncGetAttributes(&a, reinterpret_cast<const void *>((k_mix_slab<IoF32, 4, 256, 0>)));
 }
 
 }  // namespace spectre

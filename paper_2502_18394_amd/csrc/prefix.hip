@@ -755,4 +755,11 @@ hipError_t launch_tangle(const float2 *X, const float2 *g, float2 *scr, int N, i
     return hipGetLastError();
 }
 
+// Loads this translation unit's code object (the runtime loads them on first use): called by spectre_prepare so
+// that no compute call is the first to touch it.
+hipError_t load_kernels_prefix() {
+    hipFuncAttributes a;
+    return hipFuncGetAttributes(&a, reinterpret_cast<const void *>(k_fill_twiddle));
+}
+
 }  // namespace spectre

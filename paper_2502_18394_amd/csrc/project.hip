@@ -357,4 +357,11 @@ hipError_t launch_project_pooled(const double *sum_x, const float *Wq, int Hw, i
     return hipGetLastError();
 }
 
+// Loads this translation unit's code object (the runtime loads them on first use): called by spectre_prepare so
+// that no compute call is the first to touch it.
+hipError_t load_kernels_project() {
+    hipFuncAttributes a;
+    return hipFuncGetAttributes(&a, reinterpret_cast<const void *>(k_project_pooled));
+}
+
 }  // namespace spectre

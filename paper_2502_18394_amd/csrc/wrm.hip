@@ -336,4 +336,11 @@ hipError_t launch_wrm_apply(int io, const void *v, const float *s, void *out, fl
     return hipGetLastError();
 }
 
+// Loads this translation unit's code object (the runtime loads them on first use): called by spectre_prepare so
+// that no compute call is the first to touch it.
+hipError_t load_kernels_wrm() {
+    hipFuncAttributes a;
+    return hipFuncGetAttributes(&a, reinterpret_cast<const void *>(k_wrm_upper));
+}
+
 }  // namespace spectre

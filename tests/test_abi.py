@@ -99,6 +99,33 @@ def test_bad_arguments_fail_on_the_host(lib):
     assert rc == 1
 
 
+def test_options_and_prepare_argument_checks(lib):
+    """The tuning switches are host-side state: defaults, set, restore, bad values - no device needed.  spectre_prepare
+    rejects bad sizes and unsupported (n, d) before it touches a device."""
+    lib.spectre_get_option.restype = ctypes.c_long
+    defaults = {0: 2, 1: 204, 2: 1, 3: 1, 4: 1}
+    for which, val in defaults.items():
+        assert lib.spectre_get_option(which) == val
+    assert lib.spectre_set_option(0, ctypes.c_long(1)) == 0 and lib.spectre_get_option(0) == 1
+    assert lib.spectre_set_option(2, ctypes.c_long(0)) == 0 and lib.spectre_get_option(2) == 0
+    assert lib.spectre_mix_workspace_bytes(1, 4096, 8, 64, 1) > 256            # three-kernel route now needs scratch
+    assert lib.spectre_set_option(1, ctypes.c_long(12)) == 0
+    small = lib.spectre_mix_workspace_bytes(1, 8192, 32, 64, 1)
+    for which in defaults:
+        assert lib.spectre_set_option(which, ctypes.c_long(-1)) == 0
+        assert lib.spectre_get_option(which) == defaults[which]
+    assert lib.spectre_mix_workspace_bytes(1, 4096, 8, 64, 1) == 256
+    assert small < lib.spectre_mix_workspace_bytes(1, 8192, 32, 64, 1)
+    assert lib.spectre_set_option(0, ctypes.c_long(3)) == 1 and lib.spectre_get_option(0) == 2
+    assert lib.spectre_set_option(9, ctypes.c_long(1)) == 1 and lib.spectre_get_option(9) == -1
+    assert lib.spectre_prepare(0, 64) == 1
+    assert lib.spectre_prepare(1024, 32) == 2
+    assert lib.spectre_prepare(5 * 32768, 64) == 2 and b"length" in lib.spectre_last_error()
+    fake, far = ctypes.c_void_p(4096), ctypes.c_void_p(1 << 40)
+    rc = lib.spectre_mix_forward_ex(fake, fake, far, 1, 1024, 1, 64, 0, ctypes.c_uint(6), fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == 1 and b"flag" in lib.spectre_last_error()
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     from paper_2502_18394_amd import binding
     monkeypatch.setattr(binding, "_lib", None)

@@ -1,12 +1,13 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
-The GPU runs the whole workload; the oracle evaluates sampled heads (every channel of a head
-is an independent column, so a head can be checked on its own)."""
+The GPU runs the whole workload.  The mixer cases compare every head (the oracle takes a few heads at a time to
+bound host memory); the decode cases compare sampled (b, h) slabs, whose state the oracle can carry step by step
+(every channel of a head is an independent column, so a head can be checked on its own)."""
 import numpy as np
 import pytest
 import torch
 
-from gpu_util import TOL, f64, from_device, rel_l2, to_device
+from gpu_util import TOL, assert_close_elementwise, f64, from_device, rel_l2, to_device
 from paper_2502_18394_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -22,15 +23,19 @@ def test_length_sweep_llama_shape_bf16(oracle, L):
     g = synth.random_gate(synth.BASE_SEED + L + 1, B, H, L)
     out = binding.mix_forward(to_device(store, "bf16"), torch.from_numpy(g).cuda())
     torch.cuda.synchronize()
-    heads = list(range(H)) if L <= 8192 else [0, 13, 31]
-    got = from_device(out[:, :, heads, :].contiguous())
-    want = oracle.mix_forward(vals[:, :, heads, :].astype(np.float64), g[:, heads].astype(np.complex128))
-    err = rel_l2(got, want)
-    worst = max(rel_l2(got[:, :, i], want[:, :, i]) for i in range(len(heads)))
-    print(f"  rel_l2={err:.3e} worst head {worst:.3e} over {len(heads)} heads", flush=True)
+    worst, num, den = 0.0, 0.0, 0.0
+    step = 8                                           # heads per oracle call (fp64 copies of 8 heads: 0.5 GB at 128k)
+    for h0 in range(0, H, step):
+        heads = list(range(h0, min(H, h0 + step)))
+        got = from_device(out[:, :, heads, :].contiguous())
+        want = oracle.mix_forward(vals[:, :, heads, :].astype(np.float64), g[:, heads].astype(np.complex128))
+        num += float(np.sum((got - want) ** 2))
+        den += float(np.sum(want ** 2))
+        worst = max([worst] + [rel_l2(got[:, :, i], want[:, :, i]) for i in range(len(heads))])
+        assert_close_elementwise(got, want, "bf16", L)
+    err = (num / den) ** 0.5
+    print(f"  rel_l2={err:.3e} worst head {worst:.3e} over all {H} heads", flush=True)
     assert err <= TOL["bf16"] and worst <= TOL["bf16"]
-    tol = np.abs(want) * 2.0 ** -7 + 1e-5 * np.sqrt(np.mean(want ** 2))
-    assert np.all(np.abs(got - want) <= tol)
 
 
 def test_headline_shape_fp32_io(oracle):
@@ -41,12 +46,13 @@ def test_headline_shape_fp32_io(oracle):
     g = synth.random_gate(synth.BASE_SEED + 10, B, H, L)
     out = binding.mix_forward(to_device(store, "f32"), torch.from_numpy(g).cuda())
     torch.cuda.synchronize()
-    heads = [0, 5]
-    got = from_device(out[:, :, heads, :].contiguous())
-    want = oracle.mix_forward(vals[:, :, heads, :].astype(np.float64), g[:, heads].astype(np.complex128))
+    got = from_device(out)
+    want = oracle.mix_forward(vals.astype(np.float64), g.astype(np.complex128))          # all 8 heads
     err = rel_l2(got, want)
-    print(f"  rel_l2={err:.3e}", flush=True)
-    assert err <= TOL["f32"]
+    worst = max(rel_l2(got[:, :, i], want[:, :, i]) for i in range(H))
+    print(f"  rel_l2={err:.3e} worst head {worst:.3e}", flush=True)
+    assert err <= TOL["f32"] and worst <= TOL["f32"]
+    assert_close_elementwise(got, want, "f32", L)
 
 
 @pytest.mark.parametrize("L,H,io", [(50000, 32, "bf16"), (65535, 3, "f32"), (40000, 40, "f32")])

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import TOL, rel_l2
+from gpu_util import TOL, assert_close_elementwise, rel_l2
 from paper_2502_18394_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -26,14 +26,14 @@ def from_device(t):
     return t.cpu().numpy()
 
 
-def run_case(oracle, B, L, H, d, io, seed, gate="random"):
+def run_case(oracle, B, L, H, d, io, seed, gate="random", flags=0):
     from paper_2502_18394_amd import binding
     vals, store = synth.tokens(seed, (B, L, H, d), io)
     if isinstance(gate, str):
         g = synth.random_gate(seed + 1, B, H, L)
     else:
         g = gate
-    out = binding.mix_forward(to_device(vals, store, io), torch.from_numpy(g).cuda())
+    out = binding.mix_forward(to_device(vals, store, io), torch.from_numpy(g).cuda(), flags=flags)
     torch.cuda.synchronize()
     got = from_device(out)
     want = oracle.mix_forward(vals.astype(np.float64), g.astype(np.complex128))
@@ -49,26 +49,21 @@ def test_mix_forward_matches_oracle(oracle, B, L, H, io):
     err = rel_l2(got, want)
     print(f"  rel_l2={err:.3e}", flush=True)
     assert err <= TOL[io]
-    if io == "bf16":
-        # tighter than the bar: every element within one bf16 step of the oracle value, plus the
-        # fp32 arithmetic error (absolute, relative to the output's rms) that matters near zero
-        tol = np.abs(want) * 2.0 ** -7 + 1e-5 * np.sqrt(np.mean(want ** 2))
-        assert np.all(np.abs(got - want) <= tol)
+    assert_close_elementwise(got, want, io, L)
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
 @pytest.mark.parametrize("B,H", [(3, 5), (1, 32), (1, 1)])
-def test_one_kernel_path_at_4096_and_the_three_kernel_path_behind_it(oracle, monkeypatch, B, H, io):
+def test_one_kernel_path_at_4096_and_the_three_kernel_path_behind_it(oracle, options, B, H, io):
     """L = 4096 runs as a single kernel (whole columns in LDS; head counts that are and are not multiples of the
-    eight workgroup slots per round).  With SPECTRE_NO_FUSED set the same call takes the three four-step kernels
+    eight workgroup slots per round).  With the fused-4096 option off the same call takes the three four-step kernels
     (N1 = 256, N2 = 16), which keeps that plan covered by a mixer test; both must match the oracle."""
     from paper_2502_18394_amd import binding
     L = 4096
     print(f"case B={B} H={H} io={io}", flush=True)
-    monkeypatch.delenv("SPECTRE_NO_FUSED", raising=False)
     assert binding.mix_workspace_bytes(B, L, H, 64, binding.BF16) == 256
     got, want, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 11 * H)
-    monkeypatch.setenv("SPECTRE_NO_FUSED", "1")
+    options(binding.OPT_FUSED_4096, 0)
     assert binding.mix_workspace_bytes(B, L, H, 64, binding.BF16) > B * H * L * 8
     got3, _, _ = run_case(oracle, B, L, H, 64, io, seed=synth.BASE_SEED + 11 * H)
     e1, e3 = rel_l2(got, want), rel_l2(got3, want)
@@ -77,62 +72,59 @@ def test_one_kernel_path_at_4096_and_the_three_kernel_path_behind_it(oracle, mon
 
 
 @pytest.mark.parametrize("B,L,H", [(1, 8192, 3), (2, 12288, 2), (1, 32768, 5), (1, 131072, 1)])
-def test_bf16_scratch_option_stays_within_the_bf16_bar(oracle, monkeypatch, B, L, H):
-    """SPECTRE_SCRATCH_BF16: the three four-step kernels exchange bfloat16 pairs instead of fp32 pairs (opt-in, bf16
+def test_bf16_scratch_option_stays_within_the_bf16_bar(oracle, B, L, H):
+    """Flag SPECTRE_MIX_BF16_SCRATCH: the three four-step kernels exchange bfloat16 pairs instead of fp32 pairs (opt-in, bf16
     rows only).  Two more roundings to 8 mantissa bits: the error against the oracle must stay well inside the bar
     for bf16 rows; fp32 rows ignore the switch and keep the fp32 bar."""
-    monkeypatch.delenv("SPECTRE_SCRATCH_BF16", raising=False)
+    from paper_2502_18394_amd import binding
     seed = synth.BASE_SEED + 13 * H
     plain, want, _ = run_case(oracle, B, L, H, 64, "bf16", seed=seed)
-    monkeypatch.setenv("SPECTRE_SCRATCH_BF16", "1")
-    got, _, _ = run_case(oracle, B, L, H, 64, "bf16", seed=seed)
+    got, _, _ = run_case(oracle, B, L, H, 64, "bf16", seed=seed, flags=binding.MIX_BF16_SCRATCH)
     e0, e1 = rel_l2(plain, want), rel_l2(got, want)
     print(f"case B={B} L={L} H={H}: fp32 scratch {e0:.3e}  bf16 scratch {e1:.3e}", flush=True)
     assert e0 <= TOL["bf16"] and e1 <= 5e-3
     assert not np.array_equal(plain, got)                     # the switch did take the other kernels
     if L <= 12288:
-        got32, want32, _ = run_case(oracle, B, L, H, 64, "f32", seed=seed)
+        got32, want32, _ = run_case(oracle, B, L, H, 64, "f32", seed=seed, flags=binding.MIX_BF16_SCRATCH)
         assert rel_l2(got32, want32) <= TOL["f32"]
 
 
 @pytest.mark.parametrize("B,H,mb,one_lane", [(1, 11, 12, False), (1, 7, 12, False), (3, 1, 4, False), (1, 3, 4, True),
                                               (2, 5, 2, False), (1, 13, 12, True)])
-def test_head_groups_of_any_size_give_the_same_rows(oracle, monkeypatch, B, H, mb, one_lane):
+def test_head_groups_of_any_size_give_the_same_rows(oracle, options, B, H, mb, one_lane):
     """Long calls take their heads in groups (one stream, or two streams with an even number of groups whose sizes
     differ by at most one head, some of them empty when there are fewer heads than groups).  Every head is
-    transformed on its own, so the grouping must not change a bit; SPECTRE_CHUNK_MB shrinks the groups far enough
+    transformed on its own, so the grouping must not change a bit; the scratch-size option shrinks the groups far enough
     to get several of them at a small length.  The same groupings with the bfloat16 scratch stay within its bar."""
     L, io = 8192, "bf16"
     seed = synth.BASE_SEED + 17 * H + B
-    for k in ("SPECTRE_CHUNK_MB", "SPECTRE_ONE_LANE", "SPECTRE_SCRATCH_BF16"):
-        monkeypatch.delenv(k, raising=False)
+    from paper_2502_18394_amd import binding
     plain, want, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
     assert rel_l2(plain, want) <= TOL[io]
-    monkeypatch.setenv("SPECTRE_CHUNK_MB", str(mb))
+    options(binding.OPT_SCRATCH_MB, mb)
     if one_lane:
-        monkeypatch.setenv("SPECTRE_ONE_LANE", "1")
+        options(binding.OPT_LANES, 1)
     got, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
     print(f"case B={B} H={H} chunk_mb={mb} one_lane={one_lane}: identical {np.array_equal(got, plain)}", flush=True)
     assert np.array_equal(got, plain)
-    monkeypatch.setenv("SPECTRE_SCRATCH_BF16", "1")
-    got16, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
-    monkeypatch.delenv("SPECTRE_CHUNK_MB")
-    monkeypatch.delenv("SPECTRE_ONE_LANE", raising=False)
-    plain16, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    got16, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed, flags=binding.MIX_BF16_SCRATCH)
+    options(binding.OPT_SCRATCH_MB, -1)
+    options(binding.OPT_LANES, -1)
+    plain16, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed, flags=binding.MIX_BF16_SCRATCH)
     assert np.array_equal(got16, plain16) and rel_l2(got16, want) <= 5e-3
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
 @pytest.mark.parametrize("B,H", [(64, 8), (43, 12), (171, 3)])
-def test_patch_grid_length_with_many_heads_takes_its_own_kernel(oracle, monkeypatch, B, H, io):
+def test_patch_grid_length_with_many_heads_takes_its_own_kernel(oracle, options, B, H, io):
     """L = 196 (14 x 14 patches) with at least 512 heads runs a variant of the in-LDS kernel whose length and radices
     (14, 14) are compile-time constants and whose workgroups are seven waves on a whole head.  Same passes, same
-    arithmetic as the general kernel (SPECTRE_NO_SLAB_CT forces that one): both must match the oracle and each other."""
+    arithmetic as the general kernel (the compile-time-length option, switched off, forces that one): both must match the oracle and each other."""
     L = 196
     seed = synth.BASE_SEED + 19 * H + B
-    monkeypatch.delenv("SPECTRE_NO_SLAB_CT", raising=False)
+    from paper_2502_18394_amd import binding
     got, want, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
-    monkeypatch.setenv("SPECTRE_NO_SLAB_CT", "1")
+    options(binding.OPT_SLAB_COMPILE_TIME, 0)
     general, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
     e1, e2, e12 = rel_l2(got, want), rel_l2(general, want), rel_l2(got, general)
     print(f"case B={B} H={H} io={io}: own kernel {e1:.3e}  general {e2:.3e}  between {e12:.3e}", flush=True)
@@ -141,14 +133,14 @@ def test_patch_grid_length_with_many_heads_takes_its_own_kernel(oracle, monkeypa
 
 @pytest.mark.parametrize("B,L,H,io", [(1, 8192, 8, "f32"), (2, 8192, 12, "bf16"), (1, 6144, 16, "bf16"), (1, 12288, 8, "f32"),
                                        (3, 5120, 8, "bf16")])
-def test_head_affine_placement_changes_no_bit(oracle, monkeypatch, B, L, H, io):
+def test_head_affine_placement_changes_no_bit(oracle, options, B, L, H, io):
     """Four-step lengths up to 12288 with a multiple of 8 heads in a call place every workgroup of a head on one XCD
     and walk the heads up, down, up through the three kernels (L2 reuse).  It is only a renumbering of workgroups:
-    the rows must equal those of the plain numbering (SPECTRE_NO_AFFINE) bit for bit, and match the oracle."""
+    the rows must equal those of the plain numbering (head-affine option off) bit for bit, and match the oracle."""
     seed = synth.BASE_SEED + 23 * H + L
-    monkeypatch.delenv("SPECTRE_NO_AFFINE", raising=False)
+    from paper_2502_18394_amd import binding
     got, want, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
-    monkeypatch.setenv("SPECTRE_NO_AFFINE", "1")
+    options(binding.OPT_HEAD_AFFINE, 0)
     plain, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
     err = rel_l2(got, want)
     print(f"case B={B} L={L} H={H} io={io}: rel_l2 {err:.3e} identical {np.array_equal(got, plain)}", flush=True)
@@ -195,6 +187,7 @@ def test_short_and_mixed_radix_lengths(oracle, B, L, H, io):
     err = rel_l2(got, want)
     print(f"  rel_l2={err:.3e}", flush=True)
     assert err <= TOL[io]
+    assert_close_elementwise(got, want, io, L)
 
 
 def test_vit_config_full_size(oracle):
@@ -204,6 +197,7 @@ def test_vit_config_full_size(oracle):
     err = rel_l2(got, want)
     print(f"  rel_l2={err:.3e}", flush=True)
     assert err <= 1e-5
+    assert_close_elementwise(got, want, c["io"], c["L"])
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
@@ -219,6 +213,7 @@ def test_any_other_length(oracle, B, L, H, io):
     err = rel_l2(got, want)
     print(f"  rel_l2={err:.3e}", flush=True)
     assert err <= TOL[io]
+    assert_close_elementwise(got, want, io, 16 * L)        # padded transform, and the kernel came through two more
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
@@ -233,6 +228,7 @@ def test_four_step_with_an_odd_factor(oracle, B, L, H, io):
     err = rel_l2(got, want)
     print(f"  rel_l2={err:.3e}", flush=True)
     assert err <= TOL[io]
+    assert_close_elementwise(got, want, io, L)
 
 
 def test_any_other_length_identity_and_shift(oracle):
@@ -278,3 +274,4 @@ def test_shapes_around_the_route_boundaries(oracle, B, L, H, io):
     err = rel_l2(got, want)
     print(f"  rel_l2={err:.3e}", flush=True)
     assert err <= TOL[io]
+    assert_close_elementwise(got, want, io, 16 * L)

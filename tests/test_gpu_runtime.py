@@ -49,14 +49,26 @@ def test_decode_step_is_bitwise_reproducible():
 
 
 def test_shutdown_frees_tables_and_library_recovers(oracle):
+    """After spectre_shutdown a length is unprepared again: the C entry point says so and launches nothing (the output
+    keeps its sentinel), spectre_prepare brings it back, and the rows are the same bits as before."""
     from paper_2502_18394_amd import binding
     vals, store = synth.tokens(8, (1, 512, 1, 64), "f32")
-    g = synth.random_gate(9, 1, 1, 512)
-    a = binding.mix_forward(to_device(store, "f32"), torch.from_numpy(g).cuda()).cpu()
+    g = torch.from_numpy(synth.random_gate(9, 1, 1, 512)).cuda()
+    v = to_device(store, "f32")
+    a = binding.mix_forward(v, g).cpu()
     torch.cuda.synchronize()
-    binding.lib().spectre_shutdown()
-    binding.lib().spectre_shutdown()
-    b = binding.mix_forward(to_device(store, "f32"), torch.from_numpy(g).cuda()).cpu()
+    binding.shutdown()
+    binding.shutdown()
+    out = torch.full_like(v, 7.0)
+    ws = torch.empty(512, dtype=torch.uint8, device="cuda")
+    off = (-ws.data_ptr()) % 256
+    L = binding.lib()
+    rc = L.spectre_mix_forward(ctypes.c_void_p(v.data_ptr()), ctypes.c_void_p(g.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                               1, 512, 1, 64, 0, ctypes.c_void_p(ws.data_ptr() + off), ctypes.c_size_t(256), None)
+    torch.cuda.synchronize()
+    assert rc == binding.ENOTREADY and b"spectre_prepare" in L.spectre_last_error()
+    assert bool((out == 7.0).all())
+    b = binding.mix_forward(v, g).cpu()                  # the binding prepares the length again
     assert torch.equal(a, b)
 
 
@@ -86,15 +98,48 @@ def test_error_paths_launch_nothing():
         binding.PrefixCache(1, 1, 64, 1000)                      # window length without a plan
 
 
+def test_prefix_update_with_a_short_workspace_launches_nothing():
+    """A cache with deferred updates pending: spectre_prefix_update checks its workspace before it flushes them, so an
+    EWORKSPACE return leaves the spectrum, the pending list and the token counter exactly as they were."""
+    from paper_2502_18394_amd import binding
+    B, H, d, N = 1, 2, 64, 1024
+    P = binding.GateParams(synth.gate_params(80, H, d, N))
+    c = binding.PrefixCache(B, H, d, N, defer=8)
+    _, v0 = synth.tokens(81, (B, 700, H, d), "f32")
+    _, q0 = synth.tokens(82, (B, 700, H, d), "f32")
+    c.update(to_device(v0, "f32"), to_device(q0, "f32"))
+    for i in range(3):
+        _, vt = synth.tokens(83 + i, (B, 1, H, d), "f32")
+        c.step(to_device(vt, "f32"), to_device(vt, "f32"), P)
+    torch.cuda.synchronize()
+    assert c.n_pending == 3
+    before = c.prefix_fft.clone()
+    _, v2 = synth.tokens(90, (B, 4, H, d), "f32")
+    v2d = to_device(v2, "f32")
+    ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    off = (-ws.data_ptr()) % 256
+    rc = binding.lib().spectre_prefix_update(ctypes.byref(c.c), ctypes.c_void_p(v2d.data_ptr()), ctypes.c_void_p(v2d.data_ptr()),
+                                             4, 0, ctypes.c_void_p(ws.data_ptr() + off), ctypes.c_size_t(256), None)
+    torch.cuda.synchronize()
+    assert rc == binding.EWORKSPACE
+    assert c.n_pending == 3 and c.t == 703
+    assert torch.equal(before.view(torch.float32), c.prefix_fft.view(torch.float32))
+    c.update(v2d, v2d)                                        # the same call with its workspace goes through
+    assert c.n_pending == 0 and c.t == 707
+
+
 @pytest.mark.parametrize("L,H", [(4096, 4), (32768, 32)])
 def test_forward_path_replays_from_a_hip_graph(oracle, L, H):
-    """gate -> mixer -> level gates -> refinement captured once in a HIP graph (tables warmed, buffers
-    preallocated: nothing allocates or synchronises inside the calls) and replayed on fresh inputs, with eager
-    work and synchronisations between the replays; every replay must equal the eager result bit for bit.
-    The larger case runs its head groups on two streams (fork and join are captured as graph edges)."""
+    """gate -> mixer -> level gates -> refinement captured once in a HIP graph and replayed on fresh inputs, with
+    eager work and synchronisations between the replays; every replay must equal the eager result bit for bit.
+    The capture is the first thing these lengths see after a shutdown: only spectre_prepare ran before it, no eager
+    call (compute calls neither allocate nor synchronise).  The larger case runs its head groups on two streams
+    (fork and join are captured as graph edges)."""
     from paper_2502_18394_amd import binding
     B, d = 1, 64
     J = synth.max_wavelet_levels(L)
+    binding.shutdown()
+    binding.prepare(L, d)
     P = binding.GateParams(synth.gate_params(40, H, d, L))
     W = binding.WrmParams(synth.wrm_params(41, H, d, J))
 
@@ -108,8 +153,6 @@ def test_forward_path_replays_from_a_hip_graph(oracle, L, H):
         return binding.wrm_apply(binding.mix_forward(v, g), binding.wrm_gates(q, W, 1.0 / L))
 
     v0, q0 = inputs(42)
-    want0 = eager(v0, q0).clone()                       # also warms the per-length tables
-    torch.cuda.synchronize()
     v_s, q_s = v0.clone(), q0.clone()                   # static graph inputs
     g_s = torch.empty((B, H, L // 2 + 1), dtype=torch.complex64, device="cuda")
     s_s = torch.empty((B, H, J + 1, d), dtype=torch.float32, device="cuda")
@@ -123,6 +166,8 @@ def test_forward_path_replays_from_a_hip_graph(oracle, L, H):
         binding.mix_forward(v_s, g_s, out=mix_s, ws=ws[1])
         binding.wrm_gates(q_s, W, 1.0 / L, s_out=s_s, ws=ws[2])
         binding.wrm_apply(mix_s, s_s, out=out_s, ws=ws[3])
+    want0 = eager(v0, q0).clone()
+    torch.cuda.synchronize()
     for r, seed in enumerate((42, 50, 60)):
         v, q = inputs(seed)
         want = eager(v, q).clone()                      # eager work between replays
