@@ -20,11 +20,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
-# L2<->fabric bytes per spectre_mix_forward call at llama1b_128k and per decode sweep, from separate rocprofv3
-# FETCH_SIZE and WRITE_SIZE passes over this same script (scaled by what the counters read for a plain 1 GiB copy;
-# the summary is kept with the other profiler summaries)
-MIX_TRAFFIC_BYTES_128K = 5.21 * 2 ** 30
-DECODE_SWEEP_TRAFFIC_BYTES = (2085.8 + 2056.2) * 2 ** 20
+# L2<->fabric bytes per spectre_mix_forward call at llama1b_128k and per decode sweep come from separate rocprofv3
+# FETCH_SIZE and WRITE_SIZE passes over this same script (scaled by what the counters read for a plain 1 GiB copy);
+# the figures are read from the tracked summary of those passes, lines of the form `name = bytes`
+TRAFFIC_FILE = os.path.join("profiles", "traffic_llama1b_128k_and_decode_32k.txt")
+# lane-instructions per complex point (one channel pair at one position) of the three transform kernels at
+# L = 131072, counted in the ISA of the built library: 84 (column kernel) + 37 + 37 (row kernels)
+COUNTED_LANE_INSTR_PER_POINT_128K = 158
 # fp32 vector peak without packed math: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s
 VALU_PEAK_GINSTR = 256 * 4 * 16 * 2.4
 
@@ -38,7 +40,9 @@ def parse():
     ap.add_argument("--L", type=int, default=0, help="override the sequence length of the workload")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--decode-steps", type=int, default=32)
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration mixer rows")
+    ap.add_argument("--decode-steps", type=int, default=256,
+                    help="decode steps timed (the baseline's configuration appends 256 tokens, each a fresh random one)")
     ap.add_argument("--no-secondary", action="store_true",
                     help="skip the secondary decode row (window of 65536 slots), e.g. under a profiler so that every\n"
                          "cache kernel in the trace belongs to the decode_32k workload")
@@ -48,6 +52,23 @@ def parse():
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference for scaling hardware byte counters)")
     return ap.parse_args()
+
+
+def traffic_figures():
+    """{name: bytes} from the tracked counter summary, or {} if it is missing."""
+    out = {}
+    try:
+        with open(os.path.join(ROOT, TRAFFIC_FILE)) as f:
+            for line in f:
+                if "=" in line and not line.lstrip().startswith("#"):
+                    k, v = line.split("=", 1)
+                    try:
+                        out[k.strip()] = float(v.split()[0])
+                    except (ValueError, IndexError):
+                        pass
+    except OSError:
+        pass
+    return out
 
 
 def time_loop(fn, steps, warmup):
@@ -105,8 +126,7 @@ def cpu_baseline(cfg, L):
     from paper_2502_18394_amd import synth
     oracle.build()
     H, d = cfg["H"], cfg["d"]
-    Hs = max(1, min(H, (16 * 131072) // L))          # about 16 heads at 128k; all heads when short
-    Hs = min(Hs, H)
+    Hs = H                                           # the whole workload: about 6 s at 128k on 16 threads
     vals, _ = synth.tokens(synth.BASE_SEED, (1, L, Hs, d), cfg["io"])
     qv, _ = synth.tokens(synth.BASE_SEED + 1, (1, L, Hs, d), cfg["io"])
     p = synth.gate_params(synth.BASE_SEED + 2, Hs, d, L)
@@ -116,59 +136,76 @@ def cpu_baseline(cfg, L):
     g = oracle.gate(oracle.pool_q(Q), 1.0 / L, p64, L, 0)
     oracle.mix_forward(V, g)
     dt = time.time() - t0
-    full = dt * (cfg["B"] * H / Hs)
-    return {"value": cfg["B"] * L / full, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"gate+mix_forward of {Hs} of {cfg['B'] * H} heads at L={L} took {dt:.2f} s, scaled to all heads"}
+    return {"value": cfg["B"] * L / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"gate+mix_forward of all {cfg['B'] * H} heads at L={L} (the whole workload, one pass): {dt:.2f} s"}
+
+
+def mix_case(name, c, steps, graph=False):
+    """Mixer-only timing of one configuration.  A working set below the memory-side cache is rotated over enough
+    buffers (> 512 MB in total) that the figure is not a cache-resident one; the cache-resident time rides along."""
+    import torch
+    from paper_2502_18394_amd import binding, synth
+    B, H, L, d = c["B"], c["H"], c["L"], c["d"]
+    dtype = torch.bfloat16 if c["io"] == "bf16" else torch.float32
+    esize = 2 if c["io"] == "bf16" else 4
+    nbytes = B * L * H * d * esize
+    nbuf = max(1, min(64, (512 << 20) // (2 * nbytes) + 1))
+    Vs = [device_tokens((B, L, H, d), synth.BASE_SEED + i, dtype) for i in range(nbuf)]
+    outs = [torch.empty_like(Vs[0]) for _ in range(nbuf)]
+    g = torch.from_numpy(synth.random_gate(synth.BASE_SEED, B, H, L)).cuda()
+    ws = torch.empty(binding.mix_workspace_bytes(B, L, H, d, binding._dtype_code(Vs[0])) + 256, dtype=torch.uint8, device="cuda")
+    it = [0]
+
+    def call():
+        i = it[0] % nbuf
+        binding.mix_forward(Vs[i], g, out=outs[i], ws=ws)
+        it[0] += 1
+    reps = max(steps, min(200, int(2e9 // max(nbytes, 1)) + 1))
+    ms = time_loop(call, reps, 3)
+    it[0] = 0
+    ms_hot = time_loop(lambda: binding.mix_forward(Vs[0], g, out=outs[0], ws=ws), reps, 3)
+    ms_graph = None
+    if graph and nbytes <= (64 << 20):     # launch-bound sizes: the same call replayed from a HIP graph
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for i in range(min(nbuf, 8)):
+                binding.mix_forward(Vs[i], g, out=outs[i], ws=ws)
+        ms_graph = time_loop(gr.replay, max(reps // 8, 5), 2) / min(nbuf, 8)
+        del gr
+    alg = 2 * nbytes + B * H * (L // 2 + 1) * 8
+    row = {"workload": name, "B": B, "H": H, "L": L, "d": d, "io": c["io"], "ms": ms,
+           "tokens_per_s": B * L / (ms * 1e-3), "algorithmic_bytes": alg,
+           "hbm_frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "buffers_rotated": nbuf,
+           "ms_cache_resident": ms_hot}
+    if graph:
+        row["ms_hip_graph"] = ms_graph
+    del Vs, outs, g, ws
+    torch.cuda.empty_cache()
+    return row
+
+
+def config_cases():
+    """Every mixer configuration the baseline names: config 1, config 2 (= the 8192 point of the sweep), the length
+    sweep of config 3 and the ViT shape of config 5."""
+    from paper_2502_18394_amd import synth
+    cases = [("config1_single_head_1k", synth.CONFIGS["single_head_1k"])]
+    for L in synth.SWEEP_L:
+        tag = "config2_and_3" if L == 8192 else "config3"
+        cases.append((f"{tag}_llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")))
+    cases.append(("config5_vit_196", synth.CONFIGS["vit_196"]))
+    return cases
 
 
 def sweep(args):
-    """Mixer-only timing of every configuration; working sets below the memory-side cache are
-    rotated over enough buffers (> 512 MB in total) that the figure is not a cache-resident one."""
-    import torch
-    from paper_2502_18394_amd import binding, synth
-    cases = [("single_head_1k", synth.CONFIGS["single_head_1k"])]
-    cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in synth.SWEEP_L]
-    cases += [("vit_196", synth.CONFIGS["vit_196"])]
+    """One JSON line per configuration (mixer only), then lengths outside the baseline's list."""
+    cases = config_cases()
     # four-step lengths with an odd factor (3 * 4096, 24 * 4096), then lengths with no plan of their own
     # (padded power-of-two convolution)
     cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in (12288, 98304)]
     cases += [("vit_197_cls", dict(B=256, H=12, L=197, d=64, io="f32"))]
     cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in (1000, 50000)]
     for name, c in cases:
-        B, H, L, d = c["B"], c["H"], c["L"], c["d"]
-        dtype = torch.bfloat16 if c["io"] == "bf16" else torch.float32
-        esize = 2 if c["io"] == "bf16" else 4
-        nbytes = B * L * H * d * esize
-        nbuf = max(1, min(64, (512 << 20) // (2 * nbytes) + 1))
-        Vs = [device_tokens((B, L, H, d), synth.BASE_SEED + i, dtype) for i in range(nbuf)]
-        outs = [torch.empty_like(Vs[0]) for _ in range(nbuf)]
-        g = torch.from_numpy(synth.random_gate(synth.BASE_SEED, B, H, L)).cuda()
-        ws = torch.empty(binding.mix_workspace_bytes(B, L, H, d, binding._dtype_code(Vs[0])) + 256, dtype=torch.uint8, device="cuda")
-        it = [0]
-
-        def call():
-            i = it[0] % nbuf
-            binding.mix_forward(Vs[i], g, out=outs[i], ws=ws)
-            it[0] += 1
-        reps = max(args.steps, min(200, int(2e9 // max(nbytes, 1)) + 1))
-        ms = time_loop(call, reps, 3)
-        it[0] = 0
-        ms_hot = time_loop(lambda: binding.mix_forward(Vs[0], g, out=outs[0], ws=ws), reps, 3)
-        ms_graph = None
-        if nbytes <= (64 << 20):     # launch-bound sizes: the same call replayed from a HIP graph
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                for i in range(min(nbuf, 8)):
-                    binding.mix_forward(Vs[i], g, out=outs[i], ws=ws)
-            ms_graph = time_loop(graph.replay, max(reps // 8, 5), 2) / min(nbuf, 8)
-            del graph
-        alg = 2 * nbytes + B * H * (L // 2 + 1) * 8
-        print(json.dumps({"workload": name, "B": B, "H": H, "L": L, "d": d, "io": c["io"], "ms": ms,
-                          "tokens_per_s": B * L / (ms * 1e-3), "algorithmic_bytes": alg,
-                          "hbm_frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "buffers_rotated": nbuf,
-                          "ms_cache_resident": ms_hot, "ms_hip_graph": ms_graph}), flush=True)
-        del Vs, outs, g, ws
-        torch.cuda.empty_cache()
+        print(json.dumps(mix_case(name, c, args.steps, graph=True)), flush=True)
 
 
 def main():
@@ -230,21 +267,32 @@ def main():
     F = L // 2 + 1
     mix_bytes = 2 * tokens * H * d * esize + B * H * F * 8                # read V, write out, read g
     gate_bytes = tokens * H * d * esize + P.Hg * P.d_g * 2 * F * 4 + B * H * F * 8   # read Q, read W2, write g
-    mix_flops_instr = tokens * H * (d // 2) * (2 * 3.5 * (L.bit_length() - 1) + 6)   # lane-instructions: 3.5 per point per radix-2 stage each way + 6 for the gate
+    headline = (args.workload == "llama1b_128k" and not args.L)
+    traffic = traffic_figures() if headline else {}
+    if headline:      # counted in the ISA; other lengths: 3.5 per point per radix-2 stage each way + 6 for the gate
+        instr_per_point, instr_src = COUNTED_LANE_INSTR_PER_POINT_128K, "counted in the ISA of the three transform kernels"
+    else:
+        instr_per_point, instr_src = 2 * 3.5 * (L.bit_length() - 1) + 6, "model: 3.5 per point and radix-2 stage each way + 6"
+    mix_flops_instr = tokens * H * (d // 2) * instr_per_point
+    e2e_bytes = mix_bytes + gate_bytes - B * H * F * 8        # Q, V in; out; W2; g written once and read once
     res = {
         "metric": "mixer tokens/sec at L=128k (H=32,d=64) + % HBM roofline; decode tokens/sec",
         "value": tokens / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f32", "io_dtype": cfg["io"], "data": "synthetic",
         "config": {"workload": f"{args.workload}: gate+mix_forward B={B} H={H} d={d} L={L} {cfg['io']} I/O, fp32 spectra",
                    "global_batch": B, "seq_len": L, "parallelism": "single GPU"},
         "roofline": {"bound": "hbm", "kernel": "spectre_mix_forward (gate_expand + per head group: small_fwd, big, small_inv)",
                      "achieved": mix_bytes / (ms_mix * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": mix_bytes / (ms_mix * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": MIX_TRAFFIC_BYTES_128K if (args.workload == "llama1b_128k" and not args.L) else None,
+                     "traffic": traffic.get("mix_forward_bytes_per_call"),
+                     "traffic_source": TRAFFIC_FILE if "mix_forward_bytes_per_call" in traffic else None,
                      "algorithmic_bytes": mix_bytes, "ms": ms_mix},
         "roofline_alu": {"bound": "alu", "achieved": mix_flops_instr / (ms_mix * 1e-3) / 1e9, "peak": VALU_PEAK_GINSTR,
-                         "unit": "G lane-instr/s", "frac": mix_flops_instr / (ms_mix * 1e-3) / 1e9 / VALU_PEAK_GINSTR},
+                         "unit": "G lane-instr/s", "frac": mix_flops_instr / (ms_mix * 1e-3) / 1e9 / VALU_PEAK_GINSTR,
+                         "lane_instr_per_point": instr_per_point, "lane_instr_source": instr_src},
+        "end_to_end": {"what": "gate from the query rows + mixer (the timed step)", "ms": ms_step,
+                       "algorithmic_bytes": e2e_bytes, "hbm_frac": e2e_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "mix_only": {"tokens_per_s": tokens / (ms_mix * 1e-3), "ms": ms_mix, "ms_median_of_single_calls": mix_med,
                      "ms_min_of_single_calls": mix_min},
         "gate_only": {"ms": ms_gate, "algorithmic_bytes": gate_bytes,
@@ -302,17 +350,27 @@ def main():
         Pd = device_gate_params(synth.BASE_SEED + 3, Hd, dd, N, synth.D_GATE, binding)
         cache.update(device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 4, torch.float32),
                      device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 5, torch.float32))
-        vt = device_tokens((Bd, 1, Hd, dd), synth.BASE_SEED + 6, torch.float32)
-        qt = device_tokens((Bd, 1, Hd, dd), synth.BASE_SEED + 7, torch.float32)
+        # one fresh random token per step (drawn before the timed region, resident in HBM)
+        nrot = max(args.decode_steps + 8, 64)
+        vts = device_tokens((nrot, Bd, 1, Hd, dd), synth.BASE_SEED + 6, torch.float32)
+        qts = device_tokens((nrot, Bd, 1, Hd, dd), synth.BASE_SEED + 7, torch.float32)
+        vt, qt = vts[0], qts[0]
         od = torch.empty_like(vt)
-        ms_dec = time_loop(lambda: cache.step(vt, qt, Pd, out=od), args.decode_steps, 3)
+        k = [0]
+
+        def decode_step():
+            i = k[0] % nrot
+            cache.step(vts[i], qts[i], Pd, out=od)
+            k[0] += 1
+        ms_dec = time_loop(decode_step, args.decode_steps, 3)
         Fd = N // 2 + 1
         sweep_bytes = 2 * 8 * Bd * Hd * Fd * dd
         res["decode"] = {"workload": f"decode_32k: fused Prefix-FFT step B={Bd} H={Hd} d={dd} N_max={N}, cache full (eviction branch), fp32",
                          "tokens_per_s": Bd / (ms_dec * 1e-3), "ms_per_step": ms_dec, "steps": args.decode_steps,
                          "roofline": {"bound": "hbm", "kernel": "k_sweep<update,read>", "achieved": sweep_bytes / (ms_dec * 1e-3) / 1e9,
                                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sweep_bytes / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                      "traffic": DECODE_SWEEP_TRAFFIC_BYTES, "algorithmic_bytes": sweep_bytes}}
+                                      "traffic": traffic_figures().get("decode_sweep_bytes_per_step"),
+                                      "traffic_source": TRAFFIC_FILE, "algorithmic_bytes": sweep_bytes}}
         # one-time rows of the same cache: pre-fill from 32768 tokens (Alg. 1 PreFill) and the literal full-window
         # readout (inverse transform of the gated cache, all live rows)
         Vp = device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 4, torch.float32)
@@ -361,8 +419,8 @@ def main():
             cache = binding.PrefixCache(Bd, Hd, dd, N, defer=cap)
             cache.update(device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 4, torch.float32),
                          device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 5, torch.float32))
-            nsteps = max(cap, (args.decode_steps // cap) * cap)          # whole flush periods
-            ms_def = time_loop(lambda: cache.step(vt, qt, Pd, out=od), nsteps, cap)
+            nsteps = max(cap, (min(args.decode_steps, 64) // cap) * cap)          # whole flush periods
+            ms_def = time_loop(decode_step, nsteps, cap)
             own_bytes = 8 * Bd * Hd * Fd * dd * (1.0 + 1.0 / cap)    # cap - 1 reads, one read + write
             res["decode_deferred"][f"cap{cap}"] = {
                 "tokens_per_s": Bd / (ms_def * 1e-3), "ms_per_step": ms_def, "steps": nsteps,
@@ -384,7 +442,7 @@ def main():
             Pw = device_gate_params(synth.BASE_SEED + 9, Hd, dd, N2w, synth.D_GATE, binding)
             cache.update(device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 4, torch.float32),
                          device_tokens((Bd, N, Hd, dd), synth.BASE_SEED + 5, torch.float32))
-            nst = max(4, args.decode_steps // 2)
+            nst = max(4, min(args.decode_steps, 32) // 2)
             ms_w = time_loop(lambda: cache.step(vt, qt, Pw, out=od), nst, 2)
             wbytes = 2 * 8 * Bd * Hd * (N2w // 2 + 1) * dd
             res["decode_no_eviction"] = {
@@ -394,6 +452,14 @@ def main():
             del cache, Pw
             torch.cuda.empty_cache()
 
+    if not args.no_configs:
+        # every configuration the baseline names, mixer call alone (config 4 is the decode row above)
+        res["configs"] = [mix_case(name, c, args.steps) for name, c in config_cases()]
+        if "decode" in res:
+            res["configs"].append({"workload": "config4_decode_32k", "ms": res["decode"]["ms_per_step"],
+                                   "tokens_per_s": res["decode"]["tokens_per_s"],
+                                   "algorithmic_bytes": res["decode"]["roofline"]["algorithmic_bytes"],
+                                   "hbm_frac": res["decode"]["roofline"]["frac"]})
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_baseline(cfg, L)
     print(json.dumps(res), flush=True)
