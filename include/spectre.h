@@ -248,6 +248,25 @@ enum { SPECTRE_MIX_BF16_SCRATCH = 1 };
 int spectre_mix_forward_ex(const void *v, const void *g, void *out, int B, int L, int H, int d,
                            spectre_dtype io, unsigned flags, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * spectre_mix_forward_static - spectre_mix_forward for callers that cannot allocate or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments without `ws`, same result to rounding (same kernels; the roots of unity are
+ * evaluated on the device in fp64 at every call instead of being taken from spectre_prepare's tables,
+ * which can differ in the last bit of a table entry).  All scratch - tables, expanded gate, transform
+ * columns - lives in one array of spectre_mix_static_bytes() = 98 MiB that is part of the library's
+ * device image: every GPU the library runs on holds it until the process ends.  The call allocates
+ * nothing, needs no spectre_prepare, and runs entirely on `stream`.
+ *   Limits: four-step lengths only (L = N1 * N2 as above, 256 ... 131072), d = 64, and
+ *   B*H*L <= 4 194 304 (32 heads at L = 131072); anything else returns SPECTRE_EUNSUPPORTED.
+ *   Every call on a GPU uses that GPU's one array, which keeps the previous call's contents (each
+ *   call overwrites what it reads, nothing needs clearing): calls that overlap in time on one GPU -
+ *   on different streams, or from different host threads - race and must be serialised by the caller.
+ */
+size_t spectre_mix_static_bytes(void);
+int spectre_mix_forward_static(const void *v, const void *g, void *out, int B, int L, int H, int d,
+                               spectre_dtype io, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Prefix-FFT cache, Sec. 3.3 and Algorithm 1.  One cache serves B*H heads that advance in
  * lock-step (one token counter).  The caller allocates the five device arrays (sizes from

@@ -62,7 +62,8 @@ def lib():
                      "spectre_project_workspace_bytes", "spectre_wrm_gates_workspace_bytes",
                      "spectre_wrm_apply_workspace_bytes",
                      "spectre_prefix_update_workspace_bytes", "spectre_prefix_readout_workspace_bytes",
-                     "spectre_prefix_step_workspace_bytes", "spectre_prefix_set_memory_workspace_bytes"):
+                     "spectre_prefix_step_workspace_bytes", "spectre_prefix_set_memory_workspace_bytes",
+                     "spectre_mix_static_bytes"):
             getattr(L, name).restype = ctypes.c_size_t
         L.spectre_get_option.restype = ctypes.c_long
         _lib = L
@@ -155,6 +156,20 @@ def mix_forward(v, g, out=None, ws=None, stream=None, flags=0):
     _check(lib().spectre_mix_forward_ex(_dev(v, "v"), _dev(g, "g"), _dev(out, "out"), ctypes.c_int(B), ctypes.c_int(L),
                                         ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(io), ctypes.c_uint(flags),
                                         wsp, wsn, _stream(stream)))
+    return out
+
+
+def mix_forward_static(v, g, out=None, stream=None):
+    """mix_forward on the library's built-in scratch array: no workspace, no allocation inside the call
+    (spectre_mix_forward_static; four-step lengths, B*H*L <= 4 Mi)."""
+    B, L, H, d = v.shape
+    if g.dtype != torch.complex64 or tuple(g.shape) != (B, H, L // 2 + 1):
+        raise ValueError("g must be complex64 [B,H,L//2+1]")
+    if out is None:
+        out = torch.empty_like(v)
+    _check(lib().spectre_mix_forward_static(_dev(v, "v"), _dev(g, "g"), _dev(out, "out"), ctypes.c_int(B),
+                                            ctypes.c_int(L), ctypes.c_int(H), ctypes.c_int(d),
+                                            ctypes.c_int(_dtype_code(v)), _stream(stream)))
     return out
 
 

@@ -268,6 +268,35 @@ static MixGroups mix_groups(int BH, int L, int d, int scale) {
     return m;
 }
 
+// ------------------------------------------------------------------------------------------
+// Scratch of spectre_mix_forward_static: one array per GPU in the library's own device image, held until the process
+// ends.  Layout: [roots of unity, kStaticTables][expanded gate, kStaticGate][transform scratch, kStaticColumns].
+constexpr size_t kStaticTables = (size_t)2 << 20;     // (L + N1) complex64 <= 135168 * 8 bytes
+constexpr size_t kStaticGate = (size_t)32 << 20;      // B*H*L complex64: up to 4 Mi bins (32 heads at L = 131072)
+constexpr size_t kStaticColumns = (size_t)64 << 20;   // at least one head's columns (32 MiB at L = 131072)
+constexpr size_t kStaticBytes = kStaticTables + kStaticGate + kStaticColumns;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+// `scratch` is only a host-side stand-in for the device array: its device address, different on every GPU, comes
+// from hipGetSymbolAddress, once per device with that device current, and is what host code passes on.
+static std::map<int, unsigned char *> g_static_ptr;
+static int static_scratch(unsigned char **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_static_ptr.find(dev);
+    if (it == g_static_ptr.end()) {
+        unsigned char *ptr = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255)) return fail(SPECTRE_EHIP, "static scratch: bad device address");
+        it = g_static_ptr.emplace(dev, ptr).first;
+    }
+    *out = it->second;
+    return SPECTRE_OK;
+}
+
 }  // namespace spectre
 
 using namespace spectre;
@@ -451,6 +480,8 @@ int spectre_prepare(int n, int d) {
         const hipError_t e = load();
         if (e != hipSuccess) return fail_hip(e, "prepare: loading kernels");
     }
+    unsigned char *static_base = nullptr;
+    if ((rc = static_scratch(&static_base))) return rc;
     return make_lane();
 }
 
@@ -601,6 +632,43 @@ int spectre_mix_forward_ex(const void *v, const void *g, void *out, int B, int L
 int spectre_mix_forward(const void *v, const void *g, void *out, int B, int L, int H, int d,
                         spectre_dtype io, void *ws, size_t ws_bytes, void *stream) {
     return spectre_mix_forward_ex(v, g, out, B, L, H, d, io, 0u, ws, ws_bytes, stream);
+}
+
+size_t spectre_mix_static_bytes(void) { return kStaticBytes; }
+
+int spectre_mix_forward_static(const void *v, const void *g, void *out, int B, int L, int H, int d,
+                               spectre_dtype io, void *stream) {
+    int rc = check_mix_args(v, g, out, B, L, H, d, io, "mix_forward_static");
+    if (rc) return rc;
+    int N1, N2, P;
+    if (d != 64 || !pow2_split(L, &N1, &N2, &P))
+        return fail(SPECTRE_EUNSUPPORTED, "mix_forward_static: only the four-step lengths (256 ... 131072) with d = 64, not L=%d, d=%d", L, d);
+    const size_t BH = (size_t)B * H, per_head = (size_t)L * (d / 2) * sizeof(float2);
+    if (BH * L * sizeof(float2) > kStaticGate)
+        return fail(SPECTRE_EUNSUPPORTED, "mix_forward_static: B*H*L = %zu bins exceeds the built-in scratch (%zu bins)",
+                    BH * L, kStaticGate / sizeof(float2));
+    if (per_head > kStaticColumns || (size_t)(L + N1) * sizeof(float2) > kStaticTables)
+        return fail(SPECTRE_EUNSUPPORTED, "mix_forward_static: L=%d exceeds the built-in scratch", L);
+    unsigned char *base = nullptr;
+    rc = static_scratch(&base);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // everything the kernels read from the array is written earlier in this same call (tables, gate planes, columns):
+    // nothing has to start at zero, and what the previous call left behind is never read
+    float2 *twL = reinterpret_cast<float2 *>(base), *twN1 = twL + L;
+    float2 *gp = reinterpret_cast<float2 *>(base + kStaticTables);
+    char *columns = reinterpret_cast<char *>(base + kStaticTables + kStaticGate);
+    hipError_t e = launch_fill_twiddle(twL, L, st);
+    if (e == hipSuccess) e = launch_fill_twiddle(twN1, N1, st);
+    if (e != hipSuccess) return fail_hip(e, "fill_twiddle");
+    Pow2Plan pl;
+    pl.L = L; pl.N1 = N1; pl.N2 = N2; pl.P = P; pl.twL = twL; pl.twN1 = twN1;
+    MixGroups mg;                                      // one lane, groups of as many heads as the columns area holds
+    mg.BH = (int)BH;
+    mg.chunk = (int)(kStaticColumns / per_head < BH ? kStaticColumns / per_head : BH);
+    mg.ngroups = ((int)BH + mg.chunk - 1) / mg.chunk;
+    return mix_four_step(pl, v, static_cast<const float2 *>(g), out, (int)BH, L, H, d, io, gp, columns, 0, mg, false,
+                         nullptr, st);
 }
 
 // ------------------------------------------------------------------------------------------ gate

@@ -126,6 +126,20 @@ def test_options_and_prepare_argument_checks(lib):
     assert rc == 1 and b"flag" in lib.spectre_last_error()
 
 
+def test_static_scratch_entry_point_rejects_what_does_not_fit(lib):
+    lib.spectre_mix_static_bytes.restype = ctypes.c_size_t
+    assert lib.spectre_mix_static_bytes() == 98 << 20
+    fake, far = ctypes.c_void_p(4096), ctypes.c_void_p(1 << 40)
+    # a length without a four-step plan, a batch whose gate planes exceed the array, a bad dtype, overlap, d
+    assert lib.spectre_mix_forward_static(fake, fake, far, 1, 1000, 1, 64, 0, None) == 2
+    assert lib.spectre_mix_forward_static(fake, fake, far, 2, 131072, 32, 64, 1, None) == 2
+    assert b"exceeds" in lib.spectre_last_error()
+    assert lib.spectre_mix_forward_static(fake, fake, far, 1, 1024, 1, 64, 5, None) == 1
+    assert lib.spectre_mix_forward_static(fake, fake, fake, 1, 1024, 1, 64, 0, None) == 1
+    assert lib.spectre_mix_forward_static(fake, fake, far, 1, 1024, 1, 32, 0, None) == 2
+    assert lib.spectre_mix_forward_static(None, fake, far, 1, 1024, 1, 64, 0, None) == 1
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     from paper_2502_18394_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
