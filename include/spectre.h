@@ -109,9 +109,16 @@ void spectre_shutdown(void);
  *                                  for the lengths that have a compile-time form (default 1)
  *   SPECTRE_OPT_HEAD_AFFINE        0 switches off the placement of all workgroups of a head on one
  *                                  XCD that four-step lengths up to 12288 use (default 1)
+ *   SPECTRE_OPT_LANE_SHUFFLES      1 makes the column kernel of the four-step route exchange values
+ *                                  between the 16 lanes of a sub-transform with cross-lane (DPP) moves
+ *                                  instead of through LDS (default 0: measured slower or equal)
+ *   SPECTRE_OPT_GROUPS             n > 0 splits the heads of a four-step call into n groups of equal
+ *                                  size (rounded up to an even count on two lanes), whatever the
+ *                                  scratch budget says; 0 (default) sizes the groups by the budget
  */
 enum { SPECTRE_OPT_LANES = 0, SPECTRE_OPT_SCRATCH_MB = 1, SPECTRE_OPT_FUSED_4096 = 2,
-       SPECTRE_OPT_SLAB_COMPILE_TIME = 3, SPECTRE_OPT_HEAD_AFFINE = 4, SPECTRE_OPT_COUNT_ = 5 };
+       SPECTRE_OPT_SLAB_COMPILE_TIME = 3, SPECTRE_OPT_HEAD_AFFINE = 4, SPECTRE_OPT_GROUPS = 5,
+       SPECTRE_OPT_LANE_SHUFFLES = 6, SPECTRE_OPT_COUNT_ = 7 };
 int spectre_set_option(int which, long value);
 long spectre_get_option(int which);
 

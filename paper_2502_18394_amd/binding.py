@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libspectre_hip.so")
 F32, BF16 = 0, 1
 READ_NEWEST, READ_WINDOW = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ENOTREADY = 0, 1, 2, 3, 4, 5
-OPT_LANES, OPT_SCRATCH_MB, OPT_FUSED_4096, OPT_SLAB_COMPILE_TIME, OPT_HEAD_AFFINE = 0, 1, 2, 3, 4
+OPT_LANES, OPT_SCRATCH_MB, OPT_FUSED_4096, OPT_SLAB_COMPILE_TIME, OPT_HEAD_AFFINE, OPT_GROUPS, OPT_LANE_SHUFFLES = 0, 1, 2, 3, 4, 5, 6
 MIX_BF16_SCRATCH = 1
 
 _lib = None

@@ -29,7 +29,7 @@ static thread_local std::string g_err;
 
 // Process-wide tuning switches (spectre_set_option); none of them changes a result.
 static std::atomic<long> g_opt[SPECTRE_OPT_COUNT_];
-static const long kOptDefault[SPECTRE_OPT_COUNT_] = {2, 204, 1, 1, 1};
+static const long kOptDefault[SPECTRE_OPT_COUNT_] = {2, 204, 1, 1, 1, 0, 0};
 long option(int which) {
     const long v = g_opt[which].load(std::memory_order_relaxed);
     return v > 0 ? v - 1 : kOptDefault[which];       // stored as value + 1 so that zero-initialised = default
@@ -256,6 +256,15 @@ static MixGroups mix_groups(int BH, int L, int d, int scale) {
     m.BH = BH;
     const int full = mix_chunk_heads(BH, L, d);
     const int half = full / 2;
+    const long forced = option(SPECTRE_OPT_GROUPS);
+    if (forced > 0) {                                 // measurement: this many groups of (almost) equal size
+        m.ngroups = forced < BH ? (int)forced : BH;
+        m.lanes = (option(SPECTRE_OPT_LANES) >= 2 && m.ngroups >= 2) ? 2 : 1;
+        if (m.lanes == 2 && (m.ngroups & 1)) m.ngroups += 1;
+        m.chunk = (BH + m.ngroups - 1) / m.ngroups;
+        if (m.lanes == 1) m.ngroups = (BH + m.chunk - 1) / m.chunk;
+        return m;
+    }
     if (option(SPECTRE_OPT_LANES) < 2 || full >= BH || half < 1) {
         m.chunk = ((long long)full * scale < BH) ? full * scale : BH;
         m.ngroups = (BH + m.chunk - 1) / m.chunk;

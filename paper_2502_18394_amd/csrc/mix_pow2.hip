@@ -17,6 +17,7 @@
 #include "mix_pow2.h"
 
 #include "fft_regs.h"
+#include "internal.h"
 
 namespace spectre {
 
@@ -224,7 +225,52 @@ __device__ __forceinline__ void exchange(float2 (&x)[16], float2 *buf, int tau) 
     if (!CROSS) __builtin_amdgcn_wave_barrier();
 }
 
-template <int P, int MODE, typename SC>
+// The same exchange inside a group of 16 lanes without LDS: a 16 x 16 transpose (register j of lane a <-> register
+// a of lane j) as four steps, one per index bit m, each swapping the elements whose register bit and lane bit
+// differ with the partner lane a ^ m, by DPP moves (rows of 16 lanes are the DPP rows of a wave).  For m = 4, 8 the
+// lanes that receive are whole banks of four lanes, so two masked moves per value do the step; for m = 1, 2 the
+// partner's value is fetched with a quad permutation and selected per lane.  Pure data movement: results are
+// bit-identical to the LDS exchange.
+template <int M>
+__device__ __forceinline__ void transpose16_step(float (&v)[16], int a) {
+#pragma unroll
+    for (int j0 = 0; j0 < 16; ++j0) {
+        if (j0 & M) continue;
+        const int j1 = j0 | M;
+        const int lo = __float_as_int(v[j0]), hi = __float_as_int(v[j1]);
+        int nlo, nhi;
+        if constexpr (M == 8) {          // lanes 8..15 take the partner's hi into lo; lanes 0..7 the partner's lo into hi
+            nlo = __builtin_amdgcn_update_dpp(lo, hi, 0x118, 0xF, 0xC, false);   // row_shr:8, banks 2,3
+            nhi = __builtin_amdgcn_update_dpp(hi, lo, 0x108, 0xF, 0x3, false);   // row_shl:8, banks 0,1
+        } else if constexpr (M == 4) {
+            nlo = __builtin_amdgcn_update_dpp(lo, hi, 0x114, 0xF, 0xA, false);   // row_shr:4, banks 1,3
+            nhi = __builtin_amdgcn_update_dpp(hi, lo, 0x104, 0xF, 0x5, false);   // row_shl:4, banks 0,2
+        } else {
+            constexpr int ctrl = (M == 1) ? 0xB1 : 0x4E;                          // quad_perm [1,0,3,2] / [2,3,0,1]
+            const int phi = __builtin_amdgcn_update_dpp(0, hi, ctrl, 0xF, 0xF, false);
+            const int plo = __builtin_amdgcn_update_dpp(0, lo, ctrl, 0xF, 0xF, false);
+            nlo = (a & M) ? phi : lo;
+            nhi = (a & M) ? hi : plo;
+        }
+        v[j0] = __int_as_float(nlo);
+        v[j1] = __int_as_float(nhi);
+    }
+}
+__device__ __forceinline__ void transpose16(float2 (&x)[16], int tau) {
+    const int a = tau & 15;
+    float re[16], im[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { re[j] = x[j].x; im[j] = x[j].y; }
+    transpose16_step<8>(re, a); transpose16_step<8>(im, a);
+    transpose16_step<4>(re, a); transpose16_step<4>(im, a);
+    transpose16_step<2>(re, a); transpose16_step<2>(im, a);
+    transpose16_step<1>(re, a); transpose16_step<1>(im, a);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) x[j] = make_float2(re[j], im[j]);
+}
+
+// SHFL: the exchanges that stay inside 16 lanes go through transpose16 instead of LDS.
+template <int P, int MODE, typename SC, bool SHFL = false>
 __global__ __launch_bounds__(256) void k_big(typename SC::elem_t *__restrict__ scr, const float2 *__restrict__ gp,
                                              const float2 *__restrict__ twN1, int N2, int ppw, int bh0,
                                              int nplanes_xcd, int g_step, int aff) {
@@ -288,12 +334,14 @@ __global__ __launch_bounds__(256) void k_big(typename SC::elem_t *__restrict__ s
             dft<16, false>(x);
 #pragma unroll
             for (int u = 1; u < 16; ++u) x[u] = cmul(x[u], tw[0][u - 1]);
-            exchange<P, 0, 1, kCross>(x, buf_f, tau);
+            if constexpr (SHFL && !kCross) transpose16(x, tau);
+            else exchange<P, 0, 1, kCross>(x, buf_f, tau);
             dft<16, false>(x);
             if constexpr (P == 3) {
 #pragma unroll
                 for (int u = 1; u < 16; ++u) x[u] = cmul(x[u], tw[1][u - 1]);
-                exchange<P, 1, 2, false>(x, buf_f, tau);
+                if constexpr (SHFL) transpose16(x, tau);
+                else exchange<P, 1, 2, false>(x, buf_f, tau);
                 dft<16, false>(x);
             }
         }
@@ -308,12 +356,14 @@ __global__ __launch_bounds__(256) void k_big(typename SC::elem_t *__restrict__ s
         } else {
             dft<16, true>(x);
             if constexpr (P == 3) {
-                exchange<P, 2, 1, false>(x, buf_f, tau);
+                if constexpr (SHFL) transpose16(x, tau);
+                else exchange<P, 2, 1, false>(x, buf_f, tau);
 #pragma unroll
                 for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[1][u - 1]);
                 dft<16, true>(x);
             }
-            exchange<P, 1, 0, kCross>(x, buf_i, tau);
+            if constexpr (SHFL && !kCross) transpose16(x, tau);
+            else exchange<P, 1, 0, kCross>(x, buf_i, tau);
 #pragma unroll
             for (int u = 1; u < 16; ++u) x[u] = cmulc(x[u], tw[0][u - 1]);
             dft<16, true>(x);
@@ -555,13 +605,13 @@ hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, v
     SPECTRE_DISPATCH_N2(small_inv_t, pl, scratch, out, row0, out_rows, H, bh0, nbh, st, ring0, ring_w, newest, aff)
 }
 
-template <int P, int MODE, typename SC = ScrF32>
+template <int P, int MODE, typename SC = ScrF32, bool SHFL = false>
 static hipError_t big_t(const Pow2Plan &pl, float2 *scr_v, const float2 *gp, int bh0, int nbh, bool shared_gate,
                         hipStream_t st, int aff = 0) {
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
     const size_t lds = (size_t)CPI * COLW * sizeof(float2);
     const int ppw = (P == 2) ? 16 : 4;   // pairs per workgroup; a multiple of CPI dividing 32
-    auto kern = k_big<P, MODE, SC>;
+    auto kern = k_big<P, MODE, SC, SHFL>;
     typename SC::elem_t *scr = reinterpret_cast<typename SC::elem_t *>(scr_v);
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
@@ -574,10 +624,18 @@ static hipError_t big_t(const Pow2Plan &pl, float2 *scr_v, const float2 *gp, int
 
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
                       hipStream_t st, bool shared_gate, bool scr16, bool affine) {
+    const bool shfl = option(SPECTRE_OPT_LANE_SHUFFLES) != 0 && mode == 0 && !scr16;
     if (affine) {                                      // the mixer's forward-gate-inverse pass, fp32 scratch
         if (mode != 0 || scr16 || nbh % 8 != 0) return hipErrorInvalidValue;
-        if (pl.P == 2) return big_t<2, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st, nbh);
-        if (pl.P == 3) return big_t<3, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st, nbh);
+        if (pl.P == 2) return shfl ? big_t<2, 0, ScrF32, true>(pl, scratch, gp, bh0, nbh, shared_gate, st, nbh)
+                                   : big_t<2, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st, nbh);
+        if (pl.P == 3) return shfl ? big_t<3, 0, ScrF32, true>(pl, scratch, gp, bh0, nbh, shared_gate, st, nbh)
+                                   : big_t<3, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st, nbh);
+        return hipErrorInvalidValue;
+    }
+    if (shfl) {
+        if (pl.P == 2) return big_t<2, 0, ScrF32, true>(pl, scratch, gp, bh0, nbh, shared_gate, st);
+        if (pl.P == 3) return big_t<3, 0, ScrF32, true>(pl, scratch, gp, bh0, nbh, shared_gate, st);
         return hipErrorInvalidValue;
     }
     if (scr16) {                                       // the mixer's forward-gate-inverse pass only

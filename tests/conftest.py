@@ -24,5 +24,5 @@ def options():
     """Setter for the library's tuning switches; every switch is back at its default after the test."""
     from paper_2502_18394_amd import binding
     yield binding.set_option
-    for which in range(5):
+    for which in range(7):
         binding.set_option(which, -1)

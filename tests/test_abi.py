@@ -103,7 +103,7 @@ def test_options_and_prepare_argument_checks(lib):
     """The tuning switches are host-side state: defaults, set, restore, bad values - no device needed.  spectre_prepare
     rejects bad sizes and unsupported (n, d) before it touches a device."""
     lib.spectre_get_option.restype = ctypes.c_long
-    defaults = {0: 2, 1: 204, 2: 1, 3: 1, 4: 1}
+    defaults = {0: 2, 1: 204, 2: 1, 3: 1, 4: 1, 5: 0, 6: 0}
     for which, val in defaults.items():
         assert lib.spectre_get_option(which) == val
     assert lib.spectre_set_option(0, ctypes.c_long(1)) == 0 and lib.spectre_get_option(0) == 1

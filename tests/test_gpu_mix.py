@@ -147,6 +147,21 @@ def test_head_affine_placement_changes_no_bit(oracle, options, B, L, H, io):
     assert err <= TOL[io] and np.array_equal(got, plain)
 
 
+@pytest.mark.parametrize("B,L,H,io", [(1, 8192, 8, "bf16"), (2, 2048 * 3, 3, "f32"), (1, 16384, 5, "f32"), (1, 131072, 2, "bf16")])
+def test_lane_shuffle_exchange_changes_no_bit(oracle, options, B, L, H, io):
+    """The column kernel can move values between the 16 lanes of a sub-transform with cross-lane (DPP) moves instead
+    of through LDS (both 256-point columns, where every exchange is of that kind, and 4096-point ones, where the
+    inner two are).  It is data movement only: same rows bit for bit, and they match the oracle."""
+    from paper_2502_18394_amd import binding
+    seed = synth.BASE_SEED + 29 * H + L
+    got, want, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    options(binding.OPT_LANE_SHUFFLES, 1)
+    shuffled, _, _ = run_case(oracle, B, L, H, 64, io, seed=seed)
+    err = rel_l2(shuffled, want)
+    print(f"case B={B} L={L} H={H} io={io}: rel_l2 {err:.3e} identical {np.array_equal(got, shuffled)}", flush=True)
+    assert err <= TOL[io] and np.array_equal(got, shuffled)
+
+
 def test_identity_gate_returns_input_on_gpu(oracle):
     B, L, H, d = 1, 4096, 2, 64
     g = np.ones((B, H, L // 2 + 1), np.complex64)
