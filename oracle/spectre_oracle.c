@@ -50,7 +50,10 @@
  *     band 0 = the coarse approximation, band l = the details of level l, level 1
  *     the finest) which every coefficient of that band shares; the gates are the
  *     MLP output as is (no squashing); the controller that skips the module is the
- *     caller's business.
+ *     caller's business.  The other reading of "s in R^(n x d)" - one gate per
+ *     wavelet coefficient and channel, handed in by the caller in the analysis'
+ *     coefficient order - is so_wrm_apply_coeff; the band form is the special case
+ *     of gates that are constant over each band.
  *
  * Complex arrays are interleaved (re, im) doubles.  Tensors are row-major with
  * the index order written in each comment.  No function here keeps state.
@@ -761,6 +764,34 @@ int so_wrm_gates(int B, int H, int d, int dw, int J, int Hg,
     }
     free(qbar);
     return 0;
+}
+
+/* Steps (a), (c), (d) with the gate shape as Sec. 3.5 step (b) prints it, s in
+ * R^(n x d): one gate per wavelet coefficient and channel.  For every column,
+ * analyse, multiply coefficient i by s[b,h,i,c], synthesise, add to the input.
+ * Coefficient order = so_haar_fwd's: [a_J | d_J | d_(J-1) | ... | d_1].
+ *   V, out [B,L,H,d];  s [B,H,L,d]. */
+int so_wrm_apply_coeff(int B, int L, int H, int d, int J, const double *V, const double *s, double *out) {
+    if (L < 1 || J < 0 || (J > 0 && (L % (1 << J)) != 0)) return -1;
+    long long ncol = (long long)B * H * d;
+    int fail = 0;
+#pragma omp parallel for schedule(static)
+    for (long long col = 0; col < ncol; ++col) {
+        int c = (int)(col % d);
+        int h = (int)((col / d) % H);
+        int b = (int)(col / ((long long)d * H));
+        double *x = (double *)malloc(sizeof(double) * 3 * (size_t)L);
+        if (!x) { fail = 1; continue; }
+        double *w = x + L, *ref = w + L;
+        for (int t = 0; t < L; ++t) x[t] = V[(((size_t)b * L + t) * H + h) * d + c];
+        if (so_haar_fwd(L, J, x, w)) fail = 1;
+        const double *sc = s + ((size_t)b * H + h) * (size_t)L * d;
+        for (int i = 0; i < L; ++i) w[i] *= sc[(size_t)i * d + c];
+        if (so_haar_inv(L, J, w, ref)) fail = 1;
+        for (int t = 0; t < L; ++t) out[(((size_t)b * L + t) * H + h) * d + c] = x[t] + ref[t];
+        free(x);
+    }
+    return fail ? -2 : 0;
 }
 
 /* Steps (a), (c), (d): for every column, analyse, scale every coefficient by the

@@ -221,6 +221,21 @@ def wrm_apply(V, s, J):
     return out
 
 
+def wrm_apply_coeff(V, s, J):
+    """The same module with one gate per wavelet coefficient and channel, the shape Sec. 3.5 step (b) prints:
+    V [B,L,H,d], s [B,H,L,d] in the analysis' coefficient order [a_J | d_J | ... | d_1]."""
+    V = _f64(V)
+    s = _f64(s)
+    B, L, H, d = V.shape
+    assert s.shape == (B, H, L, d)
+    out = np.empty_like(V)
+    rc = _L().so_wrm_apply_coeff(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(J),
+                                 _p(V), _p(s), _p(out))
+    if rc:
+        raise RuntimeError(f"so_wrm_apply_coeff rc={rc}")
+    return out
+
+
 class PrefixCache:
     """State of Algorithm 1 for B*H heads; ``t`` counts the tokens appended."""
 

@@ -1,4 +1,4 @@
-"""The pins must catch mistakes: thirty-five deliberately wrong copies of the oracle (a flipped sign, a dropped term,
+"""The pins must catch mistakes: thirty-eight deliberately wrong copies of the oracle (a flipped sign, a dropped term,
 a wrong index, a transposed operand, ...) are compiled one by one and the pin files that cover the changed function are
 run against each copy in a child process; every copy has to fail at least one pin.  CPU only; the mistakes are planted
 in the oracle's source, nothing here touches the GPU path."""
@@ -149,6 +149,18 @@ MISTAKES = [
      'av += x[i] * wv[(size_t)i * d + j];',
      'av += x[i] * wv[(size_t)j * d + i];',
      ('tests/test_oracle_mixer_gate.py',)),
+    ('per-coefficient wavelet gate taken from the mirrored coefficient',
+     'for (int i = 0; i < L; ++i) w[i] *= sc[(size_t)i * d + c];',
+     'for (int i = 0; i < L; ++i) w[i] *= sc[(size_t)(L - 1 - i) * d + c];',
+     ('tests/test_oracle_wrm.py',)),
+    ('per-coefficient wavelet gates read channel-major',
+     'for (int i = 0; i < L; ++i) w[i] *= sc[(size_t)i * d + c];',
+     'for (int i = 0; i < L; ++i) w[i] *= sc[(size_t)c * L + i];',
+     ('tests/test_oracle_wrm.py',)),
+    ('per-coefficient wavelet module without the residual',
+     'for (int t = 0; t < L; ++t) out[(((size_t)b * L + t) * H + h) * d + c] = x[t] + ref[t];\n        free(x);\n    }\n    return fail ? -2 : 0;\n}\n\n/* Steps (a), (c), (d): for every column, analyse, scale every coefficient by the',
+     'for (int t = 0; t < L; ++t) out[(((size_t)b * L + t) * H + h) * d + c] = ref[t];\n        free(x);\n    }\n    return fail ? -2 : 0;\n}\n\n/* Steps (a), (c), (d): for every column, analyse, scale every coefficient by the',
+     ('tests/test_oracle_wrm.py',)),
     ('query pooled over the wrong axis stride',
      'for (int l = 0; l < L; ++l) s += Q[(((size_t)b * L + l) * H + h) * d + c];',
      'for (int l = 0; l < L; ++l) s += Q[(((size_t)b * L + l) * H + c % H) * d + c];',

@@ -120,6 +120,76 @@ def test_module_special_gates(oracle):
     assert np.array_equal(changed, want)
 
 
+def band_of(i, n, J):
+    """Band (0 = approximation, l = details of level l) of coefficient i in the order [a_J | d_J | ... | d_1]."""
+    if i < n >> J:
+        return 0
+    l = J
+    while i >= n >> (l - 1):
+        l -= 1
+    return l
+
+
+@pytest.mark.parametrize("B,L,H,d,J", [(2, 64, 3, 4, 6), (1, 196, 2, 8, 2), (1, 96, 2, 6, 3), (1, 50, 1, 2, 1), (1, 9, 2, 2, 0),
+                                       (1, 1024, 1, 16, 10)])
+def test_per_coefficient_gates_equal_the_explicit_basis_form(oracle, B, L, H, d, J):
+    """One gate per coefficient and channel (the printed shape, s in R^(n x d)): out = v + W^T diag(s) W v with the
+    basis matrix W written from the definition of the Haar functions - no step shared with the oracle's
+    analyse / multiply / synthesise."""
+    rng = np.random.default_rng(3 * L + J)
+    V = rng.standard_normal((B, L, H, d))
+    s = rng.standard_normal((B, H, L, d))
+    W = haar_matrix(L, J)
+    want = np.empty_like(V)
+    for b in range(B):
+        for h in range(H):
+            for c in range(d):
+                want[b, :, h, c] = V[b, :, h, c] + W.T @ (s[b, h, :, c] * (W @ V[b, :, h, c]))
+    np.testing.assert_allclose(oracle.wrm_apply_coeff(V, s, J), want, atol=1e-12)
+
+
+def test_per_coefficient_gates_reduce_to_the_band_form(oracle):
+    """Gates that are constant over each band are the band form: same output as wrm_apply, to rounding."""
+    rng = np.random.default_rng(8)
+    B, L, H, d, J = 2, 192, 2, 4, 5
+    V = rng.standard_normal((B, L, H, d))
+    sb = rng.standard_normal((B, H, J + 1, d))
+    band = np.array([band_of(i, L, J) for i in range(L)])
+    s = sb[:, :, band, :]                               # [B,H,L,d]
+    np.testing.assert_allclose(oracle.wrm_apply_coeff(V, s, J), oracle.wrm_apply(V, sb, J), atol=1e-13)
+
+
+def test_per_coefficient_gates_hand_computed_and_local(oracle):
+    """n = 4, J = 2, x = (1, 2, 3, 4): coefficients (5, -2, -r, -r), r = sqrt(1/2).  A unit gate on one coefficient
+    adds that coefficient times its basis function: the approximation adds the mean 2.5 everywhere, the level-2
+    detail adds (-1, -1, +1, +1), the first level-1 detail adds (-1/2, +1/2, 0, 0).  A single gate touches only the
+    rows its basis function covers, and only its own head and channel."""
+    x = np.array([1.0, 2.0, 3.0, 4.0]).reshape(1, 4, 1, 1)
+    adds = {0: [2.5, 2.5, 2.5, 2.5], 1: [-1.0, -1.0, 1.0, 1.0], 2: [-0.5, 0.5, 0.0, 0.0], 3: [0.0, 0.0, -0.5, 0.5]}
+    for i, add in adds.items():
+        s = np.zeros((1, 1, 4, 1))
+        s[0, 0, i, 0] = 1.0
+        np.testing.assert_allclose(oracle.wrm_apply_coeff(x, s, 2)[0, :, 0, 0], x[0, :, 0, 0] + np.array(add), atol=1e-14)
+    rng = np.random.default_rng(9)
+    B, L, H, d, J = 2, 64, 2, 3, 4
+    V = rng.standard_normal((B, L, H, d))
+    s = np.zeros((B, H, L, d))
+    i = (L >> 3) + 5                                    # detail of level 3, block 5: rows 40..47
+    assert band_of(i, L, J) == 3
+    s[1, 0, i, 2] = -0.75
+    out = oracle.wrm_apply_coeff(V, s, J)
+    changed = np.abs(out - V) > 0
+    want = np.zeros_like(changed)
+    want[1, 40:48, 0, 2] = True
+    assert np.array_equal(changed, want)
+    blk = V[1, 40:48, 0, 2]
+    coef = (blk[:4].sum() - blk[4:].sum()) / np.sqrt(8.0)
+    np.testing.assert_allclose(out[1, 40:48, 0, 2] - blk, -0.75 * coef * np.array([1, 1, 1, 1, -1, -1, -1, -1]) / np.sqrt(8.0),
+                               atol=1e-14)
+    np.testing.assert_allclose(oracle.wrm_apply_coeff(V, np.zeros((B, H, L, d)), J), V, atol=0)
+    np.testing.assert_allclose(oracle.wrm_apply_coeff(V, np.ones((B, H, L, d)), J), 2.0 * V, atol=1e-13)
+
+
 def test_module_is_linear_in_v(oracle):
     rng = np.random.default_rng(6)
     B, L, H, d, J = 1, 96, 2, 4, 5
