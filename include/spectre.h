@@ -227,6 +227,20 @@ size_t spectre_wrm_apply_workspace_bytes(int B, int L, int H, int d, int levels)
 int spectre_wrm_apply(const void *v, const void *s, void *out, int B, int L, int H, int d, int levels,
                       spectre_dtype io, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * spectre_wrm_apply_coeff - the same module under the other reading of step (b)'s "s in R^(n x d)": one
+ * real gate per wavelet coefficient and channel, handed in by the caller (an MLP that emitted them would
+ * hold d_w * n * d weights per head; none is built here).  A real Haar analysis, a multiplication of
+ * coefficient i of column (b, h, c) by s[b, h, i, c], the synthesis, and the residual add.
+ *   s   float [B, H, L, d], 8-byte aligned, coefficients in the order the analysis produces them, coarse to
+ *       fine: [ a_J (L/2^J approximations) | d_J (L/2^J details) | d_(J-1) | ... | d_1 (L/2 details) ];
+ *       the detail of level l of the block of 2^l rows number i sits at index (L >> l) + i.
+ *   Gates constant over each band give spectre_wrm_apply's result.  Same v / out / levels / workspace
+ *   (spectre_wrm_apply_workspace_bytes) rules as spectre_wrm_apply; out may be v, must not overlap s.
+ */
+int spectre_wrm_apply_coeff(const void *v, const void *s, void *out, int B, int L, int H, int d, int levels,
+                            spectre_dtype io, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * spectre_mix_forward - the mixing layer, Sec. 3.2 steps 2 and 4 (Eq. 3, Eq. 4): for every
  * sequence b, head h and channel c

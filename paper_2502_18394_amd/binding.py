@@ -310,6 +310,21 @@ def wrm_apply(v, s, out=None, ws=None, stream=None):
     return out
 
 
+def wrm_apply_coeff(v, s, levels, out=None, ws=None, stream=None):
+    """v + iDWT(s * DWT(v)) with one gate per wavelet coefficient and channel: v [B,L,H,d] f32/bf16,
+    s float32 [B,H,L,d] in the analysis' coefficient order [a_J | d_J | ... | d_1]."""
+    B, L, H, d = v.shape
+    if s.dtype != torch.float32 or tuple(s.shape) != (B, H, L, d):
+        raise ValueError("s must be float32 [B,H,L,d]")
+    if out is None:
+        out = torch.empty_like(v)
+    ws, wsp, wsn = _workspace(wrm_apply_workspace_bytes(B, L, H, d, levels), v.device, ws)
+    _check(lib().spectre_wrm_apply_coeff(_dev(v, "v"), _dev(s, "s"), _dev(out, "out"), ctypes.c_int(B), ctypes.c_int(L),
+                                         ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(levels),
+                                         ctypes.c_int(_dtype_code(v)), wsp, wsn, _stream(stream)))
+    return out
+
+
 class PrefixCache:
     """Caller-owned Prefix-FFT cache state (Algorithm 1) in device memory."""
 

@@ -880,6 +880,39 @@ int spectre_wrm_apply(const void *v, const void *s, void *out, int B, int L, int
     return SPECTRE_OK;
 }
 
+int spectre_wrm_apply_coeff(const void *v, const void *s, void *out, int B, int L, int H, int d, int levels,
+                            spectre_dtype io, void *ws, size_t ws_bytes, void *stream) {
+    if (!v || !s || !out) return fail(SPECTRE_EINVAL, "wrm_apply_coeff: null pointer");
+    if (B < 1 || L < 1 || H < 1 || d < 1) return fail(SPECTRE_EINVAL, "wrm_apply_coeff: non-positive size");
+    if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "wrm_apply_coeff: bad dtype");
+    if (levels < 0 || levels > 30) return fail(SPECTRE_EINVAL, "wrm_apply_coeff: levels=%d not in 0..30", levels);
+    if (levels > 0 && (L % (1LL << levels)) != 0)
+        return fail(SPECTRE_EINVAL, "wrm_apply_coeff: 2^%d does not divide L=%d", levels, L);
+    if (d != 64) return fail(SPECTRE_EUNSUPPORTED, "wrm_apply_coeff: d=%d (only 64 is built)", d);
+    if (B > 65535 || (L + kWrmTileRows - 1) / kWrmTileRows > 65535)
+        return fail(SPECTRE_EUNSUPPORTED, "wrm_apply_coeff: B or L/256 above 65535");
+    if (levels > kWrmTileLevels && L > 262144)
+        return fail(SPECTRE_EUNSUPPORTED, "wrm_apply_coeff: more than 8 levels needs L <= 262144");
+    if (reinterpret_cast<uintptr_t>(s) & 7) return fail(SPECTRE_EINVAL, "wrm_apply_coeff: s must be 8-byte aligned");
+    const size_t bytes = (size_t)B * L * H * d * (io == SPECTRE_BF16 ? 2 : 4);
+    const char *vb = static_cast<const char *>(v), *ob = static_cast<const char *>(out);
+    if (vb != ob && vb < ob + bytes && ob < vb + bytes)
+        return fail(SPECTRE_EINVAL, "wrm_apply_coeff: out overlaps v without being v");
+    const char *sb = static_cast<const char *>(s);
+    const size_t sbytes = (size_t)B * L * H * d * sizeof(float);
+    if (sb < ob + bytes && ob < sb + sbytes) return fail(SPECTRE_EINVAL, "wrm_apply_coeff: out overlaps s");
+    const size_t need = spectre_wrm_apply_workspace_bytes(B, L, H, d, levels);
+    if (!ws || ws_bytes < need) return fail(SPECTRE_EWORKSPACE, "wrm_apply_coeff: workspace %zu < %zu bytes", ws_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "wrm_apply_coeff: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t part = align256(wrm_scratch_floats(B * H, L, levels) * sizeof(float));
+    float *tile_sums = static_cast<float *>(ws);
+    float *upper = reinterpret_cast<float *>(static_cast<char *>(ws) + part);
+    hipError_t e = launch_wrm_apply_coeff((int)io, v, static_cast<const float *>(s), out, tile_sums, upper, B, L, H, levels, st);
+    if (e != hipSuccess) return fail_hip(e, "wrm_apply_coeff");
+    return SPECTRE_OK;
+}
+
 // ------------------------------------------------------------------------------------------ prefix cache
 static bool prefix_length_ok(int N, int d) {
     int N1, N2, P;

@@ -34,4 +34,9 @@ size_t wrm_scratch_floats(int BH, int L, int levels);
 hipError_t launch_wrm_apply(int io, const void *v, const float *s, void *out, float *tile_sums, float *upper,
                             int B, int L, int H, int levels, hipStream_t st);
 
+// The same module with one gate per wavelet coefficient and channel: s [B,H,L,64] in the analysis' coefficient order
+// [a_J | d_J | ... | d_1] (a real Haar analysis, gate, synthesis; same tiling and scratch as above).
+hipError_t launch_wrm_apply_coeff(int io, const void *v, const float *s, void *out, float *tile_sums, float *upper,
+                                  int B, int L, int H, int levels, hipStream_t st);
+
 }  // namespace spectre

@@ -288,6 +288,214 @@ __global__ __launch_bounds__(256) void k_wrm_apply(const typename IO::pair_t *__
 }
 
 // ------------------------------------------------------------------------------------------
+// One gate per wavelet coefficient and channel (Sec. 3.5 step b as printed, s in R^(n x d)): a real Haar analysis,
+// gate, synthesis.  sc [B*H][L][64] holds the gates in the analysis' coefficient order [a_J | d_J | ... | d_1]: the
+// detail of level l of the block of 2^l rows number i sits at position (L >> l) + i, the approximation of the block
+// of 2^J rows number i at position i.  With S1, S2 the sums of a block's two halves, its detail coefficient is
+// (S1 - S2) / sqrt(2^l) and contributes -/+ gate * (S1 - S2) / 2^l to the rows of its halves; the approximation
+// contributes gate * (S1 + S2) / 2^J to all rows of the block.  Same tiling as k_wrm_apply: a lane owns 32
+// consecutive rows of a channel pair (levels 1..5 in registers), levels 6..8 cross the 8 row groups of a tile through
+// LDS, and levels above 8 arrive as one per-tile constant U (k_wrm_upper_coeff, from the tile sums).
+//
+// JT = min(J, 6): the levels inside a lane's 32 rows are compile-time (JT <= 5: the analysis stops at level JT and
+// the lane also applies the approximation gates of its 32 >> JT blocks); the levels 6..8 are tested at run time.
+template <int JT>
+__device__ __forceinline__ float2 coeff_gate(const float *__restrict__ sc, size_t pos, int c0, bool valid) {
+    return valid ? *reinterpret_cast<const float2 *>(sc + pos * 64 + c0) : make_float2(0.f, 0.f);
+}
+
+template <typename IO, int JT>
+__global__ __launch_bounds__(256) void k_wrm_coeff(const typename IO::pair_t *__restrict__ v,
+                                                   const float *__restrict__ s, const float2 *__restrict__ U,
+                                                   typename IO::pair_t *__restrict__ out, int L, int H, int J,
+                                                   int ntiles) {
+    __shared__ float2 part[8][33];
+    const int tid = threadIdx.x, p = tid & 31, r = tid >> 5;
+    const int h = blockIdx.x, tile = blockIdx.y, b = blockIdx.z, bh = b * H + h;
+    const int row0 = tile * kWrmTileRows + r * 32;
+    const float *sc = s + (size_t)bh * L * 64;
+    const int c0 = 2 * p;
+    constexpr int LV = JT < 5 ? JT : 5;                // detail levels inside the lane
+
+    // every load is issued before the first use: rows, then the gates of the lane's blocks
+    typename IO::pair_t raw[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        const int l = row0 + i;
+        raw[i] = (l < L) ? IO::load_stream(v + (((size_t)b * L + l) * H + h) * 32 + p) : IO::zero();
+    }
+    float2 g1[16], g2[8], g3[4], g4[2], g5 = make_float2(0.f, 0.f), ga[JT <= 5 ? (32 >> LV) : 1];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) g1[i] = (LV >= 1) ? coeff_gate<JT>(sc, (size_t)(L >> 1) + (row0 >> 1) + i, c0, row0 + 2 * i < L) : make_float2(0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) g2[i] = (LV >= 2) ? coeff_gate<JT>(sc, (size_t)(L >> 2) + (row0 >> 2) + i, c0, row0 + 4 * i < L) : make_float2(0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) g3[i] = (LV >= 3) ? coeff_gate<JT>(sc, (size_t)(L >> 3) + (row0 >> 3) + i, c0, row0 + 8 * i < L) : make_float2(0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) g4[i] = (LV >= 4) ? coeff_gate<JT>(sc, (size_t)(L >> 4) + (row0 >> 4) + i, c0, row0 + 16 * i < L) : make_float2(0.f, 0.f);
+    if (LV >= 5) g5 = coeff_gate<JT>(sc, (size_t)(L >> 5) + (row0 >> 5), c0, row0 < L);
+    if constexpr (JT <= 5) {
+#pragma unroll
+        for (int i = 0; i < (32 >> LV); ++i) ga[i] = coeff_gate<JT>(sc, (size_t)(row0 >> LV) + i, c0, row0 + (i << LV) < L);
+    } else {
+        ga[0] = make_float2(0.f, 0.f);
+    }
+    float2 g6 = make_float2(0.f, 0.f), g7 = g6, g8 = g6, gup = g6;
+    if constexpr (JT == 6) {
+        const int t0 = tile * kWrmTileRows;
+        if (J >= 6) g6 = coeff_gate<JT>(sc, (size_t)(L >> 6) + (row0 >> 6), c0, ((row0 >> 6) << 6) < L);
+        if (J >= 7) g7 = coeff_gate<JT>(sc, (size_t)(L >> 7) + (row0 >> 7), c0, ((row0 >> 7) << 7) < L);
+        if (J >= 8) g8 = coeff_gate<JT>(sc, (size_t)(L >> 8) + (t0 >> 8), c0, t0 < L);
+        if (J <= 8) gup = coeff_gate<JT>(sc, (size_t)(row0 >> J), c0, ((row0 >> J) << J) < L);   // approximation, levels 6..8
+    }
+
+    float2 x[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) x[i] = IO::unpack(raw[i]);
+    // block sums and gated details of levels 1..5; d_l[i] is what the first half of block i gains and the second loses
+    float2 s1[16], s2[8], s3[4], s4[2], s5, d1[16], d2[8], d3[4], d4[2], d5;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        s1[i] = x[2 * i] + x[2 * i + 1];
+        d1[i] = make_float2((x[2 * i].x - x[2 * i + 1].x) * 0.5f * g1[i].x, (x[2 * i].y - x[2 * i + 1].y) * 0.5f * g1[i].y);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        s2[i] = s1[2 * i] + s1[2 * i + 1];
+        d2[i] = make_float2((s1[2 * i].x - s1[2 * i + 1].x) * 0.25f * g2[i].x, (s1[2 * i].y - s1[2 * i + 1].y) * 0.25f * g2[i].y);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s3[i] = s2[2 * i] + s2[2 * i + 1];
+        d3[i] = make_float2((s2[2 * i].x - s2[2 * i + 1].x) * 0.125f * g3[i].x, (s2[2 * i].y - s2[2 * i + 1].y) * 0.125f * g3[i].y);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        s4[i] = s3[2 * i] + s3[2 * i + 1];
+        d4[i] = make_float2((s3[2 * i].x - s3[2 * i + 1].x) * 0.0625f * g4[i].x, (s3[2 * i].y - s3[2 * i + 1].y) * 0.0625f * g4[i].y);
+    }
+    s5 = s4[0] + s4[1];
+    d5 = make_float2((s4[0].x - s4[1].x) * 0.03125f * g5.x, (s4[0].y - s4[1].y) * 0.03125f * g5.y);
+
+    float2 corr = make_float2(0.f, 0.f);               // what every row of the lane's 32 gains from levels >= 6
+    if constexpr (JT == 6) {
+        part[r][p] = s5;
+        __syncthreads();
+        if (J > kWrmTileLevels) corr = U[((size_t)bh * ntiles + tile) * 32 + p];
+        float2 q[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = part[i][p];
+        const int r4 = r & ~3, r2 = r & ~1;
+        float2 h7a = make_float2(0.f, 0.f), h7b = h7a, h6a = h7a, h6b = h7a;   // halves of the lane's level-7 / level-6 block
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if ((i & ~3) == r4) { if (i & 2) h7b = h7b + q[i]; else h7a = h7a + q[i]; }
+            if ((i & ~1) == r2) { if (i & 1) h6b = h6b + q[i]; else h6a = h6a + q[i]; }
+        }
+        const float2 h8a = (q[0] + q[1]) + (q[2] + q[3]), h8b = (q[4] + q[5]) + (q[6] + q[7]);
+        if (J >= 8) {
+            const float sg = (r & 4) ? -0.00390625f : 0.00390625f;
+            corr.x = fmaf((h8a.x - h8b.x) * sg, g8.x, corr.x);
+            corr.y = fmaf((h8a.y - h8b.y) * sg, g8.y, corr.y);
+        }
+        if (J >= 7) {
+            const float sg = (r & 2) ? -0.0078125f : 0.0078125f;
+            corr.x = fmaf((h7a.x - h7b.x) * sg, g7.x, corr.x);
+            corr.y = fmaf((h7a.y - h7b.y) * sg, g7.y, corr.y);
+        }
+        if (J >= 6) {
+            const float sg = (r & 1) ? -0.015625f : 0.015625f;
+            corr.x = fmaf((h6a.x - h6b.x) * sg, g6.x, corr.x);
+            corr.y = fmaf((h6a.y - h6b.y) * sg, g6.y, corr.y);
+        }
+        if (J <= 8) {                                  // the approximation band ends inside the tile
+            const float2 blk = (J == 8) ? h8a + h8b : (J == 7) ? h7a + h7b : h6a + h6b;
+            const float sc2 = exp2f(-(float)J);
+            corr.x = fmaf(blk.x * sc2, gup.x, corr.x);
+            corr.y = fmaf(blk.y * sc2, gup.y, corr.y);
+        }
+    }
+    // down the lane's own levels: a block's correction is its parent's, plus or minus the parent's gated detail,
+    // plus (at level JT <= 5) its own gated approximation
+    auto approx = [&](int level, int i, float2 sum) {  // level == JT <= 5: gated approximation of block i at that level
+        const float sc2 = 1.0f / (float)(1 << (level < 0 ? 0 : level));
+        return make_float2(sum.x * sc2 * ga[i].x, sum.y * sc2 * ga[i].y);
+    };
+    float2 c5 = corr;
+    if constexpr (JT == 5) c5 = c5 + approx(5, 0, s5);
+#pragma unroll
+    for (int i4 = 0; i4 < 2; ++i4) {
+        float2 c4 = (i4 == 0) ? c5 + d5 : c5 - d5;
+        if constexpr (JT == 4) c4 = c4 + approx(4, i4, s4[i4]);
+#pragma unroll
+        for (int j3 = 0; j3 < 2; ++j3) {
+            const int i3 = 2 * i4 + j3;
+            float2 c3 = (j3 == 0) ? c4 + d4[i4] : c4 - d4[i4];
+            if constexpr (JT == 3) c3 = c3 + approx(3, i3, s3[i3]);
+#pragma unroll
+            for (int j2 = 0; j2 < 2; ++j2) {
+                const int i2 = 2 * i3 + j2;
+                float2 c2 = (j2 == 0) ? c3 + d3[i3] : c3 - d3[i3];
+                if constexpr (JT == 2) c2 = c2 + approx(2, i2, s2[i2]);
+#pragma unroll
+                for (int j1 = 0; j1 < 2; ++j1) {
+                    const int i1 = 2 * i2 + j1;
+                    float2 c1 = (j1 == 0) ? c2 + d2[i2] : c2 - d2[i2];
+                    if constexpr (JT == 1) c1 = c1 + approx(1, i1, s1[i1]);
+#pragma unroll
+                    for (int j0 = 0; j0 < 2; ++j0) {
+                        const int i = 2 * i1 + j0, l = row0 + i;
+                        float2 c0v = (j0 == 0) ? c1 + d1[i1] : c1 - d1[i1];
+                        if constexpr (JT == 0) c0v = c0v + approx(0, i, x[i]);
+                        if (l < L) IO::store_stream(out + (((size_t)b * L + l) * H + h) * 32 + p, IO::pack(x[i] + c0v));
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Levels above 8 with per-coefficient gates: one workgroup per (bh, group of kUpCh channels) sums the tiles' sums
+// pairwise up to level J in LDS, then walks down: the top blocks start from their gated approximation, a block's two
+// children get its correction plus / minus its gated detail.  U[bh][tile][c] = what every row of the tile gains.
+__global__ __launch_bounds__(256) void k_wrm_upper_coeff(const float *__restrict__ S, const float *__restrict__ s,
+                                                         float *__restrict__ U, int ntiles, int J, int L) {
+    extern __shared__ float pyr[];                     // levels 8, 9, ..., J back to back, kUpCh channels each
+    const int tid = threadIdx.x, cl = tid % kUpCh, lane = tid / kUpCh;
+    const int bh = blockIdx.x, c = blockIdx.y * kUpCh + cl;
+    const float *sc = s + (size_t)bh * L * 64 + c;
+    for (int i = lane; i < ntiles; i += kUpLanes) pyr[i * kUpCh + cl] = S[((size_t)bh * ntiles + i) * 64 + c];
+    __syncthreads();
+    int off = 0, n = ntiles;
+    for (int l = kWrmTileLevels + 1; l <= J; ++l) {    // up: block sums
+        const int noff = off + n, nn = n >> 1;
+        for (int i = lane; i < nn; i += kUpLanes)
+            pyr[(noff + i) * kUpCh + cl] = pyr[(off + 2 * i) * kUpCh + cl] + pyr[(off + 2 * i + 1) * kUpCh + cl];
+        __syncthreads();
+        off = noff;
+        n = nn;
+    }
+    for (int i = lane; i < n; i += kUpLanes)            // top: gated approximation, positions 0 .. L/2^J - 1
+        pyr[(off + i) * kUpCh + cl] *= sc[(size_t)i * 64] * exp2f(-(float)J);
+    __syncthreads();
+    for (int l = J; l > kWrmTileLevels; --l) {         // down: children of the level-l blocks
+        const int coff = off - 2 * n;
+        const float sc2 = exp2f(-(float)l);
+        for (int i = lane; i < n; i += kUpLanes) {
+            const float par = pyr[(off + i) * kUpCh + cl];
+            const float a = pyr[(coff + 2 * i) * kUpCh + cl], bq = pyr[(coff + 2 * i + 1) * kUpCh + cl];
+            const float det = (a - bq) * sc2 * sc[((size_t)(L >> l) + i) * 64];
+            pyr[(coff + 2 * i) * kUpCh + cl] = par + det;
+            pyr[(coff + 2 * i + 1) * kUpCh + cl] = par - det;
+        }
+        __syncthreads();
+        off = coff;
+        n <<= 1;
+    }
+    for (int i = lane; i < ntiles; i += kUpLanes) U[((size_t)bh * ntiles + i) * 64 + c] = pyr[i * kUpCh + cl];
+}
+
+// ------------------------------------------------------------------------------------------
 hipError_t launch_wrm_gates(const double *sum_q, double inv_count, const WrmDev &P, int B, int H, float *s,
                             hipStream_t st) {
     k_wrm_gates<<<B * H, 256, 0, st>>>(sum_q, inv_count, P.ln_gamma, P.ln_beta, P.ln_eps, P.W1, P.b1, P.W2, P.b2, s,
@@ -300,22 +508,28 @@ size_t wrm_scratch_floats(int BH, int L, int levels) {
     return (size_t)BH * (size_t)(L / kWrmTileRows) * 64;
 }
 
+// tile sums S (one pass over v) for the levels above 8; 2^levels divides L there, so L is a multiple of 512
+static hipError_t tile_sums_pass(int io, const void *v, float *tile_sums, int B, int L, int H, int ntiles, hipStream_t st) {
+    const dim3 grid(H, ntiles, B);
+    if ((reinterpret_cast<uintptr_t>(v) & 15) == 0) {
+        const int ppv = H * 32 / (io ? 4 : 2);
+        const dim3 g16((ppv + 255) / 256, ntiles, B);
+        if (io) k_wrm_tile_sums_x16<true><<<g16, 256, 0, st>>>(static_cast<const uint4 *>(v), tile_sums, L, H, ntiles, ppv);
+        else k_wrm_tile_sums_x16<false><<<g16, 256, 0, st>>>(static_cast<const uint4 *>(v), tile_sums, L, H, ntiles, ppv);
+    } else if (io) k_wrm_tile_sums<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(v),
+                                                          reinterpret_cast<float2 *>(tile_sums), L, H, ntiles);
+    else k_wrm_tile_sums<IoF32><<<grid, 256, 0, st>>>(static_cast<const float2 *>(v),
+                                                      reinterpret_cast<float2 *>(tile_sums), L, H, ntiles);
+    return hipGetLastError();
+}
+
 hipError_t launch_wrm_apply(int io, const void *v, const float *s, void *out, float *tile_sums, float *upper,
                             int B, int L, int H, int levels, hipStream_t st) {
     const int BH = B * H;
     const int ntiles = (L + kWrmTileRows - 1) / kWrmTileRows;
     const dim3 grid(H, ntiles, B);
-    if (levels > kWrmTileLevels) {                      // then 2^levels divides L, so L is a multiple of 512
-        if ((reinterpret_cast<uintptr_t>(v) & 15) == 0) {
-            const int ppv = H * 32 / (io ? 4 : 2);
-            const dim3 g16((ppv + 255) / 256, ntiles, B);
-            if (io) k_wrm_tile_sums_x16<true><<<g16, 256, 0, st>>>(static_cast<const uint4 *>(v), tile_sums, L, H, ntiles, ppv);
-            else k_wrm_tile_sums_x16<false><<<g16, 256, 0, st>>>(static_cast<const uint4 *>(v), tile_sums, L, H, ntiles, ppv);
-        } else if (io) k_wrm_tile_sums<IoBf16><<<grid, 256, 0, st>>>(static_cast<const uint32_t *>(v),
-                                                              reinterpret_cast<float2 *>(tile_sums), L, H, ntiles);
-        else k_wrm_tile_sums<IoF32><<<grid, 256, 0, st>>>(static_cast<const float2 *>(v),
-                                                          reinterpret_cast<float2 *>(tile_sums), L, H, ntiles);
-        hipError_t e = hipGetLastError();
+    if (levels > kWrmTileLevels) {
+        hipError_t e = tile_sums_pass(io, v, tile_sums, B, L, H, ntiles, st);
         if (e != hipSuccess) return e;
         const size_t lds = (size_t)2 * ntiles * kUpCh * sizeof(float);
         if (lds > 48 * 1024) {
@@ -334,6 +548,43 @@ hipError_t launch_wrm_apply(int io, const void *v, const float *s, void *out, fl
                                                   reinterpret_cast<const float2 *>(upper),
                                                   static_cast<float2 *>(out), L, H, levels, ntiles);
     return hipGetLastError();
+}
+
+template <typename IO, int JT>
+static hipError_t wrm_coeff_t(const void *v, const float *s, const float *upper, void *out, int B, int L, int H, int levels,
+                              int ntiles, hipStream_t st) {
+    k_wrm_coeff<IO, JT><<<dim3(H, ntiles, B), 256, 0, st>>>(static_cast<const typename IO::pair_t *>(v), s,
+                                                           reinterpret_cast<const float2 *>(upper),
+                                                           static_cast<typename IO::pair_t *>(out), L, H, levels, ntiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_wrm_apply_coeff(int io, const void *v, const float *s, void *out, float *tile_sums, float *upper,
+                                  int B, int L, int H, int levels, hipStream_t st) {
+    const int BH = B * H;
+    const int ntiles = (L + kWrmTileRows - 1) / kWrmTileRows;
+    if (levels > kWrmTileLevels) {
+        hipError_t e = tile_sums_pass(io, v, tile_sums, B, L, H, ntiles, st);
+        if (e != hipSuccess) return e;
+        const size_t lds = (size_t)2 * ntiles * kUpCh * sizeof(float);
+        if (lds > 48 * 1024) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_wrm_upper_coeff),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        k_wrm_upper_coeff<<<dim3(BH, 64 / kUpCh), 256, lds, st>>>(tile_sums, s, upper, ntiles, levels, L);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+#define SPECTRE_WRM_JT(JTV) \
+    case JTV: return io ? wrm_coeff_t<IoBf16, JTV>(v, s, upper, out, B, L, H, levels, ntiles, st) \
+                        : wrm_coeff_t<IoF32, JTV>(v, s, upper, out, B, L, H, levels, ntiles, st);
+    switch (levels < 6 ? levels : 6) {
+        SPECTRE_WRM_JT(0) SPECTRE_WRM_JT(1) SPECTRE_WRM_JT(2) SPECTRE_WRM_JT(3) SPECTRE_WRM_JT(4) SPECTRE_WRM_JT(5)
+        SPECTRE_WRM_JT(6)
+        default: return hipErrorInvalidValue;
+    }
+#undef SPECTRE_WRM_JT
 }
 
 // Loads this translation unit's code object (the runtime loads them on first use): called by spectre_prepare so

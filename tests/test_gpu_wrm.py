@@ -140,3 +140,89 @@ def test_wrm_rejects_bad_arguments():
     with pytest.raises(binding.SpectreError) as e:
         binding.wrm_apply(torch.zeros((1, 96, 1, 32), device="cuda"), torch.zeros((1, 1, 2, 32), device="cuda"))
     assert e.value.code == binding.EUNSUPPORTED
+
+
+# ------------------------------------------------------------------------------------------ one gate per coefficient
+def band_of(i, n, J):
+    if i < n >> J:
+        return 0
+    l = J
+    while i >= n >> (l - 1):
+        l -= 1
+    return l
+
+
+def _coeff_cases():
+    """Every depth 0 .. 12 (each of the kernel's compile-time depths 0 .. 5, the run-time levels 6 .. 8 inside a
+    tile, and the levels above 8 that cross tiles), ragged tails (L not a multiple of the 256-row tile), several
+    heads and sequences, plus seeded draws."""
+    cases = [(1, 1024, 1, 10), (2, 196, 3, 2), (1, 8192, 2, 13), (2, 512, 2, 9), (1, 256, 2, 8), (1, 300, 2, 2),
+             (3, 7, 2, 0), (1, 96, 1, 5), (2, 4096, 3, 6), (1, 2, 1, 1), (1, 3 * 4096, 2, 12), (1, 1000, 2, 3),
+             (1, 2048, 2, 4), (1, 640, 3, 7), (2, 1, 1, 0), (5, 512, 1, 9), (1, 1536, 2, 8), (1, 48, 2, 4),
+             (1, 131072, 1, 17), (1, 65536, 2, 11)]
+    rng = np.random.default_rng(synth.BASE_SEED + 971)
+    for _ in range(8):
+        J = int(rng.integers(0, 13))
+        L = (1 << J) * int(rng.integers(1, 9)) * int(rng.choice([1, 1, 3, 5]))
+        if L > 40000:
+            L = 1 << J
+        cases.append((int(rng.integers(1, 4)), L, int(rng.integers(1, 5)), J))
+    return cases
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("B,L,H,J", _coeff_cases())
+def test_wrm_apply_coeff_matches_oracle(oracle, B, L, H, J, io):
+    """One gate per wavelet coefficient and channel (s [B,H,L,d]): the kernel's tiled Haar walk against the oracle's
+    plain analyse / multiply / synthesise."""
+    from paper_2502_18394_amd import binding
+    print(f"case B={B} L={L} H={H} J={J} io={io}", flush=True)
+    vals, store = synth.tokens(400 + L + J, (B, L, H, 64), io)
+    s = np.random.default_rng(401 + L + J).standard_normal((B, H, L, 64)).astype(np.float32)
+    out = binding.wrm_apply_coeff(to_device(store, io), torch.from_numpy(s).cuda(), J)
+    torch.cuda.synchronize()
+    want = oracle.wrm_apply_coeff(vals.astype(np.float64), s.astype(np.float64), J)
+    got = from_device(out)
+    err = rel_l2(got, want)
+    print(f"  rel_l2={err:.3e}", flush=True)
+    assert err <= TOL[io]
+    # per element: a row gains at most J + 1 gated terms, each a difference of block sums in fp32
+    rms = float(np.sqrt(np.mean(want ** 2)))
+    tol = 32.0 * 2.0 ** -24 * (J + 2) * rms + (np.abs(want) * 2.0 ** -7 if io == "bf16" else 0.0)
+    assert np.all(np.abs(got - want) <= tol)
+
+
+def test_wrm_apply_coeff_band_constant_gates_and_in_place(oracle):
+    """Gates constant over each band reproduce the band form (the other kernel, block means instead of a transform);
+    zero gates return the input bit for bit; in-place operation gives the same rows."""
+    from paper_2502_18394_amd import binding
+    B, L, H, J = 2, 2048, 2, 11
+    vals, store = synth.tokens(410, (B, L, H, 64), "f32")
+    v = to_device(store, "f32")
+    sb = level_gates(411, B, H, J)
+    band = np.array([band_of(i, L, J) for i in range(L)])
+    s = torch.from_numpy(np.ascontiguousarray(sb[:, :, band, :])).cuda()
+    a = binding.wrm_apply_coeff(v, s, J)
+    b = binding.wrm_apply(v, torch.from_numpy(sb).cuda())
+    torch.cuda.synchronize()
+    assert rel_l2(from_device(a), from_device(b)) <= 1e-6
+    assert torch.equal(binding.wrm_apply_coeff(v, torch.zeros_like(s), J), v)
+    w = v.clone()
+    binding.wrm_apply_coeff(w, s, J, out=w)
+    torch.cuda.synchronize()
+    assert torch.equal(w, a)
+
+
+def test_wrm_apply_coeff_rejects_bad_arguments():
+    from paper_2502_18394_amd import binding
+    v = torch.zeros((1, 96, 1, 64), device="cuda")
+    s = torch.zeros((1, 1, 96, 64), device="cuda")
+    with pytest.raises(binding.SpectreError) as e:
+        binding.wrm_apply_coeff(v, s, 6)                   # 64 does not divide 96
+    assert e.value.code == binding.EINVAL
+    with pytest.raises(ValueError):
+        binding.wrm_apply_coeff(v, s[:, :, :50], 2)
+    v32 = torch.zeros((1, 96, 1, 32), device="cuda")
+    with pytest.raises(binding.SpectreError) as e:
+        binding.wrm_apply_coeff(v32, torch.zeros((1, 1, 96, 32), device="cuda"), 2)
+    assert e.value.code == binding.EUNSUPPORTED
