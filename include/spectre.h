@@ -289,6 +289,26 @@ int spectre_mix_forward_static(const void *v, const void *g, void *out, int B, i
                                spectre_dtype io, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * spectre_layer_forward - the whole mixing layer of Sec. 3.2 (steps 1 to 4) and, optionally, the refinement of
+ * Sec. 3.5 behind it, in one call; the result is that of the chain
+ *     (V, sum_q) = spectre_project(x, Wq, Wv);   g = spectre_gate(sum_q pooled, inv_count = 1/L, phase 0);
+ *     out = spectre_mix_forward(V, g);           [ s = spectre_wrm_gates(sum_q, 1/L);  out = spectre_wrm_apply(out, s) ]
+ * On the four-step route with bf16 rows the chain's intermediate tensors do not exist: the row transforms read X and
+ * project it on the matrix cores on their way in (V is never written or re-read; it is rounded to bf16 on chip exactly
+ * as the separate call would have stored it), the pooled query comes from one streaming pass over X, and the
+ * refinement's coarse levels use block sums that the mixer's store phase emits instead of a second read of the
+ * output.  Other lengths and fp32 rows run the chain as it stands, with V in the workspace.
+ *   x, out  [B, L, H, d] of dtype io, 16-byte aligned, not overlapping;  Wq, Wv as in spectre_project
+ *   P       gate parameters with P->n_fft == L;   W  refinement parameters, or NULL for none
+ */
+size_t spectre_layer_workspace_bytes(int B, int L, int H, int d, spectre_dtype io,
+                                     const spectre_gate_params *P /*host*/, const spectre_wrm_params *W /*host*/);
+int spectre_layer_forward(const void *x, const float *Wq, const float *Wv, int Hw,
+                          const spectre_gate_params *P /*host*/, const spectre_wrm_params *W /*host or NULL*/,
+                          void *out, int B, int L, int H, int d, spectre_dtype io, void *ws, size_t ws_bytes,
+                          void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * Prefix-FFT cache, Sec. 3.3 and Algorithm 1.  One cache serves B*H heads that advance in
  * lock-step (one token counter).  The caller allocates the five device arrays (sizes from
  * spectre_prefix_bytes), fills in the dimensions, and calls spectre_prefix_init once.

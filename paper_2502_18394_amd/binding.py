@@ -63,7 +63,7 @@ def lib():
                      "spectre_wrm_apply_workspace_bytes",
                      "spectre_prefix_update_workspace_bytes", "spectre_prefix_readout_workspace_bytes",
                      "spectre_prefix_step_workspace_bytes", "spectre_prefix_set_memory_workspace_bytes",
-                     "spectre_mix_static_bytes"):
+                     "spectre_mix_static_bytes", "spectre_layer_workspace_bytes"):
             getattr(L, name).restype = ctypes.c_size_t
         L.spectre_get_option.restype = ctypes.c_long
         _lib = L
@@ -322,6 +322,26 @@ def wrm_apply_coeff(v, s, levels, out=None, ws=None, stream=None):
     _check(lib().spectre_wrm_apply_coeff(_dev(v, "v"), _dev(s, "s"), _dev(out, "out"), ctypes.c_int(B), ctypes.c_int(L),
                                          ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(levels),
                                          ctypes.c_int(_dtype_code(v)), wsp, wsn, _stream(stream)))
+    return out
+
+
+def layer_forward(x, Wq, Wv, P, W=None, out=None, ws=None, stream=None):
+    """The whole layer in one call (spectre_layer_forward): projection, pooled query, gate, mixer and, with W (a
+    WrmParams), the wavelet refinement.  x [B,L,H,64] f32/bf16; Wq, Wv float32 [Hw,64,64]; P a GateParams for L."""
+    B, L, H, d = x.shape
+    io = _dtype_code(x)
+    prepare(L, d)
+    if out is None:
+        out = torch.empty_like(x)
+    wc = ctypes.byref(W.c) if W is not None else None
+    need = lib().spectre_layer_workspace_bytes(ctypes.c_int(B), ctypes.c_int(L), ctypes.c_int(H), ctypes.c_int(d),
+                                               ctypes.c_int(io), ctypes.byref(P.c), wc)
+    if need == 0:
+        raise SpectreError(EUNSUPPORTED, lib().spectre_last_error().decode())
+    ws, wsp, wsn = _workspace(need, x.device, ws)
+    _check(lib().spectre_layer_forward(_dev(x, "x"), _dev(Wq, "Wq"), _dev(Wv, "Wv"), ctypes.c_int(Wq.shape[0]),
+                                       ctypes.byref(P.c), wc, _dev(out, "out"), ctypes.c_int(B), ctypes.c_int(L),
+                                       ctypes.c_int(H), ctypes.c_int(d), ctypes.c_int(io), wsp, wsn, _stream(stream)))
     return out
 
 

@@ -522,9 +522,12 @@ static int check_mix_args(const void *v, const void *g, const void *out, int B, 
 // The four-step route: gate expansion, then per head group the row transforms, the column kernel and the inverse
 // row transforms.  gp = expanded gate [BH][L]; lane_scr[i] = transform scratch of lane i (lane_bytes each).
 // side == nullptr keeps every group on st.
+// wpack != nullptr: v is the layer input X and the row transforms project it first (bf16 rows, fp32 scratch);
+// bsum != nullptr: the inverse row transforms also emit the sums of their blocks of adjacent rows.
 static int mix_four_step(const Pow2Plan &pl, const void *v, const float2 *g, void *out, int BH, int L, int H, int d,
                          spectre_dtype io, float2 *gp, char *scr_base, size_t lane_bytes, const MixGroups &mg,
-                         bool scr16, SideLane *side, hipStream_t st) {
+                         bool scr16, SideLane *side, hipStream_t st, const void *wpack = nullptr, int Hw = 0,
+                         float2 *bsum = nullptr) {
     hipError_t e = hipSuccess;
     if (side) {
         // fork: the helper stream starts after everything before this call on the caller's stream.  Its first
@@ -552,7 +555,8 @@ static int mix_four_step(const Pow2Plan &pl, const void *v, const float2 *g, voi
         // measured -7 % at L = 8192, -10 % at 4096 (three kernels), nothing or a loss from 16384 on
         const bool affine = !scr16 && nbh % 8 == 0 && (size_t)L * (d / 2) * sizeof(float2) <= ((size_t)3 << 20) &&
                             option(SPECTRE_OPT_HEAD_AFFINE) != 0;
-        e = launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, ls, scr16, affine);
+        e = wpack ? launch_small_fwd_proj(pl, v, wpack, Hw, scr, L, H, bh0, nbh, ls, affine)
+                  : launch_small_fwd(pl, (int)io, v, scr, L, H, bh0, nbh, ls, scr16, affine);
         if (e != hipSuccess) { what = "small_fwd"; break; }
         if (lane && !side_has_gate) {
             e = hipStreamWaitEvent(side->stream, side->gate, 0);
@@ -561,7 +565,7 @@ static int mix_four_step(const Pow2Plan &pl, const void *v, const float2 *g, voi
         }
         e = launch_big(pl, scr, gp, bh0, nbh, 0, ls, false, scr16, affine);
         if (e != hipSuccess) { what = "big"; break; }
-        e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls, 0, 0, 0, scr16, affine);
+        e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls, 0, 0, 0, scr16, affine, bsum);
         if (e != hipSuccess) { what = "small_inv"; break; }
         bh0 += nbh;
     }
@@ -913,6 +917,166 @@ int spectre_wrm_apply_coeff(const void *v, const void *s, void *out, int B, int 
     return SPECTRE_OK;
 }
 
+// ------------------------------------------------------------------------------------------ whole layer
+// Workspace sections of spectre_layer_forward.
+struct LayerLayout {
+    bool fused;                   // projection inside the row transforms (four-step route, bf16 rows)
+    bool sums;                    // block sums from the inverse row transforms feed the refinement
+    size_t partial, sum_x, sum_q, hid, raw, g, wpack, mix, vbuf, s, wrm, bsum;
+    size_t total() const { return partial + sum_x + sum_q + hid + raw + g + wpack + mix + vbuf + s + wrm + bsum; }
+};
+static LayerLayout layer_layout(int B, int L, int H, int d, spectre_dtype io, const spectre_gate_params *P,
+                                const spectre_wrm_params *W) {
+    LayerLayout y;
+    const size_t BH = (size_t)B * H, esize = (io == SPECTRE_BF16) ? 2 : 4;
+    y.fused = (io == SPECTRE_BF16) && mix_route((int)BH, L, d) == 2;
+    y.sums = y.fused && W && W->levels > kWrmTileLevels;
+    const size_t pool = align256(gate_partial_bytes(B, L, H, d));
+    const size_t proj = align256((size_t)B * project_chunks(L) * H * d * sizeof(double));
+    y.partial = pool > proj ? pool : proj;
+    y.sum_x = y.sum_q = align256(BH * d * sizeof(double));
+    y.hid = align256(BH * P->d_g * sizeof(float));
+    y.raw = gate_raw_bytes(B, H, P);
+    y.g = align256(BH * (size_t)(L / 2 + 1) * sizeof(float2));
+    y.wpack = y.fused ? align256((size_t)H * kProjPackBytes) : 0;
+    y.mix = align256(spectre_mix_workspace_bytes(B, L, H, d, io));
+    y.vbuf = y.fused ? 0 : align256(BH * (size_t)L * d * esize);
+    y.s = W ? align256(BH * (size_t)(W->levels + 1) * d * sizeof(float)) : 0;
+    y.wrm = W ? align256(spectre_wrm_apply_workspace_bytes(B, L, H, d, W->levels)) : 0;
+    y.bsum = y.sums ? align256(BH * (size_t)(L / small_tile_rows((int)io)) * d * sizeof(float)) : 0;
+    return y;
+}
+
+static int check_layer_args(int B, int L, int H, int d, spectre_dtype io, const spectre_gate_params *P,
+                            const spectre_wrm_params *W, const char *who) {
+    if (B < 1 || L < 1 || H < 1 || d < 1) return fail(SPECTRE_EINVAL, "%s: non-positive size", who);
+    if (io != SPECTRE_F32 && io != SPECTRE_BF16) return fail(SPECTRE_EINVAL, "%s: bad dtype", who);
+    if (d != 64) return fail(SPECTRE_EUNSUPPORTED, "%s: d=%d (only 64 is built)", who, d);
+    if (H > 65535 || B > 65535) return fail(SPECTRE_EUNSUPPORTED, "%s: H or B above 65535", who);
+    if ((long long)B * H > 0x7fffffffLL / 64) return fail(SPECTRE_EUNSUPPORTED, "%s: B*H too large", who);
+    int rc = check_gate_params(P, H, who);
+    if (rc) return rc;
+    if (P->n_fft != L || P->d != d) return fail(SPECTRE_EINVAL, "%s: gate is for n_fft=%d, d=%d", who, P->n_fft, P->d);
+    if (!spectre_length_supported(L, d)) return fail(SPECTRE_EUNSUPPORTED, "%s: no kernel for L=%d, d=%d", who, L, d);
+    if (W) {
+        rc = check_wrm_params(W, H, who);
+        if (rc) return rc;
+        if (W->d != d) return fail(SPECTRE_EINVAL, "%s: refinement parameters are for d=%d", who, W->d);
+        if (W->levels > 0 && (L % (1LL << W->levels)) != 0)
+            return fail(SPECTRE_EINVAL, "%s: 2^%d does not divide L=%d", who, W->levels, L);
+        if (spectre_wrm_apply_workspace_bytes(B, L, H, d, W->levels) == 0 || (L + kWrmTileRows - 1) / kWrmTileRows > 65535 ||
+            (W->levels > kWrmTileLevels && L > 262144))
+            return fail(SPECTRE_EUNSUPPORTED, "%s: refinement not available for L=%d, levels=%d", who, L, W->levels);
+    }
+    return SPECTRE_OK;
+}
+
+size_t spectre_layer_workspace_bytes(int B, int L, int H, int d, spectre_dtype io, const spectre_gate_params *P,
+                                     const spectre_wrm_params *W) {
+    if (!P || check_layer_args(B, L, H, d, io, P, W, "layer_workspace_bytes")) return 0;
+    return layer_layout(B, L, H, d, io, P, W).total();
+}
+
+int spectre_layer_forward(const void *x, const float *Wq, const float *Wv, int Hw, const spectre_gate_params *P,
+                          const spectre_wrm_params *W, void *out, int B, int L, int H, int d, spectre_dtype io,
+                          void *ws, size_t ws_bytes, void *stream) {
+    if (!x || !Wq || !Wv || !out) return fail(SPECTRE_EINVAL, "layer_forward: null pointer");
+    if (!P) return fail(SPECTRE_EINVAL, "layer_forward: null gate parameters");
+    int rc = check_layer_args(B, L, H, d, io, P, W, "layer_forward");
+    if (rc) return rc;
+    if (!(Hw == H || Hw == 1)) return fail(SPECTRE_EINVAL, "layer_forward: Hw must be H or 1");
+    const size_t bytes = (size_t)B * L * H * d * (io == SPECTRE_BF16 ? 2 : 4);
+    const char *xb = static_cast<const char *>(x), *ob = static_cast<const char *>(out);
+    if (xb < ob + bytes && ob < xb + bytes) return fail(SPECTRE_EINVAL, "layer_forward: out overlaps x");
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(out)) & 15)
+        return fail(SPECTRE_EINVAL, "layer_forward: tensors must be 16-byte aligned");
+    const LayerLayout y = layer_layout(B, L, H, d, io, P, W);
+    if (!ws || ws_bytes < y.total()) return fail(SPECTRE_EWORKSPACE, "layer_forward: workspace %zu < %zu bytes", ws_bytes, y.total());
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(SPECTRE_EINVAL, "layer_forward: ws not 256-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int BH = B * H;
+    char *w = static_cast<char *>(ws);
+    auto take = [&](size_t n) { char *p0 = w; w += n; return p0; };
+    double *partial = reinterpret_cast<double *>(take(y.partial));
+    double *sum_x = reinterpret_cast<double *>(take(y.sum_x));
+    double *sum_q = reinterpret_cast<double *>(take(y.sum_q));
+    float *hid = reinterpret_cast<float *>(take(y.hid));
+    float2 *raw = reinterpret_cast<float2 *>(take(y.raw));
+    float2 *g = reinterpret_cast<float2 *>(take(y.g));
+    void *wpack = take(y.wpack);
+    char *mix_ws = take(y.mix);
+    void *vbuf = take(y.vbuf);
+    float *s_lv = reinterpret_cast<float *>(take(y.s));
+    char *wrm_ws = take(y.wrm);
+    float2 *bsum = y.sums ? reinterpret_cast<float2 *>(take(y.bsum)) : nullptr;
+
+    // every table look-up before the first launch
+    Pow2Plan pl;
+    SideLane *side = nullptr;
+    int dev = 0;
+    MixGroups mg;
+    if (y.fused) {
+        rc = get_pow2_plan(L, &pl);
+        if (rc) return rc;
+        mg = mix_groups(BH, L, d, 1);
+    } else {
+        const float2 *probe = nullptr;                 // the unfused mixer call below looks its tables up itself; make
+        const int route = mix_route(BH, L, d);         // sure it cannot fail after the projection has been enqueued
+        if (route == 1 || route == 2) rc = get_roots(L, &probe);
+        else if (route == 4) rc = get_roots(4096, &probe);
+        else rc = get_roots(chirp_padded_length(L), &probe);
+        if (rc) return rc;
+    }
+    hipError_t e;
+    if (y.fused) {
+        // pooled query: sum_q = (sum_l x_l) W_q (pooling commutes with the projection); the rows of X are read once
+        // more by the row transforms, V itself never exists in memory
+        e = launch_pool((int)io, x, partial, sum_x, B, L, H, d, st);
+        if (e != hipSuccess) return fail_hip(e, "pool(x)");
+        e = launch_pack_w(Wv, Hw, wpack, st);
+        if (e != hipSuccess) return fail_hip(e, "pack_w");
+    } else {
+        e = launch_project((int)io, x, Wq, Wv, Hw, vbuf, nullptr, partial, B, L, H, st);
+        if (e != hipSuccess) return fail_hip(e, "project");
+        e = launch_pool_final(partial, sum_x, B, H * d, project_chunks(L), st);
+        if (e != hipSuccess) return fail_hip(e, "pool_final");
+    }
+    e = launch_project_pooled(sum_x, Wq, Hw, B, H, sum_q, st);
+    if (e != hipSuccess) return fail_hip(e, "project_pooled");
+    e = launch_gate_mlp(sum_q, 1.0 / (double)L, gate_dev(P), hid, raw, B, H, 0, g, st);
+    if (e != hipSuccess) return fail_hip(e, "gate_mlp");
+    if (y.fused) {
+        float2 *gp = reinterpret_cast<float2 *>(mix_ws);
+        char *scr_base = mix_ws + align256((size_t)BH * L * sizeof(float2));
+        const size_t lane_bytes = align256((size_t)mg.chunk * L * (d / 2) * sizeof(float2));
+        if (mg.lanes == 2) {
+            rc = acquire_lane(&dev, &side);
+            if (rc) return rc;
+        }
+        rc = mix_four_step(pl, x, g, out, BH, L, H, d, io, gp, scr_base, lane_bytes, mg, false, side, st, wpack, Hw, bsum);
+        if (side) release_lane(dev, side);
+        if (rc) return rc;
+    } else {
+        rc = spectre_mix_forward_ex(vbuf, g, out, B, L, H, d, io, 0u, mix_ws, y.mix, stream);
+        if (rc) return rc;
+    }
+    if (W) {
+        WrmDev D;
+        D.Hg = W->Hg; D.d = W->d; D.d_w = W->d_w; D.levels = W->levels;
+        D.ln_gamma = W->ln_gamma; D.ln_beta = W->ln_beta; D.ln_eps = W->ln_eps;
+        D.W1 = W->W1; D.b1 = W->b1; D.W2 = W->W2; D.b2 = W->b2;
+        e = launch_wrm_gates(sum_q, 1.0 / (double)L, D, B, H, s_lv, st);
+        if (e != hipSuccess) return fail_hip(e, "wrm_gates");
+        const size_t part = align256(wrm_scratch_floats(BH, L, W->levels) * sizeof(float));
+        float *tile_sums = reinterpret_cast<float *>(wrm_ws);
+        float *upper = reinterpret_cast<float *>(wrm_ws + part);
+        e = launch_wrm_apply((int)io, out, s_lv, out, tile_sums, upper, B, L, H, W->levels, st,
+                             reinterpret_cast<const float *>(bsum), small_tile_rows((int)io));
+        if (e != hipSuccess) return fail_hip(e, "wrm_apply");
+    }
+    return SPECTRE_OK;
+}
+
 // ------------------------------------------------------------------------------------------ prefix cache
 static bool prefix_length_ok(int N, int d) {
     int N1, N2, P;
@@ -1047,15 +1211,16 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
     hipError_t e;
     if (c->t == 0 && T > 1) {
         // the ring buffers are all zero on an empty cache (spectre_prefix_init): only the prompt's rows are written,
-        // and the same pass sums the queries
-        e = launch_ring_append((int)io, v_new, q_new, static_cast<float *>(c->v_buf), static_cast<float *>(c->q_buf), partial,
-                               B, T, H, N, M0, W, 0, 0, st);
+        // and the same pass sums the queries.  Without memory rows the value rows are read once, by the row transform,
+        // which also lays them into the ring buffer; with memory rows the window starts with them and is transformed
+        // from the ring buffer as a whole.
+        const bool fused_ring = (M0 == 0);
+        e = launch_ring_append((int)io, fused_ring ? nullptr : v_new, q_new, static_cast<float *>(c->v_buf),
+                               static_cast<float *>(c->q_buf), partial, B, T, H, N, M0, W, 0, 0, st);
         if (e != hipSuccess) return fail_hip(e, "ring_append(prompt)");
         e = launch_pool_final(partial, static_cast<double *>(c->sum_q), B, H * d, (T + 255) / 256, st, false);
         if (e != hipSuccess) return fail_hip(e, "pool_final(prompt)");
-        // with memory rows the window starts with them, and a prompt that fills most of the ring is read faster from
-        // the ring buffers just written (whole contiguous rows per head) than from the token tensor: transform the window
-        if (M0 > 0 || 2 * T >= W) {
+        if (!fused_ring) {
             rc = transform_window(c, scr, st);
             if (rc) return rc;
             c->t = T;
@@ -1064,7 +1229,8 @@ int spectre_prefix_update(spectre_prefix_cache *c, const void *v_new, const void
         const int chunk = mix_chunk_heads(BH, N, d);
         for (int bh0 = 0; bh0 < BH; bh0 += chunk) {
             const int nbh = (BH - bh0 < chunk) ? BH - bh0 : chunk;
-            e = launch_small_fwd(pl, (int)io, v_new, scr, T, H, bh0, nbh, st);
+            e = launch_small_fwd(pl, (int)io, v_new, scr, T, H, bh0, nbh, st, false, false,
+                                 static_cast<float2 *>(c->v_buf));
             if (e != hipSuccess) return fail_hip(e, "small_fwd");
             e = launch_big(pl, scr, nullptr, bh0, nbh, 1, st);
             if (e != hipSuccess) return fail_hip(e, "big(forward)");

@@ -36,13 +36,24 @@ bool pow2_split(int L, int *N1, int *N2, int *P);
 // the same element index (the buffer is used to half its size); all three kernels of a pass must agree on it.
 // affine (nbh a multiple of 8; big: mode 0, fp32 scratch): every workgroup of head bh0 + 8 s + x runs on XCD x, and the
 // three kernels walk s up, down, up, so that part of the scratch is read from the L2 it was written through.
+// ring (pre-fill of an empty cache without memory rows): the rows read are also stored, as fp32 pairs, to row l of head
+// bh of ring [B*H][L][32], the cache's value ring buffer.
 hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
-                            int bh0, int nbh, hipStream_t st, bool scr16 = false, bool affine = false);
+                            int bh0, int nbh, hipStream_t st, bool scr16 = false, bool affine = false,
+                            float2 *ring = nullptr);
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
                       hipStream_t st, bool shared_gate = false, bool scr16 = false, bool affine = false);
+// bsum (whole transforms only): sums of the blocks of small_tile_rows(io) adjacent output rows, over the values as
+// stored, to bsum [B*H][L / small_tile_rows][32 pairs] - what the wavelet refinement's coarse levels need.
+int small_tile_rows(int io);
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
                             int out_rows, int H, int bh0, int nbh, hipStream_t st, int ring0 = 0, int ring_w = 0,
-                            int newest = 0, bool scr16 = false, bool affine = false);
+                            int newest = 0, bool scr16 = false, bool affine = false, float2 *bsum = nullptr);
+// small_fwd with the token projection of Eq. 2 in front: x = the layer input [B, rows, H, 64] as bf16, wpack = the
+// heads' value matrices as packed by launch_pack_w (project.h); the projected rows are rounded to bf16 on chip, as
+// the separate projection would have stored them, and transformed.  bf16 rows and fp32 scratch only.
+hipError_t launch_small_fwd_proj(const Pow2Plan &pl, const void *x, const void *wpack, int Hw, float2 *scratch, int rows,
+                                 int H, int bh0, int nbh, hipStream_t st, bool affine = false);
 // g [BH, L/2+1] -> gp [BH][N2][N1] in the big kernel's register order, scaled by 1/L and
 // extended to all L bins by Hermitian symmetry (real parts only at DC and Nyquist).
 hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st);

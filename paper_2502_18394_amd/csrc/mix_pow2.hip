@@ -16,6 +16,8 @@
 // with W_n = exp(-j 2 pi / n) and the 1/L of the inverse folded into G.
 #include "mix_pow2.h"
 
+#include <type_traits>
+
 #include "fft_regs.h"
 #include "internal.h"
 
@@ -90,11 +92,13 @@ struct SmallTwiddles {
 // small_fwd: grid (N1/TT, nbh); block 32*TT threads.  Reads the N2*TT rows
 // {t1_0 + r + N1*t2} of one head (32 pairs each, one 128 B / 256 B segment per row),
 // stages them in LDS, then lane (pair p, t1_local) runs the N2-point DFT over t2.
+// ring != nullptr (pre-fill of an empty Prefix-FFT cache): every row read is also copied, as fp32, to row l of head bh
+// of the value ring buffer ring [B*H][N1 * N2][32 pairs] - the rows then cross HBM once for both purposes.
 template <int N2, int TT, typename IO, typename SC>
 __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t *__restrict__ v,
                                                        typename SC::elem_t *__restrict__ scr,
                                                        const float2 *__restrict__ twL, int rows, int H,
-                                                       int N1, int bh0, int aff) {
+                                                       int N1, int bh0, int aff, float2 *__restrict__ ring) {
     typedef typename IO::pair_t pair_t;
     constexpr int S = TileStride<IO>::value;
     extern __shared__ unsigned char smem_raw[];
@@ -114,6 +118,13 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
         }
 #pragma unroll
         for (int t2 = 0; t2 < N2; ++t2) lds[(t2 * TT + r) * S + lp] = val[t2];
+        if (ring) {
+#pragma unroll
+            for (int t2 = 0; t2 < N2; ++t2) {
+                const int l = t1_0 + r + N1 * t2;
+                if (l < rows) stream_store(ring + ((size_t)bh * N1 * N2 + l) * 32 + lp, IO::unpack(val[t2]));
+            }
+        }
     }
     __syncthreads();
     const int tl = tid % TT, p = tid / TT, t1 = t1_0 + tl;
@@ -130,16 +141,108 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
     }
 }
 
+// small_fwd with the token projection in front (Sec. 3.2 step 1, Eq. 2, feeding step 2): the workgroup reads rows of
+// the layer input X instead of V, multiplies every row by its head's 64 x 64 value matrix on the matrix cores and
+// rounds the products to bfloat16 into the same LDS tile the plain kernel fills from memory - the bits the separate
+// projection kernel would have stored as V (same instruction, same order of the hi/lo weight terms), which then
+// never exist in HBM.  bf16 rows, TT = 16.  wpack: the weights as the B operand (k_pack_w), held in registers.
+// A wave takes 32 tile rows at a time (two adjacent t2 of the 16 t1): lane l supplies row l % 32 and the channels
+// 16 ks + 8 (l / 32) .. + 7 of k-step ks as one 16-byte LDS read; accumulator register v of lane l is row
+// 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of a 32-column block, so a channel pair sits in two adjacent lanes:
+// even lanes pack the pairs of columns 0..31, odd lanes those of columns 32..63, each fetching the neighbour's half
+// with a quad permutation.  The rows a wave overwrites are the ones it has just read, and no other wave touches them.
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+template <int N2>
+__global__ __launch_bounds__(512) void k_small_fwd_proj(const uint32_t *__restrict__ x, const uint4 *__restrict__ wpack,
+                                                        int Hw, float2 *__restrict__ scr,
+                                                        const float2 *__restrict__ twL, int rows, int H, int N1,
+                                                        int bh0, int aff) {
+    constexpr int TT = 16, S = TileStride<IoBf16>::value, NROW = N2 * TT, NGRP = (NROW + 31) / 32;
+    extern __shared__ unsigned char smem_raw[];
+    uint32_t *lds = reinterpret_cast<uint32_t *>(smem_raw);
+    const int tid = threadIdx.x;
+    int tile = blockIdx.x, bhl = blockIdx.y;
+    if (aff) head_affine(blockIdx.x, N1 / TT, aff, false, &bhl, &tile);
+    const int t1_0 = tile * TT;
+    const int bh = bh0 + bhl, b = bh / H, h = bh % H;
+    {
+        const int lp = tid & 31, r = tid >> 5;
+        uint32_t val[N2];
+#pragma unroll
+        for (int t2 = 0; t2 < N2; ++t2) {
+            const int l = t1_0 + r + N1 * t2;
+            val[t2] = (l < rows) ? IoBf16::load_stream(x + (((size_t)b * rows + l) * H + h) * 32 + lp) : 0u;
+        }
+#pragma unroll
+        for (int t2 = 0; t2 < N2; ++t2) lds[(t2 * TT + r) * S + lp] = val[t2];
+    }
+    const int lane = tid & 63, wave = tid >> 6, i = lane & 31, half = lane >> 5;
+    uint4 whi[8], wlo[8];                              // [ks * 2 + column block]
+    {
+        const uint4 *wp = wpack + (size_t)((Hw == 1) ? 0 : h) * 1024 + lane;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            whi[e] = wp[e * 64];
+            wlo[e] = wp[512 + e * 64];
+        }
+    }
+    __syncthreads();
+    for (int g = wave; g < NGRP; g += 8) {
+        const int ri = 32 * g + i;
+        uint4 a[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            a[ks] = (ri < NROW) ? *reinterpret_cast<const uint4 *>(lds + ri * S + 8 * ks + 4 * half) : make_uint4(0, 0, 0, 0);
+        floatx16_t acc0 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, acc1 = acc0;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a[ks]);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, wlo[2 * ks]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, wlo[2 * ks + 1]), acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, whi[2 * ks]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, whi[2 * ks + 1]), acc1, 0, 0, 0);
+        }
+        const bool odd = i & 1;
+        const int pcol = odd ? 16 + (i >> 1) : (i >> 1);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = 32 * g + 8 * (v / 4) + 4 * half + (v % 4);
+            const float n0 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(acc0[v]), 0xB1, 0xF, 0xF, false));
+            const float n1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(acc1[v]), 0xB1, 0xF, 0xF, false));
+            const float2 pr = odd ? make_float2(n1, acc1[v]) : make_float2(acc0[v], n0);
+            if (row < NROW) lds[row * S + pcol] = IoBf16::pack(pr);
+        }
+    }
+    __syncthreads();
+    const int tl = tid % TT, p = tid / TT, t1 = t1_0 + tl;
+    float2 xv[N2];
+#pragma unroll
+    for (int t2 = 0; t2 < N2; ++t2) xv[t2] = IoBf16::unpack(lds[(t2 * TT + tl) * S + p]);
+    small_dft<N2, false>(xv);
+    float2 *dst = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
+    const SmallTwiddles<N2> tw(twL, t1);
+#pragma unroll
+    for (int k2 = 0; k2 < N2; ++k2) {
+        const float2 y = (k2 == 0) ? xv[0] : cmul(xv[k2], tw(k2));
+        dst[(size_t)k2 * 32 * N1] = y;
+    }
+}
+
 // small_inv: mirror image.  Rows l of the inverse transform with row0 <= l < row0+out_rows
 // are written to row l-row0 of out [B, out_rows, H, d].  With ring_w > 0 the rows are instead
 // gathered from a ring buffer that occupies rows ring0 .. ring0+ring_w-1 and whose newest entry
 // sits at ring0+newest: the out_rows newest entries are written oldest first.
+// bsum != nullptr (mixer followed by the wavelet refinement): the workgroup also emits the sums of the TT adjacent rows
+// it writes for every t2, taken over the values as stored (after rounding to the I/O type), to
+// bsum [bh][L / TT][32 pairs]; block l / TT covers rows l .. l + TT - 1.  Added in row order.
 template <int N2, int TT, typename IO, typename SC>
 __global__ __launch_bounds__(32 * TT) void k_small_inv(const typename SC::elem_t *__restrict__ scr,
                                                        typename IO::pair_t *__restrict__ out,
                                                        const float2 *__restrict__ twL, int row0,
                                                        int out_rows, int H, int N1, int bh0, int ring0,
-                                                       int ring_w, int newest, int aff) {
+                                                       int ring_w, int newest, int aff, float2 *__restrict__ bsum) {
     typedef typename IO::pair_t pair_t;
     constexpr int S = TileStride<IO>::value;
     extern __shared__ unsigned char smem_raw[];
@@ -178,6 +281,14 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const typename SC::elem_t
         }
         if (orow >= 0 && orow < out_rows)
             IO::store_stream(out + (((size_t)b * out_rows + orow) * H + h) * 32 + lp, lds[(t2 * TT + r) * S + lp]);
+    }
+    if (bsum) {                                        // lane (lp, r) sums the TT rows of t2 = r, r + TT, ...
+        for (int t2 = r; t2 < N2; t2 += TT) {
+            float2 acc = make_float2(0.f, 0.f);
+#pragma unroll
+            for (int i = 0; i < TT; ++i) acc = acc + IO::unpack(lds[(t2 * TT + i) * S + lp]);
+            bsum[((size_t)bh * (N1 / TT) * N2 + (t1_0 / TT + (N1 / TT) * t2)) * 32 + lp] = acc;
+        }
     }
 }
 
@@ -548,7 +659,7 @@ static hipError_t allow_lds(K kernel, size_t bytes) {
 
 template <int N2, int TT, typename IO, typename SC>
 static hipError_t small_fwd_t(const Pow2Plan &pl, const void *v, void *scr_v, int rows, int H, int bh0,
-                              int nbh, hipStream_t st, int aff) {
+                              int nbh, hipStream_t st, int aff, float2 *ring) {
     const size_t lds = (size_t)N2 * TT * TileStride<IO>::value * sizeof(typename IO::pair_t);
     auto kern = k_small_fwd<N2, TT, IO, SC>;
     typename SC::elem_t *scr = static_cast<typename SC::elem_t *>(scr_v);
@@ -556,13 +667,14 @@ static hipError_t small_fwd_t(const Pow2Plan &pl, const void *v, void *scr_v, in
     if (e != hipSuccess) return e;
     const dim3 grid = aff ? dim3(pl.N1 / TT * nbh) : dim3(pl.N1 / TT, nbh);
     kern<<<grid, dim3(32 * TT), lds, st>>>(
-        static_cast<const typename IO::pair_t *>(v), scr, pl.twL, rows, H, pl.N1, bh0, aff);
+        static_cast<const typename IO::pair_t *>(v), scr, pl.twL, rows, H, pl.N1, bh0, aff, ring);
     return hipGetLastError();
 }
 
 template <int N2, int TT, typename IO, typename SC>
 static hipError_t small_inv_t(const Pow2Plan &pl, const void *scr_v, void *out, int row0, int out_rows,
-                              int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w, int newest, int aff) {
+                              int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w, int newest, int aff,
+                              float2 *bsum) {
     const size_t lds = (size_t)N2 * TT * TileStride<IO>::value * sizeof(typename IO::pair_t);
     auto kern = k_small_inv<N2, TT, IO, SC>;
     const typename SC::elem_t *scr = static_cast<const typename SC::elem_t *>(scr_v);
@@ -570,7 +682,8 @@ static hipError_t small_inv_t(const Pow2Plan &pl, const void *scr_v, void *out, 
     if (e != hipSuccess) return e;
     const dim3 grid = aff ? dim3(pl.N1 / TT * nbh) : dim3(pl.N1 / TT, nbh);
     kern<<<grid, dim3(32 * TT), lds, st>>>(
-        scr, static_cast<typename IO::pair_t *>(out), pl.twL, row0, out_rows, H, pl.N1, bh0, ring0, ring_w, newest, aff);
+        scr, static_cast<typename IO::pair_t *>(out), pl.twL, row0, out_rows, H, pl.N1, bh0, ring0, ring_w, newest, aff,
+        bsum);
     return hipGetLastError();
 }
 
@@ -589,20 +702,47 @@ static hipError_t small_inv_t(const Pow2Plan &pl, const void *scr_v, void *out, 
     }
 
 hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
-                            int bh0, int nbh, hipStream_t st, bool scr16, bool affine) {
+                            int bh0, int nbh, hipStream_t st, bool scr16, bool affine, float2 *ring) {
     if (scr16 && !io) return hipErrorInvalidValue;
     if (affine && nbh % 8 != 0) return hipErrorInvalidValue;
     const int aff = affine ? nbh : 0;
-    SPECTRE_DISPATCH_N2(small_fwd_t, pl, v, scratch, rows, H, bh0, nbh, st, aff)
+    SPECTRE_DISPATCH_N2(small_fwd_t, pl, v, scratch, rows, H, bh0, nbh, st, aff, ring)
 }
+
+template <int N2, int TT, typename IO, typename SC>
+static hipError_t small_fwd_proj_t(const Pow2Plan &pl, const void *x, const void *wpack, int Hw, void *scr_v, int rows,
+                                   int H, int bh0, int nbh, hipStream_t st, int aff) {
+    if (!std::is_same<IO, IoBf16>::value || !std::is_same<SC, ScrF32>::value) return hipErrorInvalidValue;
+    const size_t lds = (size_t)N2 * 16 * TileStride<IoBf16>::value * sizeof(uint32_t);
+    auto kern = k_small_fwd_proj<N2>;
+    hipError_t e = allow_lds(kern, lds);
+    if (e != hipSuccess) return e;
+    const dim3 grid = aff ? dim3(pl.N1 / 16 * nbh) : dim3(pl.N1 / 16, nbh);
+    kern<<<grid, dim3(512), lds, st>>>(static_cast<const uint32_t *>(x), static_cast<const uint4 *>(wpack), Hw,
+                                       static_cast<float2 *>(scr_v), pl.twL, rows, H, pl.N1, bh0, aff);
+    return hipGetLastError();
+}
+
+hipError_t launch_small_fwd_proj(const Pow2Plan &pl, const void *x, const void *wpack, int Hw, float2 *scratch, int rows,
+                                 int H, int bh0, int nbh, hipStream_t st, bool affine) {
+    if (affine && nbh % 8 != 0) return hipErrorInvalidValue;
+    const int aff = affine ? nbh : 0;
+    const int io = 1;
+    const bool scr16 = false;
+    SPECTRE_DISPATCH_N2(small_fwd_proj_t, pl, x, wpack, Hw, scratch, rows, H, bh0, nbh, st, aff)
+}
+
+int small_tile_rows(int io) { return io ? 16 : 8; }
 
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
                             int out_rows, int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w,
-                            int newest, bool scr16, bool affine) {
+                            int newest, bool scr16, bool affine, float2 *bsum) {
     if (scr16 && !io) return hipErrorInvalidValue;
     if (affine && nbh % 8 != 0) return hipErrorInvalidValue;
+    if (bsum && (row0 != 0 || out_rows != pl.L || ring_w > 0)) return hipErrorInvalidValue;   // whole transforms only
     const int aff = affine ? nbh : 0;
-    SPECTRE_DISPATCH_N2(small_inv_t, pl, scratch, out, row0, out_rows, H, bh0, nbh, st, ring0, ring_w, newest, aff)
+    SPECTRE_DISPATCH_N2(small_inv_t, pl, scratch, out, row0, out_rows, H, bh0, nbh, st, ring0, ring_w, newest, aff,
+                        bsum)
 }
 
 template <int P, int MODE, typename SC = ScrF32, bool SHFL = false>

@@ -26,6 +26,7 @@ hipError_t launch_sweep(bool update, bool read, float2 *X, const float *delta, c
 constexpr int kMaxPending = 32;
 // Ring-buffer bookkeeping for T <= W tokens appended at once (token i -> slot (s0 + i) mod W behind M0 memory rows,
 // evicting when t0 + i >= W); partial [B][ceil(T/256)][H*64] doubles = per-chunk sums of q_new - q_evicted.
+// V == nullptr: only the query side (q_buf, partial); the value rows are then written by whoever reads V.
 hipError_t launch_ring_append(int io, const void *V, const void *Q, float *v_buf, float *q_buf, double *partial, int B,
                               int T, int H, int N, int M0, int W, int s0, long long t0, hipStream_t st);
 hipError_t launch_sweep_lazy(bool flush, bool read, float2 *X, const float *pending, const float2 *tw, const float2 *g,

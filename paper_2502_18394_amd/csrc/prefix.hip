@@ -506,7 +506,7 @@ __global__ __launch_bounds__(256) void k_ring_append(const typename IO::pair_t *
             const int slot = (int)(((long long)s0 + i) % W);
             ring[u] = ((size_t)bh * N + M0 + slot) * 32 + p;
             const size_t src = (((size_t)b * T + i) * H + h) * 32 + p;
-            rv[u] = V[src];
+            rv[u] = V ? V[src] : IO::zero();
             rq[u] = Q[src];
             qo[u] = (t0 + i >= W) ? q_buf[ring[u]] : make_float2(0.f, 0.f);
         }
@@ -516,7 +516,7 @@ __global__ __launch_bounds__(256) void k_ring_append(const typename IO::pair_t *
                 const float2 vn = IO::unpack(rv[u]), qn = IO::unpack(rq[u]);
                 sx += (double)qn.x - (double)qo[u].x;
                 sy += (double)qn.y - (double)qo[u].y;
-                v_buf[ring[u]] = vn;
+                if (V) v_buf[ring[u]] = vn;                          // V == nullptr: the value rows are written elsewhere
                 q_buf[ring[u]] = qn;
             }
         }

@@ -17,4 +17,9 @@ hipError_t launch_project(int io, const void *x, const float *Wq, const float *W
 hipError_t launch_project_pooled(const double *sum_x, const float *Wq, int Hw, int B, int H, double *sum_q,
                                  hipStream_t st);
 
+// W [Hw, 64, 64] fp32 -> wpack [Hw][2][512] x 16 bytes (kProjPackBytes per head): the weights in the order the bf16
+// matrix instruction takes its B operand, split into two bf16 terms (hi, then lo).
+constexpr size_t kProjPackBytes = 2 * 512 * 16;
+hipError_t launch_pack_w(const float *W, int Hw, void *wpack, hipStream_t st);
+
 }  // namespace spectre

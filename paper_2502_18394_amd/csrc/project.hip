@@ -310,6 +310,18 @@ __global__ __launch_bounds__(64) void k_project_pooled(const double *__restrict_
     sum_q[(size_t)bh * 64 + j] = s;
 }
 
+// The value weights of every head as the matrix instruction's B operand, two bf16 terms per weight, for kernels that
+// keep them in registers: wpack [Hw][2 (hi, lo)][4 k-steps x 2 column blocks x 64 lanes] of 16 bytes.
+__global__ __launch_bounds__(256) void k_pack_w(const float *__restrict__ W, uint4 *__restrict__ wpack) {
+    const int hw = blockIdx.x;
+    proj_fill_w_bf16(W + (size_t)hw * 4096, wpack + (size_t)hw * 1024, wpack + (size_t)hw * 1024 + 512, threadIdx.x);
+}
+
+hipError_t launch_pack_w(const float *W, int Hw, void *wpack, hipStream_t st) {
+    k_pack_w<<<Hw, 256, 0, st>>>(W, static_cast<uint4 *>(wpack));
+    return hipGetLastError();
+}
+
 int project_chunks(int L) { return (L + kProjRows - 1) / kProjRows; }
 
 // Sequences per workgroup: 1 unless a sequence is a single chunk; then enough of them that the launch is about two

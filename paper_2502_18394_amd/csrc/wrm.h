@@ -31,8 +31,11 @@ hipError_t launch_wrm_gates(const double *sum_q, double inv_count, const WrmDev 
 size_t wrm_scratch_floats(int BH, int L, int levels);
 
 // out = v + iDWT(s * DWT(v)) for v, out [B,L,H,64]; io 0 = fp32, 1 = bf16.  out may be v itself.
+// bsum (optional, used when levels > 8): sums of blocks of block_rows adjacent rows of v (block_rows divides 256),
+// [B*H][L / block_rows][64], emitted by whoever wrote v; then v is not read a second time for the coarse levels.
 hipError_t launch_wrm_apply(int io, const void *v, const float *s, void *out, float *tile_sums, float *upper,
-                            int B, int L, int H, int levels, hipStream_t st);
+                            int B, int L, int H, int levels, hipStream_t st, const float *bsum = nullptr,
+                            int block_rows = 0);
 
 // The same module with one gate per wavelet coefficient and channel: s [B,H,L,64] in the analysis' coefficient order
 // [a_J | d_J | ... | d_1] (a real Haar analysis, gate, synthesis; same tiling and scratch as above).

@@ -142,6 +142,20 @@ __global__ __launch_bounds__(256) void k_wrm_tile_sums_x16(const uint4 *__restri
     for (int c = 0; c < NCH; c += 4) *reinterpret_cast<float4 *>(dst + c) = make_float4(tot[c], tot[c + 1], tot[c + 2], tot[c + 3]);
 }
 
+// Tile sums from sums of smaller row blocks that the producer of v emitted on the side (the mixer's store phase):
+// S[bh][tile][c] = sum over the tile's 256 / block_rows blocks, in row order.  One lane per (bh, tile, c).
+__global__ __launch_bounds__(256) void k_wrm_tile_sums_from_blocks(const float *__restrict__ bsum, float *__restrict__ S,
+                                                                   int per_tile, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int c = (int)(idx & 63);
+    const size_t bt = idx >> 6;                        // (bh, tile)
+    const float *src = bsum + bt * per_tile * 64 + c;
+    float acc = 0.f;
+    for (int i = 0; i < per_tile; ++i) acc += src[(size_t)i * 64];
+    S[idx] = acc;
+}
+
 // coefficient of the level-l block mean in the closed form above
 __device__ __forceinline__ float wrm_coef(const float *__restrict__ sb, int l, int J, int c) {
     return (l < J) ? sb[(l + 1) * 64 + c] - sb[l * 64 + c] : sb[c] - sb[J * 64 + c];
@@ -524,12 +538,21 @@ static hipError_t tile_sums_pass(int io, const void *v, float *tile_sums, int B,
 }
 
 hipError_t launch_wrm_apply(int io, const void *v, const float *s, void *out, float *tile_sums, float *upper,
-                            int B, int L, int H, int levels, hipStream_t st) {
+                            int B, int L, int H, int levels, hipStream_t st, const float *bsum, int block_rows) {
     const int BH = B * H;
     const int ntiles = (L + kWrmTileRows - 1) / kWrmTileRows;
     const dim3 grid(H, ntiles, B);
     if (levels > kWrmTileLevels) {
-        hipError_t e = tile_sums_pass(io, v, tile_sums, B, L, H, ntiles, st);
+        hipError_t e;
+        if (bsum) {                                    // the producer of v already summed its rows in small blocks
+            if (block_rows < 1 || kWrmTileRows % block_rows != 0) return hipErrorInvalidValue;
+            const size_t total = (size_t)BH * ntiles * 64;
+            k_wrm_tile_sums_from_blocks<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(bsum, tile_sums,
+                                                                                         kWrmTileRows / block_rows, total);
+            e = hipGetLastError();
+        } else {
+            e = tile_sums_pass(io, v, tile_sums, B, L, H, ntiles, st);
+        }
         if (e != hipSuccess) return e;
         const size_t lds = (size_t)2 * ntiles * kUpCh * sizeof(float);
         if (lds > 48 * 1024) {
