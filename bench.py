@@ -11,6 +11,7 @@ is timed in the same run and reported under "decode".  Inputs are resident in HB
 timed region.  Prints ONE JSON line.
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -323,6 +324,41 @@ def main():
     res["wrm"] = {"ms": ms_wrm, "levels": J, "algorithmic_bytes": wrm_bytes,
                   "hbm_frac": wrm_bytes / (ms_wrm * 1e-3) / 1e9 / HBM_PEAK_GBS,
                   "what": "spectre_wrm_apply: V + iDWT(s * DWT(V)), Haar, one gate per band and channel"}
+    # the same module with one gate per wavelet coefficient and channel (gates: one more fp32 tensor to read)
+    s_co = torch.randn((B, H, L, d), generator=gen, device="cuda", dtype=torch.float32)
+    ms_wco = time_loop(lambda: binding.wrm_apply_coeff(out, s_co, J, out=wrm_out, ws=ws_wrm), args.steps, 2)
+    wco_bytes = wrm_bytes + tokens * H * d * 4
+    res["wrm_coeff"] = {"ms": ms_wco, "levels": J, "algorithmic_bytes": wco_bytes,
+                        "hbm_frac": wco_bytes / (ms_wco * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "what": "spectre_wrm_apply_coeff: one gate per coefficient and channel, s [B,H,L,d] fp32"}
+    del s_co
+    # the whole layer in one call: X -> projection -> pooled query -> gate -> mixer (-> refinement), against the same
+    # chain as separate calls.  Algorithmic bytes: X in, out, W2, and g written and read once.
+    layer_bytes = 2 * tokens * H * d * esize + P.Hg * P.d_g * 2 * F * 4 + 2 * B * H * F * 8
+    Wp = binding.WrmParams(synth.wrm_params(synth.BASE_SEED + 14, H, d, J))
+    res["layer"] = {"algorithmic_bytes": layer_bytes}
+    for tag, wp in (("", None), ("_with_refinement", Wp)):
+        need = int(binding.lib().spectre_layer_workspace_bytes(B, L, H, d, binding._dtype_code(V), ctypes.byref(P.c),
+                                                               ctypes.byref(wp.c) if wp is not None else None))
+        ws_layer = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+        ms_layer = time_loop(lambda: binding.layer_forward(Q, Wq, Wv, P, wp, out=out, ws=ws_layer), args.steps, 2)
+        del ws_layer
+
+        def chain():
+            v, _, sq = binding.project(Q, Wq, Wv, ws=ws_proj)
+            binding.gate(sq, P, 1.0 / L, pooled=True, g_out=g, ws=ws_gate)
+            binding.mix_forward(v, g, out=out, ws=ws_mix)
+            if wp is not None:
+                binding.wrm_apply(out, binding.wrm_gates(sq, wp, 1.0 / L, pooled=True), out=out, ws=ws_wrm)
+        ms_chain = time_loop(chain, args.steps, 2)
+        res["layer"]["ms" + tag] = ms_layer
+        res["layer"]["ms_separate_calls" + tag] = ms_chain
+        res["layer"]["tokens_per_s" + tag] = tokens / (ms_layer * 1e-3)
+        res["layer"]["hbm_frac" + tag] = (layer_bytes + (0 if wp is None else 0)) / (ms_layer * 1e-3) / 1e9 / HBM_PEAK_GBS
+    res["layer"]["what"] = ("spectre_layer_forward: projection inside the row transforms (V never in memory), gate from "
+                            "the pooled query, mixer; with refinement: Haar level gates, coarse levels from block sums "
+                            "the mixer's store phase emits")
+    del Wp
     if cfg["io"] == "bf16" and not args.no_secondary and binding.mix_workspace_bytes(B, L, H, d, binding.BF16) > 256:
         # opt-in variant, reported beside the default and never as `value`: bfloat16 pairs between the three kernels
         ms16 = time_loop(lambda: binding.mix_forward(V, g, out=out, ws=ws_mix, flags=binding.MIX_BF16_SCRATCH),

@@ -19,6 +19,8 @@ __global__ __launch_bounds__(256) void k_wrm_gates(const double *__restrict__ su
     __shared__ float qbar[256];
     __shared__ float hid[256];
     __shared__ double stat[2];
+    // grid (B*H, ceil(nout / 256)): every workgroup repeats the tiny LayerNorm and first layer and emits 256 outputs
+    // (the output layer is a chain of d_w dependent loads per output: one workgroup per head left it latency-bound)
     const int bh = blockIdx.x, h = bh % H, hp = (Hg == 1) ? 0 : h;
     const int tid = threadIdx.x;
     if (tid < d) xs[tid] = inv_count * sum_q[(size_t)bh * d + tid];
@@ -43,7 +45,8 @@ __global__ __launch_bounds__(256) void k_wrm_gates(const double *__restrict__ su
         hid[tid] = 0.5f * a * (1.0f + erff(a * 0.70710678118654752440f));
     }
     __syncthreads();
-    for (int o = tid; o < nout; o += 256) {
+    const int o = blockIdx.y * 256 + tid;
+    if (o < nout) {
         float a = b2[(size_t)hp * nout + o];
         const float *w = W2 + (size_t)hp * dw * nout + o;
         for (int j = 0; j < dw; ++j) a = fmaf(hid[j], w[(size_t)j * nout], a);
@@ -512,8 +515,9 @@ __global__ __launch_bounds__(256) void k_wrm_upper_coeff(const float *__restrict
 // ------------------------------------------------------------------------------------------
 hipError_t launch_wrm_gates(const double *sum_q, double inv_count, const WrmDev &P, int B, int H, float *s,
                             hipStream_t st) {
-    k_wrm_gates<<<B * H, 256, 0, st>>>(sum_q, inv_count, P.ln_gamma, P.ln_beta, P.ln_eps, P.W1, P.b1, P.W2, P.b2, s,
-                                       H, P.Hg, P.d, P.d_w, (P.levels + 1) * P.d);
+    const int nout = (P.levels + 1) * P.d;
+    k_wrm_gates<<<dim3(B * H, (nout + 255) / 256), 256, 0, st>>>(sum_q, inv_count, P.ln_gamma, P.ln_beta, P.ln_eps, P.W1,
+                                                                P.b1, P.W2, P.b2, s, H, P.Hg, P.d, P.d_w, nout);
     return hipGetLastError();
 }
 
