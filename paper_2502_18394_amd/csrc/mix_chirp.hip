@@ -64,7 +64,6 @@ __global__ __launch_bounds__(256) void k_chirp_gate(const float2 *__restrict__ s
                                                     int N1, int N2, int ph0, float scale, size_t total) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
-    const int TPC = N1 / 16;
     const int r = (int)(idx % N1);
     const size_t q = idx / N1;
     const int k2 = (int)(q % N2);
@@ -72,13 +71,12 @@ __global__ __launch_bounds__(256) void k_chirp_gate(const float2 *__restrict__ s
     const int phl = (int)(lh / 32), p = (int)(lh % 32);
     const size_t bh = (size_t)ph0 * 32 + lh;
     if (bh >= (size_t)BH) return;
-    const int j = r / TPC, tau = r % TPC;
-    const float2 z = scr[(((size_t)phl * N2 + k2) * 32 + p) * N1 + 16 * tau + j];
+    const float2 z = scr[(((size_t)phl * N2 + k2) * 32 + p) * N1 + r];   // same entry order on both sides
     gp[(bh * N2 + k2) * N1 + r] = make_float2(z.x * scale, z.y * scale);
 }
 
 // The same spectra in plain bin order for the in-LDS kernel: g[bh][k] = spectrum bin k = k2 + N2 k1 of pseudo-head
-// column (bh / 32, bh % 32), which the forward-only big kernel left at position digit_reverse16(k1) of column k2;
+// column (bh / 32, bh % 32), which the forward-only big kernel left at entry big_position(k1) of column k2;
 // unscaled (that kernel divides by its length itself).
 __global__ __launch_bounds__(256) void k_chirp_gate_plain(const float2 *__restrict__ scr, float2 *__restrict__ g, int BH,
                                                           int F, int N1, int N2, int P, int ph0, size_t total) {
@@ -90,8 +88,7 @@ __global__ __launch_bounds__(256) void k_chirp_gate_plain(const float2 *__restri
     const size_t bh = (size_t)ph0 * 32 + lh;
     if (bh >= (size_t)BH) return;
     const int k2 = k % N2, k1 = k / N2;
-    const int pos = (P == 2) ? (((k1 & 15) << 4) | (k1 >> 4)) : (((k1 & 15) << 8) | (k1 & 0xF0) | (k1 >> 8));
-    g[bh * F + k] = scr[(((size_t)phl * N2 + k2) * 32 + p) * N1 + pos];
+    g[bh * F + k] = scr[(((size_t)phl * N2 + k2) * 32 + p) * N1 + big_position(k1, P)];
 }
 
 hipError_t launch_chirp_gate_plain(const float2 *scr, float2 *g, int BH, int M, int N1, int N2, int P, int ph0,
@@ -146,10 +143,6 @@ static void fft_host(const std::complex<double> *in, size_t stride, size_t n, st
     }
 }
 
-static int digit_reverse16_host(int pos, int P) {
-    return P == 2 ? (((pos & 15) << 4) | (pos >> 4)) : (((pos & 15) << 8) | (pos & 0xF0) | (pos >> 8));
-}
-
 void chirp_tables_host(int L, int M, int N1, int N2, int P, float2 *w, float2 *filt) {
     std::vector<std::complex<double>> wd(L), f(M, std::complex<double>(0.0, 0.0));
     for (int n = 0; n < L; ++n) {
@@ -163,11 +156,9 @@ void chirp_tables_host(int L, int M, int N1, int N2, int P, float2 *w, float2 *f
     std::vector<std::complex<double>> root(M);
     for (int j = 0; j < M; ++j) root[j] = std::polar(1.0, -2.0 * M_PI * (double)j / (double)M);
     fft_host(ft.data(), 1, (size_t)M, f.data(), root);
-    const int TPC = N1 / 16;
     for (int k2 = 0; k2 < N2; ++k2)
         for (int r = 0; r < N1; ++r) {
-            const int j = r / TPC, tau = r % TPC;
-            const int k = k2 + N2 * digit_reverse16_host(16 * tau + j, P);
+            const int k = k2 + N2 * big_position(r, P);
             filt[(size_t)k2 * N1 + r] = make_float2((float)(f[k].real() / M), (float)(f[k].imag() / M));
         }
 }

@@ -20,6 +20,16 @@ struct Pow2Plan {
     const float2 *twN1 = nullptr;  // [N1] exp(-j 2 pi m / N1), device
 };
 
+// Order of a scratch column of N1 = 16^P entries around the big kernel (all modes, input and output): entry
+// j * (N1 / 16) + tau belongs to register j of lane tau.  In time order (input of the forward passes, output of the
+// inverse passes) that is sample t1 = entry; in frequency order (output of the forward-only mode, input of the
+// inverse-only mode, and the order of the expanded gate) the register holds bin digit_reverse16(16 tau + j), i.e. the
+// natural order for P = 2 and, for P = 3, the bin index with its two low base-16 digits exchanged.  The map is its
+// own inverse: it gives the entry of a bin and the bin of an entry.
+__host__ __device__ inline int big_position(int k1, int P) {
+    return P == 2 ? k1 : ((k1 & 0xF00) | ((k1 & 15) << 4) | ((k1 >> 4) & 15));
+}
+
 // Decomposition rule; returns false if L has no such plan.
 bool pow2_split(int L, int *N1, int *N2, int *P);
 

@@ -428,10 +428,11 @@ __global__ __launch_bounds__(256) void k_big(typename SC::elem_t *__restrict__ s
 
     typedef typename SC::elem_t elem_t;
     elem_t *col = scr + (((size_t)bhl * N2 + k2) * 32 + pg * ppw + ci) * N1;
-    const int in_off = (MODE != 2) ? tau : 16 * tau, in_step = (MODE != 2) ? TPC : 1;
+    // entry j * TPC + tau of a column <-> register j of lane tau, on the way in and on the way out, in every mode
+    // (so every access of a wave is a contiguous 512-byte run); see big_position() for the bin such an entry holds
     elem_t nx[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) nx[j] = col[in_off + in_step * j];
+    for (int j = 0; j < 16; ++j) nx[j] = col[tau + TPC * j];
     for (int c = ci; c < ppw; c += CPI) {
         float2 x[16];
 #pragma unroll
@@ -439,7 +440,7 @@ __global__ __launch_bounds__(256) void k_big(typename SC::elem_t *__restrict__ s
         if (c + CPI < ppw) {                          // next column's loads fly during this one's passes
             const elem_t *ncol = col + (size_t)CPI * N1;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) nx[j] = ncol[in_off + in_step * j];
+            for (int j = 0; j < 16; ++j) nx[j] = ncol[tau + TPC * j];
         }
         if (MODE != 2) {
             dft<16, false>(x);
@@ -462,7 +463,7 @@ __global__ __launch_bounds__(256) void k_big(typename SC::elem_t *__restrict__ s
         }
         if (MODE == 1) {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) col[16 * tau + j] = SC::put(x[j]);
+            for (int j = 0; j < 16; ++j) col[tau + TPC * j] = SC::put(x[j]);
             if (kCross) __syncthreads();              // buf_f is rewritten by the next column
         } else {
             dft<16, true>(x);

@@ -7,6 +7,7 @@
 #include "prefix.h"
 
 #include "common.h"
+#include "mix_pow2.h"
 
 namespace spectre {
 
@@ -545,91 +546,116 @@ __global__ __launch_bounds__(256) void k_set_memory(const float *__restrict__ me
     v_buf[(bh * N + m) * d + c] = mem[(src_bh * Nmem + m) * d + c];
 }
 
-__device__ __forceinline__ int digit_reverse16p(int k1, int P) {
-    return P == 2 ? (((k1 & 15) << 4) | (k1 >> 4)) : (((k1 & 15) << 8) | (k1 & 0xF0) | (k1 >> 8));
-}
+// Scratch <-> cache rows.  A scratch column (head, k2, pair) is handled in lines of 16 adjacent entries (128 bytes):
+// entry e = 16 q + c holds bin k1 = big_position(e), and the lines q < N1 / 32 are exactly the bins k = k2 + N2 k1
+// below N / 2.  The partner bin N - k lies in column (N2 - k2) mod N2 and, for k2 > 0, its 16 entries are again one
+// line (in reverse order), so a workgroup that owns one line of all 32 pairs touches whole 128-byte lines of the
+// scratch and, through an LDS tile, whole 512-byte rows (one bin, 32 pairs) of the cache.  The Nyquist bin
+// (k2 = 0, k1 = N1 / 2) is its own partner and is done by a few extra workgroups at the end of the grid.
+constexpr int kTileStride = 33;                       // float4 entries per bin row of the LDS tile
 
-// Scratch position of bin k of the complex transform of a channel pair.
-__device__ __forceinline__ size_t scratch_index(int bhl, int k, int p, int N1, int N2, int P) {
-    const int k2 = k % N2, k1 = k / N2;
-    return (((size_t)bhl * N2 + k2) * 32 + p) * N1 + digit_reverse16p(k1, P);
+__device__ __forceinline__ size_t column_base(int bhl, int k2, int p, int N1, int N2) {
+    return (((size_t)bhl * N2 + k2) * 32 + p) * N1;
 }
 
 // untangle: the complex transform Z of z = v_even + j v_odd separates into the two real
 // channels' half spectra, X_even[k] = (Z_k + conj Z_{N-k})/2, X_odd[k] = (Z_k - conj Z_{N-k})/(2j).
-// One lane per (bh, k <= N/2, pair).
-__global__ __launch_bounds__(256) void k_untangle(const float2 *__restrict__ scr, float4 *__restrict__ X,
-                                                  int N, int N1, int N2, int P, int bh0, size_t total) {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int F = N / 2 + 1;
-    // Lane order: a wave takes 8 pairs x 8 bins whose first-pass digit a differs (k1 = a N1/16 + m, a < 8 covers
-    // every bin below N/2): in the digit-reversed columns of the scratch those are 8 adjacent positions, so a wave
-    // reads 64-byte runs of 8 columns instead of 8 bytes of 64 columns; the Nyquist bins come last.
-    const int M = N1 / 16;
-    const size_t nbh = total / ((size_t)F * 32), main_total = nbh * (size_t)(N / 2) * 32;
-    int p, k, bhl;
-    if (idx < main_total) {
-        const int p_lo = (int)(idx & 7), a = (int)((idx >> 3) & 7), p_hi = (int)((idx >> 6) & 3);
-        size_t rest = idx >> 8;
-        const int m = (int)(rest % M);
-        rest /= M;
-        const int k2 = (int)(rest % N2);
-        bhl = (int)(rest / N2);
-        p = p_hi * 8 + p_lo;
-        k = k2 + N2 * (a * M + m);
-    } else {
-        const size_t j = idx - main_total;
-        p = (int)(j % 32);
-        bhl = (int)(j / 32);
-        k = N / 2;
-    }
-    const float2 zk = scr[scratch_index(bhl, k, p, N1, N2, P)];
-    const float2 zn = scr[scratch_index(bhl, (N - k) % N, p, N1, N2, P)];
+__device__ __forceinline__ float4 untangle_pair(float2 zk, float2 zn) {
     float4 o;
     o.x = 0.5f * (zk.x + zn.x);
     o.y = 0.5f * (zk.y - zn.y);
     o.z = 0.5f * (zk.y + zn.y);
     o.w = -0.5f * (zk.x - zn.x);
-    X[((size_t)(bh0 + bhl) * F + k) * 32 + p] = o;
+    return o;
+}
+
+__global__ __launch_bounds__(256) void k_untangle(const float2 *__restrict__ scr, float4 *__restrict__ X,
+                                                  int N, int N1, int N2, int P, int bh0, int nbh) {
+    __shared__ float4 tile[16 * kTileStride];
+    const int F = N / 2 + 1, lines = N1 / 32, tid = threadIdx.x;
+    const int main_blocks = nbh * N2 * lines;
+    if ((int)blockIdx.x >= main_blocks) {              // Nyquist bins: one lane per (head, pair)
+        const int idx = ((int)blockIdx.x - main_blocks) * 256 + tid;
+        if (idx >= nbh * 32) return;
+        const int p = idx & 31, bhl = idx >> 5;
+        const float2 z = scr[column_base(bhl, 0, p, N1, N2) + big_position(N1 / 2, P)];
+        X[((size_t)(bh0 + bhl) * F + N / 2) * 32 + p] = untangle_pair(z, z);
+        return;
+    }
+    const int q = blockIdx.x % lines, k2 = (blockIdx.x / lines) % N2, bhl = blockIdx.x / (lines * N2);
+    {
+        const int c = tid & 15, pl = tid >> 4, e = 16 * q + c;
+        const int k = k2 + N2 * big_position(e, P), kn = (N - k) % N;
+        const int k2n = kn % N2, en = big_position(kn / N2, P);
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+            const int p = pl + 16 * rr;
+            const float2 zk = scr[column_base(bhl, k2, p, N1, N2) + e];
+            const float2 zn = scr[column_base(bhl, k2n, p, N1, N2) + en];
+            tile[c * kTileStride + p] = untangle_pair(zk, zn);
+        }
+    }
+    __syncthreads();
+    const int p = tid & 31, c0 = tid >> 5;
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+        const int c = c0 + 8 * rr;
+        const int k = k2 + N2 * big_position(16 * q + c, P);
+        X[((size_t)(bh0 + bhl) * F + k) * 32 + p] = tile[c * kTileStride + p];
+    }
 }
 
 // tangle: the inverse of untangle with the gate applied.  Y_c[k] = g_k X_c[k] for k <= N/2
 // (real parts only at DC and Nyquist), Hermitian-extended to k > N/2; Z_k = (Y_even + j Y_odd)/N
-// goes to the scratch layout of the inverse big kernel.  One lane per (bhl, k < N, pair).
+// goes to the entry the inverse big kernel reads it from.  The lane that holds bin k < N/2 also produces bin N - k.
 __global__ __launch_bounds__(256) void k_tangle(const float4 *__restrict__ X, const float2 *__restrict__ g,
                                                 float2 *__restrict__ scr, int N, int N1, int N2, int P, int bh0,
-                                                size_t total) {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int F = N / 2 + 1;
-    // Lane order as in k_untangle: a wave takes 4 pairs x the 16 bins k1 = a N1/16 + m, a = 0..15, which are 16
-    // adjacent positions (128 bytes) of each of the 4 scratch columns it writes.
-    const int M = N1 / 16;
-    const int p_lo = (int)(idx & 3), a = (int)((idx >> 2) & 15), p_hi = (int)((idx >> 6) & 7);
-    size_t rest = idx >> 9;
-    const int m = (int)(rest % M);
-    rest /= M;
-    const int k2 = (int)(rest % N2);
-    const int bhl = (int)(rest / N2);
-    const int p = p_hi * 4 + p_lo;
-    const int k = k2 + N2 * (a * M + m);
-    const size_t bh = (size_t)(bh0 + bhl);
-    const bool upper = 2 * k > N;
-    const int ks = upper ? N - k : k;
-    const float4 x = X[(bh * F + ks) * 32 + p];
-    const float2 gk = g[bh * F + ks];
-    float2 ya = cmul(gk, make_float2(x.x, x.y)), yb = cmul(gk, make_float2(x.z, x.w));
-    if (k == 0 || 2 * k == N) {
-        ya.y = 0.f;
-        yb.y = 0.f;
-    }
-    if (upper) {
-        ya.y = -ya.y;
-        yb.y = -yb.y;
-    }
+                                                int nbh) {
+    __shared__ float4 tile[16 * kTileStride];
+    const int F = N / 2 + 1, lines = N1 / 32, tid = threadIdx.x;
     const float s = 1.0f / (float)N;
-    scr[scratch_index(bhl, k, p, N1, N2, P)] = make_float2((ya.x - yb.y) * s, (ya.y + yb.x) * s);
+    const int main_blocks = nbh * N2 * lines;
+    if ((int)blockIdx.x >= main_blocks) {              // Nyquist bins
+        const int idx = ((int)blockIdx.x - main_blocks) * 256 + tid;
+        if (idx >= nbh * 32) return;
+        const int p = idx & 31, bhl = idx >> 5;
+        const size_t bh = (size_t)(bh0 + bhl);
+        const float4 x = X[(bh * F + N / 2) * 32 + p];
+        const float2 gk = g[bh * F + N / 2];
+        const float2 ya = cmul(gk, make_float2(x.x, x.y)), yb = cmul(gk, make_float2(x.z, x.w));
+        scr[column_base(bhl, 0, p, N1, N2) + big_position(N1 / 2, P)] = make_float2(ya.x * s, yb.x * s);
+        return;
+    }
+    const int q = blockIdx.x % lines, k2 = (blockIdx.x / lines) % N2, bhl = blockIdx.x / (lines * N2);
+    const size_t bh = (size_t)(bh0 + bhl);
+    {
+        const int p = tid & 31, c0 = tid >> 5;
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+            const int c = c0 + 8 * rr;
+            const int k = k2 + N2 * big_position(16 * q + c, P);
+            const float4 x = X[(bh * F + k) * 32 + p];
+            const float2 gk = g[bh * F + k];
+            float2 ya = cmul(gk, make_float2(x.x, x.y)), yb = cmul(gk, make_float2(x.z, x.w));
+            if (k == 0) {
+                ya.y = 0.f;
+                yb.y = 0.f;
+            }
+            // Z_k = Y_even[k] + j Y_odd[k];  Z_{N-k} = conj(Y_even[k]) + j conj(Y_odd[k])
+            tile[c * kTileStride + p] = make_float4((ya.x - yb.y) * s, (ya.y + yb.x) * s, (ya.x + yb.y) * s, (yb.x - ya.y) * s);
+        }
+    }
+    __syncthreads();
+    const int c = tid & 15, pl = tid >> 4, e = 16 * q + c;
+    const int k = k2 + N2 * big_position(e, P), kn = (N - k) % N;
+    const int k2n = kn % N2, en = big_position(kn / N2, P);
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+        const int p = pl + 16 * rr;
+        const float4 v = tile[c * kTileStride + p];
+        scr[column_base(bhl, k2, p, N1, N2) + e] = make_float2(v.x, v.y);
+        if (kn != k) scr[column_base(bhl, k2n, p, N1, N2) + en] = make_float2(v.z, v.w);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -739,19 +765,20 @@ hipError_t launch_ring_append(int io, const void *V, const void *Q, float *v_buf
     return hipGetLastError();
 }
 
+static unsigned tangle_blocks(int N1, int N2, int nbh) { return (unsigned)(nbh * N2 * (N1 / 32) + (nbh * 32 + 255) / 256); }
+
 hipError_t launch_untangle(const float2 *scr, float2 *X, int N, int N1, int N2, int P, int bh0, int nbh,
                            hipStream_t st) {
-    const size_t total = (size_t)nbh * (N / 2 + 1) * 32;
-    k_untangle<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(scr, reinterpret_cast<float4 *>(X), N, N1, N2, P,
-                                                                bh0, total);
+    if ((long long)nbh * N2 * (N1 / 32) > 0x7ffffff0LL) return hipErrorInvalidValue;
+    k_untangle<<<tangle_blocks(N1, N2, nbh), 256, 0, st>>>(scr, reinterpret_cast<float4 *>(X), N, N1, N2, P, bh0, nbh);
     return hipGetLastError();
 }
 
 hipError_t launch_tangle(const float2 *X, const float2 *g, float2 *scr, int N, int N1, int N2, int P, int bh0,
                          int nbh, hipStream_t st) {
-    const size_t total = (size_t)nbh * N * 32;
-    k_tangle<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(reinterpret_cast<const float4 *>(X), g, scr, N, N1,
-                                                              N2, P, bh0, total);
+    if ((long long)nbh * N2 * (N1 / 32) > 0x7ffffff0LL) return hipErrorInvalidValue;
+    k_tangle<<<tangle_blocks(N1, N2, nbh), 256, 0, st>>>(reinterpret_cast<const float4 *>(X), g, scr, N, N1, N2, P, bh0,
+                                                         nbh);
     return hipGetLastError();
 }
 
