@@ -23,11 +23,15 @@
 
 namespace spectre {
 
-// LDS row strides (in pair_t units) of the [t2][t1_local][pair] staging tile, chosen so
-// that a wave reading along t1_local with 16 lanes per pair index hits every bank equally.
-template <typename IO> struct TileStride;
-template <> struct TileStride<IoBf16> { static constexpr int value = 36; };
-template <> struct TileStride<IoF32> { static constexpr int value = 34; };
+// Shape of the row kernels' tile: TT = 16 adjacent t1 (128-byte runs in the scratch) times kPairs channel pairs, one
+// 128-byte segment of every row: a whole bf16 head row, or one half of an fp32 head row (its two halves go to two
+// workgroups, so that rows with 8-byte pairs keep whole 128-byte lines on both sides of the kernel).
+// kStride: LDS row stride (in pair_t units) of the [t2][t1_local][pair] staging tile, chosen so that a wave reading
+// along t1_local with 16 lanes per pair index hits every bank equally.
+template <typename IO> struct RowTile;
+template <> struct RowTile<IoBf16> { static constexpr int kPairs = 32, kStride = 36; };
+template <> struct RowTile<IoF32> { static constexpr int kPairs = 16, kStride = 18; };
+template <typename IO> struct TileStride { static constexpr int value = RowTile<IO>::kStride; };
 
 // ------------------------------------------------------------------------------------------
 // Element of the transform scratch: one complex number per channel pair, as two fp32 (the default) or, on request
@@ -89,32 +93,32 @@ struct SmallTwiddles {
     }
 };
 
-// small_fwd: grid (N1/TT, nbh); block 32*TT threads.  Reads the N2*TT rows
-// {t1_0 + r + N1*t2} of one head (32 pairs each, one 128 B / 256 B segment per row),
+// small_fwd: grid (N1/TT * 32/PW, nbh); block PW*TT threads, PW = RowTile<IO>::kPairs.  Reads the N2*TT rows
+// {t1_0 + r + N1*t2} of one head (PW pairs each, one 128-byte segment per row),
 // stages them in LDS, then lane (pair p, t1_local) runs the N2-point DFT over t2.
 // ring != nullptr (pre-fill of an empty Prefix-FFT cache): every row read is also copied, as fp32, to row l of head bh
 // of the value ring buffer ring [B*H][N1 * N2][32 pairs] - the rows then cross HBM once for both purposes.
 template <int N2, int TT, typename IO, typename SC>
-__global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t *__restrict__ v,
+__global__ __launch_bounds__(RowTile<IO>::kPairs * TT) void k_small_fwd(const typename IO::pair_t *__restrict__ v,
                                                        typename SC::elem_t *__restrict__ scr,
                                                        const float2 *__restrict__ twL, int rows, int H,
                                                        int N1, int bh0, int aff, float2 *__restrict__ ring) {
     typedef typename IO::pair_t pair_t;
-    constexpr int S = TileStride<IO>::value;
+    constexpr int S = TileStride<IO>::value, PW = RowTile<IO>::kPairs, NPART = 32 / PW;
     extern __shared__ unsigned char smem_raw[];
     pair_t *lds = reinterpret_cast<pair_t *>(smem_raw);
     const int tid = threadIdx.x;
     int tile = blockIdx.x, bhl = blockIdx.y;
-    if (aff) head_affine(blockIdx.x, N1 / TT, aff, false, &bhl, &tile);
-    const int t1_0 = tile * TT;
+    if (aff) head_affine(blockIdx.x, N1 / TT * NPART, aff, false, &bhl, &tile);
+    const int t1_0 = (tile / NPART) * TT, p0 = (tile % NPART) * PW;
     const int bh = bh0 + bhl, b = bh / H, h = bh % H;
     {
-        const int lp = tid & 31, r = tid >> 5;
+        const int lp = tid % PW, r = tid / PW;
         pair_t val[N2];
 #pragma unroll
         for (int t2 = 0; t2 < N2; ++t2) {
             const int l = t1_0 + r + N1 * t2;
-            val[t2] = (l < rows) ? IO::load_stream(v + (((size_t)b * rows + l) * H + h) * 32 + lp) : IO::zero();
+            val[t2] = (l < rows) ? IO::load_stream(v + (((size_t)b * rows + l) * H + h) * 32 + p0 + lp) : IO::zero();
         }
 #pragma unroll
         for (int t2 = 0; t2 < N2; ++t2) lds[(t2 * TT + r) * S + lp] = val[t2];
@@ -122,7 +126,7 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
 #pragma unroll
             for (int t2 = 0; t2 < N2; ++t2) {
                 const int l = t1_0 + r + N1 * t2;
-                if (l < rows) stream_store(ring + ((size_t)bh * N1 * N2 + l) * 32 + lp, IO::unpack(val[t2]));
+                if (l < rows) stream_store(ring + ((size_t)bh * N1 * N2 + l) * 32 + p0 + lp, IO::unpack(val[t2]));
             }
         }
     }
@@ -132,7 +136,7 @@ __global__ __launch_bounds__(32 * TT) void k_small_fwd(const typename IO::pair_t
 #pragma unroll
     for (int t2 = 0; t2 < N2; ++t2) x[t2] = IO::unpack(lds[(t2 * TT + tl) * S + p]);
     small_dft<N2, false>(x);
-    typename SC::elem_t *dst = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
+    typename SC::elem_t *dst = scr + (((size_t)bhl * N2) * 32 + p0 + p) * N1 + t1;
     const SmallTwiddles<N2> tw(twL, t1);
 #pragma unroll
     for (int k2 = 0; k2 < N2; ++k2) {
@@ -238,23 +242,23 @@ __global__ __launch_bounds__(512) void k_small_fwd_proj(const uint32_t *__restri
 // it writes for every t2, taken over the values as stored (after rounding to the I/O type), to
 // bsum [bh][L / TT][32 pairs]; block l / TT covers rows l .. l + TT - 1.  Added in row order.
 template <int N2, int TT, typename IO, typename SC>
-__global__ __launch_bounds__(32 * TT) void k_small_inv(const typename SC::elem_t *__restrict__ scr,
+__global__ __launch_bounds__(RowTile<IO>::kPairs * TT) void k_small_inv(const typename SC::elem_t *__restrict__ scr,
                                                        typename IO::pair_t *__restrict__ out,
                                                        const float2 *__restrict__ twL, int row0,
                                                        int out_rows, int H, int N1, int bh0, int ring0,
                                                        int ring_w, int newest, int aff, float2 *__restrict__ bsum) {
     typedef typename IO::pair_t pair_t;
-    constexpr int S = TileStride<IO>::value;
+    constexpr int S = TileStride<IO>::value, PW = RowTile<IO>::kPairs, NPART = 32 / PW;
     extern __shared__ unsigned char smem_raw[];
     pair_t *lds = reinterpret_cast<pair_t *>(smem_raw);
     const int tid = threadIdx.x;
     int tile = blockIdx.x, bhl = blockIdx.y;
-    if (aff) head_affine(blockIdx.x, N1 / TT, aff, false, &bhl, &tile);
-    const int t1_0 = tile * TT;
+    if (aff) head_affine(blockIdx.x, N1 / TT * NPART, aff, false, &bhl, &tile);
+    const int t1_0 = (tile / NPART) * TT, p0 = (tile % NPART) * PW;
     const int bh = bh0 + bhl, b = bh / H, h = bh % H;
     {
         const int tl = tid % TT, p = tid / TT, t1 = t1_0 + tl;
-        const typename SC::elem_t *src = scr + (((size_t)bhl * N2) * 32 + p) * N1 + t1;
+        const typename SC::elem_t *src = scr + (((size_t)bhl * N2) * 32 + p0 + p) * N1 + t1;
         typename SC::elem_t raw[N2];
 #pragma unroll
         for (int k2 = 0; k2 < N2; ++k2) raw[k2] = src[(size_t)k2 * 32 * N1];
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const typename SC::elem_t
         for (int t2 = 0; t2 < N2; ++t2) lds[(t2 * TT + tl) * S + p] = IO::pack(y[t2]);
     }
     __syncthreads();
-    const int lp = tid & 31, r = tid >> 5;
+    const int lp = tid % PW, r = tid / PW;
 #pragma unroll
     for (int t2 = 0; t2 < N2; ++t2) {
         const int l = t1_0 + r + N1 * t2;
@@ -280,14 +284,14 @@ __global__ __launch_bounds__(32 * TT) void k_small_inv(const typename SC::elem_t
             orow = (l >= ring0) ? out_rows - 1 - age : -1;
         }
         if (orow >= 0 && orow < out_rows)
-            IO::store_stream(out + (((size_t)b * out_rows + orow) * H + h) * 32 + lp, lds[(t2 * TT + r) * S + lp]);
+            IO::store_stream(out + (((size_t)b * out_rows + orow) * H + h) * 32 + p0 + lp, lds[(t2 * TT + r) * S + lp]);
     }
     if (bsum) {                                        // lane (lp, r) sums the TT rows of t2 = r, r + TT, ...
         for (int t2 = r; t2 < N2; t2 += TT) {
             float2 acc = make_float2(0.f, 0.f);
 #pragma unroll
             for (int i = 0; i < TT; ++i) acc = acc + IO::unpack(lds[(t2 * TT + i) * S + lp]);
-            bsum[((size_t)bh * (N1 / TT) * N2 + (t1_0 / TT + (N1 / TT) * t2)) * 32 + lp] = acc;
+            bsum[((size_t)bh * (N1 / TT) * N2 + (t1_0 / TT + (N1 / TT) * t2)) * 32 + p0 + lp] = acc;
         }
     }
 }
@@ -666,8 +670,10 @@ static hipError_t small_fwd_t(const Pow2Plan &pl, const void *v, void *scr_v, in
     typename SC::elem_t *scr = static_cast<typename SC::elem_t *>(scr_v);
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
-    const dim3 grid = aff ? dim3(pl.N1 / TT * nbh) : dim3(pl.N1 / TT, nbh);
-    kern<<<grid, dim3(32 * TT), lds, st>>>(
+    constexpr int PW = RowTile<IO>::kPairs;
+    const int tiles = pl.N1 / TT * (32 / PW);
+    const dim3 grid = aff ? dim3(tiles * nbh) : dim3(tiles, nbh);
+    kern<<<grid, dim3(PW * TT), lds, st>>>(
         static_cast<const typename IO::pair_t *>(v), scr, pl.twL, rows, H, pl.N1, bh0, aff, ring);
     return hipGetLastError();
 }
@@ -681,8 +687,10 @@ static hipError_t small_inv_t(const Pow2Plan &pl, const void *scr_v, void *out, 
     const typename SC::elem_t *scr = static_cast<const typename SC::elem_t *>(scr_v);
     hipError_t e = allow_lds(kern, lds);
     if (e != hipSuccess) return e;
-    const dim3 grid = aff ? dim3(pl.N1 / TT * nbh) : dim3(pl.N1 / TT, nbh);
-    kern<<<grid, dim3(32 * TT), lds, st>>>(
+    constexpr int PW = RowTile<IO>::kPairs;
+    const int tiles = pl.N1 / TT * (32 / PW);
+    const dim3 grid = aff ? dim3(tiles * nbh) : dim3(tiles, nbh);
+    kern<<<grid, dim3(PW * TT), lds, st>>>(
         scr, static_cast<typename IO::pair_t *>(out), pl.twL, row0, out_rows, H, pl.N1, bh0, ring0, ring_w, newest, aff,
         bsum);
     return hipGetLastError();
@@ -690,7 +698,7 @@ static hipError_t small_inv_t(const Pow2Plan &pl, const void *scr_v, void *out, 
 
 #define SPECTRE_N2_CASE(FN, N, ...) \
     case N: return io ? (scr16 ? FN<N, 16, IoBf16, ScrBf16>(__VA_ARGS__) : FN<N, 16, IoBf16, ScrF32>(__VA_ARGS__)) \
-                      : FN<N, 8, IoF32, ScrF32>(__VA_ARGS__);
+                      : FN<N, 16, IoF32, ScrF32>(__VA_ARGS__);
 #define SPECTRE_DISPATCH_N2(FN, ...)                                         \
     switch (pl.N2) {                                                         \
         SPECTRE_N2_CASE(FN, 1, __VA_ARGS__) SPECTRE_N2_CASE(FN, 2, __VA_ARGS__) SPECTRE_N2_CASE(FN, 3, __VA_ARGS__)    \
@@ -733,7 +741,7 @@ hipError_t launch_small_fwd_proj(const Pow2Plan &pl, const void *x, const void *
     SPECTRE_DISPATCH_N2(small_fwd_proj_t, pl, x, wpack, Hw, scratch, rows, H, bh0, nbh, st, aff)
 }
 
-int small_tile_rows(int io) { return io ? 16 : 8; }
+int small_tile_rows(int io) { (void)io; return 16; }
 
 hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, void *out, int row0,
                             int out_rows, int H, int bh0, int nbh, hipStream_t st, int ring0, int ring_w,
