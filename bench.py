@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline line, print one JSON line per configuration (mixer only): the "
                          "length sweep at the Llama head shape, config 1 and the ViT shape")
+    ap.add_argument("--only", default="",
+                    help="with --sweep: only the configurations whose name contains this text (e.g. L8192), so that a "
+                         "profiler run covers one shape")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference for scaling hardware byte counters)")
     return ap.parse_args()
@@ -188,6 +191,18 @@ def mix_case(name, c, steps, graph=False):
     return row
 
 
+def copy_calibration():
+    """A plain 1 GiB device-to-device copy, five times: what a hardware byte counter reads for a known size."""
+    import torch
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written per copy
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+    torch.cuda.empty_cache()
+
+
 def config_cases():
     """Every mixer configuration the baseline names: config 1, config 2 (= the 8192 point of the sweep), the length
     sweep of config 3 and the ViT shape of config 5."""
@@ -209,7 +224,11 @@ def sweep(args):
     cases += [("vit_197_cls", dict(B=256, H=12, L=197, d=64, io="f32"))]
     cases += [(f"llama1b_L{L}", dict(B=1, H=32, L=L, d=64, io="bf16")) for L in (1000, 50000)]
     for name, c in cases:
-        print(json.dumps(mix_case(name, c, args.steps, graph=True)), flush=True)
+        if args.only and args.only not in name:
+            continue
+        print(json.dumps(mix_case(name, c, args.steps, graph=not args.only)), flush=True)
+    if args.copy_calib:
+        copy_calibration()
 
 
 def main():
@@ -376,13 +395,7 @@ def main():
     torch.cuda.empty_cache()
 
     if args.copy_calib:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written per copy
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-        torch.cuda.empty_cache()
+        copy_calibration()
 
     if not args.no_decode:
         dc = synth.CONFIGS["decode_32k"]

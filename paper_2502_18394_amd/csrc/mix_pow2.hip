@@ -642,6 +642,32 @@ __global__ __launch_bounds__(256) void k_gate_expand(const float2 *__restrict__ 
     for (int k2 = 0; k2 < N2; ++k2) dst[(size_t)k2 * N1] = src[k2];
 }
 
+// The same expansion for N1 = 256, where entry r of a plane is bin k1 = r: a workgroup takes 32 consecutive k1 of one
+// head, i.e. 32 N2 consecutive bins, and writes 256-byte runs into each of the N2 planes.  Eight workgroups per head
+// instead of one: at 32 heads the one-workgroup-per-head form kept 32 compute units busy for 8 us with a chain of
+// dependent loads and stores (a ninth of the whole call at L = 8192).
+__global__ __launch_bounds__(256) void k_gate_expand256(const float2 *__restrict__ g, float2 *__restrict__ gp, int L,
+                                                        int N2) {
+    __shared__ float2 tile[32 * 33];
+    const int tid = threadIdx.x, bh = blockIdx.y, F = L / 2 + 1, S = N2 + 1;
+    const int k1_0 = blockIdx.x * 32, k0 = k1_0 * N2;
+    const float scale = 1.0f / (float)L;
+    const float2 *gh = g + (size_t)bh * F;
+    for (int m = tid; m < 32 * N2; m += 256) {
+        const int k = k0 + m;
+        float2 val = gh[2 * k <= L ? k : L - k];
+        if (2 * k > L) val.y = -val.y;
+        if (k == 0 || 2 * k == L) val.y = 0.0f;
+        tile[(m / N2) * S + m % N2] = make_float2(val.x * scale, val.y * scale);
+    }
+    __syncthreads();
+    float2 *dst = gp + (size_t)bh * L + k1_0;
+    for (int i = tid; i < 32 * N2; i += 256) {
+        const int q = i & 31, k2 = i >> 5;
+        dst[(size_t)k2 * 256 + q] = tile[q * S + k2];
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 bool pow2_split(int L, int *N1, int *N2, int *P) {
     if (L < 256 || L > 131072) return false;
@@ -836,8 +862,11 @@ hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, i
     for (int bh0 = 0; bh0 < BH; bh0 += 65535) {         // grid.y limit
         const int n = (BH - bh0 < 65535) ? BH - bh0 : 65535;
         const int F = pl.L / 2 + 1;
-        k_gate_expand<<<dim3(pl.N1 / 256, n), dim3(256), lds, st>>>(g + (size_t)bh0 * F, gp + (size_t)bh0 * pl.L,
-                                                                    pl.L, pl.N1, pl.N2, pl.P);
+        if (pl.P == 2)
+            k_gate_expand256<<<dim3(8, n), dim3(256), 0, st>>>(g + (size_t)bh0 * F, gp + (size_t)bh0 * pl.L, pl.L, pl.N2);
+        else
+            k_gate_expand<<<dim3(pl.N1 / 256, n), dim3(256), lds, st>>>(g + (size_t)bh0 * F, gp + (size_t)bh0 * pl.L,
+                                                                        pl.L, pl.N1, pl.N2, pl.P);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -141,6 +141,20 @@ def test_decode_config_sampled_heads(oracle, defer):
                 print(f"  step {i} (b,h)=({b},{h}): out {e_out:.3e} spec {e_spec:.3e} sum_q {e_sum:.3e}", flush=True)
                 assert e_out <= 1e-5 and e_spec <= 1e-5 and e_sum <= 1e-12
     assert cache.t == N + steps
+    if defer == 0:
+        # the full-window readout at this size (all 32768 live rows, positional phase t): rows of the sampled heads
+        gw = binding.gate(cache.sum_q, P, 1.0 / N, pooled=True, phase_pos=cache.t)
+        win = cache.readout(gw, binding.READ_WINDOW)
+        torch.cuda.synchronize()
+        assert tuple(win.shape) == (B, N, H, d)
+        for (b, h), oc in zip(sample, ocs):
+            sub = {k: (np.asarray(v[h:h + 1], np.float64) if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+            want = oc.readout_window(oracle.gate(oc.sum_q, 1.0 / N, sub, N, oc.t))
+            got = win[b, :, h].cpu().numpy()
+            e_win = rel_l2(got, want[0, :, 0])
+            print(f"  window (b,h)=({b},{h}): {e_win:.3e}", flush=True)
+            assert e_win <= 1e-5
+            assert_close_elementwise(got, want[0, :, 0], "f32", N)
 
 
 def test_wavelet_refinement_at_the_headline_shape(oracle):
