@@ -563,7 +563,7 @@ static int mix_four_step(const Pow2Plan &pl, const void *v, const float2 *g, voi
             if (e != hipSuccess) { what = "wait for the gate expansion"; break; }
             side_has_gate = true;
         }
-        e = launch_big(pl, scr, gp, bh0, nbh, 0, ls, false, scr16, affine);
+        e = launch_big(pl, scr, gp, bh0, nbh, 0, ls, false, scr16, affine, side != nullptr);
         if (e != hipSuccess) { what = "big"; break; }
         e = launch_small_inv(pl, (int)io, scr, out, 0, L, H, bh0, nbh, ls, 0, 0, 0, scr16, affine, bsum);
         if (e != hipSuccess) { what = "small_inv"; break; }

@@ -51,8 +51,10 @@ bool pow2_split(int L, int *N1, int *N2, int *P);
 hipError_t launch_small_fwd(const Pow2Plan &pl, int io, const void *v, float2 *scratch, int rows, int H,
                             int bh0, int nbh, hipStream_t st, bool scr16 = false, bool affine = false,
                             float2 *ring = nullptr);
+// wide (mode 0, 4096-point columns, fp32 scratch): 8 instead of 4 columns per workgroup, for calls on two streams.
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
-                      hipStream_t st, bool shared_gate = false, bool scr16 = false, bool affine = false);
+                      hipStream_t st, bool shared_gate = false, bool scr16 = false, bool affine = false,
+                      bool wide = false);
 // bsum (whole transforms only): sums of the blocks of small_tile_rows(io) adjacent output rows, over the values as
 // stored, to bsum [B*H][L / small_tile_rows][32 pairs] - what the wavelet refinement's coarse levels need.
 int small_tile_rows(int io);

@@ -782,10 +782,14 @@ hipError_t launch_small_inv(const Pow2Plan &pl, int io, const float2 *scratch, v
 
 template <int P, int MODE, typename SC = ScrF32, bool SHFL = false>
 static hipError_t big_t(const Pow2Plan &pl, float2 *scr_v, const float2 *gp, int bh0, int nbh, bool shared_gate,
-                        hipStream_t st, int aff = 0) {
+                        hipStream_t st, int aff = 0, bool wide = false) {
     constexpr int N1 = 1 << (4 * P), TPC = N1 / 16, CPI = 256 / TPC, COLW = N1 + N1 / 16;
     const size_t lds = (size_t)CPI * COLW * sizeof(float2);
-    const int ppw = (P == 2) ? 16 : 4;   // pairs per workgroup; a multiple of CPI dividing 32
+    // pairs per workgroup; a multiple of CPI dividing 32.  `wide` (a call whose head groups alternate between two
+    // streams): 8 columns per workgroup, so that a group's column kernel is fewer workgroups than the chip has room for
+    // and the other stream's row kernels run beside it from its first to its last workgroup (-1.5 % at L = 131072; on
+    // one stream the longer workgroups cost 2 %)
+    const int ppw = (P == 2) ? 16 : (wide ? 8 : 4);
     auto kern = k_big<P, MODE, SC, SHFL>;
     typename SC::elem_t *scr = reinterpret_cast<typename SC::elem_t *>(scr_v);
     hipError_t e = allow_lds(kern, lds);
@@ -798,7 +802,7 @@ static hipError_t big_t(const Pow2Plan &pl, float2 *scr_v, const float2 *gp, int
 }
 
 hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int bh0, int nbh, int mode,
-                      hipStream_t st, bool shared_gate, bool scr16, bool affine) {
+                      hipStream_t st, bool shared_gate, bool scr16, bool affine, bool wide) {
     const bool shfl = option(SPECTRE_OPT_LANE_SHUFFLES) != 0 && mode == 0 && !scr16;
     if (affine) {                                      // the mixer's forward-gate-inverse pass, fp32 scratch
         if (mode != 0 || scr16 || nbh % 8 != 0) return hipErrorInvalidValue;
@@ -824,7 +828,7 @@ hipError_t launch_big(const Pow2Plan &pl, float2 *scratch, const float2 *gp, int
         if (mode == 1) return big_t<2, 1>(pl, scratch, gp, bh0, nbh, shared_gate, st);
         if (mode == 2) return big_t<2, 2>(pl, scratch, gp, bh0, nbh, shared_gate, st);
     } else if (pl.P == 3) {
-        if (mode == 0) return big_t<3, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st);
+        if (mode == 0) return big_t<3, 0>(pl, scratch, gp, bh0, nbh, shared_gate, st, 0, wide);
         if (mode == 1) return big_t<3, 1>(pl, scratch, gp, bh0, nbh, shared_gate, st);
         if (mode == 2) return big_t<3, 2>(pl, scratch, gp, bh0, nbh, shared_gate, st);
     }
