@@ -30,6 +30,23 @@ __host__ __device__ inline int big_position(int k1, int P) {
     return P == 2 ? k1 : ((k1 & 0xF00) | ((k1 & 15) << 4) | ((k1 >> 4) & 15));
 }
 
+// Where a bin of the N-point pair spectrum (N = N1 * N2) and its Hermitian partner live in the scratch: entry `e` of
+// column k2 holds bin k = k2 + N2 * big_position(e); the partner bin kn = (N - k) mod N is entry `en` of column k2n.
+// For the 16 entries of a 128-byte line (e = 16 q + c, q < N1 / 32) all k lie below N / 2, and for k2 > 0 the 16
+// partners are again one whole line, in reverse order.  Used by the kernels that turn the pair spectrum into the two
+// channels' half spectra and back, and checked on the host (every bin of every column exactly once).
+struct SpectrumPair {
+    int k, kn, k2n, en;
+};
+__host__ __device__ inline SpectrumPair spectrum_pair(int N, int N2, int P, int k2, int e) {
+    SpectrumPair s;
+    s.k = k2 + N2 * big_position(e, P);
+    s.kn = (N - s.k) % N;
+    s.k2n = s.kn % N2;
+    s.en = big_position(s.kn / N2, P);
+    return s;
+}
+
 // Decomposition rule; returns false if L has no such plan.
 bool pow2_split(int L, int *N1, int *N2, int *P);
 

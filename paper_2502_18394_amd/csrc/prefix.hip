@@ -585,13 +585,12 @@ __global__ __launch_bounds__(256) void k_untangle(const float2 *__restrict__ scr
     const int q = blockIdx.x % lines, k2 = (blockIdx.x / lines) % N2, bhl = blockIdx.x / (lines * N2);
     {
         const int c = tid & 15, pl = tid >> 4, e = 16 * q + c;
-        const int k = k2 + N2 * big_position(e, P), kn = (N - k) % N;
-        const int k2n = kn % N2, en = big_position(kn / N2, P);
+        const SpectrumPair sp = spectrum_pair(N, N2, P, k2, e);
 #pragma unroll
         for (int rr = 0; rr < 2; ++rr) {
             const int p = pl + 16 * rr;
             const float2 zk = scr[column_base(bhl, k2, p, N1, N2) + e];
-            const float2 zn = scr[column_base(bhl, k2n, p, N1, N2) + en];
+            const float2 zn = scr[column_base(bhl, sp.k2n, p, N1, N2) + sp.en];
             tile[c * kTileStride + p] = untangle_pair(zk, zn);
         }
     }
@@ -647,14 +646,13 @@ __global__ __launch_bounds__(256) void k_tangle(const float4 *__restrict__ X, co
     }
     __syncthreads();
     const int c = tid & 15, pl = tid >> 4, e = 16 * q + c;
-    const int k = k2 + N2 * big_position(e, P), kn = (N - k) % N;
-    const int k2n = kn % N2, en = big_position(kn / N2, P);
+    const SpectrumPair sp = spectrum_pair(N, N2, P, k2, e);
 #pragma unroll
     for (int rr = 0; rr < 2; ++rr) {
         const int p = pl + 16 * rr;
         const float4 v = tile[c * kTileStride + p];
         scr[column_base(bhl, k2, p, N1, N2) + e] = make_float2(v.x, v.y);
-        if (kn != k) scr[column_base(bhl, k2n, p, N1, N2) + en] = make_float2(v.z, v.w);
+        if (sp.kn != sp.k) scr[column_base(bhl, sp.k2n, p, N1, N2) + sp.en] = make_float2(v.z, v.w);
     }
 }
 
