@@ -598,54 +598,15 @@ __global__ __launch_bounds__(512) void k_fused(const typename IO::pair_t *__rest
 }
 
 // ------------------------------------------------------------------------------------------
-// gate_expand: g [BH][L/2+1] -> gp [BH][N2][N1] with gp[bh][k2][j*TPC + tau] = ext(g)[k2 + N2*k1] / L,
-// k1 = digit_reverse16(16*tau + j) (the bin a lane of the big kernel holds in register j after the
-// forward passes) and ext = Hermitian extension with real DC and Nyquist bins.
+// gate_expand: g [BH][L/2+1] -> gp [BH][N2][N1] with gp[bh][k2][r] = ext(g)[k2 + N2 * big_position(r)] / L: entry
+// r = j * N1/16 + tau of plane k2 is the bin that register j of lane tau of the big kernel holds after the forward
+// passes, and ext = Hermitian extension with real DC and Nyquist bins.  Consecutive bins run over k2 first, so a
+// workgroup loads runs of N2 consecutive bins and turns them in LDS into runs of consecutive entries of each plane.
 //
-// A block of 256*N2 consecutive bins k = k0 + q*N2 + k2 (q < 256) is exactly what 256 consecutive
-// entries r of every one of the N2 planes need: for N1 = 4096, r = 256 j + 16 b + a reads
-// q = 16 a + b (k0 = 256 N2 j); for N1 = 256 the order is the same on both sides (r = q).  One
-// workgroup per block loads the bins in order, turns them in LDS and stores whole 2 KB runs.
-// LDS strides keep the 16 x 2 lanes of a half wave on distinct banks for N2 = 32.
-__global__ __launch_bounds__(256) void k_gate_expand(const float2 *__restrict__ g, float2 *__restrict__ gp,
-                                                     int L, int N1, int N2, int P) {
-    extern __shared__ float2 lds_ge[];
-    const int tid = threadIdx.x, bh = blockIdx.y, F = L / 2 + 1;
-    const int k0 = blockIdx.x * 256 * N2;
-    const int SB = (P == 3) ? N2 + 16 : N2 + 1, SA = (P == 3) ? 16 * SB + 1 : 16 * SB;
-    const float scale = 1.0f / (float)L;
-    const float2 *gh = g + (size_t)bh * F;
-    for (int m0 = tid; m0 < 256 * N2; m0 += 256 * 8) {   // eight independent loads in flight per lane
-        float2 raw[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int m = m0 + 256 * u, k = k0 + m;
-            raw[u] = (m < 256 * N2) ? gh[2 * k <= L ? k : L - k] : make_float2(0.f, 0.f);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int m = m0 + 256 * u, k = k0 + m;
-            if (m < 256 * N2) {
-                float2 val = raw[u];
-                if (2 * k > L) val.y = -val.y;
-                if (k == 0 || 2 * k == L) val.y = 0.0f;
-                const int q = m / N2, k2 = m % N2;
-                lds_ge[(q >> 4) * SA + (q & 15) * SB + k2] = make_float2(val.x * scale, val.y * scale);
-            }
-        }
-    }
-    __syncthreads();
-    const int q = (P == 3) ? (((tid & 15) << 4) | (tid >> 4)) : tid;
-    const float2 *src = lds_ge + (q >> 4) * SA + (q & 15) * SB;
-    float2 *dst = gp + (size_t)bh * L + blockIdx.x * 256 + tid;
-#pragma unroll 8
-    for (int k2 = 0; k2 < N2; ++k2) dst[(size_t)k2 * N1] = src[k2];
-}
-
-// The same expansion for N1 = 256, where entry r of a plane is bin k1 = r: a workgroup takes 32 consecutive k1 of one
-// head, i.e. 32 N2 consecutive bins, and writes 256-byte runs into each of the N2 planes.  Eight workgroups per head
-// instead of one: at 32 heads the one-workgroup-per-head form kept 32 compute units busy for 8 us with a chain of
-// dependent loads and stores (a ninth of the whole call at L = 8192).
+// N1 = 256, where entry r of a plane is bin k1 = r: a workgroup takes 32 consecutive k1 of one
+// head, i.e. 32 N2 consecutive bins, and writes 256-byte runs into each of the N2 planes.  Eight workgroups per head:
+// one workgroup per head kept 32 compute units busy for 8 us with a chain of dependent loads and stores (a ninth
+// of the whole call at L = 8192).
 __global__ __launch_bounds__(256) void k_gate_expand256(const float2 *__restrict__ g, float2 *__restrict__ gp, int L,
                                                         int N2) {
     __shared__ float2 tile[32 * 33];
@@ -665,6 +626,33 @@ __global__ __launch_bounds__(256) void k_gate_expand256(const float2 *__restrict
     for (int i = tid; i < 32 * N2; i += 256) {
         const int q = i & 31, k2 = i >> 5;
         dst[(size_t)k2 * 256 + q] = tile[q * S + k2];
+    }
+}
+
+// N1 = 4096, one workgroup per (head, j, b): entries 256 j + 16 b + a, a = 0..15, of every plane are the bins
+// k1 = 256 j + 16 a + b, i.e. 16 chunks of N2 consecutive bins, 16 N2 bins apart.  8192 small workgroups at 32 heads
+// (two loads and two stores per lane); 512 workgroups that each walked 8192 bins in four dependent rounds took 18 us
+// alone, and the expansion sits in front of the first column kernel of a call.
+__global__ __launch_bounds__(256) void k_gate_expand4096(const float2 *__restrict__ g, float2 *__restrict__ gp, int L,
+                                                         int N2) {
+    __shared__ float2 tile[16 * 33];
+    const int tid = threadIdx.x, bh = blockIdx.y, F = L / 2 + 1, S = N2 + 1;
+    const int j = blockIdx.x >> 4, b = blockIdx.x & 15;
+    const float scale = 1.0f / (float)L;
+    const float2 *gh = g + (size_t)bh * F;
+    for (int m = tid; m < 16 * N2; m += 256) {
+        const int a = m / N2, k2 = m % N2;
+        const int k = k2 + N2 * (256 * j + 16 * a + b);
+        float2 val = gh[2 * k <= L ? k : L - k];
+        if (2 * k > L) val.y = -val.y;
+        if (k == 0 || 2 * k == L) val.y = 0.0f;
+        tile[a * S + k2] = make_float2(val.x * scale, val.y * scale);
+    }
+    __syncthreads();
+    float2 *dst = gp + (size_t)bh * L + 256 * j + 16 * b;
+    for (int i = tid; i < 16 * N2; i += 256) {
+        const int a = i & 15, k2 = i >> 4;
+        dst[(size_t)k2 * 4096 + a] = tile[a * S + k2];
     }
 }
 
@@ -859,19 +847,15 @@ hipError_t launch_fused(int io, const void *v, const float2 *g, void *out, const
 }
 
 hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, int BH, hipStream_t st) {
-    const int SB = (pl.P == 3) ? pl.N2 + 16 : pl.N2 + 1, SA = (pl.P == 3) ? 16 * SB + 1 : 16 * SB;
-    const size_t lds = (size_t)16 * SA * sizeof(float2);
-    hipError_t e = allow_lds(k_gate_expand, lds);
-    if (e != hipSuccess) return e;
+    if (pl.P != 2 && pl.P != 3) return hipErrorInvalidValue;
     for (int bh0 = 0; bh0 < BH; bh0 += 65535) {         // grid.y limit
         const int n = (BH - bh0 < 65535) ? BH - bh0 : 65535;
         const int F = pl.L / 2 + 1;
         if (pl.P == 2)
             k_gate_expand256<<<dim3(8, n), dim3(256), 0, st>>>(g + (size_t)bh0 * F, gp + (size_t)bh0 * pl.L, pl.L, pl.N2);
         else
-            k_gate_expand<<<dim3(pl.N1 / 256, n), dim3(256), lds, st>>>(g + (size_t)bh0 * F, gp + (size_t)bh0 * pl.L,
-                                                                        pl.L, pl.N1, pl.N2, pl.P);
-        e = hipGetLastError();
+            k_gate_expand4096<<<dim3(256, n), dim3(256), 0, st>>>(g + (size_t)bh0 * F, gp + (size_t)bh0 * pl.L, pl.L, pl.N2);
+        const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -881,7 +865,7 @@ hipError_t launch_gate_expand(const Pow2Plan &pl, const float2 *g, float2 *gp, i
 // that no compute call is the first to touch it.
 hipError_t load_kernels_mix_pow2() {
     hipFuncAttributes a;
-    return hipFuncGetAttributes(&a, reinterpret_cast<const void *>(k_gate_expand));
+    return hipFuncGetAttributes(&a, reinterpret_cast<const void *>(k_gate_expand256));
 }
 
 }  // namespace spectre
