@@ -13,6 +13,7 @@ timed region.  Prints ONE JSON line.
 import argparse
 import ctypes
 import json
+import math
 import os
 import sys
 import time
@@ -147,9 +148,10 @@ def cpu_baseline(cfg, L):
             "sample": f"gate+mix_forward of all {cfg['B'] * H} heads at L={L} (the whole workload, one pass): {dt:.2f} s"}
 
 
-def mix_case(name, c, steps, graph=False):
-    """Mixer-only timing of one configuration.  A working set below the memory-side cache is rotated over enough
-    buffers (> 512 MB in total) that the figure is not a cache-resident one; the cache-resident time rides along."""
+def mix_case(name, c, steps, graph=False, with_gate=False):
+    """Timing of one configuration: the mixer alone and, with_gate, the gate alone and gate + mixer.  A working set
+    below the memory-side cache is rotated over enough buffers (> 512 MB in total) that the figure is not a
+    cache-resident one; the mixer's cache-resident time rides along."""
     import torch
     from paper_2502_18394_amd import binding, synth
     B, H, L, d = c["B"], c["H"], c["L"], c["d"]
@@ -179,13 +181,44 @@ def mix_case(name, c, steps, graph=False):
                 binding.mix_forward(Vs[i], g, out=outs[i], ws=ws)
         ms_graph = time_loop(gr.replay, max(reps // 8, 5), 2) / min(nbuf, 8)
         del gr
-    alg = 2 * nbytes + B * H * (L // 2 + 1) * 8
+    F = L // 2 + 1
+    alg = 2 * nbytes + B * H * F * 8
+    # share of the fp32 vector peak (157.3 TFLOP/s, which counts packed FMAs) with the usual flop count of the
+    # transform pair and the gate product: 4 log2 L + 3 flop per real element
+    flops = B * L * H * d * (4.0 * math.log2(L) + 3.0)
     row = {"workload": name, "B": B, "H": H, "L": L, "d": d, "io": c["io"], "ms": ms,
            "tokens_per_s": B * L / (ms * 1e-3), "algorithmic_bytes": alg,
-           "hbm_frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "buffers_rotated": nbuf,
-           "ms_cache_resident": ms_hot}
+           "hbm_frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "valu_frac": flops / (ms * 1e-3) / 157.3e12,
+           "buffers_rotated": nbuf, "ms_cache_resident": ms_hot}
     if graph:
         row["ms_hip_graph"] = ms_graph
+    if with_gate:
+        # rows (ii) and (iii) of the configuration: the gate from the query rows (per-head weights), and gate + mixer
+        P = device_gate_params(synth.BASE_SEED + 2, H, d, L, synth.D_GATE, binding)
+        ws_gate = torch.empty(binding.gate_workspace_bytes(B, L, H, P) + 256, dtype=torch.uint8, device="cuda")
+        gg = torch.empty((B, H, F), dtype=torch.complex64, device="cuda")
+        jt = [0]
+
+        def gate_call():
+            i = jt[0] % nbuf
+            binding.gate(Vs[i], P, 1.0 / L, g_out=gg, ws=ws_gate)
+            jt[0] += 1
+
+        def both():
+            i = jt[0] % nbuf
+            binding.gate(Vs[(i + 1) % nbuf], P, 1.0 / L, g_out=gg, ws=ws_gate)
+            binding.mix_forward(Vs[i], gg, out=outs[i], ws=ws)
+            jt[0] += 1
+        ms_g = time_loop(gate_call, reps, max(3, nbuf))
+        ms_e = time_loop(both, reps, max(3, nbuf))
+        gate_bytes = nbytes + P.Hg * P.d_g * 2 * F * 4 + B * H * F * 8
+        e2e_bytes = alg + gate_bytes - B * H * F * 8
+        row.update({"gate_ms": ms_g, "gate_algorithmic_bytes": gate_bytes,
+                    "gate_hbm_frac": gate_bytes / (ms_g * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "end_to_end_ms": ms_e, "end_to_end_algorithmic_bytes": e2e_bytes,
+                    "end_to_end_hbm_frac": e2e_bytes / (ms_e * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "end_to_end_tokens_per_s": B * L / (ms_e * 1e-3)})
+        del P, ws_gate, gg
     del Vs, outs, g, ws
     torch.cuda.empty_cache()
     return row
@@ -226,7 +259,7 @@ def sweep(args):
     for name, c in cases:
         if args.only and args.only not in name:
             continue
-        print(json.dumps(mix_case(name, c, args.steps, graph=not args.only)), flush=True)
+        print(json.dumps(mix_case(name, c, args.steps, graph=not args.only, with_gate=not args.only)), flush=True)
     if args.copy_calib:
         copy_calibration()
 
@@ -507,8 +540,9 @@ def main():
             torch.cuda.empty_cache()
 
     if not args.no_configs:
-        # every configuration the baseline names, mixer call alone (config 4 is the decode row above)
-        res["configs"] = [mix_case(name, c, args.steps) for name, c in config_cases()]
+        # every configuration the baseline names: the mixer call alone, the gate alone, gate + mixer (config 4 is the
+        # decode row above)
+        res["configs"] = [mix_case(name, c, args.steps, with_gate=True) for name, c in config_cases()]
         if "decode" in res:
             res["configs"].append({"workload": "config4_decode_32k", "ms": res["decode"]["ms_per_step"],
                                    "tokens_per_s": res["decode"]["tokens_per_s"],
